@@ -1,0 +1,170 @@
+/*
+ * C ABI of the MI355X (gfx950) integer complex-Winograd convolution library.
+ *
+ * The library computes 3x3, stride-1, dilation-1, zero-pad-1 convolution
+ * (correlation, no kernel flip) of int8 activations with int8 filters into
+ * int32 outputs with the complex Winograd algorithm F(4x4,3x3) over the
+ * Gaussian integers of Meng & Brothers, "Efficient Winograd Convolution via
+ * Integer Arithmetic" (SysML 2019), Sections 3.3-3.4 and 4.2.
+ *
+ * Conventions shared by every entry point
+ *   - Every *_dev pointer is DEVICE memory owned by the caller; the library
+ *     never allocates, frees or keeps it.  Activation, filter and output
+ *     pointers must be 4-byte aligned, packed_dev and workspace_dev 256-byte.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the null stream).
+ *     All work is enqueued on it; no call synchronises unless it says so.
+ *   - Return value: WG_OK, or a negative wg_status; on error nothing has been
+ *     enqueued.  Validation happens on the host before the first launch.
+ *   - layout WG_NCHW: activations [N][C][H][W], filters [K][C][3][3],
+ *     outputs [N][K][H][W].  layout WG_NHWC: activations [N][H][W][C], filters
+ *     [K][3][3][C], outputs [N][H][W][K].  All dense, no strides.
+ *   - 1 <= C <= WG_MAX_CHANNELS keeps every int32 accumulator exact for any
+ *     int8 data (16 * 9 * C * 128 * 128 < 2^31).
+ */
+#ifndef WINOGRAD_C_H
+#define WINOGRAD_C_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum wg_status {
+    WG_OK = 0,
+    WG_EINVAL = -1,        /* null pointer, non-positive size, unknown enum, misaligned pointer */
+    WG_EUNSUPPORTED = -2,  /* C > WG_MAX_CHANNELS, tensor too large for 32-bit indexing, odd H/W with pooling */
+    WG_ESMALLBUF = -3,     /* packed_bytes / workspace_bytes below what the query functions return */
+    WG_EBLOB = -4,         /* packed filter blob does not match (K, C, mode) */
+    WG_ERUNTIME = -5       /* a HIP launch failed */
+};
+enum wg_layout { WG_NCHW = 0, WG_NHWC = 1 };
+enum wg_mode {
+    WG_LOSSLESS = 0, /* exact: equals the direct convolution bit for bit (Section 3.3-3.4) */
+    WG_SCALED = 1    /* Winograd-domain filters scaled back into int8 per output channel and
+                        location, inverse applied before the output transform (Section 4.2) */
+};
+#define WG_MAX_CHANNELS 896
+
+/* Human-readable name of a status code; never NULL. */
+const char* winograd_status_string(int status);
+
+/* Size in bytes of the packed Winograd-domain filter blob for K filters of C
+   channels in the given mode; 0 if the arguments are invalid. */
+size_t winograd_packed_filter_bytes(int K, int C, int mode);
+
+/* Size in bytes of the scratch workspace winograd_conv2d_int8 needs for this
+   problem (transformed activations and Winograd-domain accumulators); 0 if
+   the arguments are invalid. */
+size_t winograd_workspace_bytes(int N, int C, int H, int W, int K, int mode);
+
+/*
+ * Filter transform W = G' g G'^T with G' = 4G (Section 3.3; the conjugate
+ * structure of W is the one printed in Section 3.4), done once per layer and
+ * reused by every convolution call (Section 4.3 notes it is off the
+ * inference path).  Only the 26 free entries of each 6x6 tile are kept
+ * (16 real, 10 complex), already split into the int8 operand planes the
+ * contraction consumes.
+ *   WG_LOSSLESS: 12-bit entries as exact int8 limbs.
+ *   WG_SCALED:   Section 4.2's precision scaling for int8 filters: per output
+ *                channel and location, the largest max(|Re|,|Im|) over input
+ *                channels; if above 127 every entry there is multiplied by the
+ *                largest n/2^p (4-bit n) that brings it back within +-127,
+ *                rounding half up; the blob also holds the 8-bit reciprocal
+ *                r/2^q applied later.
+ * w_dev: int8 filters in `layout`.  packed_dev: blob of at least
+ * winograd_packed_filter_bytes(K, C, mode) bytes, fully overwritten.
+ */
+int winograd_filter_transform(const int8_t* w_dev, int K, int C, int layout, int mode,
+                              void* packed_dev, size_t packed_bytes, void* hip_stream);
+
+/*
+ * Synchronous check that a blob was produced by winograd_filter_transform
+ * for exactly (K, C, mode): copies the blob header to the host (blocks on
+ * hip_stream).  WG_OK or WG_EBLOB.  The convolution entry points do not do
+ * this themselves because they never synchronise; their kernels re-check the
+ * header on the device and leave the output untouched on a mismatch.
+ */
+int winograd_packed_filter_check(const void* packed_dev, int K, int C, int mode, void* hip_stream);
+
+/*
+ * The whole hot path Y = A^T [ sum_c W (.) (B^T d B) ] A (Section 3.4) for
+ * every 4x4 output tile: input transform of the overlapping 6x6 tiles,
+ * Winograd-domain contraction over input channels on the int8 matrix cores
+ * (16 real and 10 complex products per tile and channel pair, three real
+ * multiplications per complex one, partial products kept separate until the
+ * channel sum is complete), the inverse filter scaling in WG_SCALED mode, and
+ * the output transform followed by the rescale by 2^-4 (G' = 4G twice).
+ * WG_LOSSLESS results equal direct_conv2d_int8's bit for bit.  WG_SCALED
+ * rounds half up at the inverse scaling and at the final shift.
+ * x_dev: int8 activations; packed_dev: blob from winograd_filter_transform
+ * with the same (K, C, mode); y_dev: int32 output, every element written.
+ * workspace_dev: at least winograd_workspace_bytes(...) bytes; contents are
+ * scratch and calls sharing a workspace must not overlap in time.
+ */
+int winograd_conv2d_int8(const int8_t* x_dev, const void* packed_dev, int32_t* y_dev,
+                         int N, int C, int H, int W, int K, int layout, int mode,
+                         void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Direct evaluation of the same convolution (the 144-multiplication method
+ * that Section 3.4 compares against):
+ *   y[n,k,h,w] = sum_{c,a,b} x[n,c,h+a-1,w+b-1] * g[k,c,a,b],  x = 0 outside.
+ * w_dev: the untransformed int8 filters in `layout`.
+ */
+int direct_conv2d_int8(const int8_t* x_dev, const int8_t* w_dev, int32_t* y_dev,
+                       int N, int C, int H, int W, int K, int layout, void* hip_stream);
+
+/*
+ * Glue for stacking layers (a requantisation follows each quantised
+ * convolution, Section 4.4): v = (y + 2^(shift-1)) >> shift (shift = 0: v = y),
+ * clamped to [0,127] if relu else [-128,127], then an optional 2x2 stride-2
+ * max-pool (H and W must then be even).  y_dev int32 and out_dev int8 use
+ * `layout` with K channels; out is [N][K][H/2][W/2] (or NHWC) when pool != 0.
+ * 0 <= shift <= 31.
+ */
+int requant_relu_pool_int8(const int32_t* y_dev, int8_t* out_dev, int N, int K, int H, int W,
+                           int layout, int shift, int relu, int pool, void* hip_stream);
+
+/* ---- stage exports used by the stage-level parity tests ------------------
+ * Operand-plane numbering.  The 26 free entries of a transformed tile are
+ * ordered: real entries (r,c), r,c in {0,1,2,5}, row-major (index 4*ri+ci),
+ * then the complex ones (0,3) (1,3) (2,3) (5,3) (3,0) (3,1) (3,2) (3,5) (3,3)
+ * (3,4).  "Values": one per real entry (0..15), three per complex entry j
+ * (16+3j: Re, +1: Im, +2: Re+Im, the extra operand of the three-multiplication
+ * complex product of Section 3.1).
+ *   WG_LOSSLESS operand planes, both sides: 3*value + {0: high limb v>>6,
+ *     1: low limb v&63, 2: high+low}, 138 planes.
+ *   WG_SCALED activation planes: real entry p: 2p + {0: high, 1: low};
+ *     complex entry j: 32 + 4j + {Re high, Re low, Im high, Im low}; 72 planes.
+ *   WG_SCALED filter planes: real entry p: p; complex entry j: 16 + 3j +
+ *     {Re, Im, -Im}; 46 planes.
+ * Accumulator planes (36): real entry p: p; complex entry j: 16 + 2j + {Re, Im}.
+ */
+int winograd_num_activation_planes(int mode);
+int winograd_num_filter_planes(int mode);
+
+/* Runs only the input transform D = B^T d B (Section 3.4) and writes its int8
+   operand planes as a dense [planes][T][C] array, T = N*ceil(H/4)*ceil(W/4),
+   tile index (n*TH + ty)*TW + tx. */
+int winograd_debug_input_operands(const int8_t* x_dev, int8_t* planes_dev, int N, int C, int H,
+                                  int W, int layout, int mode, void* workspace_dev,
+                                  size_t workspace_bytes, void* hip_stream);
+
+/* Unpacks a filter blob into dense int8 [planes][K][C] and the scaling table
+   int32 [K][26][4] = (n, p, r, q) per output channel and free entry
+   (all zero-scaling entries (0,0,1,0); WG_LOSSLESS fills the table the same way). */
+int winograd_debug_filter_operands(const void* packed_dev, int K, int C, int mode,
+                                   int8_t* planes_dev, int32_t* table_dev, void* hip_stream);
+
+/* Runs input transform and contraction (and the inverse scaling in WG_SCALED)
+   and writes the 36 accumulator planes as dense int32 [36][T][K]. */
+int winograd_debug_contraction(const int8_t* x_dev, const void* packed_dev, int32_t* m_dev,
+                               int N, int C, int H, int W, int K, int layout, int mode,
+                               void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WINOGRAD_C_H */

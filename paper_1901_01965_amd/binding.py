@@ -1,0 +1,221 @@
+"""Thin ctypes binding of libwinograd_mi355x.so: argument marshalling only.
+
+Every step of the convolution runs in the library's HIP kernels.  PyTorch is
+used for device memory (tensors' ``data_ptr()``) and for the current HIP
+stream, nothing else.  There is no CPU or PyTorch fallback: if the shared
+library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+from .build import LIB_PATH
+
+NCHW, NHWC = 0, 1
+LOSSLESS, SCALED = 0, 1
+MAX_CHANNELS = 896
+_MODES = {"lossless": LOSSLESS, "scaled": SCALED, LOSSLESS: LOSSLESS, SCALED: SCALED}
+_LAYOUTS = {"nchw": NCHW, "nhwc": NHWC, NCHW: NCHW, NHWC: NHWC}
+
+_lib = None
+
+
+class WinogradError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, status_string(status), status))
+
+
+def load_library():
+    """Load the in-tree HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "HIP library %s not found: run `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(there is no fallback path)" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    sigs = {
+        "winograd_status_string": (ctypes.c_char_p, [i]),
+        "winograd_num_activation_planes": (i, [i]),
+        "winograd_num_filter_planes": (i, [i]),
+        "winograd_packed_filter_bytes": (sz, [i, i, i]),
+        "winograd_workspace_bytes": (sz, [i, i, i, i, i, i]),
+        "winograd_filter_transform": (i, [vp, i, i, i, i, vp, sz, vp]),
+        "winograd_packed_filter_check": (i, [vp, i, i, i, vp]),
+        "winograd_conv2d_int8": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp, sz, vp]),
+        "direct_conv2d_int8": (i, [vp, vp, vp, i, i, i, i, i, i, vp]),
+        "requant_relu_pool_int8": (i, [vp, vp, i, i, i, i, i, i, i, i, vp]),
+        "winograd_debug_input_operands": (i, [vp, vp, i, i, i, i, i, i, vp, sz, vp]),
+        "winograd_debug_filter_operands": (i, [vp, i, i, i, vp, vp, vp]),
+        "winograd_debug_contraction": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp, sz, vp]),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+EXPORTED_SYMBOLS = (
+    "winograd_status_string", "winograd_num_activation_planes", "winograd_num_filter_planes",
+    "winograd_packed_filter_bytes", "winograd_workspace_bytes", "winograd_filter_transform",
+    "winograd_packed_filter_check", "winograd_conv2d_int8", "direct_conv2d_int8", "requant_relu_pool_int8",
+    "winograd_debug_input_operands", "winograd_debug_filter_operands", "winograd_debug_contraction",
+)
+
+
+def status_string(status):
+    return load_library().winograd_status_string(int(status)).decode()
+
+
+def _check(status, where):
+    if status != 0:
+        raise WinogradError(status, where)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _dims(x, layout):
+    if layout == NCHW:
+        N, C, H, W = x.shape
+    else:
+        N, H, W, C = x.shape
+    return N, C, H, W
+
+
+def _need(t, dtype, what):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous CUDA tensor of %s" % (what, dtype))
+
+
+def packed_filter_bytes(K, C, mode):
+    return int(load_library().winograd_packed_filter_bytes(K, C, _MODES[mode]))
+
+
+def workspace_bytes(N, C, H, W, K, mode):
+    return int(load_library().winograd_workspace_bytes(N, C, H, W, K, _MODES[mode]))
+
+
+class PackedFilter:
+    """Device blob of Winograd-domain filters plus the (K, C, mode) it was made for."""
+
+    def __init__(self, blob, K, C, mode):
+        self.blob, self.K, self.C, self.mode = blob, K, C, mode
+
+    def check(self):
+        _check(load_library().winograd_packed_filter_check(_ptr(self.blob), self.K, self.C, self.mode, _stream()),
+               "winograd_packed_filter_check")
+
+
+def winograd_filter_transform(w, layout=NCHW, mode=LOSSLESS, blob=None):
+    """w: int8 [K,C,3,3] (NCHW) or [K,3,3,C] (NHWC) on the GPU -> PackedFilter."""
+    layout, mode = _LAYOUTS[layout], _MODES[mode]
+    _need(w, torch.int8, "w")
+    K = w.shape[0]
+    C = w.shape[1] if layout == NCHW else w.shape[3]
+    nbytes = packed_filter_bytes(K, C, mode)
+    if nbytes == 0:
+        _check(load_library().winograd_filter_transform(_ptr(w), K, C, layout, mode, None, 0, _stream()),
+               "winograd_filter_transform")
+    if blob is None:
+        blob = torch.empty(nbytes, dtype=torch.uint8, device=w.device)
+    _check(load_library().winograd_filter_transform(_ptr(w), K, C, layout, mode, _ptr(blob), blob.numel(), _stream()),
+           "winograd_filter_transform")
+    return PackedFilter(blob, K, C, mode)
+
+
+def make_workspace(N, C, H, W, K, mode, device="cuda"):
+    return torch.empty(workspace_bytes(N, C, H, W, K, mode), dtype=torch.uint8, device=device)
+
+
+def winograd_conv2d_int8(x, packed, layout=NCHW, out=None, workspace=None):
+    """x: int8 activations in `layout`; packed: PackedFilter.  Returns int32 output in `layout`."""
+    layout = _LAYOUTS[layout]
+    _need(x, torch.int8, "x")
+    N, C, H, W = _dims(x, layout)
+    K = packed.K
+    if workspace is None:
+        workspace = make_workspace(N, C, H, W, K, packed.mode, x.device)
+    if out is None:
+        shape = (N, K, H, W) if layout == NCHW else (N, H, W, K)
+        out = torch.empty(shape, dtype=torch.int32, device=x.device)
+    _check(load_library().winograd_conv2d_int8(_ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout,
+                                               packed.mode, _ptr(workspace), workspace.numel(), _stream()),
+           "winograd_conv2d_int8")
+    return out
+
+
+def direct_conv2d_int8(x, w, layout=NCHW, out=None):
+    layout = _LAYOUTS[layout]
+    _need(x, torch.int8, "x")
+    _need(w, torch.int8, "w")
+    N, C, H, W = _dims(x, layout)
+    K = w.shape[0]
+    if out is None:
+        shape = (N, K, H, W) if layout == NCHW else (N, H, W, K)
+        out = torch.empty(shape, dtype=torch.int32, device=x.device)
+    _check(load_library().direct_conv2d_int8(_ptr(x), _ptr(w), _ptr(out), N, C, H, W, K, layout, _stream()),
+           "direct_conv2d_int8")
+    return out
+
+
+def requant_relu_pool_int8(y, shift, relu=True, pool=False, layout=NCHW, out=None):
+    layout = _LAYOUTS[layout]
+    _need(y, torch.int32, "y")
+    N, K, H, W = _dims(y, layout)
+    Ho, Wo = (H // 2, W // 2) if pool else (H, W)
+    if out is None:
+        shape = (N, K, Ho, Wo) if layout == NCHW else (N, Ho, Wo, K)
+        out = torch.empty(shape, dtype=torch.int8, device=y.device)
+    _check(load_library().requant_relu_pool_int8(_ptr(y), _ptr(out), N, K, H, W, layout, int(shift), int(relu),
+                                                 int(pool), _stream()), "requant_relu_pool_int8")
+    return out
+
+
+def debug_input_operands(x, layout=NCHW, mode=LOSSLESS):
+    """int8 [planes, T, C]: the operand planes the input transform hands to the contraction."""
+    layout, mode = _LAYOUTS[layout], _MODES[mode]
+    _need(x, torch.int8, "x")
+    N, C, H, W = _dims(x, layout)
+    lib = load_library()
+    T = N * ((H + 3) // 4) * ((W + 3) // 4)
+    out = torch.empty((lib.winograd_num_activation_planes(mode), T, C), dtype=torch.int8, device=x.device)
+    ws = make_workspace(N, C, H, W, 1, mode, x.device)
+    _check(lib.winograd_debug_input_operands(_ptr(x), _ptr(out), N, C, H, W, layout, mode, _ptr(ws), ws.numel(),
+                                             _stream()), "winograd_debug_input_operands")
+    return out
+
+
+def debug_filter_operands(packed):
+    """(int8 [planes, K, C], int32 [K, 26, 4]) unpacked from a PackedFilter."""
+    lib = load_library()
+    planes = torch.empty((lib.winograd_num_filter_planes(packed.mode), packed.K, packed.C), dtype=torch.int8,
+                         device=packed.blob.device)
+    table = torch.empty((packed.K, 26, 4), dtype=torch.int32, device=packed.blob.device)
+    _check(lib.winograd_debug_filter_operands(_ptr(packed.blob), packed.K, packed.C, packed.mode, _ptr(planes),
+                                              _ptr(table), _stream()), "winograd_debug_filter_operands")
+    return planes, table
+
+
+def debug_contraction(x, packed, layout=NCHW):
+    """int32 [36, T, K]: the Winograd-domain accumulators after contraction (and inverse scaling)."""
+    layout = _LAYOUTS[layout]
+    _need(x, torch.int8, "x")
+    N, C, H, W = _dims(x, layout)
+    T = N * ((H + 3) // 4) * ((W + 3) // 4)
+    out = torch.empty((36, T, packed.K), dtype=torch.int32, device=x.device)
+    ws = make_workspace(N, C, H, W, packed.K, packed.mode, x.device)
+    _check(load_library().winograd_debug_contraction(_ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, packed.K,
+                                                     layout, packed.mode, _ptr(ws), ws.numel(), _stream()),
+           "winograd_debug_contraction")
+    return out

@@ -1,0 +1,116 @@
+// Internal declarations shared by the HIP translation units of the library:
+// problem geometry, HBM layouts of the packed filter blob and the workspace,
+// the numbering of the free Winograd-domain entries, and the stage launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "winograd_c.h"
+
+namespace wg {
+
+// ---- geometry ---------------------------------------------------------------
+constexpr int kCBlock = 64;      // input channels per operand row (bytes per row)
+constexpr int kTilePad = 64;     // tile count is padded to a multiple of this
+constexpr int kFilterPad = 64;   // filter count is padded to a multiple of this
+constexpr int kEntries = 26;     // free entries of a transformed 6x6 tile (Section 3.4)
+constexpr int kRealEntries = 16;
+constexpr int kAccPlanes = 36;   // 16 real + 10 * (Re, Im)
+constexpr int kWeightRange = 127;  // spatial range of signed int8 filters, the target of the scaling
+
+struct Problem {
+    int N, C, H, W, K;
+    int TH, TW, T;   // tiles per column / row, total tiles
+    int Tp;          // T padded to kTilePad
+    int CB;          // ceil(C / 64)
+    int Kp;          // K padded to kFilterPad
+};
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline size_t round_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
+
+inline Problem make_problem(int N, int C, int H, int W, int K) {
+    Problem p;
+    p.N = N; p.C = C; p.H = H; p.W = W; p.K = K;
+    p.TH = ceil_div(H, 4); p.TW = ceil_div(W, 4);
+    p.T = N * p.TH * p.TW;
+    p.Tp = ceil_div(p.T, kTilePad) * kTilePad;
+    p.CB = ceil_div(C, kCBlock);
+    p.Kp = ceil_div(K, kFilterPad) * kFilterPad;
+    return p;
+}
+
+__host__ __device__ inline int num_activation_planes(int mode) { return mode == WG_LOSSLESS ? 138 : 72; }
+__host__ __device__ inline int num_filter_planes(int mode) { return mode == WG_LOSSLESS ? 138 : 46; }
+
+// ---- packed filter blob -------------------------------------------------------
+// [BlobHeader, 256 B][maxmag: uint32 [Kp][26]][table: ScaleEntry [Kp][26]]
+// [operand planes: int8 [planes][CB][Kp][64]], each section 256-byte aligned.
+constexpr uint32_t kBlobMagic = 0x33344757u;  // "WG43"
+constexpr uint32_t kBlobVersion = 1;
+
+struct BlobHeader {
+    uint32_t magic, version;
+    int32_t K, C, mode, range, Kp, CB, planes;
+    uint32_t reserved[55];
+};
+static_assert(sizeof(BlobHeader) == 256, "blob header is one 256-byte block");
+
+struct ScaleEntry {  // per (filter k, free entry): down-scale n/2^p, inverse r/2^q
+    int32_t n, p, r, q;
+};
+
+struct BlobLayout {
+    size_t maxmag_off, table_off, planes_off, total;
+};
+inline BlobLayout blob_layout(int Kp, int CB, int mode) {
+    BlobLayout b;
+    b.maxmag_off = sizeof(BlobHeader);
+    b.table_off = round_up(b.maxmag_off + (size_t)Kp * kEntries * sizeof(uint32_t), 256);
+    b.planes_off = round_up(b.table_off + (size_t)Kp * kEntries * sizeof(ScaleEntry), 256);
+    b.total = b.planes_off + (size_t)num_filter_planes(mode) * CB * Kp * kCBlock;
+    return b;
+}
+
+// ---- workspace ------------------------------------------------------------------
+// [V: int8 [planes][CB][Tp][64]][M: int32 [36][Tp][Kp]]
+struct WorkspaceLayout {
+    size_t v_off, m_off, total;
+};
+inline WorkspaceLayout workspace_layout(const Problem& p, int mode) {
+    WorkspaceLayout w;
+    w.v_off = 0;
+    w.m_off = round_up((size_t)num_activation_planes(mode) * p.CB * p.Tp * kCBlock, 256);
+    w.total = w.m_off + (size_t)kAccPlanes * p.Tp * p.Kp * sizeof(int32_t);
+    return w;
+}
+
+// ---- stage launchers (each enqueues on `s` and returns the launch status) --------
+hipError_t launch_filter_transform(const int8_t* w, int K, int C, int layout, int mode, void* blob,
+                                   hipStream_t s);
+hipError_t launch_input_transform(const int8_t* x, const Problem& p, int layout, int mode,
+                                  int8_t* V, hipStream_t s);
+hipError_t launch_contraction(const int8_t* V, const void* blob, int32_t* M, const Problem& p,
+                              int mode, hipStream_t s);
+hipError_t launch_output_transform(const int32_t* M, const void* blob, int32_t* y, const Problem& p,
+                                   int layout, int mode, hipStream_t s);
+hipError_t launch_direct_conv(const int8_t* x, const int8_t* w, int32_t* y, const Problem& p,
+                              int layout, hipStream_t s);
+hipError_t launch_requant_relu_pool(const int32_t* y, int8_t* out, int N, int K, int H, int W,
+                                    int layout, int shift, int relu, int pool, hipStream_t s);
+hipError_t launch_unpack_activation_planes(const int8_t* V, int8_t* dense, const Problem& p, int mode,
+                                           hipStream_t s);
+hipError_t launch_unpack_filter_planes(const void* blob, int8_t* dense, int32_t* table, int K, int C,
+                                       int mode, hipStream_t s);
+hipError_t launch_unpack_accumulators(const int32_t* M, int32_t* dense, const Problem& p,
+                                      hipStream_t s);
+
+// True on the device when the blob header matches; kernels that consume a blob
+// return without side effects otherwise.
+__device__ inline bool blob_matches(const BlobHeader* h, int K, int C, int mode) {
+    return h->magic == kBlobMagic && h->version == kBlobVersion && h->K == K && h->C == C &&
+           h->mode == mode;
+}
+
+}  // namespace wg
