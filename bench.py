@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the integer complex-Winograd F(4x4,3x3) convolution on one MI355X.
+
+One "step" is one pass of the whole hot path (input transform, Winograd-domain
+contraction on the int8 matrix cores, output transform) over one batch of the
+ResNet-style 56x56x64 layer (N=8, C=K=64, lossless mode, channels-last), with
+activations and the packed Winograd-domain filters already resident in HBM.
+The filter transform is done once before timing, as the paper prescribes
+(Section 4.3: off the inference path); its time is reported separately.
+
+Prints ONE JSON line.  `value` is direct-equivalent int8 TOPS,
+2*9*N*K*C*H*W / time.  `roofline` describes the kernel that takes the most
+time; `cpu_baseline` is the CPU oracle timed on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8
+
+STAGES = ("input_transform", "contraction", "output_transform")
+
+
+def algorithmic_bytes(case, mode):
+    """Algorithmic HBM bytes per launch of each kernel (the unavoidable traffic of a staged pipeline):
+    input transform: 16 B read + 72 B written per (tile, channel) (36 planes of 12 bits as two int8 limbs);
+    contraction: 72 B read per (tile, channel), the packed filters once, 144 B written per (tile, filter);
+    output transform: 144 B read + 64 B written per (tile, filter)."""
+    T, C, K = case.tiles, case.C, case.K
+    filt = (72 if mode == "lossless" else 36) * K * C
+    return {
+        "input_transform": (16 + 72) * T * C,
+        "contraction": 72 * T * C + filt + 144 * T * K,
+        "output_transform": (144 + 64) * T * K,
+    }
+
+
+def contraction_int8_ops(case, mode):
+    """int8 multiply-adds x2 the method needs on the matrix cores: 46 real products per tile and channel
+    pair (Section 3.4), each three int8 limb products in lossless mode (138), 112 in scaled mode."""
+    per_pair = 138 if mode == "lossless" else 112
+    return 2 * per_pair * case.tiles * case.C * case.K
+
+
+def read_profiled_traffic(kernel):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_cfg2.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                m = re.match(r"^traffic_bytes_per_launch\s+%s\s+(\d+)" % kernel, line)
+                if m:
+                    return int(m.group(1))
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--case", default="cfg2", help="workload (default: the 56x56x64 layer the metric is quoted on)")
+    ap.add_argument("--mode", default="lossless", choices=("lossless", "scaled"))
+    ap.add_argument("--layout", default="nhwc", choices=("nhwc", "nchw"))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures one GPU only (the path has no cross-GPU step); use --gpus 1")
+
+    import numpy as np
+    import torch
+    import paper_1901_01965_amd as wg
+    from paper_1901_01965_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    wg.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    case = wl.CASES[args.case]
+    layout = wg.NHWC if args.layout == "nhwc" else wg.NCHW
+    mode = wg.LOSSLESS if args.mode == "lossless" else wg.SCALED
+
+    x_np, g_np = wl.make_case(case)
+    xd = torch.from_numpy(wl.to_nhwc(x_np) if layout == wg.NHWC else x_np).to(dev)
+    gd = torch.from_numpy(wl.to_krsc(g_np) if layout == wg.NHWC else g_np).to(dev)
+    ws = wg.make_workspace(case.N, case.C, case.H, case.W, case.K, mode, dev)
+    out_shape = (case.N, case.H, case.W, case.K) if layout == wg.NHWC else (case.N, case.K, case.H, case.W)
+    y = torch.empty(out_shape, dtype=torch.int32, device=dev)
+
+    # offline filter transform (timed on its own)
+    packed = wg.winograd_filter_transform(gd, layout, mode)
+    packed.check()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(10):
+        wg.winograd_filter_transform(gd, layout, mode, blob=packed.blob)
+    torch.cuda.synchronize()
+    filter_ms = (time.perf_counter() - t0) / 10 * 1e3
+
+    for _ in range(args.warmup):
+        wg.winograd_conv2d_int8(xd, packed, layout, out=y, workspace=ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        wg.winograd_conv2d_int8(xd, packed, layout, out=y, workspace=ws)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    tops = case.direct_ops / (elapsed / args.steps) / 1e12
+
+    # per-kernel durations: HIP events on the launch stream, inside the library
+    stage_ms = wg.stage_times(xd, packed, layout, iters=max(20, args.steps // 2), out=y, workspace=ws)
+    stage = dict(zip(STAGES, stage_ms))
+    alg = algorithmic_bytes(case, args.mode)
+    dominant = max(STAGES, key=lambda s: stage[s])
+    achieved = alg[dominant] / (stage[dominant] * 1e-3) / 1e9
+    roofline = {
+        "kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_profiled_traffic(dominant),
+        "algorithmic_bytes": alg[dominant], "kernel_ms": round(stage[dominant], 5),
+    }
+    mfma_tops = contraction_int8_ops(case, args.mode) / (stage["contraction"] * 1e-3) / 1e12
+    kernels = {
+        s: {"ms": round(stage[s], 5), "algorithmic_GBps": round(alg[s] / (stage[s] * 1e-3) / 1e9, 1),
+            "hbm_frac": round(alg[s] / (stage[s] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        for s in STAGES
+    }
+    kernels["contraction"]["int8_mfma_TOPS"] = round(mfma_tops, 1)
+    kernels["contraction"]["mfma_frac"] = round(mfma_tops / INT8_MFMA_PEAK_TOPS, 4)
+
+    # direct convolution on the same inputs, for context
+    yd = torch.empty_like(y)
+    for _ in range(3):
+        wg.direct_conv2d_int8(xd, gd, layout, out=yd)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(10):
+        wg.direct_conv2d_int8(xd, gd, layout, out=yd)
+    torch.cuda.synchronize()
+    direct_ms = (time.perf_counter() - t0) / 10 * 1e3
+    same_as_direct = bool(torch.equal(y, yd)) if mode == wg.LOSSLESS else None
+
+    result = {
+        "metric": "direct-equivalent int8 conv TOPS, 56x56x64 layer, 1 GPU" if args.case == "cfg2"
+                  else "direct-equivalent int8 conv TOPS, %s, 1 GPU" % args.case,
+        "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "%s: 3x3 s1 p1 conv N=%d C=%d K=%d H=W=%d, %s, %s mode" % (
+            case.name, case.N, case.C, case.K, case.H, args.layout.upper(), args.mode)},
+        "roofline": roofline,
+        "kernels": kernels,
+        "filter_transform_ms": round(filter_ms, 4),
+        "direct_conv_ms": round(direct_ms, 4),
+        "gpu_lossless_equals_gpu_direct": same_as_direct,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        omode = oracle.LOSSLESS if mode == wg.LOSSLESS else oracle.SCALED
+        oracle.winograd_conv2d(x_np[:1], g_np, omode)           # build + page in
+        runs, t_cpu = 0, 0.0
+        want = None
+        while t_cpu < args.cpu_seconds or runs < 2:
+            t0 = time.perf_counter()
+            want, _ = oracle.winograd_conv2d(x_np, g_np, omode)
+            t_cpu += time.perf_counter() - t0
+            runs += 1
+        cpu_tops = case.direct_ops * runs / t_cpu / 1e12
+        got = y.cpu().numpy()
+        got = wl.from_nhwc(got) if layout == wg.NHWC else got
+        result["gpu_equals_oracle"] = bool(np.array_equal(got, want))
+        result["cpu_baseline"] = {
+            "value": round(cpu_tops, 5), "unit": "TOPS", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "the whole %s batch through the oracle's Gaussian-integer Winograd path, %d runs, %.1f s"
+                      % (case.name, runs, t_cpu),
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

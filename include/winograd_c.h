@@ -127,6 +127,19 @@ int direct_conv2d_int8(const int8_t* x_dev, const int8_t* w_dev, int32_t* y_dev,
 int requant_relu_pool_int8(const int32_t* y_dev, int8_t* out_dev, int N, int K, int H, int W,
                            int layout, int shift, int relu, int pool, void* hip_stream);
 
+/*
+ * Measurement aid for benchmarks: enqueues each of winograd_conv2d_int8's three
+ * kernels (input transform, contraction, output transform; same arguments and
+ * launch configuration as that call) `iters` times back to back on hip_stream
+ * between two HIP events, waits, and writes the mean milliseconds per launch of
+ * each kernel to stage_ms_host[0..2] (HOST memory).  This call blocks.  y_dev
+ * holds the convolution result afterwards.  iters >= 1.
+ */
+int winograd_conv2d_int8_stage_times(const int8_t* x_dev, const void* packed_dev, int32_t* y_dev,
+                                     int N, int C, int H, int W, int K, int layout, int mode,
+                                     void* workspace_dev, size_t workspace_bytes, void* hip_stream,
+                                     int iters, float* stage_ms_host);
+
 /* ---- stage exports used by the stage-level parity tests ------------------
  * Operand-plane numbering.  The 26 free entries of a transformed tile are
  * ordered: real entries (r,c), r,c in {0,1,2,5}, row-major (index 4*ri+ci),

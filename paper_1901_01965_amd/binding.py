@@ -47,6 +47,7 @@ def load_library():
         "winograd_filter_transform": (i, [vp, i, i, i, i, vp, sz, vp]),
         "winograd_packed_filter_check": (i, [vp, i, i, i, vp]),
         "winograd_conv2d_int8": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp, sz, vp]),
+        "winograd_conv2d_int8_stage_times": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp, sz, vp, i, vp]),
         "direct_conv2d_int8": (i, [vp, vp, vp, i, i, i, i, i, i, vp]),
         "requant_relu_pool_int8": (i, [vp, vp, i, i, i, i, i, i, i, i, vp]),
         "winograd_debug_input_operands": (i, [vp, vp, i, i, i, i, i, i, vp, sz, vp]),
@@ -63,7 +64,8 @@ def load_library():
 EXPORTED_SYMBOLS = (
     "winograd_status_string", "winograd_num_activation_planes", "winograd_num_filter_planes",
     "winograd_packed_filter_bytes", "winograd_workspace_bytes", "winograd_filter_transform",
-    "winograd_packed_filter_check", "winograd_conv2d_int8", "direct_conv2d_int8", "requant_relu_pool_int8",
+    "winograd_packed_filter_check", "winograd_conv2d_int8", "winograd_conv2d_int8_stage_times",
+    "direct_conv2d_int8", "requant_relu_pool_int8",
     "winograd_debug_input_operands", "winograd_debug_filter_operands", "winograd_debug_contraction",
 )
 
@@ -153,6 +155,24 @@ def winograd_conv2d_int8(x, packed, layout=NCHW, out=None, workspace=None):
                                                packed.mode, _ptr(workspace), workspace.numel(), _stream()),
            "winograd_conv2d_int8")
     return out
+
+
+def stage_times(x, packed, layout=NCHW, iters=20, out=None, workspace=None):
+    """Mean milliseconds per launch of (input transform, contraction, output transform); blocks."""
+    layout = _LAYOUTS[layout]
+    _need(x, torch.int8, "x")
+    N, C, H, W = _dims(x, layout)
+    K = packed.K
+    if workspace is None:
+        workspace = make_workspace(N, C, H, W, K, packed.mode, x.device)
+    if out is None:
+        shape = (N, K, H, W) if layout == NCHW else (N, H, W, K)
+        out = torch.empty(shape, dtype=torch.int32, device=x.device)
+    ms = (ctypes.c_float * 3)()
+    _check(load_library().winograd_conv2d_int8_stage_times(
+        _ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout, packed.mode, _ptr(workspace),
+        workspace.numel(), _stream(), int(iters), ctypes.cast(ms, ctypes.c_void_p)), "winograd_conv2d_int8_stage_times")
+    return [float(v) for v in ms]
 
 
 def direct_conv2d_int8(x, w, layout=NCHW, out=None):

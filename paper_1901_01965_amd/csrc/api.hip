@@ -109,6 +109,41 @@ int winograd_conv2d_int8(const int8_t* x_dev, const void* packed_dev, int32_t* y
     return status_of(launch_output_transform(M, packed_dev, y_dev, p, layout, mode, s));
 }
 
+int winograd_conv2d_int8_stage_times(const int8_t* x_dev, const void* packed_dev, int32_t* y_dev, int N, int C,
+                                     int H, int W, int K, int layout, int mode, void* workspace_dev,
+                                     size_t workspace_bytes, void* hip_stream, int iters, float* stage_ms_host) {
+    if (!stage_ms_host || iters < 1) return WG_EINVAL;
+    if (int st = check_conv_args(x_dev, packed_dev, y_dev, N, C, H, W, K, layout, mode, workspace_dev,
+                                 workspace_bytes))
+        return st;
+    const Problem p = make_problem(N, C, H, W, K);
+    const WorkspaceLayout wl = workspace_layout(p, mode);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    int8_t* V = static_cast<int8_t*>(workspace_dev) + wl.v_off;
+    int32_t* M = reinterpret_cast<int32_t*>(static_cast<uint8_t*>(workspace_dev) + wl.m_off);
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return WG_ERUNTIME;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return WG_ERUNTIME; }
+    int status = WG_OK;
+    for (int stage = 0; stage < 3 && status == WG_OK; ++stage) {
+        hipError_t e = hipEventRecord(e0, s);
+        for (int i = 0; i < iters && e == hipSuccess; ++i) {
+            if (stage == 0)      e = launch_input_transform(x_dev, p, layout, mode, V, s);
+            else if (stage == 1) e = launch_contraction(V, packed_dev, M, p, mode, s);
+            else                 e = launch_output_transform(M, packed_dev, y_dev, p, layout, mode, s);
+        }
+        if (e == hipSuccess) e = hipEventRecord(e1, s);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        stage_ms_host[stage] = ms / (float)iters;
+        status = status_of(e);
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return status;
+}
+
 int direct_conv2d_int8(const int8_t* x_dev, const int8_t* w_dev, int32_t* y_dev, int N, int C, int H, int W,
                        int K, int layout, void* hip_stream) {
     if (!x_dev || !w_dev || !y_dev || !valid_layout(layout)) return WG_EINVAL;
