@@ -25,20 +25,22 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8
 
-STAGES = ("input_transform", "contraction", "output_transform")
+STAGES = ("input_transform", "contraction", "output_transform", "fused_conv")
 
 
 def algorithmic_bytes(case, mode):
-    """Algorithmic HBM bytes per launch of each kernel (the unavoidable traffic of a staged pipeline):
+    """Algorithmic HBM bytes per launch of each kernel (the unavoidable traffic):
     input transform: 16 B read + 72 B written per (tile, channel) (36 planes of 12 bits as two int8 limbs);
     contraction: 72 B read per (tile, channel), the packed filters once, 144 B written per (tile, filter);
-    output transform: 144 B read + 64 B written per (tile, filter)."""
+    output transform: 144 B read + 64 B written per (tile, filter);
+    fused kernel: 16 B read per (tile, channel), the packed filters once, 64 B written per (tile, filter)."""
     T, C, K = case.tiles, case.C, case.K
     filt = (72 if mode == "lossless" else 36) * K * C
     return {
         "input_transform": (16 + 72) * T * C,
         "contraction": 72 * T * C + filt + 144 * T * K,
         "output_transform": (144 + 64) * T * K,
+        "fused_conv": 16 * T * C + filt + 64 * T * K,
     }
 
 
@@ -123,21 +125,27 @@ def main():
     stage_ms = wg.stage_times(xd, packed, layout, iters=max(20, args.steps // 2), out=y, workspace=ws)
     stage = dict(zip(STAGES, stage_ms))
     alg = algorithmic_bytes(case, args.mode)
-    dominant = max(STAGES, key=lambda s: stage[s])
+    path = wg.conv2d_path(case.N, case.C, case.H, case.W, case.K, mode)
+    used = ("fused_conv",) if path == wg.FUSED else STAGES[:3]
+    dominant = max(used, key=lambda s: stage[s])
     achieved = alg[dominant] / (stage[dominant] * 1e-3) / 1e9
     roofline = {
         "kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_profiled_traffic(dominant),
         "algorithmic_bytes": alg[dominant], "kernel_ms": round(stage[dominant], 5),
     }
-    mfma_tops = contraction_int8_ops(case, args.mode) / (stage["contraction"] * 1e-3) / 1e12
     kernels = {
         s: {"ms": round(stage[s], 5), "algorithmic_GBps": round(alg[s] / (stage[s] * 1e-3) / 1e9, 1),
             "hbm_frac": round(alg[s] / (stage[s] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        for s in STAGES
+        for s in STAGES if stage[s] > 0
     }
-    kernels["contraction"]["int8_mfma_TOPS"] = round(mfma_tops, 1)
-    kernels["contraction"]["mfma_frac"] = round(mfma_tops / INT8_MFMA_PEAK_TOPS, 4)
+    for s in kernels:
+        kernels[s]["on_timed_path"] = s in used
+    for s in ("contraction", "fused_conv"):
+        if s in kernels:
+            mfma_tops = contraction_int8_ops(case, args.mode) / (stage[s] * 1e-3) / 1e12
+            kernels[s]["int8_mfma_TOPS"] = round(mfma_tops, 1)
+            kernels[s]["mfma_frac"] = round(mfma_tops / INT8_MFMA_PEAK_TOPS, 4)
 
     # direct convolution on the same inputs, for context
     yd = torch.empty_like(y)
@@ -159,6 +167,7 @@ def main():
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "%s: 3x3 s1 p1 conv N=%d C=%d K=%d H=W=%d, %s, %s mode" % (
             case.name, case.N, case.C, case.K, case.H, args.layout.upper(), args.mode)},
+        "path": "fused" if path == wg.FUSED else "staged",
         "roofline": roofline,
         "kernels": kernels,
         "filter_transform_ms": round(filter_ms, 4),

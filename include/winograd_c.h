@@ -128,12 +128,20 @@ int requant_relu_pool_int8(const int32_t* y_dev, int8_t* out_dev, int N, int K, 
                            int layout, int shift, int relu, int pool, void* hip_stream);
 
 /*
- * Measurement aid for benchmarks: enqueues each of winograd_conv2d_int8's three
- * kernels (input transform, contraction, output transform; same arguments and
- * launch configuration as that call) `iters` times back to back on hip_stream
- * between two HIP events, waits, and writes the mean milliseconds per launch of
- * each kernel to stage_ms_host[0..2] (HOST memory).  This call blocks.  y_dev
- * holds the convolution result afterwards.  iters >= 1.
+ * Which implementation winograd_conv2d_int8 runs for this problem: 1 = staged
+ * (input transform, contraction, output transform through the workspace),
+ * 2 = fused single kernel; negative status on invalid arguments.
+ */
+int winograd_conv2d_path(int N, int C, int H, int W, int K, int mode);
+
+/*
+ * Measurement aid for benchmarks: enqueues each kernel of winograd_conv2d_int8
+ * (same arguments and launch configuration as that call) `iters` times back to
+ * back on hip_stream between two HIP events, waits, and writes the mean
+ * milliseconds per launch to stage_ms_host[0..3] (HOST memory): the staged
+ * pipeline's input transform, contraction and output transform, then the fused
+ * kernel (0 where it does not apply).  This call blocks.  y_dev holds the
+ * convolution result afterwards.  iters >= 1.
  */
 int winograd_conv2d_int8_stage_times(const int8_t* x_dev, const void* packed_dev, int32_t* y_dev,
                                      int N, int C, int H, int W, int K, int layout, int mode,
@@ -156,6 +164,14 @@ int winograd_conv2d_int8_stage_times(const int8_t* x_dev, const void* packed_dev
  * Accumulator planes (36): real entry p: p; complex entry j: 16 + 2j + {Re, Im}.
  */
 int winograd_num_activation_planes(int mode);
+
+/* winograd_conv2d_int8 has two implementations of the same arithmetic: a staged
+   pipeline (input transform, contraction, output transform as three kernels
+   through the workspace) and a fused single kernel used for small channel
+   counts.  path 0 = library's choice (default), 1 = always staged, 2 = fused
+   wherever it applies (lossless: any C; scaled: C <= 64).  Process-wide; for
+   tests and benchmarks.  Returns WG_EINVAL for any other value. */
+int winograd_debug_force_path(int path);
 int winograd_num_filter_planes(int mode);
 
 /* Runs only the input transform D = B^T d B (Section 3.4) and writes its int8

@@ -42,6 +42,8 @@ def load_library():
         "winograd_status_string": (ctypes.c_char_p, [i]),
         "winograd_num_activation_planes": (i, [i]),
         "winograd_num_filter_planes": (i, [i]),
+        "winograd_debug_force_path": (i, [i]),
+        "winograd_conv2d_path": (i, [i, i, i, i, i, i]),
         "winograd_packed_filter_bytes": (sz, [i, i, i]),
         "winograd_workspace_bytes": (sz, [i, i, i, i, i, i]),
         "winograd_filter_transform": (i, [vp, i, i, i, i, vp, sz, vp]),
@@ -63,6 +65,7 @@ def load_library():
 
 EXPORTED_SYMBOLS = (
     "winograd_status_string", "winograd_num_activation_planes", "winograd_num_filter_planes",
+    "winograd_debug_force_path", "winograd_conv2d_path",
     "winograd_packed_filter_bytes", "winograd_workspace_bytes", "winograd_filter_transform",
     "winograd_packed_filter_check", "winograd_conv2d_int8", "winograd_conv2d_int8_stage_times",
     "direct_conv2d_int8", "requant_relu_pool_int8",
@@ -98,6 +101,22 @@ def _dims(x, layout):
 def _need(t, dtype, what):
     if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
         raise TypeError("%s must be a contiguous CUDA tensor of %s" % (what, dtype))
+
+
+AUTO, STAGED, FUSED = 0, 1, 2
+
+
+def force_path(path):
+    """0: library's choice, 1: staged three-kernel pipeline, 2: fused kernel wherever it applies."""
+    _check(load_library().winograd_debug_force_path(int(path)), "winograd_debug_force_path")
+
+
+def conv2d_path(N, C, H, W, K, mode):
+    """STAGED or FUSED: which implementation winograd_conv2d_int8 runs for this problem."""
+    r = int(load_library().winograd_conv2d_path(N, C, H, W, K, _MODES[mode]))
+    if r < 0:
+        raise WinogradError(r, "winograd_conv2d_path")
+    return r
 
 
 def packed_filter_bytes(K, C, mode):
@@ -158,7 +177,7 @@ def winograd_conv2d_int8(x, packed, layout=NCHW, out=None, workspace=None):
 
 
 def stage_times(x, packed, layout=NCHW, iters=20, out=None, workspace=None):
-    """Mean milliseconds per launch of (input transform, contraction, output transform); blocks."""
+    """Mean milliseconds per launch of (input transform, contraction, output transform, fused kernel); blocks."""
     layout = _LAYOUTS[layout]
     _need(x, torch.int8, "x")
     N, C, H, W = _dims(x, layout)
@@ -168,7 +187,7 @@ def stage_times(x, packed, layout=NCHW, iters=20, out=None, workspace=None):
     if out is None:
         shape = (N, K, H, W) if layout == NCHW else (N, H, W, K)
         out = torch.empty(shape, dtype=torch.int32, device=x.device)
-    ms = (ctypes.c_float * 3)()
+    ms = (ctypes.c_float * 4)()
     _check(load_library().winograd_conv2d_int8_stage_times(
         _ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout, packed.mode, _ptr(workspace),
         workspace.numel(), _stream(), int(iters), ctypes.cast(ms, ctypes.c_void_p)), "winograd_conv2d_int8_stage_times")

@@ -34,6 +34,16 @@ int check_filter_shape(int K, int C) {
 
 int status_of(hipError_t e) { return e == hipSuccess ? WG_OK : WG_ERUNTIME; }
 
+// 0: choose per problem; 1: always the staged three-kernel pipeline; 2: the fused kernel wherever
+// it is supported.
+int g_forced_path = 0;
+
+bool use_fused(const Problem& p, int mode) {
+    if (!fused_conv_supported(p, mode) || g_forced_path == 1) return false;
+    if (g_forced_path == 2) return true;
+    return p.CB <= 2;   // beyond two channel blocks the staged pipeline's larger matrix-core blocks win
+}
+
 }  // namespace
 
 extern "C" {
@@ -102,11 +112,24 @@ int winograd_conv2d_int8(const int8_t* x_dev, const void* packed_dev, int32_t* y
     const Problem p = make_problem(N, C, H, W, K);
     const WorkspaceLayout wl = workspace_layout(p, mode);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (use_fused(p, mode)) return status_of(launch_fused_conv(x_dev, packed_dev, y_dev, p, layout, mode, s));
     int8_t* V = static_cast<int8_t*>(workspace_dev) + wl.v_off;
     int32_t* M = reinterpret_cast<int32_t*>(static_cast<uint8_t*>(workspace_dev) + wl.m_off);
     if (int st = status_of(launch_input_transform(x_dev, p, layout, mode, V, s))) return st;
     if (int st = status_of(launch_contraction(V, packed_dev, M, p, mode, s))) return st;
     return status_of(launch_output_transform(M, packed_dev, y_dev, p, layout, mode, s));
+}
+
+int winograd_conv2d_path(int N, int C, int H, int W, int K, int mode) {
+    if (!valid_mode(mode)) return WG_EINVAL;
+    if (int st = check_shape(N, C, H, W, K)) return st;
+    return use_fused(make_problem(N, C, H, W, K), mode) ? 2 : 1;
+}
+
+int winograd_debug_force_path(int path) {
+    if (path < 0 || path > 2) return WG_EINVAL;
+    g_forced_path = path;
+    return WG_OK;
 }
 
 int winograd_conv2d_int8_stage_times(const int8_t* x_dev, const void* packed_dev, int32_t* y_dev, int N, int C,
@@ -125,12 +148,14 @@ int winograd_conv2d_int8_stage_times(const int8_t* x_dev, const void* packed_dev
     if (hipEventCreate(&e0) != hipSuccess) return WG_ERUNTIME;
     if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return WG_ERUNTIME; }
     int status = WG_OK;
-    for (int stage = 0; stage < 3 && status == WG_OK; ++stage) {
+    for (int stage = 0; stage < 4 && status == WG_OK; ++stage) {
+        if (stage == 3 && !fused_conv_supported(p, mode)) { stage_ms_host[3] = 0.f; break; }
         hipError_t e = hipEventRecord(e0, s);
         for (int i = 0; i < iters && e == hipSuccess; ++i) {
             if (stage == 0)      e = launch_input_transform(x_dev, p, layout, mode, V, s);
             else if (stage == 1) e = launch_contraction(V, packed_dev, M, p, mode, s);
-            else                 e = launch_output_transform(M, packed_dev, y_dev, p, layout, mode, s);
+            else if (stage == 2) e = launch_output_transform(M, packed_dev, y_dev, p, layout, mode, s);
+            else                 e = launch_fused_conv(x_dev, packed_dev, y_dev, p, layout, mode, s);
         }
         if (e == hipSuccess) e = hipEventRecord(e1, s);
         if (e == hipSuccess) e = hipEventSynchronize(e1);

@@ -134,12 +134,23 @@ def test_contraction_accumulators(shape, mode, layout):
     assert np.array_equal(got.astype(np.int64), want)      # every accumulator fits int32 at these sizes
 
 
-E2E_SHAPES = SHAPES + [(2, 64, 64, 12, 12), (1, 32, 48, 30, 18)]
+E2E_SHAPES = SHAPES + [(2, 64, 64, 12, 12), (1, 32, 48, 30, 18), (1, 200, 40, 9, 9)]
+PATHS = [wg.STAGED, wg.FUSED]
 
 
+@pytest.fixture
+def path(request):
+    """Pins winograd_conv2d_int8 to one implementation for the test, then restores the default."""
+    wg.force_path(request.param)
+    yield request.param
+    wg.force_path(wg.AUTO)
+
+
+
+@pytest.mark.parametrize("path", PATHS, indirect=True)
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("shape", E2E_SHAPES)
-def test_lossless_conv_equals_oracle_direct(shape, layout):
+def test_lossless_conv_equals_oracle_direct(shape, layout, path):
     N, C, K, H, W = shape
     x, g = wl.make_custom(N, C, K, H, W, seed=36)
     packed = wg.winograd_filter_transform(_g(g, layout), layout, wg.LOSSLESS)
@@ -147,9 +158,10 @@ def test_lossless_conv_equals_oracle_direct(shape, layout):
     assert np.array_equal(_y(y, layout), oracle.direct_conv2d(x, g))
 
 
+@pytest.mark.parametrize("path", PATHS, indirect=True)
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("shape", E2E_SHAPES)
-def test_scaled_conv_equals_oracle_scaled(shape, layout):
+def test_scaled_conv_equals_oracle_scaled(shape, layout, path):
     N, C, K, H, W = shape
     x, g = wl.make_custom(N, C, K, H, W, act="relu", wgt="gauss", seed=37)
     packed = wg.winograd_filter_transform(_g(g, layout), layout, wg.SCALED)
@@ -159,8 +171,9 @@ def test_scaled_conv_equals_oracle_scaled(shape, layout):
     assert np.array_equal(_y(y, layout), want)
 
 
+@pytest.mark.parametrize("path", PATHS, indirect=True)
 @pytest.mark.parametrize("layout", LAYOUTS)
-def test_extreme_values_lossless(layout):
+def test_extreme_values_lossless(layout, path):
     """All-extreme int8 data drives every 12-bit operand and the limb recombination to their limits."""
     for xv, gv in ((-128, -128), (127, -128), (-128, 127)):
         x = np.full((1, 64, 8, 8), xv, np.int8)
@@ -170,7 +183,8 @@ def test_extreme_values_lossless(layout):
         assert np.array_equal(_y(y, layout), oracle.direct_conv2d(x, g))
 
 
-def test_max_channels_lossless_wraparound_is_exact():
+@pytest.mark.parametrize("path", PATHS, indirect=True)
+def test_max_channels_lossless_wraparound_is_exact(path):
     """C = 896 with worst-case data: intermediate accumulators wrap modulo 2^32, the result is exact."""
     C = wg.MAX_CHANNELS
     x = np.full((1, C, 4, 4), -128, np.int8)
@@ -201,7 +215,8 @@ def test_requant_relu_pool(layout):
                 assert np.array_equal(_y(got, layout), oracle.requant_relu_pool(y, shift, relu, pool))
 
 
-def test_results_do_not_depend_on_workspace_contents_and_repeat_exactly():
+@pytest.mark.parametrize("path", PATHS, indirect=True)
+def test_results_do_not_depend_on_workspace_contents_and_repeat_exactly(path):
     x, g = wl.make_custom(2, 24, 40, 14, 9, seed=40)
     packed = wg.winograd_filter_transform(_g(g, wg.NHWC), wg.NHWC, wg.LOSSLESS)
     xd = _x(x, wg.NHWC)
@@ -214,7 +229,8 @@ def test_results_do_not_depend_on_workspace_contents_and_repeat_exactly():
     assert np.array_equal(wl.from_nhwc(outs[0]), oracle.direct_conv2d(x, g))
 
 
-def test_output_canaries_survive_partial_tiles():
+@pytest.mark.parametrize("path", PATHS, indirect=True)
+def test_output_canaries_survive_partial_tiles(path):
     """H, W not multiples of 4: stores are clipped to the image; guard elements around y stay intact."""
     x, g = wl.make_custom(1, 8, 6, 7, 5, seed=41)
     packed = wg.winograd_filter_transform(_g(g, wg.NCHW), wg.NCHW, wg.LOSSLESS)
@@ -225,7 +241,8 @@ def test_output_canaries_survive_partial_tiles():
     assert (buf[:64] == 0x5A5A5A5A).all() and (buf[-64:] == 0x5A5A5A5A).all()
 
 
-def test_mismatched_blob_is_rejected_and_output_untouched():
+@pytest.mark.parametrize("path", PATHS, indirect=True)
+def test_mismatched_blob_is_rejected_and_output_untouched(path):
     x, g = wl.make_custom(1, 8, 6, 8, 8, seed=42)
     packed = wg.winograd_filter_transform(_g(g, wg.NCHW), wg.NCHW, wg.LOSSLESS)
     wrong = wg.PackedFilter(packed.blob, packed.K, packed.C, wg.SCALED)
