@@ -10,11 +10,17 @@
 // valid for any number of channel blocks in lossless mode; the reverse scaling of
 // Section 4.2 is not linear (it rounds), so scaled mode uses this kernel only
 // when all input channels fit one block.
-#include "input_transform_core.h"
+//
+// This kernel is bound by operand bandwidth and vector ALU work, not by the
+// matrix cores, so it trades multiplications for traffic: a 12-bit x 12-bit
+// product is taken as the four limb products hh, hl, lh, ll (two activation and
+// two filter planes per value) and a complex product as its four real products,
+// instead of the three-multiplication forms of Section 3.1 that the staged
+// contraction kernel uses; those would need half again as many operand planes.
 #include <type_traits>
 #include <utility>
 
-#include "subproducts.h"
+#include "input_transform_core.h"
 
 namespace wg {
 namespace {
@@ -23,7 +29,11 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 
 constexpr int kFusedTiles = 16;     // tiles per workgroup (rows of the 16x16x64 matrix-core product)
 constexpr int kFusedFilters = 32;   // filters per workgroup: two 16-wide column blocks
+constexpr int kFusedPlanes = 72;    // two-limb activation planes (kSplitTwoLimb)
 constexpr int kPlaneBytes = kFusedTiles * kCBlock;   // one operand plane of the tile block in LDS
+constexpr int kLdsBytes = kFusedPlanes * kPlaneBytes;
+constexpr int kParkBytes = 4 * 16 * 64 * 16;         // four waves x 16 outputs x 64 lanes x 4 registers
+static_assert(kParkBytes + 3 * 16 * 4 <= kLdsBytes, "output staging reuses the operand planes' LDS");
 
 // LDS operand plane: the 16-byte piece holding 16 consecutive channels (group c16) of a tile
 // sits in slot c16*16 + ((tile + 4*c16) & 15); lane l of a wave reads slot(l/16, l%16), which
@@ -32,16 +42,9 @@ __device__ inline int lds_slot(int c16, int tile) { return c16 * 16 + ((tile + 4
 
 struct LdsPlaneSink {
     int8_t* base;
-    __device__ inline void put(int plane, s8x4 bytes) const {
-        *reinterpret_cast<s8x4*>(base + plane * kPlaneBytes) = bytes;
+    __device__ inline void put(int plane, uint32_t bytes) const {
+        *reinterpret_cast<uint32_t*>(base + plane * kPlaneBytes) = bytes;
     }
-};
-
-struct LaneContext {
-    const int8_t* a_lds;        // this lane's 16-byte slot in plane 0
-    const int8_t* b_glob;       // this lane's 16 bytes of filter plane 0, current channel block
-    size_t b_plane_stride;      // bytes between filter planes
-    const ScaleEntry* table_k;  // scaling table row of this lane's filter (scaled mode)
 };
 
 // compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(<N-1>)
@@ -54,46 +57,88 @@ __device__ inline void static_for(F&& f) {
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-// The sub-products one wave issues, in order.  Half 0 owns rows 0,1,2 of M, half 1 rows 5
-// and 3.  A real row RI (rows 0,1,2,5) holds entries 4RI..4RI+3 and the complex entry 16+RI;
-// the complex row holds entries 20..25.
-struct Step {
-    int entry, sub;      // which entry, which of its sub-products
-    int row;             // 0..3: real row RI, 4: the complex row
-    int pos;             // position of the entry within its row
-    bool last_sub;       // last sub-product of the entry
-    bool last_in_row;    // ... and last entry of the row
+// ---- per-entry programs ----------------------------------------------------------------
+// An entry's product uses a few activation fragments (from LDS) and filter fragments (from
+// the packed blob) and a short list of matrix-core instructions into a few accumulators.
+//   lossless, real:    A = (h, l)  B = (h, l)          acc = (hh, hl+lh, ll)
+//   lossless, complex: A = (Re h, Re l, Im h, Im l)  B = (Wr h, Wr l, Wi h, Wi l)
+//                      acc 0-2: Dr*Wr, 3-5: Di*Wi, 6-8: Dr*Wi + Di*Wr, each as (hh, mid, ll)
+//   scaled, real:      A = (h, l)  B = (W)             acc = (h, l)
+//   scaled, complex:   B = (Wr, Wi, -Wi)               acc = (Re h, Re l, Im h, Im l)
+struct Op {
+    int a, b, acc;
+    bool init;   // first instruction into this accumulator (starts from zero)
 };
-__host__ __device__ constexpr int row_entries(int row) { return row < 4 ? 5 : 6; }
-__host__ __device__ constexpr int row_entry(int row, int pos) {
+constexpr bool is_real(int entry) { return entry < kRealEntries; }
+template <int MODE> constexpr int num_a(int entry) { return is_real(entry) ? 2 : 4; }
+template <int MODE> constexpr int num_b(int entry) {
+    return MODE == WG_LOSSLESS ? (is_real(entry) ? 2 : 4) : (is_real(entry) ? 1 : 3);
+}
+template <int MODE> constexpr int num_ops(int entry) {
+    return MODE == WG_LOSSLESS ? (is_real(entry) ? 4 : 16) : (is_real(entry) ? 2 : 8);
+}
+template <int MODE> constexpr int a_plane(int entry, int i) {
+    return is_real(entry) ? 2 * entry + i : 32 + 4 * (entry - kRealEntries) + i;
+}
+template <int MODE> constexpr int b_plane(int entry, int i) {
+    if (MODE == WG_LOSSLESS) {   // blob planes 3*value + {0: high limb, 1: low limb}
+        if (is_real(entry)) return 3 * entry + i;
+        const int value = 16 + 3 * (entry - kRealEntries) + (i >> 1);   // Re, then Im
+        return 3 * value + (i & 1);
+    }
+    return is_real(entry) ? entry : 16 + 3 * (entry - kRealEntries) + i;
+}
+template <int MODE> constexpr Op entry_op(int entry, int i) {
+    constexpr Op lossless_real[4] = {{0, 0, 0, true}, {0, 1, 1, true}, {1, 1, 2, true}, {1, 0, 1, false}};
+    // dependent instructions into one accumulator are kept at least three apart
+    constexpr Op lossless_complex[16] = {
+        {0, 0, 0, true}, {0, 1, 1, true}, {1, 1, 2, true},    // Dr*Wr: hh, mid, ll
+        {2, 2, 3, true}, {2, 3, 4, true}, {3, 3, 5, true},    // Di*Wi
+        {0, 2, 6, true}, {0, 3, 7, true}, {1, 3, 8, true},    // Dr*Wi
+        {1, 2, 7, false}, {1, 0, 1, false}, {3, 2, 4, false},
+        {2, 1, 7, false}, {2, 0, 6, false}, {3, 1, 8, false}, {3, 0, 7, false}};
+    constexpr Op scaled_real[2] = {{0, 0, 0, true}, {1, 0, 1, true}};
+    constexpr Op scaled_complex[8] = {{0, 0, 0, true}, {1, 0, 1, true}, {0, 1, 2, true}, {1, 1, 3, true},
+                                      {2, 2, 0, false}, {3, 2, 1, false}, {2, 0, 2, false}, {3, 0, 3, false}};
+    if (MODE == WG_LOSSLESS) return is_real(entry) ? lossless_real[i] : lossless_complex[i];
+    return is_real(entry) ? scaled_real[i] : scaled_complex[i];
+}
+
+// ---- which entries a wave owns, in order ---------------------------------------------------
+// Half 0 owns rows 0,1,2 of M, half 1 rows 5 and 3.  A real row RI (rows 0,1,2,5) holds
+// entries 4RI..4RI+3 and the complex entry 16+RI; the complex row holds entries 20..25.
+constexpr int row_entries(int row) { return row < 4 ? 5 : 6; }
+constexpr int row_entry(int row, int pos) {
     return row < 4 ? (pos < 4 ? 4 * row + pos : kRealEntries + row) : kRealEntries + 4 + pos;
 }
-__host__ __device__ constexpr int half_rows(int half) { return half == 0 ? 3 : 2; }
-__host__ __device__ constexpr int half_row(int half, int i) { return half == 0 ? i : (i == 0 ? 3 : 4); }
-
-template <int MODE, int HALF>
-__host__ __device__ constexpr int sequence_length() {
+constexpr int half_rows(int half) { return half == 0 ? 3 : 2; }
+constexpr int half_row(int half, int i) { return half == 0 ? i : (i == 0 ? 3 : 4); }
+constexpr int half_entries(int half) { return half == 0 ? 15 : 11; }
+struct Slot {
+    int entry, row, pos;
+    bool last_in_row;
+};
+constexpr Slot half_slot(int half, int i) {
     int n = 0;
-    for (int r = 0; r < half_rows(HALF); ++r)
-        for (int e = 0; e < row_entries(half_row(HALF, r)); ++e)
-            n += num_subproducts<MODE>(row_entry(half_row(HALF, r), e));
+    for (int r = 0; r < half_rows(half); ++r) {
+        const int row = half_row(half, r);
+        if (i < n + row_entries(row))
+            return Slot{row_entry(row, i - n), row, i - n, i - n == row_entries(row) - 1};
+        n += row_entries(row);
+    }
+    return Slot{0, 0, 0, false};
+}
+// index of the first filter fragment of slot i in the wave's fragment stream
+template <int MODE> constexpr int b_start(int half, int i) {
+    int n = 0;
+    for (int s = 0; s < i; ++s) n += num_b<MODE>(half_slot(half, s).entry);
     return n;
 }
-template <int MODE, int HALF>
-__host__ __device__ constexpr Step sequence_step(int i) {
-    int n = 0;
-    for (int r = 0; r < half_rows(HALF); ++r) {
-        const int row = half_row(HALF, r);
-        for (int e = 0; e < row_entries(row); ++e) {
-            const int entry = row_entry(row, e), ns = num_subproducts<MODE>(entry);
-            if (i < n + ns) {
-                const bool last = (i - n) == ns - 1;
-                return Step{entry, i - n, row, e, last, last && e == row_entries(row) - 1};
-            }
-            n += ns;
-        }
-    }
-    return Step{0, 0, 0, 0, false, false};
+// the slot that filter fragment f of the stream belongs to
+template <int MODE> constexpr int b_slot_of(int half, int f) {
+    int s = 0;
+    while (b_start<MODE>(half, s + 1) <= f) ++s;
+    return s;
 }
 
 // Row rule of A^T on (m0, m1, m2, m3, conj(m3), m5) with m0,m1,m2,m5 real:
@@ -142,78 +187,98 @@ __device__ inline void finish_row(const v4i (&er)[6], const v4i (&ei)[6], v4i (&
     }
 }
 
-constexpr int kFilterPrefetch = 16;   // filter fragments in flight per wave (L2 latency cover)
-constexpr int kLdsPrefetch = 2;       // activation fragments in flight from LDS
+struct LaneContext {
+    const int8_t* a_lds;        // this lane's 16-byte slot in plane 0
+    const int8_t* b_glob;       // this lane's 16 bytes of filter plane 0, current channel block
+    uint32_t b_plane_stride;    // bytes between filter planes
+    const ScaleEntry* table_k;  // scaling table row of this lane's filter (scaled mode)
+};
+
+constexpr int kFilterPrefetch = 16;   // filter fragments in flight per wave (covers L2 latency)
+
+// value = 4096 hh + 64 mid + ll, modulo 2^32
+__device__ inline v4i join_limbs(v4i hh, v4i mid, v4i ll) { return (((hh << 6) + mid) << 6) + ll; }
 
 template <int MODE, int HALF>
 struct ProductPhase {
-    static constexpr int N = sequence_length<MODE, HALF>();
+    static constexpr int NE = half_entries(HALF);
+    static constexpr int NB = b_start<MODE>(HALF, NE);
+    static constexpr int NPRE = NB < kFilterPrefetch ? NB : kFilterPrefetch;
     v4i bring[kFilterPrefetch];
 
-    __device__ inline static v4i load_b(const LaneContext& cx, int i) {
-        const Step st = sequence_step<MODE, HALF>(i);
-        const SubProduct sp = subproduct<MODE>(st.entry, st.sub);
-        return *reinterpret_cast<const v4i*>(cx.b_glob + (size_t)sp.b_plane * cx.b_plane_stride);
+    template <int F>   // F-th filter fragment of this wave's stream
+    __device__ inline static v4i load_b(const LaneContext& cx) {
+        constexpr int slot = b_slot_of<MODE>(HALF, F);
+        constexpr int plane = b_plane<MODE>(half_slot(HALF, slot).entry, F - b_start<MODE>(HALF, slot));
+        return *reinterpret_cast<const v4i*>(cx.b_glob + (uint32_t)plane * cx.b_plane_stride);
     }
-    __device__ inline static v4i load_a(const LaneContext& cx, int i) {
-        const Step st = sequence_step<MODE, HALF>(i);
-        const SubProduct sp = subproduct<MODE>(st.entry, st.sub);
-        return *reinterpret_cast<const v4i*>(cx.a_lds + sp.a_plane * kPlaneBytes);
+    template <int SLOT, int I>
+    __device__ inline static v4i load_a(const LaneContext& cx) {
+        constexpr int plane = a_plane<MODE>(half_slot(HALF, SLOT).entry, I);
+        return *reinterpret_cast<const v4i*>(cx.a_lds + plane * kPlaneBytes);
     }
 
     // Filter fragments do not depend on the transform phase: start them before it.
     __device__ inline void prefetch(const LaneContext& cx) {
-        static_for<kFilterPrefetch>([&](auto I) {
-            if constexpr (I < N) bring[I] = load_b(cx, I);
-        });
+        static_for<NPRE>([&](auto I) { bring[I] = load_b<I>(cx); });
     }
 
-    // One 64-channel block of this wave's rows: every sub-product is a single 16x16x64
-    // matrix-core instruction (channel sum complete within the block); its result is weighted
-    // into Re/Im of its entry one step later, while the next instruction runs.
+    // One 64-channel block of this wave's rows.  Software pipeline over entries: while entry i's
+    // matrix-core instructions run, entry i+1's activation fragments come from LDS, the filter
+    // ring is refilled sixteen fragments ahead, and entry i-1's accumulators are joined,
+    // (un)scaled and reduced into the outputs.
     __device__ inline void run(const LaneContext& cx, v4i (&Y)[16]) {
-        v4i aring[kLdsPrefetch];
-        static_for<kLdsPrefetch>([&](auto I) { aring[I] = load_a(cx, I); });
-        v4i re = {0, 0, 0, 0}, im = {0, 0, 0, 0}, acc_prev = {0, 0, 0, 0};
-        v4i er[6], ei[6];
-        static_for<N + 1>([&](auto I) {
-            constexpr int i = I;
-            v4i acc_cur = {0, 0, 0, 0};
-            if constexpr (i < N) {
-                const v4i a = aring[i % kLdsPrefetch], b = bring[i % kFilterPrefetch];
-                constexpr v4i zero = {0, 0, 0, 0};
-                acc_cur = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, zero, 0, 0, 0);
-                if constexpr (i + kLdsPrefetch < N) aring[i % kLdsPrefetch] = load_a(cx, i + kLdsPrefetch);
-                if constexpr (i + kFilterPrefetch < N) bring[i % kFilterPrefetch] = load_b(cx, i + kFilterPrefetch);
+        v4i afr[2][4], acc[2][9], er[6], ei[6];
+        static_for<num_a<MODE>(half_slot(HALF, 0).entry)>([&](auto I) { afr[0][I] = load_a<0, I>(cx); });
+        static_for<NE + 1>([&](auto S) {
+            constexpr int s = S;
+            if constexpr (s < NE) {
+                constexpr int entry = half_slot(HALF, s).entry;
+                constexpr int b0 = b_start<MODE>(HALF, s);
+                if constexpr (s + 1 < NE)
+                    static_for<num_a<MODE>(half_slot(HALF, s + 1).entry)>(
+                        [&](auto I) { afr[(s + 1) & 1][I] = load_a<s + 1, I>(cx); });
+                static_for<num_ops<MODE>(entry)>([&](auto I) {
+                    constexpr Op op = entry_op<MODE>(entry, I);
+                    constexpr v4i zero = {0, 0, 0, 0};
+                    acc[s & 1][op.acc] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
+                        afr[s & 1][op.a], bring[(b0 + op.b) % kFilterPrefetch],
+                        op.init ? zero : acc[s & 1][op.acc], 0, 0, 0);
+                });
+                static_for<num_b<MODE>(entry)>([&](auto I) {
+                    if constexpr (b0 + I + kFilterPrefetch < NB)
+                        bring[(b0 + I) % kFilterPrefetch] = load_b<b0 + I + kFilterPrefetch>(cx);
+                });
             }
-            if constexpr (i > 0) {
-                constexpr Step st = sequence_step<MODE, HALF>(i - 1);
-                constexpr SubProduct sp = subproduct<MODE>(st.entry, st.sub);
-                if constexpr (st.sub == 0) { re = (v4i){0, 0, 0, 0}; im = (v4i){0, 0, 0, 0}; }
+            if constexpr (s > 0) {
+                constexpr Slot sl = half_slot(HALF, s - 1);
+                const v4i(&a)[9] = acc[(s - 1) & 1];
+                v4i re, im = {0, 0, 0, 0};
+                if constexpr (MODE == WG_LOSSLESS) {
+                    if constexpr (is_real(sl.entry)) {
+                        re = join_limbs(a[0], a[1], a[2]);
+                    } else {   // Re = Dr Wr - Di Wi,  Im = Dr Wi + Di Wr
+                        re = join_limbs(a[0] - a[3], a[1] - a[4], a[2] - a[5]);
+                        im = join_limbs(a[6], a[7], a[8]);
+                    }
+                } else {
+                    re = (a[0] << 6) + a[1];
+                    if constexpr (!is_real(sl.entry)) im = (a[2] << 6) + a[3];
+                    // reverse scaling (Section 4.2): (m * r + 2^(q-1)) >> q, 64-bit intermediate
+                    const ScaleEntry se = cx.table_k[sl.entry];
+                    if (se.n != 0) {
+                        const long long rnd = se.q > 0 ? (1ll << (se.q - 1)) : 0ll;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    if (sp.w_re != 0) re[q] += __mul24(acc_prev[q], sp.w_re);
-                    if (sp.w_im != 0) im[q] += __mul24(acc_prev[q], sp.w_im);
-                }
-                if constexpr (st.last_sub) {
-                    if constexpr (MODE == WG_SCALED) {
-                        // reverse scaling (Section 4.2): (m * r + 2^(q-1)) >> q, 64-bit intermediate
-                        const ScaleEntry se = cx.table_k[st.entry];
-                        if (se.n != 0) {
-                            const long long rnd = se.q > 0 ? (1ll << (se.q - 1)) : 0ll;
-#pragma unroll
-                            for (int q = 0; q < 4; ++q) {
-                                re[q] = (int)(((long long)re[q] * se.r + rnd) >> se.q);
-                                im[q] = (int)(((long long)im[q] * se.r + rnd) >> se.q);
-                            }
+                        for (int q = 0; q < 4; ++q) {
+                            re[q] = (int)(((long long)re[q] * se.r + rnd) >> se.q);
+                            im[q] = (int)(((long long)im[q] * se.r + rnd) >> se.q);
                         }
                     }
-                    er[st.pos] = re;
-                    ei[st.pos] = im;
-                    if constexpr (st.last_in_row) finish_row<st.row>(er, ei, Y);
                 }
+                er[sl.pos] = re;
+                ei[sl.pos] = im;
+                if constexpr (sl.last_in_row) finish_row<sl.row>(er, ei, Y);
             }
-            acc_prev = acc_cur;
             __builtin_amdgcn_sched_barrier(0);
         });
     }
@@ -221,7 +286,8 @@ struct ProductPhase {
 
 // grid: (ceil(T/16), Kp/32).  256 threads: in the transform phase one thread per (tile,
 // four channels); in the product phase wave w owns filter block (w & 1) and half of the
-// rows of M (w >> 1: rows 0,1,2 or rows 5,3); the two halves are added through LDS.
+// rows of M (w >> 1: rows 0,1,2 or rows 5,3); all four waves stage their partial outputs
+// in LDS and the block stores the sums with full-line writes.
 template <int LAYOUT, bool VEC4, int MODE>
 __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restrict__ x,
                                                          const uint8_t* __restrict__ blob, size_t table_off,
@@ -231,18 +297,19 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kblock = wave & 1, half = wave >> 1;
     const int tile0 = blockIdx.x * kFusedTiles;
-    const int k = blockIdx.y * kFusedFilters + kblock * 16 + (lane & 15);
+    const int k0 = blockIdx.y * kFusedFilters;
+    const int k = k0 + kblock * 16 + (lane & 15);
 
     // transform-phase identity
     const int a_tile = tid >> 4, a_cq = tid & 15;
     const int a_t = tile0 + a_tile;
     const int a_tx = a_t % p.TW, a_ty = (a_t / p.TW) % p.TH, a_n = a_t / (p.TW * p.TH);
-    OperandSplitter<MODE, LdsPlaneSink> out;
+    OperandSplitter<kSplitTwoLimb, LdsPlaneSink> out;
     out.sink.base = lds + lds_slot(a_cq >> 2, a_tile) * 16 + (a_cq & 3) * 4;
 
     LaneContext cx;
     cx.a_lds = lds + lds_slot(lane >> 4, lane & 15) * 16;
-    cx.b_plane_stride = (size_t)p.CB * p.Kp * kCBlock;
+    cx.b_plane_stride = (uint32_t)p.CB * p.Kp * kCBlock;
     cx.table_k = reinterpret_cast<const ScaleEntry*>(blob + table_off) + (size_t)k * kEntries;
     const int8_t* b_lane = reinterpret_cast<const int8_t*>(blob + planes_off) + (size_t)k * kCBlock + (lane >> 4) * 16;
 
@@ -256,41 +323,53 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
         cx.b_glob = b_lane + (size_t)cb * p.Kp * kCBlock;
         if (half == 0) phase0.prefetch(cx); else phase1.prefetch(cx);
         if (cb > 0) __syncthreads();   // everyone is done reading the previous block's planes
-        if (a_t < p.T) transform_tile<LAYOUT, VEC4, MODE>(x, p, a_n, a_ty, a_tx, cb * kCBlock + 4 * a_cq, out);
+        if (a_t < p.T)
+            transform_tile<LAYOUT, VEC4, kSplitTwoLimb>(x, p, a_n, a_ty, a_tx, cb * kCBlock + 4 * a_cq, out);
         __syncthreads();
         if (half == 0) phase0.run(cx, Y); else phase1.run(cx, Y);
     }
 
-    // add the two halves: waves 2,3 park their partial outputs in LDS, waves 0,1 finish
+    // stage the partial outputs: park[wave][output 0..15][lane] (four registers = four tiles each)
     __syncthreads();
-    v4i* park = reinterpret_cast<v4i*>(lds) + (kblock * 16) * 64 + lane;
-    if (half == 1) {
+    v4i* park = reinterpret_cast<v4i*>(lds);
+    int* tile_info = reinterpret_cast<int*>(lds + kParkBytes);   // per tile: offset, first row, first column
 #pragma unroll
-        for (int i = 0; i < 16; ++i) park[i * 64] = Y[i];
+    for (int i = 0; i < 16; ++i) park[(wave * 16 + i) * 64 + lane] = Y[i];
+    if (tid < kFusedTiles) {
+        // offsets fit 32 bits (checked on the host); -1 marks tiles beyond T
+        int origin = -1, row = 0, col = 0;
+        const int t = tile0 + tid;
+        if (t < p.T) {
+            const int tx = t % p.TW, ty = (t / p.TW) % p.TH, n = t / (p.TW * p.TH);
+            row = 4 * ty;
+            col = 4 * tx;
+            origin = LAYOUT == WG_NHWC ? ((n * p.H + row) * p.W + col) * p.K : (n * p.K * p.H + row) * p.W + col;
+        }
+        tile_info[tid] = origin;
+        tile_info[16 + tid] = row;
+        tile_info[32 + tid] = col;
     }
     __syncthreads();
-    if (half == 1 || k >= p.K) return;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) Y[i] += park[i * 64];
 
+    // 16 tiles x 16 outputs x 32 filters = 8192 results, 32 per thread, ordered so that a wave
+    // writes whole lines: channels-last, 32 filters of one pixel are 128 contiguous bytes;
+    // channel-major, 16 consecutive tiles x 4 columns of one output row are 256 contiguous bytes.
+    const int* parki = reinterpret_cast<const int*>(lds);
     const int rnd = MODE == WG_SCALED ? 8 : 0;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int t = tile0 + 4 * (lane >> 4) + q;     // row of the matrix-core result held in register q
-        if (t >= p.T) continue;
-        const int tx = t % p.TW, ty = (t / p.TW) % p.TH, n = t / (p.TW * p.TH);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int h = 4 * ty + i;
-            if (h >= p.H) continue;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int w = 4 * tx + j;
-                if (w >= p.W) continue;
-                const int v = (Y[4 * i + j][q] + rnd) >> 4;
-                if (LAYOUT == WG_NHWC) y[(((size_t)n * p.H + h) * p.W + w) * p.K + k] = v;
-                else                   y[(((size_t)n * p.K + k) * p.H + h) * p.W + w] = v;
-            }
+#pragma unroll 4
+    for (int it = 0; it < 32; ++it) {
+        const int idx = it * 256 + tid;
+        int tile, i, j, kl;
+        if (LAYOUT == WG_NHWC) { kl = idx & 31; j = (idx >> 5) & 3; i = (idx >> 7) & 3; tile = idx >> 9; }
+        else                   { j = idx & 3; tile = (idx >> 2) & 15; i = (idx >> 6) & 3; kl = idx >> 8; }
+        const int origin = tile_info[tile];
+        const int h = tile_info[16 + tile] + i, w = tile_info[32 + tile] + j, kk = k0 + kl;
+        // the value sits in waves kl/16 and 2 + kl/16, output 4i+j, lane (tile/4)*16 + kl%16, register tile%4
+        const int at = (((kl >> 4) * 16 + 4 * i + j) * 64 + (tile >> 2) * 16 + (kl & 15)) * 4 + (tile & 3);
+        const int v = (parki[at] + parki[at + 2 * 16 * 64 * 4] + rnd) >> 4;
+        if (origin >= 0 && h < p.H && w < p.W && kk < p.K) {
+            if (LAYOUT == WG_NHWC) y[(size_t)origin + ((size_t)i * p.W + j) * p.K + kk] = v;
+            else                   y[(size_t)origin + ((size_t)kk * p.H + i) * p.W + j] = v;
         }
     }
 }
@@ -298,22 +377,25 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
 template <int LAYOUT, bool VEC4, int MODE>
 hipError_t launch(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
                   hipStream_t s) {
-    const size_t lds_bytes = (size_t)num_activation_planes(MODE) * kPlaneBytes;
     static bool configured = false;   // per template instance
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_conv_kernel<LAYOUT, VEC4, MODE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;
         configured = true;
     }
     dim3 grid(ceil_div(p.T, kFusedTiles), p.Kp / kFusedFilters);
-    fused_conv_kernel<LAYOUT, VEC4, MODE><<<grid, 256, lds_bytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p);
+    fused_conv_kernel<LAYOUT, VEC4, MODE><<<grid, 256, kLdsBytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p);
     return hipGetLastError();
 }
 
 }  // namespace
 
-bool fused_conv_supported(const Problem& p, int mode) { return mode == WG_LOSSLESS || p.CB == 1; }
+bool fused_conv_supported(const Problem& p, int mode) {
+    // 32-bit plane offsets inside the blob; scaled mode needs the whole channel sum in one block
+    const unsigned long long span = (unsigned long long)num_filter_planes(mode) * p.CB * p.Kp * kCBlock;
+    return span < (1ull << 32) && (mode == WG_LOSSLESS || p.CB == 1);
+}
 
 hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int layout, int mode,
                              hipStream_t s) {

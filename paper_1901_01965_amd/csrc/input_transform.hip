@@ -12,8 +12,8 @@ namespace {
 struct GlobalPlaneSink {
     int8_t* base;          // V + ((cb * Tp + t) * 64 + 4 * cq)
     size_t plane_stride;   // CB * Tp * 64
-    __device__ inline void put(int plane, s8x4 bytes) const {
-        *reinterpret_cast<s8x4*>(base + (size_t)plane * plane_stride) = bytes;
+    __device__ inline void put(int plane, uint32_t bytes) const {
+        *reinterpret_cast<uint32_t*>(base + (size_t)plane * plane_stride) = bytes;
     }
 };
 
@@ -27,10 +27,11 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const int8_t* __re
     const int cb = blockIdx.y;
     if (t >= p.T) return;
     const int tx = t % p.TW, ty = (t / p.TW) % p.TH, n = t / (p.TW * p.TH);
-    OperandSplitter<MODE, GlobalPlaneSink> out;
+    constexpr int SPLIT = MODE == WG_LOSSLESS ? kSplitKaratsuba : kSplitTwoLimb;
+    OperandSplitter<SPLIT, GlobalPlaneSink> out;
     out.sink.base = V + (((size_t)cb * p.Tp + t) * kCBlock + 4 * cq);
     out.sink.plane_stride = (size_t)p.CB * p.Tp * kCBlock;
-    transform_tile<LAYOUT, VEC4, MODE>(x, p, n, ty, tx, cb * kCBlock + 4 * cq, out);
+    transform_tile<LAYOUT, VEC4, SPLIT>(x, p, n, ty, tx, cb * kCBlock + 4 * cq, out);
 }
 
 __global__ void unpack_activation_planes_kernel(const int8_t* V, int8_t* dense, Problem p, int nplanes) {

@@ -1,29 +1,51 @@
 // The arithmetic of the input transform D = B^T d B (Section 3.3) on the 26 free
 // entries (Section 3.4), shared by the stand-alone transform kernel and the
 // fused convolution kernel.  Four channels are processed at a time in packed
-// 16-bit lanes; `Writer` decides where each int8 operand plane goes.
+// 16-bit lanes; `Sink` decides where each int8 operand plane goes.
+//
+// Activations are handled in the biased form u = x + 128 (one XOR on the packed
+// bytes, so that unpacking is a plain zero extension).  A constant patch maps to
+// zero at every entry of B^T d B except (1,1), where the sixteen +1 coefficients
+// add up: D(u) = D(x) + 2048 at (1,1) only, so the bias is removed by one
+// subtraction.  Padding pixels and channels beyond C carry the bias value 128.
 #pragma once
 #include "wg_internal.h"
 
 namespace wg {
 
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef signed char s8x4 __attribute__((ext_vector_type(4)));
+typedef short s16x2 __attribute__((ext_vector_type(2)));
 
-// The 6x6 input patch of one tile, four consecutive channels c0..c0+3 per pixel, zero outside
-// the image (pad 1) and beyond C.  All loads are issued before any is used: addresses are
-// clamped into the image and out-of-range pixels are zeroed afterwards, so no load sits
-// behind a branch.
+// four channels: a = (c0, c1), b = (c2, c3)
+struct Quad {
+    s16x2 a, b;
+};
+__device__ inline Quad operator+(Quad x, Quad y) { return Quad{x.a + y.a, x.b + y.b}; }
+__device__ inline Quad operator-(Quad x, Quad y) { return Quad{x.a - y.a, x.b - y.b}; }
+
+__device__ inline uint32_t as_u32(s16x2 v) { return __builtin_bit_cast(uint32_t, v); }
+__device__ inline s16x2 as_s16x2(uint32_t v) { return __builtin_bit_cast(s16x2, v); }
+
+// bytes (u0,u1,u2,u3) -> 16-bit lanes (u0,u1), (u2,u3), zero extended
+__device__ inline Quad unpack_u8x4(uint32_t u) {
+    return Quad{as_s16x2(__builtin_amdgcn_perm(0u, u, 0x0c010c00u)), as_s16x2(__builtin_amdgcn_perm(0u, u, 0x0c030c02u))};
+}
+// low bytes of the four 16-bit lanes -> one dword (c0,c1,c2,c3)
+__device__ inline uint32_t pack_low_bytes(Quad v) { return __builtin_amdgcn_perm(as_u32(v.b), as_u32(v.a), 0x06040200u); }
+
+constexpr uint32_t kBiasBytes = 0x80808080u;
+
+// The biased 6x6 input patch of one tile, four consecutive channels c0..c0+3 per pixel.
+// All loads are issued before any is used: addresses are clamped into the image and
+// out-of-range pixels are replaced afterwards, so no load sits behind a branch.
 // VEC4 (channels-last input whose C is a multiple of four, chosen on the host): one 4-byte
 // load per pixel; a channel group is then either wholly inside or wholly beyond C.
 template <int LAYOUT, bool VEC4>
 __device__ inline void load_patch(const int8_t* __restrict__ x, const Problem& p, int n, int ty, int tx, int c0,
-                                  s16x4 d[6][6]) {
+                                  uint32_t u[6][6]) {
     const int h0 = 4 * ty - 1, w0 = 4 * tx - 1;
     if constexpr (VEC4) {
         static_assert(LAYOUT == WG_NHWC, "4-byte pixel loads need channels-last input");
         const bool have = c0 < p.C;
-        s8x4 raw[6][6];
         const int8_t* img = x + (size_t)n * p.H * p.W * p.C + (have ? c0 : 0);
 #pragma unroll
         for (int a = 0; a < 6; ++a) {
@@ -31,7 +53,7 @@ __device__ inline void load_patch(const int8_t* __restrict__ x, const Problem& p
 #pragma unroll
             for (int b = 0; b < 6; ++b) {
                 const int w = min(max(w0 + b, 0), p.W - 1);
-                raw[a][b] = *reinterpret_cast<const s8x4*>(img + ((size_t)h * p.W + w) * p.C);
+                u[a][b] = *reinterpret_cast<const uint32_t*>(img + ((size_t)h * p.W + w) * p.C);
             }
         }
 #pragma unroll
@@ -39,31 +61,31 @@ __device__ inline void load_patch(const int8_t* __restrict__ x, const Problem& p
 #pragma unroll
             for (int b = 0; b < 6; ++b) {
                 const bool inside = have && (unsigned)(h0 + a) < (unsigned)p.H && (unsigned)(w0 + b) < (unsigned)p.W;
-                const s16x4 v = __builtin_convertvector(raw[a][b], s16x4);
-                d[a][b] = inside ? v : (s16x4){0, 0, 0, 0};
+                u[a][b] = inside ? (u[a][b] ^ kBiasBytes) : kBiasBytes;
             }
-        return;
-    }
-    // general path: channel counts that are not a multiple of four, the ragged last group, and
-    // channel-major inputs (one byte per channel, stride H*W)
-    const size_t cstride = LAYOUT == WG_NHWC ? 1 : (size_t)p.H * p.W;
+    } else {
+        // general path: channel counts that are not a multiple of four, and channel-major inputs
+        // (one byte per channel, stride H*W)
+        const size_t cstride = LAYOUT == WG_NHWC ? 1 : (size_t)p.H * p.W;
 #pragma unroll
-    for (int a = 0; a < 6; ++a) {
-        const int h = min(max(h0 + a, 0), p.H - 1);
+        for (int a = 0; a < 6; ++a) {
+            const int h = min(max(h0 + a, 0), p.H - 1);
 #pragma unroll
-        for (int b = 0; b < 6; ++b) {
-            const int w = min(max(w0 + b, 0), p.W - 1);
-            const bool inside = (unsigned)(h0 + a) < (unsigned)p.H && (unsigned)(w0 + b) < (unsigned)p.W;
-            const int8_t* px = LAYOUT == WG_NHWC ? x + (((size_t)n * p.H + h) * p.W + w) * p.C
-                                                 : x + (size_t)n * p.C * cstride + (size_t)h * p.W + w;
-            s16x4 v = {0, 0, 0, 0};
+            for (int b = 0; b < 6; ++b) {
+                const int w = min(max(w0 + b, 0), p.W - 1);
+                const bool inside = (unsigned)(h0 + a) < (unsigned)p.H && (unsigned)(w0 + b) < (unsigned)p.W;
+                const int8_t* px = LAYOUT == WG_NHWC ? x + (((size_t)n * p.H + h) * p.W + w) * p.C
+                                                     : x + (size_t)n * p.C * cstride + (size_t)h * p.W + w;
+                uint32_t word = 0;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int c = min(c0 + i, p.C - 1);
-                const short e = px[(size_t)c * cstride];
-                v[i] = (inside && c0 + i < p.C) ? e : (short)0;
+                for (int i = 0; i < 4; ++i) {
+                    const int c = min(c0 + i, p.C - 1);
+                    const uint32_t e = (uint8_t)px[(size_t)c * cstride];
+                    const uint32_t byte = (inside && c0 + i < p.C) ? (e ^ 0x80u) : 0x80u;
+                    word |= byte << (8 * i);
+                }
+                u[a][b] = word;
             }
-            d[a][b] = v;
         }
     }
 }
@@ -72,11 +94,11 @@ __device__ inline void load_patch(const int8_t* __restrict__ x, const Problem& p
 //   t0 = v0 - v4, t1 = v1+v2+v3+v4, t2 = -v1+v2-v3+v4, t3 = (v4-v2) + i (v3-v1), t5 = v5 - v1
 // (t4 is the conjugate of t3 and never formed).
 struct Line {
-    s16x4 t0, t1, t2, t3r, t3i, t5;
+    Quad t0, t1, t2, t3r, t3i, t5;
 };
-__device__ inline Line bt_rule(s16x4 v0, s16x4 v1, s16x4 v2, s16x4 v3, s16x4 v4, s16x4 v5) {
+__device__ inline Line bt_rule(Quad v0, Quad v1, Quad v2, Quad v3, Quad v4, Quad v5) {
     Line o;
-    s16x4 s13 = v1 + v3, s24 = v2 + v4;
+    const Quad s13 = v1 + v3, s24 = v2 + v4;
     o.t0 = v0 - v4;
     o.t1 = s24 + s13;
     o.t2 = s24 - s13;
@@ -86,31 +108,40 @@ __device__ inline Line bt_rule(s16x4 v0, s16x4 v1, s16x4 v2, s16x4 v3, s16x4 v4,
     return o;
 }
 
-// Splits values into the int8 operand planes of `MODE` and hands each plane's four
-// bytes to `Sink::put(plane, bytes)`.
-template <int MODE, class Sink>
+// How a 12-bit value v = 64 h + l is handed to the matrix cores:
+//   kSplitKaratsuba: three planes per value, h, l and h + l (the middle operand of the
+//                    three-multiplication split of Section 3.1), and a third value Re+Im per
+//                    complex entry (the extra operand of the three-multiplication complex
+//                    product): 138 planes, the lossless staged layout;
+//   kSplitTwoLimb:   two planes per value, h and l: real entry p -> 2p, 2p+1; complex entry j
+//                    -> 32+4j + {Re h, Re l, Im h, Im l}: 72 planes.
+constexpr int kSplitKaratsuba = 0, kSplitTwoLimb = 1;
+
+template <int SPLIT, class Sink>
 struct OperandSplitter {
     Sink sink;
-    __device__ inline void put(int plane, s16x4 limb) const { sink.put(plane, __builtin_convertvector(limb, s8x4)); }
-    // lossless: value index q -> planes 3q (v >> 6), 3q+1 (v & 63), 3q+2 (their sum)
-    __device__ inline void value(int q, s16x4 v) const {
-        s16x4 hi = v >> 6, lo = v & (short)63;
-        put(3 * q, hi);
-        put(3 * q + 1, lo);
-        put(3 * q + 2, hi + lo);
+    __device__ inline static Quad high(Quad v) { return Quad{v.a >> 6, v.b >> 6}; }
+    __device__ inline static Quad low(Quad v) {
+        return Quad{as_s16x2(as_u32(v.a) & 0x003f003fu), as_s16x2(as_u32(v.b) & 0x003f003fu)};
     }
-    __device__ inline void limbs(int first, s16x4 v) const {
-        put(first, v >> 6);
-        put(first + 1, v & (short)63);
+    __device__ inline void value(int q, Quad v) const {   // planes 3q, 3q+1, 3q+2
+        const Quad hi = high(v), lo = low(v);
+        sink.put(3 * q, pack_low_bytes(hi));
+        sink.put(3 * q + 1, pack_low_bytes(lo));
+        sink.put(3 * q + 2, pack_low_bytes(hi + lo));
     }
-    __device__ inline void real_entry(int p, s16x4 v) const {
-        if (MODE == WG_LOSSLESS) value(p, v); else limbs(2 * p, v);
+    __device__ inline void limbs(int first, Quad v) const {
+        sink.put(first, pack_low_bytes(high(v)));
+        sink.put(first + 1, pack_low_bytes(low(v)));
     }
-    __device__ inline void complex_entry(int j, s16x4 re, s16x4 im) const {
-        if (MODE == WG_LOSSLESS) {
+    __device__ inline void real_entry(int p, Quad v) const {
+        if (SPLIT == kSplitKaratsuba) value(p, v); else limbs(2 * p, v);
+    }
+    __device__ inline void complex_entry(int j, Quad re, Quad im) const {
+        if (SPLIT == kSplitKaratsuba) {
             value(16 + 3 * j, re);
             value(16 + 3 * j + 1, im);
-            value(16 + 3 * j + 2, re + im);   // third operand of the 3-multiplication product (Section 3.1)
+            value(16 + 3 * j + 2, re + im);
         } else {
             limbs(32 + 4 * j, re);
             limbs(32 + 4 * j + 2, im);
@@ -119,20 +150,24 @@ struct OperandSplitter {
 };
 
 // Transforms one tile (four channels c0..c0+3) and emits every operand plane.
-template <int LAYOUT, bool VEC4, int MODE, class Sink>
+template <int LAYOUT, bool VEC4, int SPLIT, class Sink>
 __device__ inline void transform_tile(const int8_t* __restrict__ x, const Problem& p, int n, int ty, int tx, int c0,
-                                      const OperandSplitter<MODE, Sink>& out) {
-    s16x4 d[6][6];
-    load_patch<LAYOUT, VEC4>(x, p, n, ty, tx, c0, d);
+                                      const OperandSplitter<SPLIT, Sink>& out) {
+    uint32_t u[6][6];
+    load_patch<LAYOUT, VEC4>(x, p, n, ty, tx, c0, u);
     // column pass: d'[.][b] = B^T applied down each of the six tile columns
     Line col[6];
 #pragma unroll
-    for (int b = 0; b < 6; ++b) col[b] = bt_rule(d[0][b], d[1][b], d[2][b], d[3][b], d[4][b], d[5][b]);
+    for (int b = 0; b < 6; ++b)
+        col[b] = bt_rule(unpack_u8x4(u[0][b]), unpack_u8x4(u[1][b]), unpack_u8x4(u[2][b]), unpack_u8x4(u[3][b]),
+                         unpack_u8x4(u[4][b]), unpack_u8x4(u[5][b]));
+    const s16x2 bias11 = {2048, 2048};   // what the +128 bias leaves at entry (1,1)
     // row pass on the real rows 0,1,2,5 of d': entries (r, {0,1,2,5}) real, (r,3) complex
 #define WG_REAL_ROW(ri, field)                                                                      \
     {                                                                                               \
         Line r = bt_rule(col[0].field, col[1].field, col[2].field, col[3].field, col[4].field,      \
                          col[5].field);                                                             \
+        if (ri == 1) r.t1 = Quad{r.t1.a - bias11, r.t1.b - bias11};                                 \
         out.real_entry(4 * ri + 0, r.t0);                                                           \
         out.real_entry(4 * ri + 1, r.t1);                                                           \
         out.real_entry(4 * ri + 2, r.t2);                                                           \
@@ -146,8 +181,8 @@ __device__ inline void transform_tile(const int8_t* __restrict__ x, const Proble
 #undef WG_REAL_ROW
     // row 3 of d' is complex, a + i b: the rule acts on a and b separately; the two
     // entries (3,3) and (3,4) mix them: (x4-x2) +- i (x3-x1).
-    Line ra = bt_rule(col[0].t3r, col[1].t3r, col[2].t3r, col[3].t3r, col[4].t3r, col[5].t3r);
-    Line rb = bt_rule(col[0].t3i, col[1].t3i, col[2].t3i, col[3].t3i, col[4].t3i, col[5].t3i);
+    const Line ra = bt_rule(col[0].t3r, col[1].t3r, col[2].t3r, col[3].t3r, col[4].t3r, col[5].t3r);
+    const Line rb = bt_rule(col[0].t3i, col[1].t3i, col[2].t3i, col[3].t3i, col[4].t3i, col[5].t3i);
     out.complex_entry(4, ra.t0, rb.t0);
     out.complex_entry(5, ra.t1, rb.t1);
     out.complex_entry(6, ra.t2, rb.t2);
