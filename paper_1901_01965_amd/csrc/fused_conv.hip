@@ -33,7 +33,7 @@ constexpr int kFusedPlanes = 72;    // two-limb activation planes (kSplitTwoLimb
 constexpr int kPlaneBytes = kFusedTiles * kCBlock;   // one operand plane of the tile block in LDS
 constexpr int kLdsBytes = kFusedPlanes * kPlaneBytes;
 constexpr int kParkBytes = 4 * 16 * 64 * 16;         // four waves x 16 outputs x 64 lanes x 4 registers
-static_assert(kParkBytes + 3 * 16 * 4 <= kLdsBytes, "output staging reuses the operand planes' LDS");
+static_assert(kParkBytes <= kLdsBytes, "output staging reuses the operand planes' LDS");
 
 // LDS operand plane: the 16-byte piece holding 16 consecutive channels (group c16) of a tile
 // sits in slot c16*16 + ((tile + 4*c16) & 15); lane l of a wave reads slot(l/16, l%16), which
@@ -332,45 +332,64 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
     // stage the partial outputs: park[wave][output 0..15][lane] (four registers = four tiles each)
     __syncthreads();
     v4i* park = reinterpret_cast<v4i*>(lds);
-    int* tile_info = reinterpret_cast<int*>(lds + kParkBytes);   // per tile: offset, first row, first column
 #pragma unroll
     for (int i = 0; i < 16; ++i) park[(wave * 16 + i) * 64 + lane] = Y[i];
-    if (tid < kFusedTiles) {
-        // offsets fit 32 bits (checked on the host); -1 marks tiles beyond T
-        int origin = -1, row = 0, col = 0;
-        const int t = tile0 + tid;
+
+    // Where tile (lane & 15) of this block starts in y (offsets fit 32 bits, checked on the
+    // host; -1 marks tiles beyond T), and its first output row and column.
+    int my_origin = -1, my_row = 0, my_col = 0;
+    {
+        const int t = tile0 + (lane & 15);
         if (t < p.T) {
             const int tx = t % p.TW, ty = (t / p.TW) % p.TH, n = t / (p.TW * p.TH);
-            row = 4 * ty;
-            col = 4 * tx;
-            origin = LAYOUT == WG_NHWC ? ((n * p.H + row) * p.W + col) * p.K : (n * p.K * p.H + row) * p.W + col;
+            my_row = 4 * ty;
+            my_col = 4 * tx;
+            my_origin = LAYOUT == WG_NHWC ? ((n * p.H + my_row) * p.W + my_col) * p.K
+                                          : (n * p.K * p.H + my_row) * p.W + my_col;
         }
-        tile_info[tid] = origin;
-        tile_info[16 + tid] = row;
-        tile_info[32 + tid] = col;
     }
     __syncthreads();
 
     // 16 tiles x 16 outputs x 32 filters = 8192 results, 32 per thread, ordered so that a wave
-    // writes whole lines: channels-last, 32 filters of one pixel are 128 contiguous bytes;
-    // channel-major, 16 consecutive tiles x 4 columns of one output row are 256 contiguous bytes.
+    // writes whole lines.  The value of (tile, output 4i+j, filter kl) was parked by waves kl/16
+    // and 2 + kl/16 at output 4i+j, lane (tile/4)*16 + kl%16, register tile%4.
     const int* parki = reinterpret_cast<const int*>(lds);
     const int rnd = MODE == WG_SCALED ? 8 : 0;
-#pragma unroll 4
-    for (int it = 0; it < 32; ++it) {
-        const int idx = it * 256 + tid;
-        int tile, i, j, kl;
-        if (LAYOUT == WG_NHWC) { kl = idx & 31; j = (idx >> 5) & 3; i = (idx >> 7) & 3; tile = idx >> 9; }
-        else                   { j = idx & 3; tile = (idx >> 2) & 15; i = (idx >> 6) & 3; kl = idx >> 8; }
-        const int origin = tile_info[tile];
-        const int h = tile_info[16 + tile] + i, w = tile_info[32 + tile] + j, kk = k0 + kl;
-        // the value sits in waves kl/16 and 2 + kl/16, output 4i+j, lane (tile/4)*16 + kl%16, register tile%4
-        const int at = (((kl >> 4) * 16 + 4 * i + j) * 64 + (tile >> 2) * 16 + (kl & 15)) * 4 + (tile & 3);
-        const int v = (parki[at] + parki[at + 2 * 16 * 64 * 4] + rnd) >> 4;
-        if (origin >= 0 && h < p.H && w < p.W && kk < p.K) {
-            if (LAYOUT == WG_NHWC) y[(size_t)origin + ((size_t)i * p.W + j) * p.K + kk] = v;
-            else                   y[(size_t)origin + ((size_t)kk * p.H + i) * p.W + j] = v;
+    int v[32];
+    if constexpr (LAYOUT == WG_NHWC) {
+        // thread: filter kl and output column j fixed; iteration it: tile it/2, output row 2(it%2) + tid/128.
+        // A wave writes 2 pixels x 32 filters = 2 x 128 contiguous bytes.
+        const int kl = tid & 31, j = (tid >> 5) & 3, ih = tid >> 7;
+        const int kk = k0 + kl;
+        const int at0 = (((kl >> 4) * 16 + j) * 64 + (kl & 15)) * 4;
+#pragma unroll
+        for (int it = 0; it < 32; ++it) {
+            const int tile = it >> 1, i = 2 * (it & 1) + ih;
+            const int at = at0 + (4 * i * 64 + (tile >> 2) * 16) * 4 + (tile & 3);
+            v[it] = (parki[at] + parki[at + 2 * 16 * 64 * 4] + rnd) >> 4;
         }
+#pragma unroll
+        for (int it = 0; it < 32; ++it) {
+            const int tile = it >> 1, i = 2 * (it & 1) + ih;
+            const int origin = __builtin_amdgcn_readlane(my_origin, tile);
+            const int h = __builtin_amdgcn_readlane(my_row, tile) + i, w = __builtin_amdgcn_readlane(my_col, tile) + j;
+            if (origin >= 0 && h < p.H && w < p.W && kk < p.K) y[(size_t)origin + (i * p.W + j) * p.K + kk] = v[it];
+        }
+    } else {
+        // thread: tile, output row i and column j fixed; iteration it: filter it.  A wave writes one
+        // output row of 16 consecutive tiles = 256 contiguous bytes.
+        const int j = tid & 3, tile = (tid >> 2) & 15, i = tid >> 6;
+        const int origin = __shfl(my_origin, tile), h = __shfl(my_row, tile) + i, w = __shfl(my_col, tile) + j;
+        const bool ok = origin >= 0 && h < p.H && w < p.W;
+        const int at0 = ((4 * i + j) * 64 + (tile >> 2) * 16) * 4 + (tile & 3);
+#pragma unroll
+        for (int it = 0; it < 32; ++it) {
+            const int at = at0 + ((it >> 4) * 16 * 64 + (it & 15)) * 4;
+            v[it] = (parki[at] + parki[at + 2 * 16 * 64 * 4] + rnd) >> 4;
+        }
+#pragma unroll
+        for (int it = 0; it < 32; ++it)
+            if (ok && k0 + it < p.K) y[(size_t)origin + ((size_t)(k0 + it) * p.H + i) * p.W + j] = v[it];
     }
 }
 
