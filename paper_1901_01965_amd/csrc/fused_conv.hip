@@ -329,12 +329,7 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
         if (half == 0) phase0.run(cx, Y); else phase1.run(cx, Y);
     }
 
-    // stage the partial outputs: park[wave][output 0..15][lane] (four registers = four tiles each)
-    __syncthreads();
-    v4i* park = reinterpret_cast<v4i*>(lds);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) park[(wave * 16 + i) * 64 + lane] = Y[i];
-
+    // ---- add the two halves and store ------------------------------------------------------
     // Where tile (lane & 15) of this block starts in y (offsets fit 32 bits, checked on the
     // host; -1 marks tiles beyond T), and its first output row and column.
     int my_origin = -1, my_row = 0, my_col = 0;
@@ -348,17 +343,62 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
                                           : (n * p.K * p.H + my_row) * p.W + my_col;
         }
     }
-    __syncthreads();
-
-    // 16 tiles x 16 outputs x 32 filters = 8192 results, 32 per thread, ordered so that a wave
-    // writes whole lines.  The value of (tile, output 4i+j, filter kl) was parked by waves kl/16
-    // and 2 + kl/16 at output 4i+j, lane (tile/4)*16 + kl%16, register tile%4.
-    const int* parki = reinterpret_cast<const int*>(lds);
     const int rnd = MODE == WG_SCALED ? 8 : 0;
+    int* parki = reinterpret_cast<int*>(lds);
+    __syncthreads();   // the operand planes are dead: their LDS now stages the outputs
+
+    if (LAYOUT == WG_NHWC && (p.K & 3) == 0) {
+        // Channels-last with K a multiple of four: outputs are staged filter-fastest,
+        // stage[half][output 4i+j][tile][36] (32 filters, rows padded to 36 dwords so that the
+        // four 16-lane groups of a wave land in different banks), then every thread adds the
+        // halves for four consecutive filters and stores 16 bytes; eight lanes cover the 128
+        // contiguous bytes this block owns of a pixel.
+        constexpr int kRow = 36, kHalf = 16 * 16 * kRow;
+        static_assert(2 * kHalf * 4 <= kLdsBytes, "staging fits the operand planes' LDS");
+        {
+            int* dst = parki + half * kHalf + (4 * (lane >> 4)) * kRow + kblock * 16 + (lane & 15);
+#pragma unroll
+            for (int o = 0; o < 16; ++o)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) dst[(o * 16 + q) * kRow] = Y[o][q];
+        }
+        __syncthreads();
+        // thread: filters 4*k4..4*k4+3; pass ps: output row i = ps/2, tile = 8*(ps%2) + px/4, column j = px%4
+        const int k4 = tid & 7, px = tid >> 3, j = px & 3;
+        const int kk = k0 + 4 * k4;
+        int origin2[2], row2[2], col2[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            origin2[e] = __shfl(my_origin, 8 * e + (px >> 2));
+            row2[e] = __shfl(my_row, 8 * e + (px >> 2));
+            col2[e] = __shfl(my_col, 8 * e + (px >> 2));
+        }
+        v4i v[8];
+#pragma unroll
+        for (int ps = 0; ps < 8; ++ps) {
+            const int i = ps >> 1, tile = 8 * (ps & 1) + (px >> 2);
+            const int at = ((4 * i + j) * 16 + tile) * kRow + 4 * k4;
+            v[ps] = (*reinterpret_cast<const v4i*>(parki + at) + *reinterpret_cast<const v4i*>(parki + kHalf + at) + rnd) >> 4;
+        }
+#pragma unroll
+        for (int ps = 0; ps < 8; ++ps) {
+            const int i = ps >> 1, e = ps & 1;
+            if (origin2[e] >= 0 && row2[e] + i < p.H && col2[e] + j < p.W && kk < p.K)
+                *reinterpret_cast<v4i*>(y + (size_t)origin2[e] + (i * p.W + j) * p.K + kk) = v[ps];
+        }
+        return;
+    }
+
+    // General path: park[wave][output 0..15][lane] (four registers = four tiles each); the value
+    // of (tile, output 4i+j, filter kl) sits in waves kl/16 and 2 + kl/16 at output 4i+j, lane
+    // (tile/4)*16 + kl%16, register tile%4.  16 x 16 x 32 = 8192 results, 32 per thread.
+    v4i* park = reinterpret_cast<v4i*>(lds);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) park[(wave * 16 + i) * 64 + lane] = Y[i];
+    __syncthreads();
     int v[32];
     if constexpr (LAYOUT == WG_NHWC) {
-        // thread: filter kl and output column j fixed; iteration it: tile it/2, output row 2(it%2) + tid/128.
-        // A wave writes 2 pixels x 32 filters = 2 x 128 contiguous bytes.
+        // thread: filter kl and output column j fixed; iteration it: tile it/2, output row 2(it%2) + tid/128
         const int kl = tid & 31, j = (tid >> 5) & 3, ih = tid >> 7;
         const int kk = k0 + kl;
         const int at0 = (((kl >> 4) * 16 + j) * 64 + (kl & 15)) * 4;
