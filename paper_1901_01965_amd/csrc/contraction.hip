@@ -29,14 +29,15 @@ __global__ __launch_bounds__(256) void contraction_kernel(const int8_t* __restri
     const int t0 = blockIdx.x * 64 + (wave & 1) * 32;
     const int k0 = blockIdx.y * 64 + (wave >> 1) * 32;
     const int row = lane & 31, half = lane >> 5;
-    const size_t a_cb = (size_t)p.Tp * kCBlock, b_cb = (size_t)p.Kp * kCBlock;
+    constexpr int NP = MODE == WG_LOSSLESS ? 138 : 46;
+    const size_t a_cb = (size_t)p.Tp * kCBlock, b_cb = (size_t)(p.Kp >> 4) * NP * kFilterFragBytes;
 
     v16i re = {0}, im = {0};
     const int nsub = num_subproducts<MODE>(entry);
     for (int s = 0; s < nsub; ++s) {
         const SubProduct sp = subproduct<MODE>(entry, s);
         const int8_t* A = V + ((size_t)sp.a_plane * p.CB * p.Tp + t0 + row) * kCBlock + half * 16;
-        const int8_t* B = U + ((size_t)sp.b_plane * p.CB * p.Kp + k0 + row) * kCBlock + half * 16;
+        const int8_t* B = U + filter_plane_offset(sp.b_plane, 0, k0 + row, half * 16, p.Kp, NP);
         v16i acc = {0};
         for (int cb = 0; cb < p.CB; ++cb) {
             v4i a0 = *reinterpret_cast<const v4i*>(A + cb * a_cb);

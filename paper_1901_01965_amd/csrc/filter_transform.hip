@@ -114,8 +114,8 @@ __global__ __launch_bounds__(256) void filter_pack_kernel(const int8_t* w, int K
     int g[9], re[16], cr[10], ci[10];
     load_filter(w, k, c, K, C, layout, g);
     filter_entries(g, re, cr, ci);
-    const size_t plane_stride = (size_t)CB * Kp * kCBlock;
-    int8_t* base = planes + ((size_t)(c >> 6) * Kp + k) * kCBlock + (c & 63);
+    const size_t plane_stride = kFilterFragBytes;
+    int8_t* base = planes + filter_plane_offset(0, c >> 6, k, c & 63, Kp, num_filter_planes(mode));
     if (mode == WG_LOSSLESS) {
         // value v -> planes 3v: v>>6, 3v+1: v&63, 3v+2: their sum (Karatsuba's middle operand, Section 3.1)
         auto put = [&](int value_index, int v) {
@@ -156,7 +156,7 @@ __global__ void unpack_filter_planes_kernel(const int8_t* planes, const ScaleEnt
         int c = (int)(i % C);
         int k = (int)((i / C) % K);
         int pl = (int)(i / ((size_t)C * K));
-        dense[i] = planes[(((size_t)pl * CB + (c >> 6)) * Kp + k) * kCBlock + (c & 63)];
+        dense[i] = planes[filter_plane_offset(pl, c >> 6, k, c & 63, Kp, nplanes)];
     }
     if (i < (size_t)K * kEntries) {
         ScaleEntry s = table[i];

@@ -190,7 +190,6 @@ __device__ inline void finish_row(const v4i (&er)[6], const v4i (&ei)[6], v4i (&
 struct LaneContext {
     const int8_t* a_lds;        // this lane's 16-byte slot in plane 0
     const int8_t* b_glob;       // this lane's 16 bytes of filter plane 0, current channel block
-    uint32_t b_plane_stride;    // bytes between filter planes
     const ScaleEntry* table_k;  // scaling table row of this lane's filter (scaled mode)
 };
 
@@ -210,7 +209,7 @@ struct ProductPhase {
     __device__ inline static v4i load_b(const LaneContext& cx) {
         constexpr int slot = b_slot_of<MODE>(HALF, F);
         constexpr int plane = b_plane<MODE>(half_slot(HALF, slot).entry, F - b_start<MODE>(HALF, slot));
-        return *reinterpret_cast<const v4i*>(cx.b_glob + (uint32_t)plane * cx.b_plane_stride);
+        return *reinterpret_cast<const v4i*>(cx.b_glob + plane * kFilterFragBytes);
     }
     template <int SLOT, int I>
     __device__ inline static v4i load_a(const LaneContext& cx) {
@@ -293,7 +292,6 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
                                                          const uint8_t* __restrict__ blob, size_t table_off,
                                                          size_t planes_off, int32_t* __restrict__ y, Problem p) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
-    if (!blob_matches(reinterpret_cast<const BlobHeader*>(blob), p.K, p.C, MODE)) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kblock = wave & 1, half = wave >> 1;
     const int tile0 = blockIdx.x * kFusedTiles;
@@ -309,22 +307,34 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
 
     LaneContext cx;
     cx.a_lds = lds + lds_slot(lane >> 4, lane & 15) * 16;
-    cx.b_plane_stride = (uint32_t)p.CB * p.Kp * kCBlock;
     cx.table_k = reinterpret_cast<const ScaleEntry*>(blob + table_off) + (size_t)k * kEntries;
-    const int8_t* b_lane = reinterpret_cast<const int8_t*>(blob + planes_off) + (size_t)k * kCBlock + (lane >> 4) * 16;
+    constexpr int NP = MODE == WG_LOSSLESS ? 138 : 46;
+    const int8_t* b_lane = reinterpret_cast<const int8_t*>(blob + planes_off) +
+                           filter_plane_offset(0, 0, k, (lane >> 4) * 16, p.Kp, NP);
+    const size_t b_block_stride = (size_t)(p.Kp >> 4) * NP * kFilterFragBytes;
 
     v4i Y[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) Y[i] = (v4i){0, 0, 0, 0};
 
+    // The activation patch of the first channel block does not depend on the blob: its loads
+    // go out first, and the blob header is checked while they are in flight.
+    uint32_t patch[6][6];
+    if (a_t < p.T) load_patch<LAYOUT, VEC4>(x, p, a_n, a_ty, a_tx, 4 * a_cq, patch);
+    if (!blob_matches(reinterpret_cast<const BlobHeader*>(blob), p.K, p.C, MODE)) return;
+
     ProductPhase<MODE, 0> phase0;
     ProductPhase<MODE, 1> phase1;
     for (int cb = 0; cb < p.CB; ++cb) {
-        cx.b_glob = b_lane + (size_t)cb * p.Kp * kCBlock;
+        cx.b_glob = b_lane + cb * b_block_stride;
         if (half == 0) phase0.prefetch(cx); else phase1.prefetch(cx);
         if (cb > 0) __syncthreads();   // everyone is done reading the previous block's planes
-        if (a_t < p.T)
-            transform_tile<LAYOUT, VEC4, kSplitTwoLimb>(x, p, a_n, a_ty, a_tx, cb * kCBlock + 4 * a_cq, out);
+        if (a_t < p.T) {
+            bias_patch(p, a_ty, a_tx, cb * kCBlock + 4 * a_cq, patch);
+            transform_patch(patch, out);
+            if (cb + 1 < p.CB)       // next block's patch travels while this block's products run
+                load_patch<LAYOUT, VEC4>(x, p, a_n, a_ty, a_tx, (cb + 1) * kCBlock + 4 * a_cq, patch);
+        }
         __syncthreads();
         if (half == 0) phase0.run(cx, Y); else phase1.run(cx, Y);
     }
@@ -451,9 +461,8 @@ hipError_t launch(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, in
 }  // namespace
 
 bool fused_conv_supported(const Problem& p, int mode) {
-    // 32-bit plane offsets inside the blob; scaled mode needs the whole channel sum in one block
-    const unsigned long long span = (unsigned long long)num_filter_planes(mode) * p.CB * p.Kp * kCBlock;
-    return span < (1ull << 32) && (mode == WG_LOSSLESS || p.CB == 1);
+    // scaled mode needs the whole channel sum in one block (the reverse scaling rounds)
+    return mode == WG_LOSSLESS || p.CB == 1;
 }
 
 hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int layout, int mode,

@@ -34,9 +34,9 @@ __device__ inline uint32_t pack_low_bytes(Quad v) { return __builtin_amdgcn_perm
 
 constexpr uint32_t kBiasBytes = 0x80808080u;
 
-// The biased 6x6 input patch of one tile, four consecutive channels c0..c0+3 per pixel.
-// All loads are issued before any is used: addresses are clamped into the image and
-// out-of-range pixels are replaced afterwards, so no load sits behind a branch.
+// The 6x6 input patch of one tile, four consecutive channels c0..c0+3 per pixel, as raw loads:
+// addresses are clamped into the image so no load sits behind a branch and nothing here waits
+// for data; bias_patch() then applies the bias and replaces out-of-range pixels.
 // VEC4 (channels-last input whose C is a multiple of four, chosen on the host): one 4-byte
 // load per pixel; a channel group is then either wholly inside or wholly beyond C.
 template <int LAYOUT, bool VEC4>
@@ -56,13 +56,6 @@ __device__ inline void load_patch(const int8_t* __restrict__ x, const Problem& p
                 u[a][b] = *reinterpret_cast<const uint32_t*>(img + ((size_t)h * p.W + w) * p.C);
             }
         }
-#pragma unroll
-        for (int a = 0; a < 6; ++a)
-#pragma unroll
-            for (int b = 0; b < 6; ++b) {
-                const bool inside = have && (unsigned)(h0 + a) < (unsigned)p.H && (unsigned)(w0 + b) < (unsigned)p.W;
-                u[a][b] = inside ? (u[a][b] ^ kBiasBytes) : kBiasBytes;
-            }
     } else {
         // general path: channel counts that are not a multiple of four, and channel-major inputs
         // (one byte per channel, stride H*W)
@@ -73,7 +66,6 @@ __device__ inline void load_patch(const int8_t* __restrict__ x, const Problem& p
 #pragma unroll
             for (int b = 0; b < 6; ++b) {
                 const int w = min(max(w0 + b, 0), p.W - 1);
-                const bool inside = (unsigned)(h0 + a) < (unsigned)p.H && (unsigned)(w0 + b) < (unsigned)p.W;
                 const int8_t* px = LAYOUT == WG_NHWC ? x + (((size_t)n * p.H + h) * p.W + w) * p.C
                                                      : x + (size_t)n * p.C * cstride + (size_t)h * p.W + w;
                 uint32_t word = 0;
@@ -81,13 +73,26 @@ __device__ inline void load_patch(const int8_t* __restrict__ x, const Problem& p
                 for (int i = 0; i < 4; ++i) {
                     const int c = min(c0 + i, p.C - 1);
                     const uint32_t e = (uint8_t)px[(size_t)c * cstride];
-                    const uint32_t byte = (inside && c0 + i < p.C) ? (e ^ 0x80u) : 0x80u;
-                    word |= byte << (8 * i);
+                    word |= (c0 + i < p.C ? e : 0u) << (8 * i);   // zero = no contribution beyond C
                 }
                 u[a][b] = word;
             }
         }
     }
+}
+
+// u = x + 128 on every byte; pixels outside the image (pad 1) and channel groups beyond C
+// become the bias value itself, i.e. x = 0.
+__device__ inline void bias_patch(const Problem& p, int ty, int tx, int c0, uint32_t u[6][6]) {
+    const int h0 = 4 * ty - 1, w0 = 4 * tx - 1;
+    const bool have = c0 < p.C;
+#pragma unroll
+    for (int a = 0; a < 6; ++a)
+#pragma unroll
+        for (int b = 0; b < 6; ++b) {
+            const bool inside = have && (unsigned)(h0 + a) < (unsigned)p.H && (unsigned)(w0 + b) < (unsigned)p.W;
+            u[a][b] = inside ? (u[a][b] ^ kBiasBytes) : kBiasBytes;
+        }
 }
 
 // The 1-D rule of B^T on a real 6-vector (Section 3.4, the expansion of d' = B^T d):
@@ -149,12 +154,9 @@ struct OperandSplitter {
     }
 };
 
-// Transforms one tile (four channels c0..c0+3) and emits every operand plane.
-template <int LAYOUT, bool VEC4, int SPLIT, class Sink>
-__device__ inline void transform_tile(const int8_t* __restrict__ x, const Problem& p, int n, int ty, int tx, int c0,
-                                      const OperandSplitter<SPLIT, Sink>& out) {
-    uint32_t u[6][6];
-    load_patch<LAYOUT, VEC4>(x, p, n, ty, tx, c0, u);
+// Transforms one loaded patch (four channels) and emits every operand plane.
+template <int SPLIT, class Sink>
+__device__ inline void transform_patch(const uint32_t u[6][6], const OperandSplitter<SPLIT, Sink>& out) {
     // column pass: d'[.][b] = B^T applied down each of the six tile columns
     Line col[6];
 #pragma unroll
@@ -191,4 +193,16 @@ __device__ inline void transform_tile(const int8_t* __restrict__ x, const Proble
     out.complex_entry(9, ra.t3r + rb.t3i, rb.t3r - ra.t3i);
 }
 
+}  // namespace wg
+
+namespace wg {
+// Loads and transforms one tile (four channels c0..c0+3).
+template <int LAYOUT, bool VEC4, int SPLIT, class Sink>
+__device__ inline void transform_tile(const int8_t* __restrict__ x, const Problem& p, int n, int ty, int tx, int c0,
+                                      const OperandSplitter<SPLIT, Sink>& out) {
+    uint32_t u[6][6];
+    load_patch<LAYOUT, VEC4>(x, p, n, ty, tx, c0, u);
+    bias_patch(p, ty, tx, c0, u);
+    transform_patch(u, out);
+}
 }  // namespace wg

@@ -46,9 +46,12 @@ __host__ __device__ inline int num_filter_planes(int mode) { return mode == WG_L
 
 // ---- packed filter blob -------------------------------------------------------
 // [BlobHeader, 256 B][maxmag: uint32 [Kp][26]][table: ScaleEntry [Kp][26]]
-// [operand planes: int8 [planes][CB][Kp][64]], each section 256-byte aligned.
+// [operand planes: int8 [CB][Kp/16][planes][16][64]], each section 256-byte aligned.
+// The operand planes are fragment-major: the 1 KB piece (16 filters x 64 channels) that one
+// matrix-core instruction consumes is contiguous, and all planes of a (channel block, filter
+// block) follow each other, so a kernel steps from plane to plane with constant offsets.
 constexpr uint32_t kBlobMagic = 0x33344757u;  // "WG43"
-constexpr uint32_t kBlobVersion = 1;
+constexpr uint32_t kBlobVersion = 2;
 
 struct BlobHeader {
     uint32_t magic, version;
@@ -60,6 +63,11 @@ static_assert(sizeof(BlobHeader) == 256, "blob header is one 256-byte block");
 struct ScaleEntry {  // per (filter k, free entry): down-scale n/2^p, inverse r/2^q
     int32_t n, p, r, q;
 };
+
+constexpr int kFilterFragBytes = 16 * kCBlock;
+__host__ __device__ inline size_t filter_plane_offset(int plane, int cb, int k, int c64, int Kp, int nplanes) {
+    return ((((size_t)cb * (Kp >> 4) + (k >> 4)) * nplanes + plane) * 16 + (k & 15)) * kCBlock + c64;
+}
 
 struct BlobLayout {
     size_t maxmag_off, table_off, planes_off, total;
