@@ -75,6 +75,9 @@ def main():
     ap.add_argument("--layout", default="nhwc", choices=("nhwc", "nchw"))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one 256 MiB device-to-device tensor copy, the known-size kernel that "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (the path has no cross-GPU step); use --gpus 1")
@@ -146,6 +149,14 @@ def main():
             mfma_tops = contraction_int8_ops(case, args.mode) / (stage[s] * 1e-3) / 1e12
             kernels[s]["int8_mfma_TOPS"] = round(mfma_tops, 1)
             kernels[s]["mfma_frac"] = round(mfma_tops / INT8_MFMA_PEAK_TOPS, 4)
+
+    if args.calibration_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # direct convolution on the same inputs, for context
     yd = torch.empty_like(y)
