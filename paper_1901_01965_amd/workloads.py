@@ -58,6 +58,9 @@ VGG16_LAYERS: List[Tuple[int, int, int, bool]] = [
     (512, 512, 14, False), (512, 512, 14, False), (512, 512, 14, True),
 ]
 VGG16_BATCH = 16
+# Fixed requantisation shifts per layer (harness constants): s = max(0, bitlen(max y) - 7) measured by the CPU
+# oracle on image 0, written by tests/golden/make_vgg16_shifts.py into tests/golden/vgg16_shifts.txt.
+VGG16_SHIFTS = [9, 9, 9, 10, 10, 10, 10, 11, 10, 10, 11, 11, 10]
 
 
 def _rng(config, tensor_id):

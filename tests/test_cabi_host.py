@@ -1,0 +1,132 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function the header
+declares, sizes are consistent, and every validation error path returns its code before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_1901_01965_amd as wg
+from paper_1901_01965_amd import binding, workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "winograd_c.h")
+
+OK, EINVAL, EUNSUPPORTED, ESMALLBUF = 0, -1, -2, -3
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_1901_01965_amd import build
+        build.build()
+    return wg.load_library()
+
+
+def _declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(winograd_\w+|direct_conv2d_int8|requant_relu_pool_int8)\s*\(", text)))
+
+
+def test_every_declared_function_is_exported(lib):
+    names = _declared_functions()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.EXPORTED_SYMBOLS) == names
+
+
+def test_status_strings(lib):
+    for code in range(-6, 1):
+        assert wg.binding.status_string(code)
+    assert "blob" in wg.binding.status_string(-4)
+
+
+def test_size_queries(lib):
+    assert wg.packed_filter_bytes(0, 4, 0) == 0 and lib.winograd_packed_filter_bytes(4, 4, 7) == 0
+    assert wg.packed_filter_bytes(4, 897, 0) == 0            # beyond WG_MAX_CHANNELS
+    lossless, scaled = wg.packed_filter_bytes(64, 64, wg.LOSSLESS), wg.packed_filter_bytes(64, 64, wg.SCALED)
+    assert lossless > 138 * 64 * 64 and scaled > 46 * 64 * 64 and lossless > scaled
+    assert lossless % 256 == 0
+    # padding: K up to 64, C up to 64
+    assert wg.packed_filter_bytes(1, 1, 0) == wg.packed_filter_bytes(64, 64, 0)
+    assert wg.workspace_bytes(0, 1, 1, 1, 1, 0) == 0
+    c = wl.CASES["cfg2"]
+    ws = wg.workspace_bytes(c.N, c.C, c.H, c.W, c.K, wg.LOSSLESS)
+    assert ws >= 138 * c.tiles * c.C + 36 * 4 * c.tiles * c.K
+    assert lib.winograd_num_activation_planes(0) == 138 and lib.winograd_num_activation_planes(1) == 72
+    assert lib.winograd_num_filter_planes(0) == 138 and lib.winograd_num_filter_planes(1) == 46
+    assert lib.winograd_num_filter_planes(5) == 0
+
+
+def test_path_query(lib):
+    assert wg.conv2d_path(8, 64, 56, 56, 64, wg.LOSSLESS) == wg.FUSED
+    assert wg.conv2d_path(64, 512, 7, 7, 512, wg.SCALED) == wg.STAGED
+    assert lib.winograd_conv2d_path(8, 64, 56, 56, 64, 9) == EINVAL
+    assert lib.winograd_debug_force_path(3) == EINVAL
+    assert lib.winograd_debug_force_path(0) == OK
+
+
+def test_validation_errors_return_before_any_launch(lib):
+    """Fake but well-aligned addresses: every call must be rejected on the host (nothing dereferences them)."""
+    p = ctypes.c_void_p
+    good, good2, good3 = p(0x10000), p(0x20000), p(0x30000)
+    odd = p(0x10001)
+    big = 1 << 40
+    ft = lib.winograd_filter_transform
+    assert ft(None, 4, 4, 0, 0, good, big, None) == EINVAL
+    assert ft(good, 4, 4, 0, 0, None, big, None) == EINVAL
+    assert ft(good, 0, 4, 0, 0, good2, big, None) == EINVAL
+    assert ft(good, 4, -1, 0, 0, good2, big, None) == EINVAL
+    assert ft(good, 4, 4, 2, 0, good2, big, None) == EINVAL          # unknown layout
+    assert ft(good, 4, 4, 0, 2, good2, big, None) == EINVAL          # unknown mode
+    assert ft(good, 4, 897, 0, 0, good2, big, None) == EUNSUPPORTED  # int32 exactness bound
+    assert ft(odd, 4, 4, 0, 0, good2, big, None) == EINVAL           # misaligned filters
+    assert ft(good, 4, 4, 0, 0, p(0x20010), big, None) == EINVAL     # misaligned blob
+    assert ft(good, 4, 4, 0, 0, good2, 100, None) == ESMALLBUF
+
+    conv = lib.winograd_conv2d_int8
+    args = dict(N=1, C=4, H=8, W=8, K=4)
+    ws_bytes = wg.workspace_bytes(1, 4, 8, 8, 4, 0)
+
+    def call(x=good, blob=good2, y=good3, N=1, C=4, H=8, W=8, K=4, layout=0, mode=0, ws=p(0x40000), wsb=ws_bytes):
+        return conv(x, blob, y, N, C, H, W, K, layout, mode, ws, wsb, None)
+
+    assert call(x=None) == EINVAL and call(blob=None) == EINVAL and call(y=None) == EINVAL and call(ws=None) == EINVAL
+    assert call(N=0) == EINVAL and call(H=-3) == EINVAL and call(K=0) == EINVAL
+    assert call(layout=5) == EINVAL and call(mode=-1) == EINVAL
+    assert call(C=1000) == EUNSUPPORTED
+    assert call(N=1 << 20, H=1 << 10, W=1 << 10) == EUNSUPPORTED      # beyond 32-bit indexing
+    assert call(wsb=ws_bytes - 1) == ESMALLBUF
+    assert call(x=odd) == EINVAL and call(ws=p(0x40010)) == EINVAL
+
+    direct = lib.direct_conv2d_int8
+    assert direct(None, good, good2, 1, 4, 8, 8, 4, 0, None) == EINVAL
+    assert direct(good, good2, good3, 1, 4, 8, 8, 4, 3, None) == EINVAL
+    assert direct(good, good2, good3, 1, 900, 8, 8, 4, 0, None) == EUNSUPPORTED
+
+    rq = lib.requant_relu_pool_int8
+    assert rq(None, good, 1, 4, 8, 8, 0, 3, 1, 0, None) == EINVAL
+    assert rq(good, good2, 1, 4, 8, 8, 0, 32, 1, 0, None) == EINVAL   # shift out of range
+    assert rq(good, good2, 1, 4, 7, 8, 0, 3, 1, 1, None) == EUNSUPPORTED   # odd H with pooling
+
+    st = lib.winograd_conv2d_int8_stage_times
+    assert st(good, good2, good3, 1, 4, 8, 8, 4, 0, 0, p(0x40000), ws_bytes, None, 0, good) == EINVAL
+    assert st(good, good2, good3, 1, 4, 8, 8, 4, 0, 0, p(0x40000), ws_bytes, None, 1, None) == EINVAL
+    assert lib.winograd_packed_filter_check(None, 4, 4, 0, None) == EINVAL
+    assert lib.winograd_debug_input_operands(None, good, 1, 4, 8, 8, 0, 0, good2, big, None) == EINVAL
+    assert lib.winograd_debug_filter_operands(good2, 4, 4, 3, good, good3, None) == EINVAL
+    assert lib.winograd_debug_contraction(good, good2, good3, 1, 4, 8, 8, 4, 0, 0, None, big, None) == EINVAL
+
+
+def test_binding_refuses_cpu_tensors(lib):
+    import torch
+    x = torch.zeros((1, 4, 8, 8), dtype=torch.int8)
+    with pytest.raises(TypeError):
+        wg.direct_conv2d_int8(x, torch.zeros((4, 4, 3, 3), dtype=torch.int8))
+
+
+def test_vgg_shift_constants_match_the_generated_fixture():
+    with open(os.path.join(ROOT, "tests", "golden", "vgg16_shifts.txt")) as f:
+        line = [l for l in f if not l.startswith("#")][0]
+    assert [int(t) for t in line.split()] == wl.VGG16_SHIFTS
