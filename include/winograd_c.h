@@ -174,6 +174,11 @@ int winograd_num_activation_planes(int mode);
 int winograd_debug_force_path(int path);
 int winograd_num_filter_planes(int mode);
 
+/* Host-only: the (n, ty, tx) the kernels derive from tile index t = (n*TH + ty)*TW + tx for
+   this problem (they divide by multiply-and-shift with constants prepared on the host; this
+   lets a CPU test compare that arithmetic against plain division).  out3_host: 3 ints. */
+int winograd_debug_tile_decode(int N, int C, int H, int W, int K, int t, int* out3_host);
+
 /* Runs only the input transform D = B^T d B (Section 3.4) and writes its int8
    operand planes as a dense [planes][T][C] array, T = N*ceil(H/4)*ceil(W/4),
    tile index (n*TH + ty)*TW + tx. */

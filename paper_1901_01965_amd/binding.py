@@ -44,6 +44,7 @@ def load_library():
         "winograd_num_filter_planes": (i, [i]),
         "winograd_debug_force_path": (i, [i]),
         "winograd_conv2d_path": (i, [i, i, i, i, i, i]),
+        "winograd_debug_tile_decode": (i, [i, i, i, i, i, i, vp]),
         "winograd_packed_filter_bytes": (sz, [i, i, i]),
         "winograd_workspace_bytes": (sz, [i, i, i, i, i, i]),
         "winograd_filter_transform": (i, [vp, i, i, i, i, vp, sz, vp]),
@@ -65,7 +66,7 @@ def load_library():
 
 EXPORTED_SYMBOLS = (
     "winograd_status_string", "winograd_num_activation_planes", "winograd_num_filter_planes",
-    "winograd_debug_force_path", "winograd_conv2d_path",
+    "winograd_debug_force_path", "winograd_conv2d_path", "winograd_debug_tile_decode",
     "winograd_packed_filter_bytes", "winograd_workspace_bytes", "winograd_filter_transform",
     "winograd_packed_filter_check", "winograd_conv2d_int8", "winograd_conv2d_int8_stage_times",
     "direct_conv2d_int8", "requant_relu_pool_int8",

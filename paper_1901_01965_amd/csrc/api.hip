@@ -126,6 +126,15 @@ int winograd_conv2d_path(int N, int C, int H, int W, int K, int mode) {
     return use_fused(make_problem(N, C, H, W, K), mode) ? 2 : 1;
 }
 
+int winograd_debug_tile_decode(int N, int C, int H, int W, int K, int t, int* out3_host) {
+    if (!out3_host || t < 0) return WG_EINVAL;
+    if (int st = check_shape(N, C, H, W, K)) return st;
+    const Problem p = make_problem(N, C, H, W, K);
+    if (t >= p.T) return WG_EINVAL;
+    decode_tile(p, t, out3_host[0], out3_host[1], out3_host[2]);
+    return WG_OK;
+}
+
 int winograd_debug_force_path(int path) {
     if (path < 0 || path > 2) return WG_EINVAL;
     g_forced_path = path;

@@ -299,9 +299,13 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
     const int k = k0 + kblock * 16 + (lane & 15);
 
     // transform-phase identity
+    // every lane decodes tile (lane & 15) of the block once; the transform phase fetches the
+    // coordinates of its own tile (tid / 16) from that lane
+    int my_n = 0, my_ty = 0, my_tx = 0;
+    if (tile0 + (lane & 15) < p.T) decode_tile(p, tile0 + (lane & 15), my_n, my_ty, my_tx);
     const int a_tile = tid >> 4, a_cq = tid & 15;
     const int a_t = tile0 + a_tile;
-    const int a_tx = a_t % p.TW, a_ty = (a_t / p.TW) % p.TH, a_n = a_t / (p.TW * p.TH);
+    const int a_tx = __shfl(my_tx, a_tile), a_ty = __shfl(my_ty, a_tile), a_n = __shfl(my_n, a_tile);
     OperandSplitter<kSplitTwoLimb, LdsPlaneSink> out;
     out.sink.base = lds + lds_slot(a_cq >> 2, a_tile) * 16 + (a_cq & 3) * 4;
 
@@ -342,17 +346,11 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
     // ---- add the two halves and store ------------------------------------------------------
     // Where tile (lane & 15) of this block starts in y (offsets fit 32 bits, checked on the
     // host; -1 marks tiles beyond T), and its first output row and column.
-    int my_origin = -1, my_row = 0, my_col = 0;
-    {
-        const int t = tile0 + (lane & 15);
-        if (t < p.T) {
-            const int tx = t % p.TW, ty = (t / p.TW) % p.TH, n = t / (p.TW * p.TH);
-            my_row = 4 * ty;
-            my_col = 4 * tx;
-            my_origin = LAYOUT == WG_NHWC ? ((n * p.H + my_row) * p.W + my_col) * p.K
-                                          : (n * p.K * p.H + my_row) * p.W + my_col;
-        }
-    }
+    const int my_row = 4 * my_ty, my_col = 4 * my_tx;
+    int my_origin = -1;
+    if (tile0 + (lane & 15) < p.T)
+        my_origin = LAYOUT == WG_NHWC ? ((my_n * p.H + my_row) * p.W + my_col) * p.K
+                                      : (my_n * p.K * p.H + my_row) * p.W + my_col;
     const int rnd = MODE == WG_SCALED ? 8 : 0;
     int* parki = reinterpret_cast<int*>(lds);
     __syncthreads();   // the operand planes are dead: their LDS now stages the outputs

@@ -26,7 +26,8 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const int8_t* __re
     const int t = blockIdx.x * 16 + (threadIdx.x >> 4);
     const int cb = blockIdx.y;
     if (t >= p.T) return;
-    const int tx = t % p.TW, ty = (t / p.TW) % p.TH, n = t / (p.TW * p.TH);
+    int n, ty, tx;
+    decode_tile(p, t, n, ty, tx);
     constexpr int SPLIT = MODE == WG_LOSSLESS ? kSplitKaratsuba : kSplitTwoLimb;
     OperandSplitter<SPLIT, GlobalPlaneSink> out;
     out.sink.base = V + (((size_t)cb * p.Tp + t) * kCBlock + 4 * cq);

@@ -42,42 +42,43 @@ constexpr uint32_t kBiasBytes = 0x80808080u;
 template <int LAYOUT, bool VEC4>
 __device__ inline void load_patch(const int8_t* __restrict__ x, const Problem& p, int n, int ty, int tx, int c0,
                                   uint32_t u[6][6]) {
+    // Offsets fit 32 bits (the host checks N*C*H*W < 2^31): one multiply per patch row and
+    // column instead of 64-bit address arithmetic per pixel.
     const int h0 = 4 * ty - 1, w0 = 4 * tx - 1;
+    const uint32_t pixel_stride = LAYOUT == WG_NHWC ? (uint32_t)p.C : 1u;
+    uint32_t row_off[6], col_off[6];
+#pragma unroll
+    for (int a = 0; a < 6; ++a) {
+        row_off[a] = (uint32_t)min(max(h0 + a, 0), p.H - 1) * (uint32_t)p.W * pixel_stride;
+        col_off[a] = (uint32_t)min(max(w0 + a, 0), p.W - 1) * pixel_stride;
+    }
     if constexpr (VEC4) {
         static_assert(LAYOUT == WG_NHWC, "4-byte pixel loads need channels-last input");
-        const bool have = c0 < p.C;
-        const int8_t* img = x + (size_t)n * p.H * p.W * p.C + (have ? c0 : 0);
+        const int8_t* img = x + (size_t)n * p.H * p.W * p.C + (c0 < p.C ? c0 : 0);
 #pragma unroll
-        for (int a = 0; a < 6; ++a) {
-            const int h = min(max(h0 + a, 0), p.H - 1);
+        for (int a = 0; a < 6; ++a)
 #pragma unroll
-            for (int b = 0; b < 6; ++b) {
-                const int w = min(max(w0 + b, 0), p.W - 1);
-                u[a][b] = *reinterpret_cast<const uint32_t*>(img + ((size_t)h * p.W + w) * p.C);
-            }
-        }
+            for (int b = 0; b < 6; ++b) u[a][b] = *reinterpret_cast<const uint32_t*>(img + (row_off[a] + col_off[b]));
     } else {
         // general path: channel counts that are not a multiple of four, and channel-major inputs
         // (one byte per channel, stride H*W)
-        const size_t cstride = LAYOUT == WG_NHWC ? 1 : (size_t)p.H * p.W;
+        const uint32_t cstride = LAYOUT == WG_NHWC ? 1u : (uint32_t)p.H * (uint32_t)p.W;
+        const int8_t* img = x + (size_t)n * p.C * p.H * p.W;
+        uint32_t chan_off[4];
 #pragma unroll
-        for (int a = 0; a < 6; ++a) {
-            const int h = min(max(h0 + a, 0), p.H - 1);
+        for (int i = 0; i < 4; ++i) chan_off[i] = (uint32_t)min(c0 + i, p.C - 1) * cstride;
+#pragma unroll
+        for (int a = 0; a < 6; ++a)
 #pragma unroll
             for (int b = 0; b < 6; ++b) {
-                const int w = min(max(w0 + b, 0), p.W - 1);
-                const int8_t* px = LAYOUT == WG_NHWC ? x + (((size_t)n * p.H + h) * p.W + w) * p.C
-                                                     : x + (size_t)n * p.C * cstride + (size_t)h * p.W + w;
                 uint32_t word = 0;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const int c = min(c0 + i, p.C - 1);
-                    const uint32_t e = (uint8_t)px[(size_t)c * cstride];
+                    const uint32_t e = (uint8_t)img[row_off[a] + col_off[b] + chan_off[i]];
                     word |= (c0 + i < p.C ? e : 0u) << (8 * i);   // zero = no contribution beyond C
                 }
                 u[a][b] = word;
             }
-        }
     }
 }
 

@@ -57,7 +57,8 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const int32_t* __
         z3r[3] = br + di + cr[7];        z3i[3] = bi - dr + ci[7];  // (e1-e2) - i (e3-e4) + e5
     }
 
-    const int tx = t % p.TW, ty = (t / p.TW) % p.TH, n = t / (p.TW * p.TH);
+    int n, ty, tx;
+    decode_tile(p, t, n, ty, tx);
     const int rnd = MODE == WG_SCALED ? 8 : 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {

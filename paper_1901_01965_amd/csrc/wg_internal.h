@@ -19,13 +19,45 @@ constexpr int kRealEntries = 16;
 constexpr int kAccPlanes = 36;   // 16 real + 10 * (Re, Im)
 constexpr int kWeightRange = 127;  // spatial range of signed int8 filters, the target of the scaling
 
+// Division of a 31-bit unsigned n by a fixed divisor d as one high multiply and a shift:
+// with l = ceil(log2 d) and m = floor(2^(31+l) / d) + 1 (which fits 32 bits),
+// floor(n / d) = (n * m) >> (31 + l) for every n < 2^31.  d = 1 is flagged by mul = 0.
+struct FastDiv {
+    uint32_t mul, shift;
+};
+inline FastDiv make_fast_div(uint32_t d) {
+    FastDiv f = {0, 0};
+    if (d <= 1) return f;
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;
+    f.mul = (uint32_t)((1ull << (31 + l)) / d + 1);
+    f.shift = l - 1;
+    return f;
+}
+__host__ __device__ inline uint32_t fast_div(uint32_t n, FastDiv f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return f.mul ? __umulhi(n, f.mul) >> f.shift : n;
+#else
+    return f.mul ? (uint32_t)(((unsigned long long)n * f.mul) >> 32) >> f.shift : n;
+#endif
+}
+
 struct Problem {
     int N, C, H, W, K;
     int TH, TW, T;   // tiles per column / row, total tiles
     int Tp;          // T padded to kTilePad
     int CB;          // ceil(C / 64)
     int Kp;          // K padded to kFilterPad
+    FastDiv div_tw, div_th;   // by TW and by TH
 };
+
+// tile index t = (n*TH + ty)*TW + tx
+__host__ __device__ inline void decode_tile(const Problem& p, int t, int& n, int& ty, int& tx) {
+    const uint32_t row = fast_div((uint32_t)t, p.div_tw);   // n*TH + ty
+    tx = t - (int)row * p.TW;
+    n = (int)fast_div(row, p.div_th);
+    ty = (int)row - n * p.TH;
+}
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 inline size_t round_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
@@ -38,6 +70,8 @@ inline Problem make_problem(int N, int C, int H, int W, int K) {
     p.Tp = ceil_div(p.T, kTilePad) * kTilePad;
     p.CB = ceil_div(C, kCBlock);
     p.Kp = ceil_div(K, kFilterPad) * kFilterPad;
+    p.div_tw = make_fast_div((uint32_t)p.TW);
+    p.div_th = make_fast_div((uint32_t)p.TH);
     return p;
 }
 

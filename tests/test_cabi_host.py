@@ -130,3 +130,22 @@ def test_vgg_shift_constants_match_the_generated_fixture():
     with open(os.path.join(ROOT, "tests", "golden", "vgg16_shifts.txt")) as f:
         line = [l for l in f if not l.startswith("#")][0]
     assert [int(t) for t in line.split()] == wl.VGG16_SHIFTS
+
+
+def test_tile_decode_by_multiply_and_shift_matches_division(lib):
+    """The kernels split a tile index with precomputed multiply-and-shift constants; compare with divmod
+    over awkward tile grids, at the ends of every row and image."""
+    out = (ctypes.c_int * 3)()
+    shapes = [(1, 1, 1), (3, 4, 4), (5, 9, 7), (2, 56, 56), (16, 224, 224), (7, 13, 1021), (4000, 29, 31),
+              (1, 4093, 4099), (65536, 8, 8)]
+    for N, H, W in shapes:
+        TH, TW = (H + 3) // 4, (W + 3) // 4
+        T = N * TH * TW
+        picks = {0, T - 1, T // 2, TW - 1, TW, TH * TW - 1, TH * TW, T - TW, max(0, T - TH * TW - 1)}
+        picks |= {(i * 2654435761) % T for i in range(200)}
+        for t in sorted(x for x in picks if 0 <= x < T):
+            assert lib.winograd_debug_tile_decode(N, 4, H, W, 4, t, out) == 0
+            n, rem = divmod(t, TH * TW)
+            ty, tx = divmod(rem, TW)
+            assert (out[0], out[1], out[2]) == (n, ty, tx), (N, H, W, t)
+    assert lib.winograd_debug_tile_decode(1, 4, 8, 8, 4, 4, out) == EINVAL      # only 4 tiles
