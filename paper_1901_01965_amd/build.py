@@ -12,6 +12,9 @@ LIB_PATH = os.path.join(LIB_DIR, "libwinograd_mi355x.so")
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # keep matrix-core results in ordinary vector registers where they fit: the vector ALU reads
+    # them right away (limb joins, output transform) and would otherwise pay one copy per register
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-Wall", "-Wno-unused-function",
 ]
 

@@ -234,7 +234,7 @@ int winograd_debug_contraction(const int8_t* x_dev, const void* packed_dev, int3
     int32_t* M = reinterpret_cast<int32_t*>(static_cast<uint8_t*>(workspace_dev) + wl.m_off);
     if (int st = status_of(launch_input_transform(x_dev, p, layout, mode, V, s))) return st;
     if (int st = status_of(launch_contraction(V, packed_dev, M, p, mode, s))) return st;
-    return status_of(launch_unpack_accumulators(M, m_dev, p, s));
+    return status_of(launch_unpack_accumulators(M, m_dev, p, mode, s));
 }
 
 }  // extern "C"

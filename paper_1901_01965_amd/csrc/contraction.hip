@@ -1,19 +1,18 @@
-// Winograd-domain contraction M[e][t][k] = sum_c W[e][k][c] * D[e][t][c] at the 26
-// free entries (Section 3.4): 16 real and 10 complex products per tile and
-// channel pair, each complex one by the three-multiplication rule of Section
-// 3.1, with the partial products kept apart until the channel sum is complete.
-// Every real product of two 12-bit operands is three int8 matrix-core products
-// (limb-level Karatsuba, Section 3.1), accumulated in int32 and recombined once.
-// In scaled mode (Section 4.2) the filters are single int8 limbs and the
-// reciprocal r/2^q is applied to the finished sums.
+// Winograd-domain contraction (Section 3.4): for every free entry of the transformed
+// tile, the product of the transformed filter and activation summed over input
+// channels, on the int8 matrix cores.  The work is cut into uniform units (see
+// subproducts.h): lossless mode keeps the paper's three-multiplication forms
+// (46 real 12-bit products, each as three int8 limb products); scaled mode
+// (Section 4.2) uses single-limb filters and applies the reciprocal r/2^q to the
+// finished sums.
 //
-// One workgroup owns one entry and a 128-tile x 128-filter block of it.  Each of
-// the entry's sub-products is a [128 x C] x [C x 128] int8 GEMM.  Operand blocks
-// of 64 channels travel from L2 straight into a four-stage LDS ring
-// (global_load_lds_dwordx4, no register staging), three stages ahead of the
+// One workgroup owns one unit and a 128-tile x 128-filter block of it.  Each of
+// the unit's sub-products is a [128 x C] x [C x 128] int8 GEMM.  Operand blocks
+// of 64 channels travel from L2 straight into a six-stage LDS ring
+// (global_load_lds_dwordx4, no register staging), several stages ahead of the
 // matrix cores; every wave keeps a 64x64 block of v_mfma_i32_32x32x32_i8
-// accumulators; the finished channel sum is folded into Re/Im with the
-// sub-product's integer weights.
+// accumulators; the finished channel sum is folded into the unit's output with
+// the sub-product's integer weight.
 #include "subproducts.h"
 
 namespace wg {
@@ -25,8 +24,8 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int kBlockTiles = 128, kBlockFilters = 128;
 constexpr int kOperandBytes = 128 * kCBlock;        // one staged operand block: 128 rows x 64 bytes
 constexpr int kStageBytes = 2 * kOperandBytes;      // activations + filters
-constexpr int kStages = 4;
-constexpr int kContractionLds = kStages * kStageBytes;   // 64 KB
+constexpr int kStages = 6;
+constexpr int kContractionLds = kStages * kStageBytes;   // 96 KB
 
 // A staged row keeps its 64 bytes but stores 16-byte chunk c at position c ^ swizzle(row), which
 // spreads the fragment reads of 16 consecutive rows over all banks.  The permutation is applied
@@ -71,36 +70,57 @@ struct BlockLoader {
     }
 };
 
-// 64 channels of one staged block into the wave's 2x2 accumulators.  a_row/b_row: byte offset of
-// this lane's row (lane % 32) in each operand block; sw = swizzle of that row (the same for the
-// row 32 further on); half = lane / 32 selects the 16-byte half of a 32-channel step.
-template <bool FIRST>
-__device__ inline void mma_block(const int8_t* stage, int a_row, int b_row, int sw_a, int sw_b, int half,
-                                 v16i (&acc)[2][2]) {
+// Fragments of one 32-channel step (ks = 0, 1) of a staged block: two activation and two filter
+// fragments.  a_row/b_row: byte offset of this lane's row (lane % 32) in each operand block; sw =
+// swizzle of that row (the same for the row 32 further on); half = lane / 32 selects the 16-byte
+// half of the step.
+struct Frags {
+    v4i a[2], b[2];
+};
+__device__ inline void read_frags(Frags& f, const int8_t* stage, int ks, int a_row, int b_row, int sw_a, int sw_b,
+                                  int half) {
+    const int ca = ((2 * ks + half) ^ sw_a) * 16, cb = ((2 * ks + half) ^ sw_b) * 16;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-        v4i a[2], b[2];
-        const int ca = ((2 * ks + half) ^ sw_a) * 16, cbb = ((2 * ks + half) ^ sw_b) * 16;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            a[i] = *reinterpret_cast<const v4i*>(stage + a_row + i * 32 * kCBlock + ca);
-            b[i] = *reinterpret_cast<const v4i*>(stage + kOperandBytes + b_row + i * 32 * kCBlock + cbb);
-        }
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                if (FIRST && ks == 0) {
-                    constexpr v16i zero = {0};
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], zero, 0, 0, 0);
-                } else {
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
-                }
-            }
+    for (int i = 0; i < 2; ++i) {
+        f.a[i] = *reinterpret_cast<const v4i*>(stage + a_row + i * 32 * kCBlock + ca);
+        f.b[i] = *reinterpret_cast<const v4i*>(stage + kOperandBytes + b_row + i * 32 * kCBlock + cb);
     }
 }
+template <bool ZERO>
+__device__ inline void multiply(const Frags& f, v16i (&acc)[2][2]) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            if (ZERO) {
+                constexpr v16i zero = {0};
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.a[i], f.b[j], zero, 0, 0, 0);
+            } else {
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+            }
+        }
+}
 
-// grid: (ceil(T/128), ceil(K/128), 26 entries), complex entries (nine sub-products) first.
+// Which units each of the eight XCDs works on.  Workgroups are handed to the XCDs round-robin
+// by linear index, and every XCD has its own L2: all blocks of one unit are therefore given to
+// one XCD, back to back, so that an activation block (shared by the filter blocks of its row)
+// and a filter block (shared by the tile blocks of its column) can hit in that L2.  Lossless
+// units all cost the same (unit = xcd + 8 i).  Scaled units cost 2 (real) or 4 (complex part)
+// sub-products: XCDs 0-3 take three complex parts and one real, XCDs 4-7 two and three.
+constexpr int kXcds = 8;
+template <int MODE> constexpr int units_per_xcd() { return MODE == WG_LOSSLESS ? 6 : 5; }
+template <int MODE>
+__device__ inline int unit_of(int xcd, int i) {
+    if (MODE == WG_LOSSLESS) {
+        const int u = xcd + kXcds * i;
+        return u < num_units<MODE>() ? u : -1;
+    }
+    if (xcd < 4) return i < 3 ? kRealEntries + 4 * i + xcd : (i == 3 ? xcd : -1);
+    const int x = xcd - 4;
+    return i < 2 ? kRealEntries + 12 + 2 * x + i : 4 + 3 * x + (i - 2);
+}
+
+// grid: 8 XCDs x units per XCD x (tile blocks x filter blocks), one dimension.
 template <int MODE>
 __global__ __launch_bounds__(256) void contraction_kernel(const int8_t* __restrict__ V,
                                                           const uint8_t* __restrict__ blob,
@@ -108,9 +128,14 @@ __global__ __launch_bounds__(256) void contraction_kernel(const int8_t* __restri
                                                           int32_t* __restrict__ M, Problem p) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     if (!blob_matches(reinterpret_cast<const BlobHeader*>(blob), p.K, p.C, MODE)) return;
-    const int entry = kEntries - 1 - (int)blockIdx.z;
+    const int tile_blocks = (p.T + kBlockTiles - 1) / kBlockTiles;
+    const int blocks_per_unit = tile_blocks * ((p.K + kBlockFilters - 1) / kBlockFilters);
+    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    const int unit = unit_of<MODE>(xcd, slot / blocks_per_unit);
+    if (unit < 0) return;
+    const int within = slot % blocks_per_unit;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int t0 = blockIdx.x * kBlockTiles, k0 = blockIdx.y * kBlockFilters;
+    const int t0 = (within % tile_blocks) * kBlockTiles, k0 = (within / tile_blocks) * kBlockFilters;
     const int wm = wave & 1, wn = wave >> 1;
 
     BlockLoader<MODE> loader;
@@ -118,38 +143,60 @@ __global__ __launch_bounds__(256) void contraction_kernel(const int8_t* __restri
     const int a_row = (wm * 64 + (lane & 31)) * kCBlock, b_row = (wn * 64 + (lane & 31)) * kCBlock;
     const int sw_a = swizzle(wm * 64 + (lane & 31)), sw_b = swizzle(wn * 64 + (lane & 31)), half = lane >> 5;
 
-    v16i re[2][2], im[2][2], acc[2][2];
+    v16i out[2][2], acc[2][2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) { re[i][j] = (v16i){0}; im[i][j] = (v16i){0}; }
+        for (int j = 0; j < 2; ++j) out[i][j] = (v16i){0};
 
-    const int nsub = entry < kRealEntries ? num_subproducts<MODE>(0) : num_subproducts<MODE>(kRealEntries);
+    const int nsub = num_subproducts<MODE>(unit);
     const int total = nsub * p.CB;
-    // stage f of the stream = (sub-product f / CB, channel block f % CB); fill the first three
+    // stage f of the stream = (sub-product f / CB, channel block f % CB)
     int fs = 0, fcb = 0;   // sub-product and channel block of the next stage to request
     auto request = [&](int f) {
-        const SubProduct sp = subproduct<MODE>(entry, fs);
+        const SubProduct sp = subproduct<MODE>(unit, fs);
         loader.issue(lds + (f % kStages) * kStageBytes, sp.a_plane, sp.b_plane, fcb);
         if (++fcb == p.CB) { fcb = 0; ++fs; }
     };
     for (int f = 0; f < kStages - 1; ++f) {
         if (f < total) request(f);
     }
+    // stage f has landed once at most the requests of the (up to kStages-2) stages after it are
+    // pending; every request is four load instructions per wave
+    auto wait_stage = [&](int f) {
+        switch (min(total - 1 - f, kStages - 2)) {
+            case 4:  asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); break;
+            case 3:  asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
+            case 2:  asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+            case 1:  asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+            default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+        }
+    };
+    static_assert(kStages == 6, "wait_stage covers up to four later stages");
+    // Per stage: the fragments of its second 32-channel step are read while the first step is
+    // multiplied, and the next stage's first fragments while the second step is multiplied, so
+    // LDS traffic overlaps the matrix cores instead of alternating with them.
+    Frags f0, f1;
+    wait_stage(0);
+    __builtin_amdgcn_s_barrier();
+    if (kStages - 1 < total) request(kStages - 1);
+    read_frags(f0, lds, 0, a_row, b_row, sw_a, sw_b, half);
     int it = 0;
     for (int s = 0; s < nsub; ++s) {
-        const SubProduct sp = subproduct<MODE>(entry, s);
+        const SubProduct sp = subproduct<MODE>(unit, s);
         for (int cb = 0; cb < p.CB; ++cb, ++it) {
-            // stage `it` has landed once at most the requests of the stages after it are pending
-            const int later = min(total - 1 - it, kStages - 2);
-            if (later >= 2)      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-            else if (later == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-            else                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __builtin_amdgcn_s_barrier();   // all parts of stage `it` are in LDS; stage it-1 is no longer read
-            if (it + kStages - 1 < total) request(it + kStages - 1);
             const int8_t* stage = lds + (it % kStages) * kStageBytes;
-            if (cb == 0) mma_block<true>(stage, a_row, b_row, sw_a, sw_b, half, acc);
-            else         mma_block<false>(stage, a_row, b_row, sw_a, sw_b, half, acc);
+            read_frags(f1, stage, 1, a_row, b_row, sw_a, sw_b, half);
+            if (cb == 0) multiply<true>(f0, acc); else multiply<false>(f0, acc);
+            if (it + 1 < total) {
+                wait_stage(it + 1);
+                // f1 has arrived; after the barrier nobody reads stage `it` or earlier any more
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                if (it + kStages < total) request(it + kStages);
+                read_frags(f0, lds + ((it + 1) % kStages) * kStageBytes, 0, a_row, b_row, sw_a, sw_b, half);
+            }
+            multiply<false>(f1, acc);
         }
         // |acc| <= 94*94*896 < 2^23: the 24-bit multiply-add is exact modulo 2^32
 #pragma unroll
@@ -157,50 +204,52 @@ __global__ __launch_bounds__(256) void contraction_kernel(const int8_t* __restri
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    re[i][j][r] += __mul24(acc[i][j][r], sp.w_re);
-                    im[i][j][r] += __mul24(acc[i][j][r], sp.w_im);
-                }
+                for (int r = 0; r < 16; ++r) out[i][j][r] += __mul24(acc[i][j][r], sp.weight);
     }
 
-    const int plane_re = entry < kRealEntries ? entry : kRealEntries + 2 * (entry - kRealEntries);
-    const size_t plane = (size_t)p.Tp * p.Kp;
+    int32_t* Mu = M + (size_t)unit * p.Tp * p.Kp;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int k = k0 + wn * 64 + j * 32 + (lane & 31);
+        if (k >= p.K) continue;
         ScaleEntry se = {0, 0, 1, 0};
-        if (MODE == WG_SCALED && k < p.Kp)
-            se = reinterpret_cast<const ScaleEntry*>(blob + table_off)[(size_t)k * kEntries + entry];
+        if (MODE == WG_SCALED)
+            se = reinterpret_cast<const ScaleEntry*>(blob + table_off)[(size_t)k * kEntries + unit_entry<MODE>(unit)];
         const long long rnd = se.q > 0 ? (1ll << (se.q - 1)) : 0ll;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
+            const int tb = t0 + wm * 64 + i * 32 + 4 * (lane >> 5);
+            int32_t* m = Mu + (size_t)tb * p.Kp + k;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                int vr = re[i][j][r], vi = im[i][j][r];
-                if (MODE == WG_SCALED && se.n != 0) {
-                    // reverse scaling (Section 4.2): (m * r + 2^(q-1)) >> q, 64-bit intermediate
-                    vr = (int)(((long long)vr * se.r + rnd) >> se.q);
-                    vi = (int)(((long long)vi * se.r + rnd) >> se.q);
-                }
-                const int t = t0 + wm * 64 + i * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
-                if (t < p.T && k < p.K) {
-                    int32_t* m = M + plane_re * plane + (size_t)t * p.Kp + k;
-                    m[0] = vr;
-                    if (entry >= kRealEntries) m[plane] = vi;
-                }
+                int v = out[i][j][r];
+                // reverse scaling (Section 4.2): (m * r + 2^(q-1)) >> q, 64-bit intermediate
+                if (MODE == WG_SCALED && se.n != 0) v = (int)(((long long)v * se.r + rnd) >> se.q);
+                const int dt = 8 * (r / 4) + (r % 4);
+                if (tb + dt < p.T) m[dt * p.Kp] = v;
             }
         }
     }
 }
 
-__global__ void unpack_accumulators_kernel(const int32_t* M, int32_t* dense, Problem p) {
+// The 36 planes the output transform is defined on (real entry p: p; complex entry j:
+// 16 + 2j + {Re, Im}) from the workspace planes: lossless Re = P1 - P2, Im = P3 - P1 - P2.
+__device__ inline int accumulator_plane(const int32_t* M, size_t plane_stride, size_t at, int mode, int pl) {
+    if (mode != WG_LOSSLESS || pl < kRealEntries) return M[pl * plane_stride + at];
+    const int j = (pl - kRealEntries) >> 1;
+    const int32_t* P = M + (size_t)(kRealEntries + 3 * j) * plane_stride + at;
+    const int p1 = P[0], p2 = P[plane_stride], p3 = P[2 * plane_stride];
+    return ((pl - kRealEntries) & 1) ? p3 - p1 - p2 : p1 - p2;
+}
+
+__global__ void unpack_accumulators_kernel(const int32_t* M, int32_t* dense, Problem p, int mode) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t total = (size_t)kAccPlanes * p.T * p.K;
     if (i >= total) return;
     int k = (int)(i % p.K);
     int t = (int)((i / p.K) % p.T);
     int pl = (int)(i / ((size_t)p.K * p.T));
-    dense[i] = M[((size_t)pl * p.Tp + t) * p.Kp + k];
+    dense[i] = accumulator_plane(M, (size_t)p.Tp * p.Kp, (size_t)t * p.Kp + k, mode, pl);
 }
 
 template <int MODE>
@@ -220,7 +269,8 @@ hipError_t launch_contraction(const int8_t* V, const void* blob, int32_t* M, con
     if (hipError_t e = mode == WG_LOSSLESS ? configure_contraction<WG_LOSSLESS>() : configure_contraction<WG_SCALED>())
         return e;
     const BlobLayout bl = blob_layout(p.Kp, p.CB, mode);
-    dim3 grid(ceil_div(p.T, kBlockTiles), ceil_div(p.K, kBlockFilters), kEntries);
+    const unsigned blocks = ceil_div(p.T, kBlockTiles) * ceil_div(p.K, kBlockFilters);
+    const unsigned grid = kXcds * (mode == WG_LOSSLESS ? units_per_xcd<WG_LOSSLESS>() : units_per_xcd<WG_SCALED>()) * blocks;
     const uint8_t* b = static_cast<const uint8_t*>(blob);
     if (mode == WG_LOSSLESS)
         contraction_kernel<WG_LOSSLESS><<<grid, 256, kContractionLds, s>>>(V, b, bl.table_off, bl.planes_off, M, p);
@@ -229,9 +279,9 @@ hipError_t launch_contraction(const int8_t* V, const void* blob, int32_t* M, con
     return hipGetLastError();
 }
 
-hipError_t launch_unpack_accumulators(const int32_t* M, int32_t* dense, const Problem& p, hipStream_t s) {
+hipError_t launch_unpack_accumulators(const int32_t* M, int32_t* dense, const Problem& p, int mode, hipStream_t s) {
     size_t total = (size_t)kAccPlanes * p.T * p.K;
-    unpack_accumulators_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(M, dense, p);
+    unpack_accumulators_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(M, dense, p, mode);
     return hipGetLastError();
 }
 

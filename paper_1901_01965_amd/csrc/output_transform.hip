@@ -35,8 +35,16 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const int32_t* __
     for (int e = 0; e < 16; ++e) re[e] = m[e * plane];
 #pragma unroll
     for (int j = 0; j < 10; ++j) {
-        cr[j] = m[(16 + 2 * j) * plane];
-        ci[j] = m[(17 + 2 * j) * plane];
+        if (MODE == WG_LOSSLESS) {
+            // the contraction keeps the three real products of a complex entry apart (Section 3.4);
+            // Re = P1 - P2, Im = P3 - P1 - P2 (Section 3.1), formed here after the channel sum
+            const int p1 = m[(16 + 3 * j) * plane], p2 = m[(17 + 3 * j) * plane], p3 = m[(18 + 3 * j) * plane];
+            cr[j] = p1 - p2;
+            ci[j] = p3 - p1 - p2;
+        } else {
+            cr[j] = m[(16 + 2 * j) * plane];
+            ci[j] = m[(17 + 2 * j) * plane];
+        }
     }
 
     // Z = M A: rows 0,1,2,5 are real; row 3 is complex (row 4 is its conjugate)

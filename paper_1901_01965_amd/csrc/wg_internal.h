@@ -16,7 +16,8 @@ constexpr int kTilePad = 64;     // tile count is padded to a multiple of this
 constexpr int kFilterPad = 64;   // filter count is padded to a multiple of this
 constexpr int kEntries = 26;     // free entries of a transformed 6x6 tile (Section 3.4)
 constexpr int kRealEntries = 16;
-constexpr int kAccPlanes = 36;   // 16 real + 10 * (Re, Im)
+constexpr int kAccPlanes = 36;   // 16 real + 10 * (Re, Im): the planes the output transform consumes
+constexpr int kMaxWorkspacePlanes = 46;   // lossless keeps the three products of a complex entry apart
 constexpr int kWeightRange = 127;  // spatial range of signed int8 filters, the target of the scaling
 
 // Division of a 31-bit unsigned n by a fixed divisor d as one high multiply and a shift:
@@ -116,7 +117,7 @@ inline BlobLayout blob_layout(int Kp, int CB, int mode) {
 }
 
 // ---- workspace ------------------------------------------------------------------
-// [V: int8 [planes][CB][Tp][64]][M: int32 [36][Tp][Kp]]
+// [V: int8 [planes][CB][Tp][64]][M: int32 [46 lossless | 36 scaled][Tp][Kp]]
 struct WorkspaceLayout {
     size_t v_off, m_off, total;
 };
@@ -124,7 +125,7 @@ inline WorkspaceLayout workspace_layout(const Problem& p, int mode) {
     WorkspaceLayout w;
     w.v_off = 0;
     w.m_off = round_up((size_t)num_activation_planes(mode) * p.CB * p.Tp * kCBlock, 256);
-    w.total = w.m_off + (size_t)kAccPlanes * p.Tp * p.Kp * sizeof(int32_t);
+    w.total = w.m_off + (size_t)(mode == WG_LOSSLESS ? kMaxWorkspacePlanes : kAccPlanes) * p.Tp * p.Kp * sizeof(int32_t);
     return w;
 }
 
@@ -150,7 +151,7 @@ hipError_t launch_unpack_activation_planes(const int8_t* V, int8_t* dense, const
                                            hipStream_t s);
 hipError_t launch_unpack_filter_planes(const void* blob, int8_t* dense, int32_t* table, int K, int C,
                                        int mode, hipStream_t s);
-hipError_t launch_unpack_accumulators(const int32_t* M, int32_t* dense, const Problem& p,
+hipError_t launch_unpack_accumulators(const int32_t* M, int32_t* dense, const Problem& p, int mode,
                                       hipStream_t s);
 
 // True on the device when the blob header matches; kernels that consume a blob
