@@ -70,35 +70,45 @@ struct BlockLoader {
     }
 };
 
-// Fragments of one 32-channel step (ks = 0, 1) of a staged block: two activation and two filter
-// fragments.  a_row/b_row: byte offset of this lane's row (lane % 32) in each operand block; sw =
-// swizzle of that row (the same for the row 32 further on); half = lane / 32 selects the 16-byte
-// half of the step.
+// Fragments of one staged block for one multiplying wave: for each of the two 32-channel steps,
+// two activation and two filter fragments.  a_row/b_row: byte offset of this lane's row
+// (lane % 32) in each operand block; sw = swizzle of that row (the same for the row 32 further
+// on); half = lane / 32 selects the 16-byte half of a step.
 struct Frags {
-    v4i a[2], b[2];
+    v4i a[2][2], b[2][2];   // [step][fragment]
 };
-__device__ inline void read_frags(Frags& f, const int8_t* stage, int ks, int a_row, int b_row, int sw_a, int sw_b,
-                                  int half) {
-    const int ca = ((2 * ks + half) ^ sw_a) * 16, cb = ((2 * ks + half) ^ sw_b) * 16;
+__device__ inline void read_frags(Frags& f, const int8_t* stage, int a_row, int b_row, int sw_a, int sw_b, int half) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        f.a[i] = *reinterpret_cast<const v4i*>(stage + a_row + i * 32 * kCBlock + ca);
-        f.b[i] = *reinterpret_cast<const v4i*>(stage + kOperandBytes + b_row + i * 32 * kCBlock + cb);
+    for (int ks = 0; ks < 2; ++ks) {
+        const int ca = ((2 * ks + half) ^ sw_a) * 16, cb = ((2 * ks + half) ^ sw_b) * 16;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            f.a[ks][i] = *reinterpret_cast<const v4i*>(stage + a_row + i * 32 * kCBlock + ca);
+            f.b[ks][i] = *reinterpret_cast<const v4i*>(stage + kOperandBytes + b_row + i * 32 * kCBlock + cb);
+        }
     }
 }
-template <bool ZERO>
-__device__ inline void multiply(const Frags& f, v16i (&acc)[2][2]) {
+__device__ inline void multiply(const Frags& f, v16i (&acc)[2][2], bool zero) {
+    if (zero) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                constexpr v16i z = {0};
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.a[0][i], f.b[0][j], z, 0, 0, 0);
+            }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.a[0][i], f.b[0][j], acc[i][j], 0, 0, 0);
+    }
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            if (ZERO) {
-                constexpr v16i zero = {0};
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.a[i], f.b[j], zero, 0, 0, 0);
-            } else {
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
-            }
-        }
+        for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.a[1][i], f.b[1][j], acc[i][j], 0, 0, 0);
 }
 
 // Which units each of the eight XCDs works on.  Workgroups are handed to the XCDs round-robin
@@ -120,9 +130,18 @@ __device__ inline int unit_of(int xcd, int i) {
     return i < 2 ? kRealEntries + 12 + 2 * x + i : 4 + 3 * x + (i - 2);
 }
 
-// grid: 8 XCDs x units per XCD x (tile blocks x filter blocks), one dimension.
+// grid: 8 XCDs x units per XCD x (tile blocks x filter blocks), one dimension.  512 threads:
+// waves 0-3 multiply (one per SIMD, each a 64x64 quadrant of the block), waves 4-7 only move
+// operands.  A wave issues in order, and a vector-memory instruction stalls at issue while the
+// memory pipeline is full; keeping the loads in waves of their own lets the matrix-core
+// instructions of the other wave on the same SIMD issue meanwhile.
+//
+// Stage f of a unit's stream = (sub-product f / CB, channel block f % CB); it lives in ring slot
+// f % kStages.  Both roles pass one barrier per stage: barrier f tells the multiplying waves
+// that stage f has landed, and the loading waves that the reads of stage f-1 are complete, so
+// that its slot can take stage f + kStages - 1.
 template <int MODE>
-__global__ __launch_bounds__(256) void contraction_kernel(const int8_t* __restrict__ V,
+__global__ __launch_bounds__(512) void contraction_kernel(const int8_t* __restrict__ V,
                                                           const uint8_t* __restrict__ blob,
                                                           size_t table_off, size_t planes_off,
                                                           int32_t* __restrict__ M, Problem p) {
@@ -136,10 +155,39 @@ __global__ __launch_bounds__(256) void contraction_kernel(const int8_t* __restri
     const int within = slot % blocks_per_unit;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int t0 = (within % tile_blocks) * kBlockTiles, k0 = (within / tile_blocks) * kBlockFilters;
-    const int wm = wave & 1, wn = wave >> 1;
+    const int nsub = num_subproducts<MODE>(unit);
+    const int total = nsub * p.CB;
 
-    BlockLoader<MODE> loader;
-    loader.init(V, reinterpret_cast<const int8_t*>(blob + planes_off), p, t0, k0, wave, lane);
+    if (wave >= 4) {
+        BlockLoader<MODE> loader;
+        loader.init(V, reinterpret_cast<const int8_t*>(blob + planes_off), p, t0, k0, wave - 4, lane);
+        int fs = 0, fcb = 0;   // sub-product and channel block of the next stage to request
+        auto request = [&](int f) {
+            const SubProduct sp = subproduct<MODE>(unit, fs);
+            loader.issue(lds + (f % kStages) * kStageBytes, sp.a_plane, sp.b_plane, fcb);
+            if (++fcb == p.CB) { fcb = 0; ++fs; }
+        };
+        for (int f = 0; f < kStages - 1; ++f) {
+            if (f < total) request(f);
+        }
+        static_assert(kStages == 6, "the wait below covers up to four later stages");
+        for (int f = 0; f < total; ++f) {
+            // stage f has landed once only the requests of the (up to four) stages after it are
+            // pending; every request is four load instructions per wave
+            switch (min(total - 1 - f, kStages - 2)) {
+                case 4:  asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); break;
+                case 3:  asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
+                case 2:  asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+                case 1:  asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+                default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+            }
+            __builtin_amdgcn_s_barrier();
+            if (f + kStages - 1 < total) request(f + kStages - 1);
+        }
+        return;
+    }
+
+    const int wm = wave & 1, wn = wave >> 1;
     const int a_row = (wm * 64 + (lane & 31)) * kCBlock, b_row = (wn * 64 + (lane & 31)) * kCBlock;
     const int sw_a = swizzle(wm * 64 + (lane & 31)), sw_b = swizzle(wn * 64 + (lane & 31)), half = lane >> 5;
 
@@ -149,62 +197,50 @@ __global__ __launch_bounds__(256) void contraction_kernel(const int8_t* __restri
 #pragma unroll
         for (int j = 0; j < 2; ++j) out[i][j] = (v16i){0};
 
-    const int nsub = num_subproducts<MODE>(unit);
-    const int total = nsub * p.CB;
-    // stage f of the stream = (sub-product f / CB, channel block f % CB)
-    int fs = 0, fcb = 0;   // sub-product and channel block of the next stage to request
-    auto request = [&](int f) {
-        const SubProduct sp = subproduct<MODE>(unit, fs);
-        loader.issue(lds + (f % kStages) * kStageBytes, sp.a_plane, sp.b_plane, fcb);
-        if (++fcb == p.CB) { fcb = 0; ++fs; }
-    };
-    for (int f = 0; f < kStages - 1; ++f) {
-        if (f < total) request(f);
-    }
-    // stage f has landed once at most the requests of the (up to kStages-2) stages after it are
-    // pending; every request is four load instructions per wave
-    auto wait_stage = [&](int f) {
-        switch (min(total - 1 - f, kStages - 2)) {
-            case 4:  asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); break;
-            case 3:  asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
-            case 2:  asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
-            case 1:  asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
-            default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
-        }
-    };
-    static_assert(kStages == 6, "wait_stage covers up to four later stages");
-    // Per stage: the fragments of its second 32-channel step are read while the first step is
-    // multiplied, and the next stage's first fragments while the second step is multiplied, so
-    // LDS traffic overlaps the matrix cores instead of alternating with them.
-    Frags f0, f1;
-    wait_stage(0);
-    __builtin_amdgcn_s_barrier();
-    if (kStages - 1 < total) request(kStages - 1);
-    read_frags(f0, lds, 0, a_row, b_row, sw_a, sw_b, half);
-    int it = 0;
-    for (int s = 0; s < nsub; ++s) {
-        const SubProduct sp = subproduct<MODE>(unit, s);
-        for (int cb = 0; cb < p.CB; ++cb, ++it) {
-            const int8_t* stage = lds + (it % kStages) * kStageBytes;
-            read_frags(f1, stage, 1, a_row, b_row, sw_a, sw_b, half);
-            if (cb == 0) multiply<true>(f0, acc); else multiply<false>(f0, acc);
-            if (it + 1 < total) {
-                wait_stage(it + 1);
-                // f1 has arrived; after the barrier nobody reads stage `it` or earlier any more
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                __builtin_amdgcn_s_barrier();
-                if (it + kStages < total) request(it + kStages);
-                read_frags(f0, lds + ((it + 1) % kStages) * kStageBytes, 0, a_row, b_row, sw_a, sw_b, half);
+    // Consecutive sub-products of equal weight share one channel sum; it is folded into the
+    // unit's output when the weight changes.  Lossless: every sub-product has its own weight and
+    // |acc| <= 94 * 94 * 896 < 2^23, so a 24-bit multiply-add is exact modulo 2^32.  Scaled: the
+    // weights are 64 and 1, a shift.
+    int fs = 0, fcb = 0;       // sub-product and channel block of the stage being multiplied
+    bool zero = true;
+    auto multiply_stage = [&](const Frags& f) {
+        multiply(f, acc, zero);
+        zero = false;
+        if (++fcb == p.CB) {
+            fcb = 0;
+            const int w = subproduct<MODE>(unit, fs).weight;
+            ++fs;
+            if (fs == nsub || subproduct<MODE>(unit, fs).weight != w) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            out[i][j][r] += MODE == WG_LOSSLESS ? __mul24(acc[i][j][r], w) : acc[i][j][r] << (w == 64 ? 6 : 0);
+                zero = true;
             }
-            multiply<false>(f1, acc);
         }
-        // |acc| <= 94*94*896 < 2^23: the 24-bit multiply-add is exact modulo 2^32
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) out[i][j][r] += __mul24(acc[i][j][r], sp.weight);
+    };
+    // The fragments of stage f+1 are requested from LDS right after barrier f+1 and before the
+    // matrix-core instructions of stage f are issued, so LDS latency hides behind them.
+    Frags fa, fb;
+    __builtin_amdgcn_s_barrier();   // barrier 0
+    read_frags(fa, lds, a_row, b_row, sw_a, sw_b, half);
+    for (int f = 0; f < total; f += 2) {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // fa (stage f) is in registers
+        if (f + 1 < total) {
+            __builtin_amdgcn_s_barrier();
+            read_frags(fb, lds + ((f + 1) % kStages) * kStageBytes, a_row, b_row, sw_a, sw_b, half);
+        }
+        multiply_stage(fa);
+        if (f + 1 >= total) break;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // fb (stage f+1) is in registers
+        if (f + 2 < total) {
+            __builtin_amdgcn_s_barrier();
+            read_frags(fa, lds + ((f + 2) % kStages) * kStageBytes, a_row, b_row, sw_a, sw_b, half);
+        }
+        multiply_stage(fb);
     }
 
     int32_t* Mu = M + (size_t)unit * p.Tp * p.Kp;
@@ -273,9 +309,9 @@ hipError_t launch_contraction(const int8_t* V, const void* blob, int32_t* M, con
     const unsigned grid = kXcds * (mode == WG_LOSSLESS ? units_per_xcd<WG_LOSSLESS>() : units_per_xcd<WG_SCALED>()) * blocks;
     const uint8_t* b = static_cast<const uint8_t*>(blob);
     if (mode == WG_LOSSLESS)
-        contraction_kernel<WG_LOSSLESS><<<grid, 256, kContractionLds, s>>>(V, b, bl.table_off, bl.planes_off, M, p);
+        contraction_kernel<WG_LOSSLESS><<<grid, 512, kContractionLds, s>>>(V, b, bl.table_off, bl.planes_off, M, p);
     else
-        contraction_kernel<WG_SCALED><<<grid, 256, kContractionLds, s>>>(V, b, bl.table_off, bl.planes_off, M, p);
+        contraction_kernel<WG_SCALED><<<grid, 512, kContractionLds, s>>>(V, b, bl.table_off, bl.planes_off, M, p);
     return hipGetLastError();
 }
 
