@@ -33,6 +33,15 @@ constexpr int kFusedPlanes = 72;    // two-limb activation planes (kSplitTwoLimb
 constexpr int kPlaneBytes = kFusedTiles * kCBlock;   // one operand plane of the tile block in LDS
 constexpr int kLdsBytes = kFusedPlanes * kPlaneBytes;
 constexpr int kParkBytes = 4 * 16 * 64 * 16;         // four waves x 16 outputs x 64 lanes x 4 registers
+// How the activation patch reaches the transform threads (chosen on the host):
+//   kLoadBytes:  one byte per load, any layout and channel count;
+//   kLoadDwords: channels-last, C a multiple of 4: one 4-byte load per pixel and thread;
+//   kLoadDirect: channels-last, C a multiple of 16, 16-byte aligned input: 16-byte pieces travel
+//                from global memory straight into LDS (nine instructions per wave instead of
+//                thirty-six), and the threads pick their four channels from there.
+constexpr int kLoadBytes = 0, kLoadDwords = 1, kLoadDirect = 2;
+constexpr int kRawWaveBytes = 4 * 36 * kCBlock;      // raw patches of a wave's four tiles: 36 pixels x 64 channels
+constexpr int kRawBytes = 4 * kRawWaveBytes;
 static_assert(kParkBytes <= kLdsBytes, "output staging reuses the operand planes' LDS");
 
 // LDS operand plane: the 16-byte piece holding 16 consecutive channels (group c16) of a tile
@@ -187,6 +196,42 @@ __device__ inline void finish_row(const v4i (&er)[6], const v4i (&ei)[6], v4i (&
     }
 }
 
+// Direct global -> LDS transfer of the raw 6x6 patches of a wave's four tiles (one 64-channel
+// block).  Instruction i (0..8) moves pixels 4i..4i+3 of the patch (pixel = 6 a + b): lane l
+// carries 16 channels (piece l % 4) of tile (l % 16) / 4 at pixel 4i + l / 16, and the hardware
+// puts lane l's piece at (wave-uniform destination) + 16 l.  The raw area of a wave is therefore
+// [pixel][tile][64 channels], and transform thread (tile, channel quad) = lane reads its pixel
+// p at p * 256 + 4 * lane: a wave reads 256 contiguous bytes.
+struct DirectPatch {
+    uint32_t pixel_off[9];   // byte offset of this lane's pixel (channel 0) for each instruction
+    __device__ inline void init(const Problem& p, int n, int ty, int tx, int lane) {
+        const int h0 = 4 * ty - 1, w0 = 4 * tx - 1;
+#pragma unroll
+        for (int i = 0; i < 9; ++i) {
+            const int pix = 4 * i + (lane >> 4);
+            const int a = (pix * 43) >> 8, b = pix - 6 * a;   // pix / 6, pix % 6 for pix < 36
+            const int h = min(max(h0 + a, 0), p.H - 1), w = min(max(w0 + b, 0), p.W - 1);
+            pixel_off[i] = (uint32_t)(((n * p.H + h) * p.W + w) * p.C);
+        }
+    }
+    // Pieces beyond C (the last channel block of a C that is not a multiple of 64) re-read
+    // channel 0; bias_patch() discards them.
+    __device__ inline void issue(const int8_t* __restrict__ x, const Problem& p, int cb, int lane,
+                                 int8_t* raw_wave) const {
+        const int c = cb * kCBlock + (lane & 3) * 16;
+        const int8_t* src = x + (c < p.C ? c : 0);
+#pragma unroll
+        for (int i = 0; i < 9; ++i) __builtin_amdgcn_global_load_lds(src + pixel_off[i], raw_wave + i * 1024, 16, 0, 0);
+    }
+    __device__ inline static void read(const int8_t* raw_wave, int lane, uint32_t u[6][6]) {
+#pragma unroll
+        for (int a = 0; a < 6; ++a)
+#pragma unroll
+            for (int b = 0; b < 6; ++b)
+                u[a][b] = *reinterpret_cast<const uint32_t*>(raw_wave + (6 * a + b) * 256 + 4 * lane);
+    }
+};
+
 struct LaneContext {
     const int8_t* a_lds;        // this lane's 16-byte slot in plane 0
     const int8_t* b_glob;       // this lane's 16 bytes of filter plane 0, current channel block
@@ -287,7 +332,7 @@ struct ProductPhase {
 // four channels); in the product phase wave w owns filter block (w & 1) and half of the
 // rows of M (w >> 1: rows 0,1,2 or rows 5,3); all four waves stage their partial outputs
 // in LDS and the block stores the sums with full-line writes.
-template <int LAYOUT, bool VEC4, int MODE>
+template <int LAYOUT, int LOAD, int MODE>
 __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restrict__ x,
                                                          const uint8_t* __restrict__ blob, size_t table_off,
                                                          size_t planes_off, int32_t* __restrict__ y, Problem p) {
@@ -323,23 +368,52 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
 
     // The activation patch of the first channel block does not depend on the blob: its loads
     // go out first, and the blob header is checked while they are in flight.
+    constexpr bool VEC4 = LOAD == kLoadDwords;
     uint32_t patch[6][6];
-    if (a_t < p.T) load_patch<LAYOUT, VEC4>(x, p, a_n, a_ty, a_tx, 4 * a_cq, patch);
+    DirectPatch direct;
+    int8_t* raw_wave = lds + kLdsBytes + wave * kRawWaveBytes;
+    if constexpr (LOAD == kLoadDirect) {
+        const int dt = 4 * wave + ((lane & 15) >> 2);   // the tile this lane moves pieces of
+        direct.init(p, __shfl(my_n, dt), __shfl(my_ty, dt), __shfl(my_tx, dt), lane);
+        direct.issue(x, p, 0, lane, raw_wave);
+    } else {
+        if (a_t < p.T) load_patch<LAYOUT, VEC4>(x, p, a_n, a_ty, a_tx, 4 * a_cq, patch);
+    }
     if (!blob_matches(reinterpret_cast<const BlobHeader*>(blob), p.K, p.C, MODE)) return;
 
     ProductPhase<MODE, 0> phase0;
     ProductPhase<MODE, 1> phase1;
+    static_assert(ProductPhase<MODE, 0>::NPRE == kFilterPrefetch && ProductPhase<MODE, 1>::NPRE == kFilterPrefetch,
+                  "the wait for the direct patch transfer counts the filter fragments requested after it");
     for (int cb = 0; cb < p.CB; ++cb) {
         cx.b_glob = b_lane + cb * b_block_stride;
         if (half == 0) phase0.prefetch(cx); else phase1.prefetch(cx);
-        if (cb > 0) __syncthreads();   // everyone is done reading the previous block's planes
+        if (cb > 0) {   // everyone is done reading the previous block's planes
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+        }
+        if constexpr (LOAD == kLoadDirect) {
+            // the patch pieces were requested before the sixteen filter fragments above, and
+            // loads complete in order; the pieces a thread reads were moved by its own wave
+            asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+            DirectPatch::read(raw_wave, lane, patch);
+            if (cb + 1 < p.CB) {
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the raw area has been read
+                direct.issue(x, p, cb + 1, lane, raw_wave);
+            }
+        }
         if (a_t < p.T) {
             bias_patch(p, a_ty, a_tx, cb * kCBlock + 4 * a_cq, patch);
             transform_patch(patch, out);
-            if (cb + 1 < p.CB)       // next block's patch travels while this block's products run
-                load_patch<LAYOUT, VEC4>(x, p, a_n, a_ty, a_tx, (cb + 1) * kCBlock + 4 * a_cq, patch);
+            if constexpr (LOAD != kLoadDirect) {
+                if (cb + 1 < p.CB)   // next block's patch travels while this block's products run
+                    load_patch<LAYOUT, VEC4>(x, p, a_n, a_ty, a_tx, (cb + 1) * kCBlock + 4 * a_cq, patch);
+            }
         }
-        __syncthreads();
+        // the operand planes are complete once every wave's LDS writes have landed; global
+        // requests (filter fragments, the next block's patch) stay in flight across the barrier
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
         if (half == 0) phase0.run(cx, Y); else phase1.run(cx, Y);
     }
 
@@ -441,19 +515,27 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
     }
 }
 
-template <int LAYOUT, bool VEC4, int MODE>
+template <int LAYOUT, int LOAD, int MODE>
 hipError_t launch(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
                   hipStream_t s) {
+    constexpr int lds_bytes = kLdsBytes + (LOAD == kLoadDirect ? kRawBytes : 0);
     static bool configured = false;   // per template instance
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_conv_kernel<LAYOUT, VEC4, MODE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_conv_kernel<LAYOUT, LOAD, MODE>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         configured = true;
     }
     dim3 grid(ceil_div(p.T, kFusedTiles), p.Kp / kFusedFilters);
-    fused_conv_kernel<LAYOUT, VEC4, MODE><<<grid, 256, kLdsBytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p);
+    fused_conv_kernel<LAYOUT, LOAD, MODE><<<grid, 256, lds_bytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p);
     return hipGetLastError();
+}
+
+template <int LAYOUT, int LOAD>
+hipError_t launch_mode(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
+                       int mode, hipStream_t s) {
+    return mode == WG_LOSSLESS ? launch<LAYOUT, LOAD, WG_LOSSLESS>(x, blob, bl, y, p, s)
+                               : launch<LAYOUT, LOAD, WG_SCALED>(x, blob, bl, y, p, s);
 }
 
 }  // namespace
@@ -467,14 +549,11 @@ hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, cons
                              hipStream_t s) {
     const BlobLayout bl = blob_layout(p.Kp, p.CB, mode);
     const uint8_t* b = static_cast<const uint8_t*>(blob);
-    if (layout == WG_NHWC && p.C % 4 == 0)
-        return mode == WG_LOSSLESS ? launch<WG_NHWC, true, WG_LOSSLESS>(x, b, bl, y, p, s)
-                                   : launch<WG_NHWC, true, WG_SCALED>(x, b, bl, y, p, s);
-    if (layout == WG_NHWC)
-        return mode == WG_LOSSLESS ? launch<WG_NHWC, false, WG_LOSSLESS>(x, b, bl, y, p, s)
-                                   : launch<WG_NHWC, false, WG_SCALED>(x, b, bl, y, p, s);
-    return mode == WG_LOSSLESS ? launch<WG_NCHW, false, WG_LOSSLESS>(x, b, bl, y, p, s)
-                               : launch<WG_NCHW, false, WG_SCALED>(x, b, bl, y, p, s);
+    if (layout == WG_NHWC && p.C % 16 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0)
+        return launch_mode<WG_NHWC, kLoadDirect>(x, b, bl, y, p, mode, s);
+    if (layout == WG_NHWC && p.C % 4 == 0) return launch_mode<WG_NHWC, kLoadDwords>(x, b, bl, y, p, mode, s);
+    if (layout == WG_NHWC) return launch_mode<WG_NHWC, kLoadBytes>(x, b, bl, y, p, mode, s);
+    return launch_mode<WG_NCHW, kLoadBytes>(x, b, bl, y, p, mode, s);
 }
 
 }  // namespace wg
