@@ -137,10 +137,11 @@ int winograd_conv2d_path(int N, int C, int H, int W, int K, int mode);
 /*
  * Measurement aid for benchmarks: enqueues each kernel of winograd_conv2d_int8
  * (same arguments and launch configuration as that call) `iters` times back to
- * back on hip_stream between two HIP events, waits, and writes the mean
+ * back on hip_stream between two HIP events (after `iters` untimed launches of
+ * the same kernel, so that clocks have settled), waits, and writes the mean
  * milliseconds per launch to stage_ms_host[0..3] (HOST memory): the staged
  * pipeline's input transform, contraction and output transform, then the fused
- * kernel (0 where it does not apply).  This call blocks.  y_dev holds the
+ * kernel.  This call blocks.  y_dev holds the
  * convolution result afterwards.  iters >= 1.
  */
 int winograd_conv2d_int8_stage_times(const int8_t* x_dev, const void* packed_dev, int32_t* y_dev,
@@ -165,12 +166,13 @@ int winograd_conv2d_int8_stage_times(const int8_t* x_dev, const void* packed_dev
  */
 int winograd_num_activation_planes(int mode);
 
-/* winograd_conv2d_int8 has two implementations of the same arithmetic: a staged
-   pipeline (input transform, contraction, output transform as three kernels
-   through the workspace) and a fused single kernel used for small channel
-   counts.  path 0 = library's choice (default), 1 = always staged, 2 = fused
-   wherever it applies (lossless: any C; scaled: C <= 64).  Process-wide; for
-   tests and benchmarks.  Returns WG_EINVAL for any other value. */
+/* winograd_conv2d_int8 has two implementations of the same arithmetic: a fused
+   single kernel, which the library runs by default, and a staged pipeline
+   (input transform, contraction, output transform as three kernels through
+   the workspace) whose intermediate arrays the stage exports below expose.
+   path 0 = library's choice (default), 1 = always staged, 2 = always fused.
+   Process-wide; for tests and benchmarks.  Returns WG_EINVAL for any other
+   value. */
 int winograd_debug_force_path(int path);
 int winograd_num_filter_planes(int mode);
 

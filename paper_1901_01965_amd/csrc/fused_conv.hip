@@ -7,9 +7,11 @@
 // The output transform Y = A^T M A is linear in M, and M is a sum over input
 // channels, so each finished row of M (for one 64-channel block) is reduced by
 // the row rule of A^T at once and added into the 16 outputs of the tile.  That is
-// valid for any number of channel blocks in lossless mode; the reverse scaling of
-// Section 4.2 is not linear (it rounds), so scaled mode uses this kernel only
-// when all input channels fit one block.
+// valid for any number of channel blocks in lossless mode.  The reverse scaling of
+// Section 4.2 is not linear (it rounds): with more than one channel block, scaled
+// mode keeps the sums of all of a wave's entries in registers (36 accumulators of
+// four registers per wave) across the channel blocks and reduces them once at the
+// end.
 //
 // This kernel is bound by operand bandwidth and vector ALU work, not by the
 // matrix cores, so it trades multiplications for traffic: a 12-bit x 12-bit
@@ -328,11 +330,76 @@ struct ProductPhase {
     }
 };
 
+// Scaled mode over several channel blocks: the products of every entry a wave owns accumulate
+// in registers across the blocks (run, once per block), and the reverse scaling and the output
+// transform are applied to the finished channel sums (finish, once).
+template <int HALF>
+struct ScaledSums {
+    static constexpr int MODE = WG_SCALED;
+    using Phase = ProductPhase<MODE, HALF>;
+    static constexpr int NE = Phase::NE, NB = Phase::NB;
+    static constexpr int acc_start(int slot) {   // first accumulator of a slot: 2 per real entry, 4 per complex
+        int n = 0;
+        for (int s = 0; s < slot; ++s) n += is_real(half_slot(HALF, s).entry) ? 2 : 4;
+        return n;
+    }
+    static constexpr int kSums = acc_start(NE);
+
+    __device__ inline static void run(const LaneContext& cx, v4i (&bring)[kFilterPrefetch], v4i (&sums)[kSums]) {
+        v4i afr[2][4];
+        static_for<num_a<MODE>(half_slot(HALF, 0).entry)>([&](auto I) { afr[0][I] = Phase::template load_a<0, I>(cx); });
+        static_for<NE>([&](auto S) {
+            constexpr int s = S;
+            constexpr int entry = half_slot(HALF, s).entry;
+            constexpr int b0 = b_start<MODE>(HALF, s);
+            if constexpr (s + 1 < NE)
+                static_for<num_a<MODE>(half_slot(HALF, s + 1).entry)>(
+                    [&](auto I) { afr[(s + 1) & 1][I] = Phase::template load_a<s + 1, I>(cx); });
+            static_for<num_ops<MODE>(entry)>([&](auto I) {
+                constexpr Op op = entry_op<MODE>(entry, I);
+                constexpr int a = acc_start(s) + op.acc;
+                sums[a] = __builtin_amdgcn_mfma_i32_16x16x64_i8(afr[s & 1][op.a], bring[(b0 + op.b) % kFilterPrefetch],
+                                                                sums[a], 0, 0, 0);
+            });
+            static_for<num_b<MODE>(entry)>([&](auto I) {
+                if constexpr (b0 + I + kFilterPrefetch < NB)
+                    bring[(b0 + I) % kFilterPrefetch] = Phase::template load_b<b0 + I + kFilterPrefetch>(cx);
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    }
+
+    __device__ inline static void finish(const LaneContext& cx, const v4i (&sums)[kSums], v4i (&Y)[16]) {
+        v4i er[6], ei[6];
+        static_for<NE>([&](auto S) {
+            constexpr Slot sl = half_slot(HALF, S);
+            constexpr int a = acc_start(S);
+            v4i re = (sums[a] << 6) + sums[a + 1], im = {0, 0, 0, 0};
+            if constexpr (!is_real(sl.entry)) im = (sums[a + 2] << 6) + sums[a + 3];
+            // reverse scaling (Section 4.2): (m * r + 2^(q-1)) >> q, 64-bit intermediate
+            const ScaleEntry se = cx.table_k[sl.entry];
+            if (se.n != 0) {
+                const long long rnd = se.q > 0 ? (1ll << (se.q - 1)) : 0ll;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    re[q] = (int)(((long long)re[q] * se.r + rnd) >> se.q);
+                    im[q] = (int)(((long long)im[q] * se.r + rnd) >> se.q);
+                }
+            }
+            er[sl.pos] = re;
+            ei[sl.pos] = im;
+            if constexpr (sl.last_in_row) finish_row<sl.row>(er, ei, Y);
+        });
+    }
+};
+static_assert(ScaledSums<0>::kSums == 36 && ScaledSums<1>::kSums == 36, "both halves keep 36 accumulators");
+
 // grid: (ceil(T/16), Kp/32).  256 threads: in the transform phase one thread per (tile,
 // four channels); in the product phase wave w owns filter block (w & 1) and half of the
 // rows of M (w >> 1: rows 0,1,2 or rows 5,3); all four waves stage their partial outputs
 // in LDS and the block stores the sums with full-line writes.
-template <int LAYOUT, int LOAD, int MODE>
+// SUMS: scaled mode with more than one channel block (see ScaledSums).
+template <int LAYOUT, int LOAD, int MODE, bool SUMS>
 __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restrict__ x,
                                                          const uint8_t* __restrict__ blob, size_t table_off,
                                                          size_t planes_off, int32_t* __restrict__ y, Problem p) {
@@ -383,6 +450,12 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
 
     ProductPhase<MODE, 0> phase0;
     ProductPhase<MODE, 1> phase1;
+    static_assert(!SUMS || MODE == WG_SCALED, "channel sums are kept apart in scaled mode only");
+    v4i sums[SUMS ? 36 : 1];
+    if constexpr (SUMS) {
+#pragma unroll
+        for (int i = 0; i < 36; ++i) sums[i] = (v4i){0, 0, 0, 0};
+    }
     static_assert(ProductPhase<MODE, 0>::NPRE == kFilterPrefetch && ProductPhase<MODE, 1>::NPRE == kFilterPrefetch,
                   "the wait for the direct patch transfer counts the filter fragments requested after it");
     for (int cb = 0; cb < p.CB; ++cb) {
@@ -414,7 +487,14 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
         // requests (filter fragments, the next block's patch) stay in flight across the barrier
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
-        if (half == 0) phase0.run(cx, Y); else phase1.run(cx, Y);
+        if constexpr (SUMS) {
+            if (half == 0) ScaledSums<0>::run(cx, phase0.bring, sums); else ScaledSums<1>::run(cx, phase1.bring, sums);
+        } else {
+            if (half == 0) phase0.run(cx, Y); else phase1.run(cx, Y);
+        }
+    }
+    if constexpr (SUMS) {
+        if (half == 0) ScaledSums<0>::finish(cx, sums, Y); else ScaledSums<1>::finish(cx, sums, Y);
     }
 
     // ---- add the two halves and store ------------------------------------------------------
@@ -515,35 +595,31 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
     }
 }
 
-template <int LAYOUT, int LOAD, int MODE>
+template <int LAYOUT, int LOAD, int MODE, bool SUMS>
 hipError_t launch(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
                   hipStream_t s) {
     constexpr int lds_bytes = kLdsBytes + (LOAD == kLoadDirect ? kRawBytes : 0);
     static bool configured = false;   // per template instance
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_conv_kernel<LAYOUT, LOAD, MODE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_conv_kernel<LAYOUT, LOAD, MODE, SUMS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         configured = true;
     }
     dim3 grid(ceil_div(p.T, kFusedTiles), p.Kp / kFusedFilters);
-    fused_conv_kernel<LAYOUT, LOAD, MODE><<<grid, 256, lds_bytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p);
+    fused_conv_kernel<LAYOUT, LOAD, MODE, SUMS><<<grid, 256, lds_bytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p);
     return hipGetLastError();
 }
 
 template <int LAYOUT, int LOAD>
 hipError_t launch_mode(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
                        int mode, hipStream_t s) {
-    return mode == WG_LOSSLESS ? launch<LAYOUT, LOAD, WG_LOSSLESS>(x, blob, bl, y, p, s)
-                               : launch<LAYOUT, LOAD, WG_SCALED>(x, blob, bl, y, p, s);
+    if (mode == WG_LOSSLESS) return launch<LAYOUT, LOAD, WG_LOSSLESS, false>(x, blob, bl, y, p, s);
+    return p.CB == 1 ? launch<LAYOUT, LOAD, WG_SCALED, false>(x, blob, bl, y, p, s)
+                     : launch<LAYOUT, LOAD, WG_SCALED, true>(x, blob, bl, y, p, s);
 }
 
 }  // namespace
-
-bool fused_conv_supported(const Problem& p, int mode) {
-    // scaled mode needs the whole channel sum in one block (the reverse scaling rounds)
-    return mode == WG_LOSSLESS || p.CB == 1;
-}
 
 hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int layout, int mode,
                              hipStream_t s) {

@@ -138,9 +138,7 @@ hipError_t launch_contraction(const int8_t* V, const void* blob, int32_t* M, con
                               int mode, hipStream_t s);
 hipError_t launch_output_transform(const int32_t* M, const void* blob, int32_t* y, const Problem& p,
                                    int layout, int mode, hipStream_t s);
-// Single-kernel path (no workspace traffic).  Supported for lossless mode with any C and for
-// scaled mode when all input channels fit one 64-channel block.
-bool fused_conv_supported(const Problem& p, int mode);
+// Single-kernel path (no workspace traffic).
 hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int layout,
                              int mode, hipStream_t s);
 hipError_t launch_direct_conv(const int8_t* x, const int8_t* w, int32_t* y, const Problem& p,

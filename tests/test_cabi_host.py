@@ -61,7 +61,10 @@ def test_size_queries(lib):
 
 def test_path_query(lib):
     assert wg.conv2d_path(8, 64, 56, 56, 64, wg.LOSSLESS) == wg.FUSED
-    assert wg.conv2d_path(64, 512, 7, 7, 512, wg.SCALED) == wg.STAGED
+    assert wg.conv2d_path(64, 512, 7, 7, 512, wg.SCALED) == wg.FUSED
+    assert lib.winograd_debug_force_path(wg.STAGED) == OK
+    assert wg.conv2d_path(8, 64, 56, 56, 64, wg.LOSSLESS) == wg.STAGED
+    assert lib.winograd_debug_force_path(wg.AUTO) == OK
     assert lib.winograd_conv2d_path(8, 64, 56, 56, 64, 9) == EINVAL
     assert lib.winograd_debug_force_path(3) == EINVAL
     assert lib.winograd_debug_force_path(0) == OK
