@@ -60,8 +60,13 @@ def test_cfg4_scaled(name):
     x, g = wl.make_case(name)
     want, flags = oracle.winograd_conv2d(x, g, oracle.SCALED, 127)
     assert (flags & 5) == 0
-    got = _run(x, g, wg.NHWC, wg.SCALED)
-    assert np.array_equal(got, want)
+    try:
+        for path in (wg.STAGED, wg.FUSED):   # both implementations at full size
+            wg.force_path(path)
+            got = _run(x, g, wg.NHWC, wg.SCALED)
+            assert np.array_equal(got, want), path
+    finally:
+        wg.force_path(wg.AUTO)
     _report(name, got, oracle.direct_conv2d(x, g))
     # the same layers in lossless mode, and in the other layout
     assert np.array_equal(_run(x, g, wg.NCHW, wg.LOSSLESS), oracle.direct_conv2d(x, g))
