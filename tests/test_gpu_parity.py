@@ -171,6 +171,28 @@ def test_scaled_conv_equals_oracle_scaled(shape, layout, path):
     assert np.array_equal(_y(y, layout), want)
 
 
+@pytest.mark.parametrize("mode", [wg.LOSSLESS, wg.SCALED])
+@pytest.mark.parametrize("offset", [0, 4, 8])
+def test_channels_last_input_alignment_selects_equivalent_load_paths(offset, mode):
+    """Channels-last inputs with C % 16 == 0 are moved in 16-byte pieces only when the pointer is 16-byte
+    aligned; a pointer that is only 4-byte aligned takes the 4-byte loads.  Same results either way."""
+    N, C, K, H, W = 2, 80, 40, 11, 13
+    x, g = wl.make_custom(N, C, K, H, W, act="relu", wgt="gauss", seed=41)
+    xs = np.ascontiguousarray(wl.to_nhwc(x))
+    buf = torch.zeros(xs.size + 16, dtype=torch.int8, device="cuda")
+    xd = buf[offset:offset + xs.size].view(N, H, W, C)
+    xd.copy_(torch.from_numpy(xs))
+    assert xd.data_ptr() % 16 == offset
+    packed = wg.winograd_filter_transform(_g(g, wg.NHWC), wg.NHWC, mode)
+    y = wg.winograd_conv2d_int8(xd, packed, wg.NHWC)
+    if mode == wg.LOSSLESS:
+        want = oracle.direct_conv2d(x, g)
+    else:
+        want, flags = oracle.winograd_conv2d(x, g, oracle.SCALED, 127)
+        assert (flags & 5) == 0
+    assert np.array_equal(_y(y, wg.NHWC), want)
+
+
 @pytest.mark.parametrize("path", PATHS, indirect=True)
 @pytest.mark.parametrize("layout", LAYOUTS)
 def test_extreme_values_lossless(layout, path):
