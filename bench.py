@@ -51,6 +51,20 @@ def contraction_int8_ops(case, mode):
     return 2 * per_pair * case.tiles * case.C * case.K
 
 
+def capture_steps(torch, step, count):
+    """`count` calls of step() recorded into one HIP graph on a side stream; None if capture is not possible."""
+    try:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(count):
+                step()
+        return graph
+    except Exception as exc:   # fall back to eager launches, and say so
+        print("bench.py: HIP graph capture failed (%s); timing eager launches" % exc, file=sys.stderr)
+        torch.cuda.synchronize()
+        return None
+
+
 def read_profiled_traffic(kernel):
     """HBM bytes per launch from the committed rocprofv3 counter summary, or None."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic_cfg2.txt")
@@ -75,6 +89,7 @@ def main():
     ap.add_argument("--layout", default="nhwc", choices=("nhwc", "nchw"))
     ap.add_argument("--batch", type=int, default=None,
                     help="override the workload's batch size N (batch sweeps; the default is the quoted configuration)")
+    ap.add_argument("--eager", action="store_true", help="launch the timed steps one by one instead of as one HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--calibration-copy", action="store_true",
@@ -118,12 +133,24 @@ def main():
     torch.cuda.synchronize()
     filter_ms = (time.perf_counter() - t0) / 10 * 1e3
 
-    for _ in range(args.warmup):
+    def step():
         wg.winograd_conv2d_int8(xd, packed, layout, out=y, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # The K timed steps are recorded into one HIP graph (the steps are a few microseconds each, so
+    # an interpreter loop would be launch-bound) and replayed once inside the timed region.
+    graph = None if args.eager else capture_steps(torch, step, args.steps)
+    if graph is not None:       # one untimed replay, so that the timed one does not pay the upload
+        graph.replay()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        wg.winograd_conv2d_int8(xd, packed, layout, out=y, workspace=ws)
+    if graph is not None:
+        graph.replay()
+    else:
+        for _ in range(args.steps):
+            step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
@@ -169,14 +196,26 @@ def main():
 
     # direct convolution on the same inputs, for context
     yd = torch.empty_like(y)
-    for _ in range(3):
+
+    def direct_step():
         wg.direct_conv2d_int8(xd, gd, layout, out=yd)
+
+    for _ in range(3):
+        direct_step()
+    torch.cuda.synchronize()
+    direct_runs = 20
+    dgraph = None if args.eager else capture_steps(torch, direct_step, direct_runs)
+    if dgraph is not None:
+        dgraph.replay()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(10):
-        wg.direct_conv2d_int8(xd, gd, layout, out=yd)
+    if dgraph is not None:
+        dgraph.replay()
+    else:
+        for _ in range(direct_runs):
+            direct_step()
     torch.cuda.synchronize()
-    direct_ms = (time.perf_counter() - t0) / 10 * 1e3
+    direct_ms = (time.perf_counter() - t0) / direct_runs * 1e3
     same_as_direct = bool(torch.equal(y, yd)) if mode == wg.LOSSLESS else None
 
     result = {
@@ -188,6 +227,7 @@ def main():
         "config": {"workload": "%s: 3x3 s1 p1 conv N=%d C=%d K=%d H=W=%d, %s, %s mode" % (
             case.name, case.N, case.C, case.K, case.H, args.layout.upper(), args.mode)},
         "path": "fused" if path == wg.FUSED else "staged",
+        "launch": "hip graph of %d steps, one replay" % args.steps if graph is not None else "eager",
         "roofline": roofline,
         "kernels": kernels,
         "filter_transform_ms": round(filter_ms, 4),

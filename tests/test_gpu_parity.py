@@ -217,8 +217,13 @@ def test_max_channels_lossless_wraparound_is_exact(path):
     assert np.array_equal(_y(y, wg.NHWC), oracle.direct_conv2d(x, g))
 
 
+# plus shapes for the matrix-core direct kernel (channels-last, C % 16 == 0, K % 4 == 0): several
+# channel blocks with a ragged last one, ragged patches, more than 64 filters
+DIRECT_SHAPES = E2E_SHAPES + [(1, 144, 72, 9, 20), (2, 16, 132, 17, 33), (1, 64, 4, 8, 16)]
+
+
 @pytest.mark.parametrize("layout", LAYOUTS)
-@pytest.mark.parametrize("shape", E2E_SHAPES)
+@pytest.mark.parametrize("shape", DIRECT_SHAPES)
 def test_direct_conv_equals_oracle(shape, layout):
     N, C, K, H, W = shape
     x, g = wl.make_custom(N, C, K, H, W, seed=38)
