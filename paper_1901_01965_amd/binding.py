@@ -108,7 +108,7 @@ AUTO, STAGED, FUSED = 0, 1, 2
 
 
 def force_path(path):
-    """0: library's choice, 1: staged three-kernel pipeline, 2: fused kernel wherever it applies."""
+    """0: library's choice (the fused kernel), 1: staged three-kernel pipeline, 2: fused kernel."""
     _check(load_library().winograd_debug_force_path(int(path)), "winograd_debug_force_path")
 
 
