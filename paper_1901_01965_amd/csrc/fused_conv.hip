@@ -206,14 +206,29 @@ __device__ inline void finish_row(const v4i (&er)[6], const v4i (&ei)[6], v4i (&
 // p at p * 256 + 4 * lane: a wave reads 256 contiguous bytes.
 struct DirectPatch {
     uint32_t pixel_off[9];   // byte offset of this lane's pixel (channel 0) for each instruction
+    // (n, ty, tx): the tile this lane moves pieces of.  With j = lane / 16, instruction i covers
+    // pixel 4i + j = 6a + b of the patch: a = {0,0,1,2,2,3,4,4,5}[i] + (i % 3 == 1 and j >= 2),
+    // and b takes only three values per lane: j (i % 3 == 0), (j + 4) % 6 (i % 3 == 1) and j + 2
+    // (i % 3 == 2).  Row terms follow each other by one clamped row step, so the whole table
+    // costs four multiplications.
     __device__ inline void init(const Problem& p, int n, int ty, int tx, int lane) {
-        const int h0 = 4 * ty - 1, w0 = 4 * tx - 1;
+        const int h0 = 4 * ty - 1, w0 = 4 * tx - 1, j = lane >> 4;
+        const uint32_t row_step = (uint32_t)(p.W * p.C);
+        uint32_t row_term[6];
+        row_term[0] = (uint32_t)(n * p.H + max(h0, 0)) * row_step;
+#pragma unroll
+        for (int a = 1; a < 6; ++a)   // rows clamp to [0, H-1]: the step is taken only inside the image
+            row_term[a] = row_term[a - 1] + ((unsigned)(h0 + a - 1) < (unsigned)(p.H - 1) ? row_step : 0u);
+        const int b1 = j < 2 ? j + 4 : j - 2;
+        const uint32_t col_term[3] = {(uint32_t)(min(max(w0 + j, 0), p.W - 1) * p.C),
+                                      (uint32_t)(min(max(w0 + b1, 0), p.W - 1) * p.C),
+                                      (uint32_t)(min(max(w0 + j + 2, 0), p.W - 1) * p.C)};
+        constexpr int a_base[9] = {0, 0, 1, 2, 2, 3, 4, 4, 5};
 #pragma unroll
         for (int i = 0; i < 9; ++i) {
-            const int pix = 4 * i + (lane >> 4);
-            const int a = (pix * 43) >> 8, b = pix - 6 * a;   // pix / 6, pix % 6 for pix < 36
-            const int h = min(max(h0 + a, 0), p.H - 1), w = min(max(w0 + b, 0), p.W - 1);
-            pixel_off[i] = (uint32_t)(((n * p.H + h) * p.W + w) * p.C);
+            uint32_t row = row_term[a_base[i]];
+            if (i % 3 == 1) row = j >= 2 ? row_term[a_base[i] + 1] : row;
+            pixel_off[i] = row + col_term[i % 3];
         }
     }
     // Pieces beyond C (the last channel block of a C that is not a multiple of 64) re-read
@@ -410,6 +425,18 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
     const int k0 = blockIdx.y * kFusedFilters;
     const int k = k0 + kblock * 16 + (lane & 15);
 
+    // The activation patch of the first channel block does not depend on the blob and is the
+    // longest wait of the kernel: its requests go out before anything else.
+    DirectPatch direct;
+    int8_t* raw_wave = lds + kLdsBytes + wave * kRawWaveBytes;
+    if constexpr (LOAD == kLoadDirect) {
+        const int dt = tile0 + 4 * wave + ((lane & 15) >> 2);   // the tile this lane moves pieces of
+        int dn = 0, dty = 0, dtx = 0;
+        if (dt < p.T) decode_tile(p, dt, dn, dty, dtx);
+        direct.init(p, dn, dty, dtx, lane);
+        direct.issue(x, p, 0, lane, raw_wave);
+    }
+
     // transform-phase identity
     // every lane decodes tile (lane & 15) of the block once; the transform phase fetches the
     // coordinates of its own tile (tid / 16) from that lane
@@ -433,17 +460,10 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
 #pragma unroll
     for (int i = 0; i < 16; ++i) Y[i] = (v4i){0, 0, 0, 0};
 
-    // The activation patch of the first channel block does not depend on the blob: its loads
-    // go out first, and the blob header is checked while they are in flight.
+    // The blob header is checked while the patch requests are in flight.
     constexpr bool VEC4 = LOAD == kLoadDwords;
     uint32_t patch[6][6];
-    DirectPatch direct;
-    int8_t* raw_wave = lds + kLdsBytes + wave * kRawWaveBytes;
-    if constexpr (LOAD == kLoadDirect) {
-        const int dt = 4 * wave + ((lane & 15) >> 2);   // the tile this lane moves pieces of
-        direct.init(p, __shfl(my_n, dt), __shfl(my_ty, dt), __shfl(my_tx, dt), lane);
-        direct.issue(x, p, 0, lane, raw_wave);
-    } else {
+    if constexpr (LOAD != kLoadDirect) {
         if (a_t < p.T) load_patch<LAYOUT, VEC4>(x, p, a_n, a_ty, a_tx, 4 * a_cq, patch);
     }
     if (!blob_matches(reinterpret_cast<const BlobHeader*>(blob), p.K, p.C, MODE)) return;
@@ -528,13 +548,16 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
         // thread: filters 4*k4..4*k4+3; pass ps: output row i = ps/2, tile = 8*(ps%2) + px/4, column j = px%4
         const int k4 = tid & 7, px = tid >> 3, j = px & 3;
         const int kk = k0 + 4 * k4;
-        int origin2[2], row2[2], col2[2];
+        int32_t* first[2];   // output row 0 of the thread's two tiles (e = 0, 1); null where nothing is stored
+        int rows[2];         // output rows of that tile inside the image
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
-            origin2[e] = __shfl(my_origin, 8 * e + (px >> 2));
-            row2[e] = __shfl(my_row, 8 * e + (px >> 2));
-            col2[e] = __shfl(my_col, 8 * e + (px >> 2));
+            const int origin = __shfl(my_origin, 8 * e + (px >> 2));
+            const bool ok = origin >= 0 && __shfl(my_col, 8 * e + (px >> 2)) + j < p.W && kk < p.K;
+            first[e] = ok ? y + (size_t)origin + j * p.K + kk : nullptr;
+            rows[e] = p.H - __shfl(my_row, 8 * e + (px >> 2));
         }
+        const size_t row_pitch = (size_t)p.W * p.K;
         v4i v[8];
 #pragma unroll
         for (int ps = 0; ps < 8; ++ps) {
@@ -545,8 +568,7 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
 #pragma unroll
         for (int ps = 0; ps < 8; ++ps) {
             const int i = ps >> 1, e = ps & 1;
-            if (origin2[e] >= 0 && row2[e] + i < p.H && col2[e] + j < p.W && kk < p.K)
-                *reinterpret_cast<v4i*>(y + (size_t)origin2[e] + (i * p.W + j) * p.K + kk) = v[ps];
+            if (first[e] != nullptr && i < rows[e]) *reinterpret_cast<v4i*>(first[e] + i * row_pitch) = v[ps];
         }
         return;
     }
