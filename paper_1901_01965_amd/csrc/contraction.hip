@@ -251,7 +251,7 @@ __global__ __launch_bounds__(512) void contraction_kernel(const int8_t* __restri
         ScaleEntry se = {0, 0, 1, 0};
         if (MODE == WG_SCALED)
             se = reinterpret_cast<const ScaleEntry*>(blob + table_off)[(size_t)k * kEntries + unit_entry<MODE>(unit)];
-        const long long rnd = se.q > 0 ? (1ll << (se.q - 1)) : 0ll;
+        const ReverseScale unscale(se);   // Section 4.2
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int tb = t0 + wm * 64 + i * 32 + 4 * (lane >> 5);
@@ -259,8 +259,7 @@ __global__ __launch_bounds__(512) void contraction_kernel(const int8_t* __restri
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 int v = out[i][j][r];
-                // reverse scaling (Section 4.2): (m * r + 2^(q-1)) >> q, 64-bit intermediate
-                if (MODE == WG_SCALED && se.n != 0) v = (int)(((long long)v * se.r + rnd) >> se.q);
+                if (MODE == WG_SCALED) v = unscale(v);
                 const int dt = 8 * (r / 4) + (r % 4);
                 if (tb + dt < p.T) m[dt * p.Kp] = v;
             }

@@ -325,15 +325,11 @@ struct ProductPhase {
                 } else {
                     re = (a[0] << 6) + a[1];
                     if constexpr (!is_real(sl.entry)) im = (a[2] << 6) + a[3];
-                    // reverse scaling (Section 4.2): (m * r + 2^(q-1)) >> q, 64-bit intermediate
-                    const ScaleEntry se = cx.table_k[sl.entry];
-                    if (se.n != 0) {
-                        const long long rnd = se.q > 0 ? (1ll << (se.q - 1)) : 0ll;
+                    const ReverseScale unscale(cx.table_k[sl.entry]);   // Section 4.2
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            re[q] = (int)(((long long)re[q] * se.r + rnd) >> se.q);
-                            im[q] = (int)(((long long)im[q] * se.r + rnd) >> se.q);
-                        }
+                    for (int q = 0; q < 4; ++q) {
+                        re[q] = unscale(re[q]);
+                        if constexpr (!is_real(sl.entry)) im[q] = unscale(im[q]);
                     }
                 }
                 er[sl.pos] = re;
@@ -391,15 +387,11 @@ struct ScaledSums {
             constexpr int a = acc_start(S);
             v4i re = (sums[a] << 6) + sums[a + 1], im = {0, 0, 0, 0};
             if constexpr (!is_real(sl.entry)) im = (sums[a + 2] << 6) + sums[a + 3];
-            // reverse scaling (Section 4.2): (m * r + 2^(q-1)) >> q, 64-bit intermediate
-            const ScaleEntry se = cx.table_k[sl.entry];
-            if (se.n != 0) {
-                const long long rnd = se.q > 0 ? (1ll << (se.q - 1)) : 0ll;
+            const ReverseScale unscale(cx.table_k[sl.entry]);   // Section 4.2
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    re[q] = (int)(((long long)re[q] * se.r + rnd) >> se.q);
-                    im[q] = (int)(((long long)im[q] * se.r + rnd) >> se.q);
-                }
+            for (int q = 0; q < 4; ++q) {
+                re[q] = unscale(re[q]);
+                if constexpr (!is_real(sl.entry)) im[q] = unscale(im[q]);
             }
             er[sl.pos] = re;
             ei[sl.pos] = im;

@@ -104,6 +104,18 @@ __host__ __device__ inline size_t filter_plane_offset(int plane, int cb, int k, 
     return ((((size_t)cb * (Kp >> 4) + (k >> 4)) * nplanes + plane) * 16 + (k & 15)) * kCBlock + c64;
 }
 
+// Reverse scaling of Section 4.2 for a 32-bit channel sum m: (m * r + 2^(q-1)) >> q with an
+// arithmetic shift (q = 0: m * r), r <= 255, q <= 7.  No 64-bit product is needed: with
+// m = a 2^q + b, 0 <= b < 2^q, the value is a r + ((b r + 2^(q-1)) >> q) exactly, and since the
+// result fits 32 bits, wrap-around in a r is harmless.  Entries that were not scaled carry
+// (r, q) = (1, 0), for which this returns m.
+struct ReverseScale {
+    int r, q, mask, rnd;
+    __device__ inline explicit ReverseScale(const ScaleEntry& se)
+        : r(se.r), q(se.q), mask((1 << se.q) - 1), rnd(se.q > 0 ? 1 << (se.q - 1) : 0) {}
+    __device__ inline int operator()(int m) const { return (m >> q) * r + ((__mul24(m & mask, r) + rnd) >> q); }
+};
+
 struct BlobLayout {
     size_t maxmag_off, table_off, planes_off, total;
 };
