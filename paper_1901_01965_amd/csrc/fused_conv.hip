@@ -257,8 +257,19 @@ struct LaneContext {
 
 constexpr int kFilterPrefetch = 16;   // filter fragments in flight per wave (covers L2 latency)
 
-// value = 4096 hh + 64 mid + ll, modulo 2^32
-__device__ inline v4i join_limbs(v4i hh, v4i mid, v4i ll) { return (((hh << 6) + mid) << 6) + ll; }
+// value = 4096 hh + 64 mid + ll, modulo 2^32, as two shift-and-add instructions per register.
+// The empty statement only pins the intermediate value, so that the compiler does not rewrite
+// the expression as two shifts and a three-operand add.
+__device__ inline v4i join_limbs(v4i hh, v4i mid, v4i ll) {
+    v4i out;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        int t = (hh[q] << 6) + mid[q];
+        asm("" : "+v"(t));
+        out[q] = (t << 6) + ll[q];
+    }
+    return out;
+}
 
 template <int MODE, int HALF>
 struct ProductPhase {
