@@ -138,7 +138,7 @@ struct OperandSplitter {
     }
     __device__ inline void limbs(int first, Quad v) const {
         sink.put(first, pack_low_bytes(high(v)));
-        sink.put(first + 1, pack_low_bytes(low(v)));
+        sink.put(first + 1, pack_low_bytes(v) & 0x3f3f3f3fu);   // v & 63 on all four channels at once
     }
     __device__ inline void real_entry(int p, Quad v) const {
         if (SPLIT == kSplitKaratsuba) value(p, v); else limbs(2 * p, v);
