@@ -89,6 +89,9 @@ def main():
     ap.add_argument("--layout", default="nhwc", choices=("nhwc", "nchw"))
     ap.add_argument("--batch", type=int, default=None,
                     help="override the workload's batch size N (batch sweeps; the default is the quoted configuration)")
+    ap.add_argument("--rotate", type=int, default=1,
+                    help="cycle the timed steps over this many separate input/output buffer sets (a working set above "
+                         "256 MB defeats the Infinity Cache; the default, 1, is the resident case)")
     ap.add_argument("--eager", action="store_true", help="launch the timed steps one by one instead of as one HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
@@ -133,8 +136,14 @@ def main():
     torch.cuda.synchronize()
     filter_ms = (time.perf_counter() - t0) / 10 * 1e3
 
+    # optional rotation over several buffer sets (same contents), to take the caches out of the picture
+    sets = [(xd, y)] + [(xd.clone(), torch.empty_like(y)) for _ in range(max(1, args.rotate) - 1)]
+    turn = [0]
+
     def step():
-        wg.winograd_conv2d_int8(xd, packed, layout, out=y, workspace=ws)
+        xi, yi = sets[turn[0] % len(sets)]
+        turn[0] += 1
+        wg.winograd_conv2d_int8(xi, packed, layout, out=yi, workspace=ws)
 
     for _ in range(args.warmup):
         step()
@@ -228,6 +237,7 @@ def main():
             case.name, case.N, case.C, case.K, case.H, args.layout.upper(), args.mode)},
         "path": "fused" if path == wg.FUSED else "staged",
         "launch": "hip graph of %d steps, one replay" % args.steps if graph is not None else "eager",
+        "buffer_sets": len(sets),
         "roofline": roofline,
         "kernels": kernels,
         "filter_transform_ms": round(filter_ms, 4),
