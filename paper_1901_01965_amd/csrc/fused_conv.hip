@@ -13,8 +13,9 @@
 // four registers per wave) across the channel blocks and reduces them once at the
 // end.
 //
-// This kernel is bound by operand bandwidth and vector ALU work, not by the
-// matrix cores, so it trades multiplications for traffic: a 12-bit x 12-bit
+// This kernel is bound by vector ALU work (transform, limb re-assembly, output
+// transform) and memory latency, not by the matrix cores, so it trades
+// multiplications for vector work and traffic: a 12-bit x 12-bit
 // product is taken as the four limb products hh, hl, lh, ll (two activation and
 // two filter planes per value) and a complex product as its four real products,
 // instead of the three-multiplication forms of Section 3.1 that the staged
