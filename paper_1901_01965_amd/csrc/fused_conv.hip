@@ -279,11 +279,16 @@ struct ProductPhase {
     static constexpr int NPRE = NB < kFilterPrefetch ? NB : kFilterPrefetch;
     v4i bring[kFilterPrefetch];
 
-    template <int F>   // F-th filter fragment of this wave's stream
+    // F-th filter fragment of this wave's stream.  A workgroup that covers more than 32 filters
+    // goes through its entries once per 32 (pass F / NB); the wave's 16-filter fragment of the
+    // next pass lies two fragments (2 * planes KB) further on in the blob.
+    template <int F>
     __device__ inline static v4i load_b(const LaneContext& cx) {
-        constexpr int slot = b_slot_of<MODE>(HALF, F);
-        constexpr int plane = b_plane<MODE>(half_slot(HALF, slot).entry, F - b_start<MODE>(HALF, slot));
-        return *reinterpret_cast<const v4i*>(cx.b_glob + plane * kFilterFragBytes);
+        constexpr int pass = F / NB, f = F % NB;
+        constexpr int slot = b_slot_of<MODE>(HALF, f);
+        constexpr int plane = b_plane<MODE>(half_slot(HALF, slot).entry, f - b_start<MODE>(HALF, slot));
+        constexpr int planes = MODE == WG_LOSSLESS ? 138 : 46;
+        return *reinterpret_cast<const v4i*>(cx.b_glob + (pass * 2 * planes + plane) * kFilterFragBytes);
     }
     template <int SLOT, int I>
     __device__ inline static v4i load_a(const LaneContext& cx) {
@@ -295,12 +300,16 @@ struct ProductPhase {
     __device__ inline void prefetch(const LaneContext& cx) {
         static_for<NPRE>([&](auto I) { bring[I] = load_b<I>(cx); });
     }
+    static_assert(NB >= kFilterPrefetch || MODE == WG_SCALED, "the ring is full from the first pass on");
 
     // One 64-channel block of this wave's rows.  Software pipeline over entries: while entry i's
     // matrix-core instructions run, entry i+1's activation fragments come from LDS, the filter
     // ring is refilled sixteen fragments ahead, and entry i-1's accumulators are joined,
     // (un)scaled and reduced into the outputs.
+    // PASS of NPASS: which 32 of the workgroup's filters (see load_b).
+    template <int PASS = 0, int NPASS = 1>
     __device__ inline void run(const LaneContext& cx, v4i (&Y)[16]) {
+        constexpr int F0 = PASS * NB, FEND = NPASS * NB;   // this pass's place in the fragment stream
         v4i afr[2][4], acc[2][9], er[6], ei[6];
         static_for<num_a<MODE>(half_slot(HALF, 0).entry)>([&](auto I) { afr[0][I] = load_a<0, I>(cx); });
         static_for<NE + 1>([&](auto S) {
@@ -315,12 +324,12 @@ struct ProductPhase {
                     constexpr Op op = entry_op<MODE>(entry, I);
                     constexpr v4i zero = {0, 0, 0, 0};
                     acc[s & 1][op.acc] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
-                        afr[s & 1][op.a], bring[(b0 + op.b) % kFilterPrefetch],
+                        afr[s & 1][op.a], bring[(F0 + b0 + op.b) % kFilterPrefetch],
                         op.init ? zero : acc[s & 1][op.acc], 0, 0, 0);
                 });
                 static_for<num_b<MODE>(entry)>([&](auto I) {
-                    if constexpr (b0 + I + kFilterPrefetch < NB)
-                        bring[(b0 + I) % kFilterPrefetch] = load_b<b0 + I + kFilterPrefetch>(cx);
+                    if constexpr (F0 + b0 + I + kFilterPrefetch < FEND)
+                        bring[(F0 + b0 + I) % kFilterPrefetch] = load_b<F0 + b0 + I + kFilterPrefetch>(cx);
                 });
             }
             if constexpr (s > 0) {
@@ -418,7 +427,11 @@ static_assert(ScaledSums<0>::kSums == 36 && ScaledSums<1>::kSums == 36, "both ha
 // rows of M (w >> 1: rows 0,1,2 or rows 5,3); all four waves stage their partial outputs
 // in LDS and the block stores the sums with full-line writes.
 // SUMS: scaled mode with more than one channel block (see ScaledSums).
-template <int LAYOUT, int LOAD, int MODE, bool SUMS>
+// WIDE: the workgroup covers 64 filters instead of 32 (lossless mode): the transform of a
+// channel block is followed by two passes over the entries, one per 32 filters, each with its own
+// outputs; used when there are more workgroups than compute units, where halving the number of
+// repeated transforms outweighs the longer workgroup.
+template <int LAYOUT, int LOAD, int MODE, bool SUMS, bool WIDE>
 __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restrict__ x,
                                                          const uint8_t* __restrict__ blob, size_t table_off,
                                                          size_t planes_off, int32_t* __restrict__ y, Problem p) {
@@ -426,7 +439,9 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kblock = wave & 1, half = wave >> 1;
     const int tile0 = blockIdx.x * kFusedTiles;
-    const int k0 = blockIdx.y * kFusedFilters;
+    constexpr int NPASS = WIDE ? 2 : 1;
+    static_assert(!WIDE || (MODE == WG_LOSSLESS && !SUMS), "the wide variant exists for lossless mode");
+    const int k0 = blockIdx.y * (kFusedFilters * NPASS);
     const int k = k0 + kblock * 16 + (lane & 15);
 
     // The activation patch of the first channel block does not depend on the blob and is the
@@ -460,9 +475,12 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
                            filter_plane_offset(0, 0, k, (lane >> 4) * 16, p.Kp, NP);
     const size_t b_block_stride = (size_t)(p.Kp >> 4) * NP * kFilterFragBytes;
 
-    v4i Y[16];
+    v4i Yall[NPASS][16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) Y[i] = (v4i){0, 0, 0, 0};
+    for (int pass = 0; pass < NPASS; ++pass)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) Yall[pass][i] = (v4i){0, 0, 0, 0};
+    v4i (&Y)[16] = Yall[0];
 
     // The blob header is checked while the patch requests are in flight.
     constexpr bool VEC4 = LOAD == kLoadDwords;
@@ -513,6 +531,9 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
         __builtin_amdgcn_s_barrier();
         if constexpr (SUMS) {
             if (half == 0) ScaledSums<0>::run(cx, phase0.bring, sums); else ScaledSums<1>::run(cx, phase1.bring, sums);
+        } else if constexpr (WIDE) {
+            if (half == 0) { phase0.template run<0, 2>(cx, Yall[0]); phase0.template run<1, 2>(cx, Yall[1]); }
+            else           { phase1.template run<0, 2>(cx, Yall[0]); phase1.template run<1, 2>(cx, Yall[1]); }
         } else {
             if (half == 0) phase0.run(cx, Y); else phase1.run(cx, Y);
         }
@@ -531,118 +552,144 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
                                       : (my_n * p.K * p.H + my_row) * p.W + my_col;
     const int rnd = MODE == WG_SCALED ? 8 : 0;
     int* parki = reinterpret_cast<int*>(lds);
-    __syncthreads();   // the operand planes are dead: their LDS now stages the outputs
-
-    if (LAYOUT == WG_NHWC && (p.K & 3) == 0) {
-        // Channels-last with K a multiple of four: outputs are staged filter-fastest,
-        // stage[half][output 4i+j][tile][36] (32 filters, rows padded to 36 dwords so that the
-        // four 16-lane groups of a wave land in different banks), then every thread adds the
-        // halves for four consecutive filters and stores 16 bytes; eight lanes cover the 128
-        // contiguous bytes this block owns of a pixel.
-        constexpr int kRow = 36, kHalf = 16 * 16 * kRow;
-        static_assert(2 * kHalf * 4 <= kLdsBytes, "staging fits the operand planes' LDS");
-        {
-            int* dst = parki + half * kHalf + (4 * (lane >> 4)) * kRow + kblock * 16 + (lane & 15);
-#pragma unroll
-            for (int o = 0; o < 16; ++o)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) dst[(o * 16 + q) * kRow] = Y[o][q];
+    // stores the 16 tiles x 32 filters (from kbase) whose partial outputs the four waves hold in Yp
+    auto store_block = [&](const v4i (&Yp)[16], int kbase) {
+        if (LAYOUT == WG_NHWC && (p.K & 3) == 0) {
+            // Channels-last with K a multiple of four: outputs are staged filter-fastest,
+            // stage[half][output 4i+j][tile][36] (32 filters, rows padded to 36 dwords so that the
+            // four 16-lane groups of a wave land in different banks), then every thread adds the
+            // halves for four consecutive filters and stores 16 bytes; eight lanes cover the 128
+            // contiguous bytes this block owns of a pixel.
+            constexpr int kRow = 36, kHalf = 16 * 16 * kRow;
+            static_assert(2 * kHalf * 4 <= kLdsBytes, "staging fits the operand planes' LDS");
+            {
+                int* dst = parki + half * kHalf + (4 * (lane >> 4)) * kRow + kblock * 16 + (lane & 15);
+    #pragma unroll
+                for (int o = 0; o < 16; ++o)
+    #pragma unroll
+                    for (int q = 0; q < 4; ++q) dst[(o * 16 + q) * kRow] = Yp[o][q];
+            }
+            __syncthreads();
+            // thread: filters 4*k4..4*k4+3; pass ps: output row i = ps/2, tile = 8*(ps%2) + px/4, column j = px%4
+            const int k4 = tid & 7, px = tid >> 3, j = px & 3;
+            const int kk = kbase + 4 * k4;
+            int32_t* first[2];   // output row 0 of the thread's two tiles (e = 0, 1); null where nothing is stored
+            int rows[2];         // output rows of that tile inside the image
+    #pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int origin = __shfl(my_origin, 8 * e + (px >> 2));
+                const bool ok = origin >= 0 && __shfl(my_col, 8 * e + (px >> 2)) + j < p.W && kk < p.K;
+                first[e] = ok ? y + (size_t)origin + j * p.K + kk : nullptr;
+                rows[e] = p.H - __shfl(my_row, 8 * e + (px >> 2));
+            }
+            const size_t row_pitch = (size_t)p.W * p.K;
+            v4i v[8];
+    #pragma unroll
+            for (int ps = 0; ps < 8; ++ps) {
+                const int i = ps >> 1, tile = 8 * (ps & 1) + (px >> 2);
+                const int at = ((4 * i + j) * 16 + tile) * kRow + 4 * k4;
+                v[ps] = (*reinterpret_cast<const v4i*>(parki + at) + *reinterpret_cast<const v4i*>(parki + kHalf + at) + rnd) >> 4;
+            }
+    #pragma unroll
+            for (int ps = 0; ps < 8; ++ps) {
+                const int i = ps >> 1, e = ps & 1;
+                if (first[e] != nullptr && i < rows[e]) *reinterpret_cast<v4i*>(first[e] + i * row_pitch) = v[ps];
+            }
+            return;
         }
+        // General path: park[wave][output 0..15][lane] (four registers = four tiles each); the value
+        // of (tile, output 4i+j, filter kl) sits in waves kl/16 and 2 + kl/16 at output 4i+j, lane
+        // (tile/4)*16 + kl%16, register tile%4.  16 x 16 x 32 = 8192 results, 32 per thread.
+        v4i* park = reinterpret_cast<v4i*>(lds);
+    #pragma unroll
+        for (int i = 0; i < 16; ++i) park[(wave * 16 + i) * 64 + lane] = Yp[i];
         __syncthreads();
-        // thread: filters 4*k4..4*k4+3; pass ps: output row i = ps/2, tile = 8*(ps%2) + px/4, column j = px%4
-        const int k4 = tid & 7, px = tid >> 3, j = px & 3;
-        const int kk = k0 + 4 * k4;
-        int32_t* first[2];   // output row 0 of the thread's two tiles (e = 0, 1); null where nothing is stored
-        int rows[2];         // output rows of that tile inside the image
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const int origin = __shfl(my_origin, 8 * e + (px >> 2));
-            const bool ok = origin >= 0 && __shfl(my_col, 8 * e + (px >> 2)) + j < p.W && kk < p.K;
-            first[e] = ok ? y + (size_t)origin + j * p.K + kk : nullptr;
-            rows[e] = p.H - __shfl(my_row, 8 * e + (px >> 2));
+        int v[32];
+        if constexpr (LAYOUT == WG_NHWC) {
+            // thread: filter kl and output column j fixed; iteration it: tile it/2, output row 2(it%2) + tid/128
+            const int kl = tid & 31, j = (tid >> 5) & 3, ih = tid >> 7;
+            const int kk = kbase + kl;
+            const int at0 = (((kl >> 4) * 16 + j) * 64 + (kl & 15)) * 4;
+    #pragma unroll
+            for (int it = 0; it < 32; ++it) {
+                const int tile = it >> 1, i = 2 * (it & 1) + ih;
+                const int at = at0 + (4 * i * 64 + (tile >> 2) * 16) * 4 + (tile & 3);
+                v[it] = (parki[at] + parki[at + 2 * 16 * 64 * 4] + rnd) >> 4;
+            }
+    #pragma unroll
+            for (int it = 0; it < 32; ++it) {
+                const int tile = it >> 1, i = 2 * (it & 1) + ih;
+                const int origin = __builtin_amdgcn_readlane(my_origin, tile);
+                const int h = __builtin_amdgcn_readlane(my_row, tile) + i, w = __builtin_amdgcn_readlane(my_col, tile) + j;
+                if (origin >= 0 && h < p.H && w < p.W && kk < p.K) y[(size_t)origin + (i * p.W + j) * p.K + kk] = v[it];
+            }
+        } else {
+            // thread: tile, output row i and column j fixed; iteration it: filter it.  A wave writes one
+            // output row of 16 consecutive tiles = 256 contiguous bytes.
+            const int j = tid & 3, tile = (tid >> 2) & 15, i = tid >> 6;
+            const int origin = __shfl(my_origin, tile), h = __shfl(my_row, tile) + i, w = __shfl(my_col, tile) + j;
+            const bool ok = origin >= 0 && h < p.H && w < p.W;
+            const int at0 = ((4 * i + j) * 64 + (tile >> 2) * 16) * 4 + (tile & 3);
+    #pragma unroll
+            for (int it = 0; it < 32; ++it) {
+                const int at = at0 + ((it >> 4) * 16 * 64 + (it & 15)) * 4;
+                v[it] = (parki[at] + parki[at + 2 * 16 * 64 * 4] + rnd) >> 4;
+            }
+    #pragma unroll
+            for (int it = 0; it < 32; ++it)
+                if (ok && kbase + it < p.K) y[(size_t)origin + ((size_t)(kbase + it) * p.H + i) * p.W + j] = v[it];
         }
-        const size_t row_pitch = (size_t)p.W * p.K;
-        v4i v[8];
-#pragma unroll
-        for (int ps = 0; ps < 8; ++ps) {
-            const int i = ps >> 1, tile = 8 * (ps & 1) + (px >> 2);
-            const int at = ((4 * i + j) * 16 + tile) * kRow + 4 * k4;
-            v[ps] = (*reinterpret_cast<const v4i*>(parki + at) + *reinterpret_cast<const v4i*>(parki + kHalf + at) + rnd) >> 4;
-        }
-#pragma unroll
-        for (int ps = 0; ps < 8; ++ps) {
-            const int i = ps >> 1, e = ps & 1;
-            if (first[e] != nullptr && i < rows[e]) *reinterpret_cast<v4i*>(first[e] + i * row_pitch) = v[ps];
-        }
-        return;
-    }
 
-    // General path: park[wave][output 0..15][lane] (four registers = four tiles each); the value
-    // of (tile, output 4i+j, filter kl) sits in waves kl/16 and 2 + kl/16 at output 4i+j, lane
-    // (tile/4)*16 + kl%16, register tile%4.  16 x 16 x 32 = 8192 results, 32 per thread.
-    v4i* park = reinterpret_cast<v4i*>(lds);
+    };
 #pragma unroll
-    for (int i = 0; i < 16; ++i) park[(wave * 16 + i) * 64 + lane] = Y[i];
-    __syncthreads();
-    int v[32];
-    if constexpr (LAYOUT == WG_NHWC) {
-        // thread: filter kl and output column j fixed; iteration it: tile it/2, output row 2(it%2) + tid/128
-        const int kl = tid & 31, j = (tid >> 5) & 3, ih = tid >> 7;
-        const int kk = k0 + kl;
-        const int at0 = (((kl >> 4) * 16 + j) * 64 + (kl & 15)) * 4;
-#pragma unroll
-        for (int it = 0; it < 32; ++it) {
-            const int tile = it >> 1, i = 2 * (it & 1) + ih;
-            const int at = at0 + (4 * i * 64 + (tile >> 2) * 16) * 4 + (tile & 3);
-            v[it] = (parki[at] + parki[at + 2 * 16 * 64 * 4] + rnd) >> 4;
-        }
-#pragma unroll
-        for (int it = 0; it < 32; ++it) {
-            const int tile = it >> 1, i = 2 * (it & 1) + ih;
-            const int origin = __builtin_amdgcn_readlane(my_origin, tile);
-            const int h = __builtin_amdgcn_readlane(my_row, tile) + i, w = __builtin_amdgcn_readlane(my_col, tile) + j;
-            if (origin >= 0 && h < p.H && w < p.W && kk < p.K) y[(size_t)origin + (i * p.W + j) * p.K + kk] = v[it];
-        }
-    } else {
-        // thread: tile, output row i and column j fixed; iteration it: filter it.  A wave writes one
-        // output row of 16 consecutive tiles = 256 contiguous bytes.
-        const int j = tid & 3, tile = (tid >> 2) & 15, i = tid >> 6;
-        const int origin = __shfl(my_origin, tile), h = __shfl(my_row, tile) + i, w = __shfl(my_col, tile) + j;
-        const bool ok = origin >= 0 && h < p.H && w < p.W;
-        const int at0 = ((4 * i + j) * 64 + (tile >> 2) * 16) * 4 + (tile & 3);
-#pragma unroll
-        for (int it = 0; it < 32; ++it) {
-            const int at = at0 + ((it >> 4) * 16 * 64 + (it & 15)) * 4;
-            v[it] = (parki[at] + parki[at + 2 * 16 * 64 * 4] + rnd) >> 4;
-        }
-#pragma unroll
-        for (int it = 0; it < 32; ++it)
-            if (ok && k0 + it < p.K) y[(size_t)origin + ((size_t)(k0 + it) * p.H + i) * p.W + j] = v[it];
+    for (int pass = 0; pass < NPASS; ++pass) {
+        __syncthreads();   // the operand planes (or the previous pass's staged outputs) are dead
+        store_block(Yall[pass], k0 + pass * kFusedFilters);
     }
 }
 
-template <int LAYOUT, int LOAD, int MODE, bool SUMS>
+// Compute units of the current device (256 on MI355X), asked once.
+int compute_units() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
+}
+
+template <int LAYOUT, int LOAD, int MODE, bool SUMS, bool WIDE>
 hipError_t launch(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
                   hipStream_t s) {
     constexpr int lds_bytes = kLdsBytes + (LOAD == kLoadDirect ? kRawBytes : 0);
     static bool configured = false;   // per template instance
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_conv_kernel<LAYOUT, LOAD, MODE, SUMS>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_conv_kernel<LAYOUT, LOAD, MODE, SUMS, WIDE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    dim3 grid(ceil_div(p.T, kFusedTiles), p.Kp / kFusedFilters);
-    fused_conv_kernel<LAYOUT, LOAD, MODE, SUMS><<<grid, 256, lds_bytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p);
+    dim3 grid(ceil_div(p.T, kFusedTiles), p.Kp / (kFusedFilters * (WIDE ? 2 : 1)));
+    fused_conv_kernel<LAYOUT, LOAD, MODE, SUMS, WIDE><<<grid, 256, lds_bytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p);
     return hipGetLastError();
 }
 
 template <int LAYOUT, int LOAD>
 hipError_t launch_mode(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
                        int mode, hipStream_t s) {
-    if (mode == WG_LOSSLESS) return launch<LAYOUT, LOAD, WG_LOSSLESS, false>(x, blob, bl, y, p, s);
-    return p.CB == 1 ? launch<LAYOUT, LOAD, WG_SCALED, false>(x, blob, bl, y, p, s)
-                     : launch<LAYOUT, LOAD, WG_SCALED, true>(x, blob, bl, y, p, s);
+    if (mode == WG_LOSSLESS) {
+        // 64 filters per workgroup once the 32-filter grid would need more than one round of the
+        // compute units (Kp is a multiple of 64)
+        const long long workgroups = (long long)ceil_div(p.T, kFusedTiles) * (p.Kp / kFusedFilters);
+        return workgroups > compute_units() ? launch<LAYOUT, LOAD, WG_LOSSLESS, false, true>(x, blob, bl, y, p, s)
+                                            : launch<LAYOUT, LOAD, WG_LOSSLESS, false, false>(x, blob, bl, y, p, s);
+    }
+    return p.CB == 1 ? launch<LAYOUT, LOAD, WG_SCALED, false, false>(x, blob, bl, y, p, s)
+                     : launch<LAYOUT, LOAD, WG_SCALED, true, false>(x, blob, bl, y, p, s);
 }
 
 }  // namespace
