@@ -346,7 +346,7 @@ struct ProductPhase {
                 } else {
                     re = (a[0] << 6) + a[1];
                     if constexpr (!is_real(sl.entry)) im = (a[2] << 6) + a[3];
-                    const ReverseScale unscale(cx.table_k[sl.entry]);   // Section 4.2
+                    const ReverseScale unscale(cx.table_k[PASS * kFusedFilters * kEntries + sl.entry]);   // Section 4.2
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         re[q] = unscale(re[q]);
@@ -377,7 +377,9 @@ struct ScaledSums {
     }
     static constexpr int kSums = acc_start(NE);
 
+    template <int PASS = 0, int NPASS = 1>
     __device__ inline static void run(const LaneContext& cx, v4i (&bring)[kFilterPrefetch], v4i (&sums)[kSums]) {
+        constexpr int F0 = PASS * NB, FEND = NPASS * NB;   // this pass's place in the fragment stream
         v4i afr[2][4];
         static_for<num_a<MODE>(half_slot(HALF, 0).entry)>([&](auto I) { afr[0][I] = Phase::template load_a<0, I>(cx); });
         static_for<NE>([&](auto S) {
@@ -390,17 +392,18 @@ struct ScaledSums {
             static_for<num_ops<MODE>(entry)>([&](auto I) {
                 constexpr Op op = entry_op<MODE>(entry, I);
                 constexpr int a = acc_start(s) + op.acc;
-                sums[a] = __builtin_amdgcn_mfma_i32_16x16x64_i8(afr[s & 1][op.a], bring[(b0 + op.b) % kFilterPrefetch],
+                sums[a] = __builtin_amdgcn_mfma_i32_16x16x64_i8(afr[s & 1][op.a], bring[(F0 + b0 + op.b) % kFilterPrefetch],
                                                                 sums[a], 0, 0, 0);
             });
             static_for<num_b<MODE>(entry)>([&](auto I) {
-                if constexpr (b0 + I + kFilterPrefetch < NB)
-                    bring[(b0 + I) % kFilterPrefetch] = Phase::template load_b<b0 + I + kFilterPrefetch>(cx);
+                if constexpr (F0 + b0 + I + kFilterPrefetch < FEND)
+                    bring[(F0 + b0 + I) % kFilterPrefetch] = Phase::template load_b<F0 + b0 + I + kFilterPrefetch>(cx);
             });
             __builtin_amdgcn_sched_barrier(0);
         });
     }
 
+    template <int PASS = 0>
     __device__ inline static void finish(const LaneContext& cx, const v4i (&sums)[kSums], v4i (&Y)[16]) {
         v4i er[6], ei[6];
         static_for<NE>([&](auto S) {
@@ -408,7 +411,7 @@ struct ScaledSums {
             constexpr int a = acc_start(S);
             v4i re = (sums[a] << 6) + sums[a + 1], im = {0, 0, 0, 0};
             if constexpr (!is_real(sl.entry)) im = (sums[a + 2] << 6) + sums[a + 3];
-            const ReverseScale unscale(cx.table_k[sl.entry]);   // Section 4.2
+            const ReverseScale unscale(cx.table_k[PASS * kFusedFilters * kEntries + sl.entry]);   // Section 4.2
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 re[q] = unscale(re[q]);
@@ -427,7 +430,7 @@ static_assert(ScaledSums<0>::kSums == 36 && ScaledSums<1>::kSums == 36, "both ha
 // rows of M (w >> 1: rows 0,1,2 or rows 5,3); all four waves stage their partial outputs
 // in LDS and the block stores the sums with full-line writes.
 // SUMS: scaled mode with more than one channel block (see ScaledSums).
-// WIDE: the workgroup covers 64 filters instead of 32 (lossless mode): the transform of a
+// WIDE: the workgroup covers 64 filters instead of 32: the transform of a
 // channel block is followed by two passes over the entries, one per 32 filters, each with its own
 // outputs; used when there are more workgroups than compute units, where halving the number of
 // repeated transforms outweighs the longer workgroup.
@@ -440,7 +443,7 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
     const int kblock = wave & 1, half = wave >> 1;
     const int tile0 = blockIdx.x * kFusedTiles;
     constexpr int NPASS = WIDE ? 2 : 1;
-    static_assert(!WIDE || (MODE == WG_LOSSLESS && !SUMS), "the wide variant exists for lossless mode");
+    static_assert(!(WIDE && SUMS), "separate channel sums for 64 filters do not fit the register file");
     const int k0 = blockIdx.y * (kFusedFilters * NPASS);
     const int k = k0 + kblock * 16 + (lane & 15);
 
@@ -493,10 +496,12 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
     ProductPhase<MODE, 0> phase0;
     ProductPhase<MODE, 1> phase1;
     static_assert(!SUMS || MODE == WG_SCALED, "channel sums are kept apart in scaled mode only");
-    v4i sums[SUMS ? 36 : 1];
+    v4i sums[SUMS ? NPASS : 1][SUMS ? 36 : 1];
     if constexpr (SUMS) {
 #pragma unroll
-        for (int i = 0; i < 36; ++i) sums[i] = (v4i){0, 0, 0, 0};
+        for (int pass = 0; pass < NPASS; ++pass)
+#pragma unroll
+            for (int i = 0; i < 36; ++i) sums[pass][i] = (v4i){0, 0, 0, 0};
     }
     static_assert(ProductPhase<MODE, 0>::NPRE == kFilterPrefetch && ProductPhase<MODE, 1>::NPRE == kFilterPrefetch,
                   "the wait for the direct patch transfer counts the filter fragments requested after it");
@@ -529,8 +534,16 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
         // requests (filter fragments, the next block's patch) stay in flight across the barrier
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
-        if constexpr (SUMS) {
-            if (half == 0) ScaledSums<0>::run(cx, phase0.bring, sums); else ScaledSums<1>::run(cx, phase1.bring, sums);
+        if constexpr (SUMS && WIDE) {
+            if (half == 0) {
+                ScaledSums<0>::template run<0, 2>(cx, phase0.bring, sums[0]);
+                ScaledSums<0>::template run<1, 2>(cx, phase0.bring, sums[1]);
+            } else {
+                ScaledSums<1>::template run<0, 2>(cx, phase1.bring, sums[0]);
+                ScaledSums<1>::template run<1, 2>(cx, phase1.bring, sums[1]);
+            }
+        } else if constexpr (SUMS) {
+            if (half == 0) ScaledSums<0>::run(cx, phase0.bring, sums[0]); else ScaledSums<1>::run(cx, phase1.bring, sums[0]);
         } else if constexpr (WIDE) {
             if (half == 0) { phase0.template run<0, 2>(cx, Yall[0]); phase0.template run<1, 2>(cx, Yall[1]); }
             else           { phase1.template run<0, 2>(cx, Yall[0]); phase1.template run<1, 2>(cx, Yall[1]); }
@@ -539,7 +552,12 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
         }
     }
     if constexpr (SUMS) {
-        if (half == 0) ScaledSums<0>::finish(cx, sums, Y); else ScaledSums<1>::finish(cx, sums, Y);
+        if (half == 0) ScaledSums<0>::template finish<0>(cx, sums[0], Yall[0]);
+        else           ScaledSums<1>::template finish<0>(cx, sums[0], Yall[0]);
+        if constexpr (WIDE) {
+            if (half == 0) ScaledSums<0>::template finish<1>(cx, sums[1], Yall[1]);
+            else           ScaledSums<1>::template finish<1>(cx, sums[1], Yall[1]);
+        }
     }
 
     // ---- add the two halves and store ------------------------------------------------------
@@ -681,15 +699,20 @@ hipError_t launch(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, in
 template <int LAYOUT, int LOAD>
 hipError_t launch_mode(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
                        int mode, hipStream_t s) {
-    if (mode == WG_LOSSLESS) {
-        // 64 filters per workgroup once the 32-filter grid would need more than one round of the
-        // compute units (Kp is a multiple of 64)
+    // 64 filters per workgroup once the 32-filter grid would need more than one round of the
+    // compute units (Kp is a multiple of 64).  Only the direct-transfer variants have the
+    // registers for it (the others hold a patch in registers across the product phase).
+    if constexpr (LOAD == kLoadDirect) {
         const long long workgroups = (long long)ceil_div(p.T, kFusedTiles) * (p.Kp / kFusedFilters);
-        return workgroups > compute_units() ? launch<LAYOUT, LOAD, WG_LOSSLESS, false, true>(x, blob, bl, y, p, s)
-                                            : launch<LAYOUT, LOAD, WG_LOSSLESS, false, false>(x, blob, bl, y, p, s);
+        if (workgroups > compute_units()) {
+            if (mode == WG_LOSSLESS) return launch<LAYOUT, LOAD, WG_LOSSLESS, false, true>(x, blob, bl, y, p, s);
+            if (p.CB == 1) return launch<LAYOUT, LOAD, WG_SCALED, false, true>(x, blob, bl, y, p, s);
+        }
     }
-    return p.CB == 1 ? launch<LAYOUT, LOAD, WG_SCALED, false, false>(x, blob, bl, y, p, s)
-                     : launch<LAYOUT, LOAD, WG_SCALED, true, false>(x, blob, bl, y, p, s);
+    if (mode == WG_LOSSLESS) return launch<LAYOUT, LOAD, WG_LOSSLESS, false, false>(x, blob, bl, y, p, s);
+    if (p.CB == 1) return launch<LAYOUT, LOAD, WG_SCALED, false, false>(x, blob, bl, y, p, s);
+    // with separate channel sums for 64 filters the kernel no longer fits the register file
+    return launch<LAYOUT, LOAD, WG_SCALED, true, false>(x, blob, bl, y, p, s);
 }
 
 }  // namespace

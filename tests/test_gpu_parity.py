@@ -193,6 +193,24 @@ def test_channels_last_input_alignment_selects_equivalent_load_paths(offset, mod
     assert np.array_equal(_y(y, wg.NHWC), want)
 
 
+@pytest.mark.parametrize("mode", [wg.LOSSLESS, wg.SCALED])
+def test_many_tiles_ragged_filters(mode):
+    """More (tile block, 32-filter block) pairs than compute units: the fused kernel then covers 64 filters per
+    workgroup (two passes over the entries).  K = 72 leaves the last pass of the last workgroup mostly padding;
+    H = W = 131 leaves ragged tiles."""
+    N, C, K, H, W = 1, 16, 72, 131, 131
+    assert ((H + 3) // 4) * ((W + 3) // 4) // 16 * ((K + 63) // 64 * 2) > 256
+    x, g = wl.make_custom(N, C, K, H, W, act="relu", wgt="gauss", seed=42)
+    packed = wg.winograd_filter_transform(_g(g, wg.NHWC), wg.NHWC, mode)
+    y = wg.winograd_conv2d_int8(_x(x, wg.NHWC), packed, wg.NHWC)
+    if mode == wg.LOSSLESS:
+        want = oracle.direct_conv2d(x, g)
+    else:
+        want, flags = oracle.winograd_conv2d(x, g, oracle.SCALED, 127)
+        assert (flags & 5) == 0
+    assert np.array_equal(_y(y, wg.NHWC), want)
+
+
 @pytest.mark.parametrize("path", PATHS, indirect=True)
 @pytest.mark.parametrize("layout", LAYOUTS)
 def test_extreme_values_lossless(layout, path):
