@@ -9,9 +9,9 @@
 // the row rule of A^T at once and added into the 16 outputs of the tile.  That is
 // valid for any number of channel blocks in lossless mode.  The reverse scaling of
 // Section 4.2 is not linear (it rounds): with more than one channel block, scaled
-// mode keeps the sums of all of a wave's entries in registers (36 accumulators of
-// four registers per wave) across the channel blocks and reduces them once at the
-// end.
+// mode keeps the channel sums of all of a wave's entries in registers (18 sums of
+// four registers per wave) across the channel blocks and scales and reduces them
+// once at the end.
 //
 // This kernel is bound by vector ALU work (transform, limb re-assembly, output
 // transform) and memory latency, not by the matrix cores, so it trades
@@ -370,47 +370,59 @@ struct ScaledSums {
     static constexpr int MODE = WG_SCALED;
     using Phase = ProductPhase<MODE, HALF>;
     static constexpr int NE = Phase::NE, NB = Phase::NB;
-    static constexpr int acc_start(int slot) {   // first accumulator of a slot: 2 per real entry, 4 per complex
+    static constexpr int sum_start(int slot) {   // first sum of a slot: one per real entry, Re and Im per complex
         int n = 0;
-        for (int s = 0; s < slot; ++s) n += is_real(half_slot(HALF, s).entry) ? 2 : 4;
+        for (int s = 0; s < slot; ++s) n += is_real(half_slot(HALF, s).entry) ? 1 : 2;
         return n;
     }
-    static constexpr int kSums = acc_start(NE);
+    static constexpr int kSums = sum_start(NE);
 
+    // One channel block: each entry's limb products are formed from zero, and its value
+    // 64 * high + low joins the entry's running sum one entry later.
     template <int PASS = 0, int NPASS = 1>
     __device__ inline static void run(const LaneContext& cx, v4i (&bring)[kFilterPrefetch], v4i (&sums)[kSums]) {
         constexpr int F0 = PASS * NB, FEND = NPASS * NB;   // this pass's place in the fragment stream
-        v4i afr[2][4];
+        v4i afr[2][4], acc[2][4];
         static_for<num_a<MODE>(half_slot(HALF, 0).entry)>([&](auto I) { afr[0][I] = Phase::template load_a<0, I>(cx); });
-        static_for<NE>([&](auto S) {
+        static_for<NE + 1>([&](auto S) {
             constexpr int s = S;
-            constexpr int entry = half_slot(HALF, s).entry;
-            constexpr int b0 = b_start<MODE>(HALF, s);
-            if constexpr (s + 1 < NE)
-                static_for<num_a<MODE>(half_slot(HALF, s + 1).entry)>(
-                    [&](auto I) { afr[(s + 1) & 1][I] = Phase::template load_a<s + 1, I>(cx); });
-            static_for<num_ops<MODE>(entry)>([&](auto I) {
-                constexpr Op op = entry_op<MODE>(entry, I);
-                constexpr int a = acc_start(s) + op.acc;
-                sums[a] = __builtin_amdgcn_mfma_i32_16x16x64_i8(afr[s & 1][op.a], bring[(F0 + b0 + op.b) % kFilterPrefetch],
-                                                                sums[a], 0, 0, 0);
-            });
-            static_for<num_b<MODE>(entry)>([&](auto I) {
-                if constexpr (F0 + b0 + I + kFilterPrefetch < FEND)
-                    bring[(F0 + b0 + I) % kFilterPrefetch] = Phase::template load_b<F0 + b0 + I + kFilterPrefetch>(cx);
-            });
+            if constexpr (s < NE) {
+                constexpr int entry = half_slot(HALF, s).entry;
+                constexpr int b0 = b_start<MODE>(HALF, s);
+                if constexpr (s + 1 < NE)
+                    static_for<num_a<MODE>(half_slot(HALF, s + 1).entry)>(
+                        [&](auto I) { afr[(s + 1) & 1][I] = Phase::template load_a<s + 1, I>(cx); });
+                static_for<num_ops<MODE>(entry)>([&](auto I) {
+                    constexpr Op op = entry_op<MODE>(entry, I);
+                    constexpr v4i zero = {0, 0, 0, 0};
+                    acc[s & 1][op.acc] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
+                        afr[s & 1][op.a], bring[(F0 + b0 + op.b) % kFilterPrefetch],
+                        op.init ? zero : acc[s & 1][op.acc], 0, 0, 0);
+                });
+                static_for<num_b<MODE>(entry)>([&](auto I) {
+                    if constexpr (F0 + b0 + I + kFilterPrefetch < FEND)
+                        bring[(F0 + b0 + I) % kFilterPrefetch] = Phase::template load_b<F0 + b0 + I + kFilterPrefetch>(cx);
+                });
+            }
+            if constexpr (s > 0) {
+                constexpr int v = sum_start(s - 1);
+                const v4i(&a)[4] = acc[(s - 1) & 1];
+                sums[v] += (a[0] << 6) + a[1];
+                if constexpr (!is_real(half_slot(HALF, s - 1).entry)) sums[v + 1] += (a[2] << 6) + a[3];
+            }
             __builtin_amdgcn_sched_barrier(0);
         });
     }
 
+    // After the last channel block: reverse scaling of the finished sums and the output transform.
     template <int PASS = 0>
     __device__ inline static void finish(const LaneContext& cx, const v4i (&sums)[kSums], v4i (&Y)[16]) {
         v4i er[6], ei[6];
         static_for<NE>([&](auto S) {
             constexpr Slot sl = half_slot(HALF, S);
-            constexpr int a = acc_start(S);
-            v4i re = (sums[a] << 6) + sums[a + 1], im = {0, 0, 0, 0};
-            if constexpr (!is_real(sl.entry)) im = (sums[a + 2] << 6) + sums[a + 3];
+            constexpr int v = sum_start(S);
+            v4i re = sums[v], im = {0, 0, 0, 0};
+            if constexpr (!is_real(sl.entry)) im = sums[v + 1];
             const ReverseScale unscale(cx.table_k[PASS * kFusedFilters * kEntries + sl.entry]);   // Section 4.2
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -423,7 +435,8 @@ struct ScaledSums {
         });
     }
 };
-static_assert(ScaledSums<0>::kSums == 36 && ScaledSums<1>::kSums == 36, "both halves keep 36 accumulators");
+constexpr int kChannelSums = 18;
+static_assert(ScaledSums<0>::kSums == kChannelSums && ScaledSums<1>::kSums == kChannelSums, "both halves keep 18 sums");
 
 // grid: (ceil(T/16), Kp/32).  256 threads: in the transform phase one thread per (tile,
 // four channels); in the product phase wave w owns filter block (w & 1) and half of the
@@ -443,7 +456,6 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
     const int kblock = wave & 1, half = wave >> 1;
     const int tile0 = blockIdx.x * kFusedTiles;
     constexpr int NPASS = WIDE ? 2 : 1;
-    static_assert(!(WIDE && SUMS), "separate channel sums for 64 filters do not fit the register file");
     const int k0 = blockIdx.y * (kFusedFilters * NPASS);
     const int k = k0 + kblock * 16 + (lane & 15);
 
@@ -496,12 +508,12 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
     ProductPhase<MODE, 0> phase0;
     ProductPhase<MODE, 1> phase1;
     static_assert(!SUMS || MODE == WG_SCALED, "channel sums are kept apart in scaled mode only");
-    v4i sums[SUMS ? NPASS : 1][SUMS ? 36 : 1];
+    v4i sums[SUMS ? NPASS : 1][SUMS ? kChannelSums : 1];
     if constexpr (SUMS) {
 #pragma unroll
         for (int pass = 0; pass < NPASS; ++pass)
 #pragma unroll
-            for (int i = 0; i < 36; ++i) sums[pass][i] = (v4i){0, 0, 0, 0};
+            for (int i = 0; i < kChannelSums; ++i) sums[pass][i] = (v4i){0, 0, 0, 0};
     }
     static_assert(ProductPhase<MODE, 0>::NPRE == kFilterPrefetch && ProductPhase<MODE, 1>::NPRE == kFilterPrefetch,
                   "the wait for the direct patch transfer counts the filter fragments requested after it");
@@ -706,12 +718,12 @@ hipError_t launch_mode(const int8_t* x, const uint8_t* blob, const BlobLayout& b
         const long long workgroups = (long long)ceil_div(p.T, kFusedTiles) * (p.Kp / kFusedFilters);
         if (workgroups > compute_units()) {
             if (mode == WG_LOSSLESS) return launch<LAYOUT, LOAD, WG_LOSSLESS, false, true>(x, blob, bl, y, p, s);
-            if (p.CB == 1) return launch<LAYOUT, LOAD, WG_SCALED, false, true>(x, blob, bl, y, p, s);
+            return p.CB == 1 ? launch<LAYOUT, LOAD, WG_SCALED, false, true>(x, blob, bl, y, p, s)
+                             : launch<LAYOUT, LOAD, WG_SCALED, true, true>(x, blob, bl, y, p, s);
         }
     }
     if (mode == WG_LOSSLESS) return launch<LAYOUT, LOAD, WG_LOSSLESS, false, false>(x, blob, bl, y, p, s);
     if (p.CB == 1) return launch<LAYOUT, LOAD, WG_SCALED, false, false>(x, blob, bl, y, p, s);
-    // with separate channel sums for 64 filters the kernel no longer fits the register file
     return launch<LAYOUT, LOAD, WG_SCALED, true, false>(x, blob, bl, y, p, s);
 }
 
