@@ -2,7 +2,8 @@
 // multiplications per 4x4 output tile and channel pair that Section 3.4 compares
 // against:  y[n,k,h,w] = sum_{c,a,b} x[n,c,h+a-1,w+b-1] g[k,c,a,b].
 // Serves as the on-device cross-check and the direct baseline.  Channels-last tensors with
-// C % 16 == 0, K % 4 == 0 and 16-byte aligned pointers run on the matrix cores; everything else
+// K % 4 == 0 and a 16-byte aligned output run on the matrix cores (operands are staged with
+// 16-byte loads when C % 16 == 0 and the pointers allow it, else byte by byte); everything else
 // takes the plain kernel.
 #include "wg_internal.h"
 
@@ -65,6 +66,22 @@ constexpr int kDirectFilters = 64;
 
 __device__ inline int row_swizzle(int row) { return (row >> 2) & 3; }
 
+// 16 bytes of channels c..c+15 at `at` (channel 0 of a pixel or filter tap): one 16-byte load when
+// the tensors allow it (VEC16), else byte by byte with channels beyond C read as zero.
+template <bool VEC16>
+__device__ inline v4i load_channels(const int8_t* at, int c, int C) {
+    if constexpr (VEC16) {
+        return *reinterpret_cast<const v4i*>(at + c);
+    } else {
+        v4i v = {0, 0, 0, 0};
+#pragma unroll
+        for (int b = 0; b < 16; ++b)
+            if (c + b < C) v[b >> 2] |= (int)(uint8_t)at[c + b] << (8 * (b & 3));
+        return v;
+    }
+}
+
+template <bool VEC16>
 __global__ __launch_bounds__(256) void direct_conv_mfma_kernel(const int8_t* __restrict__ x,
                                                                const int8_t* __restrict__ g,
                                                                int32_t* __restrict__ y, Problem p, int patches_h,
@@ -92,14 +109,14 @@ __global__ __launch_bounds__(256) void direct_conv_mfma_kernel(const int8_t* __r
             const int h = h0 - 1 + pix / kHaloCols, w = w0 - 1 + pix % kHaloCols, c = cb * kCBlock + (item & 3) * 16;
             const bool ok = pix < kHaloPixels && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W && c < p.C;
             in[it] = zero;
-            if (ok) in[it] = *reinterpret_cast<const v4i*>(x + (((size_t)n * p.H + h) * p.W + w) * p.C + c);
+            if (ok) in[it] = load_channels<VEC16>(x + (((size_t)n * p.H + h) * p.W + w) * p.C, c, p.C);
         }
 #pragma unroll
         for (int it = 0; it < 9; ++it) {
             const int item = tid + 256 * it, kt = item >> 2;   // kt = filter * 9 + tap: contiguous in memory
             const int kk = k0 + kt / 9, c = cb * kCBlock + (item & 3) * 16;
             flt[it] = zero;
-            if (kk < p.K && c < p.C) flt[it] = *reinterpret_cast<const v4i*>(g + ((size_t)k0 * 9 + kt) * p.C + c);
+            if (kk < p.K && c < p.C) flt[it] = load_channels<VEC16>(g + ((size_t)k0 * 9 + kt) * p.C, c, p.C);
         }
 #pragma unroll
         for (int it = 0; it < 3; ++it) {
@@ -181,10 +198,13 @@ __global__ __launch_bounds__(256) void requant_relu_pool_kernel(const int32_t* _
 hipError_t launch_direct_conv(const int8_t* x, const int8_t* w, int32_t* y, const Problem& p, int layout,
                               hipStream_t s) {
     auto aligned16 = [](const void* q) { return reinterpret_cast<uintptr_t>(q) % 16 == 0; };
-    if (layout == WG_NHWC && p.C % 16 == 0 && p.K % 4 == 0 && aligned16(x) && aligned16(w) && aligned16(y)) {
+    if (layout == WG_NHWC && p.K % 4 == 0 && aligned16(y)) {
         const int patches_h = ceil_div(p.H, kPatchRows), patches_w = ceil_div(p.W, kPatchCols);
         dim3 grid((unsigned)(p.N * patches_h * patches_w), ceil_div(p.K, kDirectFilters));
-        direct_conv_mfma_kernel<<<grid, 256, 0, s>>>(x, w, y, p, patches_h, patches_w);
+        if (p.C % 16 == 0 && aligned16(x) && aligned16(w))
+            direct_conv_mfma_kernel<true><<<grid, 256, 0, s>>>(x, w, y, p, patches_h, patches_w);
+        else
+            direct_conv_mfma_kernel<false><<<grid, 256, 0, s>>>(x, w, y, p, patches_h, patches_w);
         return hipGetLastError();
     }
     const long long npix = (long long)p.N * p.H * p.W;
