@@ -108,6 +108,23 @@ int winograd_conv2d_int8(const int8_t* x_dev, const void* packed_dev, int32_t* y
                          void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The same convolution with the requantisation that follows each quantised
+ * convolution in a network (Section 4.4) applied before the store, so a layer
+ * stack passes int8 from layer to layer and the int32 outputs never reach
+ * memory.  The result equals winograd_conv2d_int8 followed by
+ * requant_relu_pool_int8 with the same (shift, relu, pool) bit for bit:
+ *   v = (y + 2^(shift-1)) >> shift (shift = 0: v = y), clamped to [0,127] if
+ *   relu else [-128,127], then an optional 2x2 stride-2 maximum (H and W must
+ *   then be even, else WG_EUNSUPPORTED).
+ * out_dev: int8 in `layout`, [N][K][H][W] or [N][H][W][K], with H/2 and W/2
+ * when pool != 0; every element written.  0 <= shift <= 31.  Always runs the
+ * single-kernel path and needs no workspace.
+ */
+int winograd_conv2d_int8_requant(const int8_t* x_dev, const void* packed_dev, int8_t* out_dev,
+                                 int N, int C, int H, int W, int K, int layout, int mode,
+                                 int shift, int relu, int pool, void* hip_stream);
+
+/*
  * Direct evaluation of the same convolution (the 144-multiplication method
  * that Section 3.4 compares against):
  *   y[n,k,h,w] = sum_{c,a,b} x[n,c,h+a-1,w+b-1] * g[k,c,a,b],  x = 0 outside.

@@ -8,7 +8,8 @@ not load the library; the first call does, and fails loudly if it is absent.
 from . import workloads  # noqa: F401
 from .binding import (  # noqa: F401
     LOSSLESS, SCALED, NCHW, NHWC, MAX_CHANNELS, PackedFilter, WinogradError,
-    winograd_filter_transform, winograd_conv2d_int8, direct_conv2d_int8, requant_relu_pool_int8,
+    winograd_filter_transform, winograd_conv2d_int8, winograd_conv2d_int8_requant, direct_conv2d_int8,
+    requant_relu_pool_int8,
     packed_filter_bytes, workspace_bytes, make_workspace, load_library,
     debug_input_operands, debug_filter_operands, debug_contraction, stage_times, force_path, conv2d_path, AUTO, STAGED, FUSED,
 )

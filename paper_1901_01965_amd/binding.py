@@ -50,6 +50,7 @@ def load_library():
         "winograd_filter_transform": (i, [vp, i, i, i, i, vp, sz, vp]),
         "winograd_packed_filter_check": (i, [vp, i, i, i, vp]),
         "winograd_conv2d_int8": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp, sz, vp]),
+        "winograd_conv2d_int8_requant": (i, [vp, vp, vp, i, i, i, i, i, i, i, i, i, i, vp]),
         "winograd_conv2d_int8_stage_times": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp, sz, vp, i, vp]),
         "direct_conv2d_int8": (i, [vp, vp, vp, i, i, i, i, i, i, vp]),
         "requant_relu_pool_int8": (i, [vp, vp, i, i, i, i, i, i, i, i, vp]),
@@ -68,7 +69,8 @@ EXPORTED_SYMBOLS = (
     "winograd_status_string", "winograd_num_activation_planes", "winograd_num_filter_planes",
     "winograd_debug_force_path", "winograd_conv2d_path", "winograd_debug_tile_decode",
     "winograd_packed_filter_bytes", "winograd_workspace_bytes", "winograd_filter_transform",
-    "winograd_packed_filter_check", "winograd_conv2d_int8", "winograd_conv2d_int8_stage_times",
+    "winograd_packed_filter_check", "winograd_conv2d_int8", "winograd_conv2d_int8_requant",
+    "winograd_conv2d_int8_stage_times",
     "direct_conv2d_int8", "requant_relu_pool_int8",
     "winograd_debug_input_operands", "winograd_debug_filter_operands", "winograd_debug_contraction",
 )
@@ -174,6 +176,23 @@ def winograd_conv2d_int8(x, packed, layout=NCHW, out=None, workspace=None):
     _check(load_library().winograd_conv2d_int8(_ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout,
                                                packed.mode, _ptr(workspace), workspace.numel(), _stream()),
            "winograd_conv2d_int8")
+    return out
+
+
+def winograd_conv2d_int8_requant(x, packed, shift, relu=True, pool=False, layout=NCHW, out=None):
+    """Convolution with requantisation, ReLU and optional 2x2 max-pool applied before the store: int8 output in
+    `layout` (H/2 x W/2 when pool), equal to winograd_conv2d_int8 followed by requant_relu_pool_int8."""
+    layout = _LAYOUTS[layout]
+    _need(x, torch.int8, "x")
+    N, C, H, W = _dims(x, layout)
+    K = packed.K
+    Ho, Wo = (H // 2, W // 2) if pool else (H, W)
+    if out is None:
+        shape = (N, K, Ho, Wo) if layout == NCHW else (N, Ho, Wo, K)
+        out = torch.empty(shape, dtype=torch.int8, device=x.device)
+    _check(load_library().winograd_conv2d_int8_requant(_ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout,
+                                                       packed.mode, int(shift), int(relu), int(pool), _stream()),
+           "winograd_conv2d_int8_requant")
     return out
 
 

@@ -109,12 +109,26 @@ int winograd_conv2d_int8(const int8_t* x_dev, const void* packed_dev, int32_t* y
     const Problem p = make_problem(N, C, H, W, K);
     const WorkspaceLayout wl = workspace_layout(p, mode);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    if (use_fused()) return status_of(launch_fused_conv(x_dev, packed_dev, y_dev, p, layout, mode, s));
+    if (use_fused()) return status_of(launch_fused_conv(x_dev, packed_dev, y_dev, p, layout, mode, no_int8_epilogue(), s));
     int8_t* V = static_cast<int8_t*>(workspace_dev) + wl.v_off;
     int32_t* M = reinterpret_cast<int32_t*>(static_cast<uint8_t*>(workspace_dev) + wl.m_off);
     if (int st = status_of(launch_input_transform(x_dev, p, layout, mode, V, s))) return st;
     if (int st = status_of(launch_contraction(V, packed_dev, M, p, mode, s))) return st;
     return status_of(launch_output_transform(M, packed_dev, y_dev, p, layout, mode, s));
+}
+
+int winograd_conv2d_int8_requant(const int8_t* x_dev, const void* packed_dev, int8_t* out_dev, int N, int C, int H,
+                                 int W, int K, int layout, int mode, int shift, int relu, int pool,
+                                 void* hip_stream) {
+    if (!x_dev || !packed_dev || !out_dev || !valid_layout(layout) || !valid_mode(mode)) return WG_EINVAL;
+    if (shift < 0 || shift > 31) return WG_EINVAL;
+    if (int st = check_shape(N, C, H, W, K)) return st;
+    if (!aligned(x_dev, 4) || !aligned(out_dev, 4) || !aligned(packed_dev, 256)) return WG_EINVAL;
+    if (pool && ((H | W) & 1)) return WG_EUNSUPPORTED;
+    const Problem p = make_problem(N, C, H, W, K);
+    return status_of(launch_fused_conv(x_dev, packed_dev, nullptr, p, layout, mode,
+                                       make_int8_epilogue(out_dev, shift, relu != 0, pool != 0),
+                                       static_cast<hipStream_t>(hip_stream)));
 }
 
 int winograd_conv2d_path(int N, int C, int H, int W, int K, int mode) {
@@ -163,7 +177,7 @@ int winograd_conv2d_int8_stage_times(const int8_t* x_dev, const void* packed_dev
             if (stage == 0)      e = launch_input_transform(x_dev, p, layout, mode, V, s);
             else if (stage == 1) e = launch_contraction(V, packed_dev, M, p, mode, s);
             else if (stage == 2) e = launch_output_transform(M, packed_dev, y_dev, p, layout, mode, s);
-            else                 e = launch_fused_conv(x_dev, packed_dev, y_dev, p, layout, mode, s);
+            else                 e = launch_fused_conv(x_dev, packed_dev, y_dev, p, layout, mode, no_int8_epilogue(), s);
         }
         if (e == hipSuccess) e = hipEventRecord(e1, s);
         if (e == hipSuccess) e = hipEventSynchronize(e1);

@@ -438,6 +438,19 @@ struct ScaledSums {
 constexpr int kChannelSums = 18;
 static_assert(ScaledSums<0>::kSums == kChannelSums && ScaledSums<1>::kSums == kChannelSums, "both halves keep 18 sums");
 
+// The optional int8 epilogue: v = (y + round) >> shift clamped to [lo, 127].
+__device__ inline int requantise(int y, const Int8Epilogue& q) {
+    return min(max((y + q.round) >> q.shift, q.lo), 127);
+}
+__device__ inline v4i requantise(v4i y, const Int8Epilogue& q) {
+    y = (y + q.round) >> q.shift;
+    const v4i lo = {q.lo, q.lo, q.lo, q.lo}, hi = {127, 127, 127, 127};
+    return __builtin_elementwise_min(__builtin_elementwise_max(y, lo), hi);
+}
+__device__ inline uint32_t pack_bytes(v4i v) {
+    return (uint32_t)(v[0] & 0xff) | ((uint32_t)(v[1] & 0xff) << 8) | ((uint32_t)(v[2] & 0xff) << 16) | ((uint32_t)v[3] << 24);
+}
+
 // grid: (ceil(T/16), Kp/32).  256 threads: in the transform phase one thread per (tile,
 // four channels); in the product phase wave w owns filter block (w & 1) and half of the
 // rows of M (w >> 1: rows 0,1,2 or rows 5,3); all four waves stage their partial outputs
@@ -447,10 +460,11 @@ static_assert(ScaledSums<0>::kSums == kChannelSums && ScaledSums<1>::kSums == kC
 // channel block is followed by two passes over the entries, one per 32 filters, each with its own
 // outputs; used when there are more workgroups than compute units, where halving the number of
 // repeated transforms outweighs the longer workgroup.
-template <int LAYOUT, int LOAD, int MODE, bool SUMS, bool WIDE>
-__global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restrict__ x,
-                                                         const uint8_t* __restrict__ blob, size_t table_off,
-                                                         size_t planes_off, int32_t* __restrict__ y, Problem p) {
+// Q8: the finished outputs are requantised (and pooled) to int8 at q8.out instead of stored to y.
+template <int LAYOUT, int LOAD, int MODE, bool SUMS, bool WIDE, bool Q8>
+__device__ __forceinline__ void fused_conv_body(const int8_t* __restrict__ x, const uint8_t* __restrict__ blob,
+                                                size_t table_off, size_t planes_off, int32_t* __restrict__ y,
+                                                const Problem p, const Int8Epilogue q8) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kblock = wave & 1, half = wave >> 1;
@@ -603,6 +617,39 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
             // thread: filters 4*k4..4*k4+3; pass ps: output row i = ps/2, tile = 8*(ps%2) + px/4, column j = px%4
             const int k4 = tid & 7, px = tid >> 3, j = px & 3;
             const int kk = kbase + 4 * k4;
+            if constexpr (Q8) {
+            auto staged = [&](int o, int tile) {   // finished int32 outputs of four filters
+                const int at = (o * 16 + tile) * kRow + 4 * k4;
+                return (*reinterpret_cast<const v4i*>(parki + at) + *reinterpret_cast<const v4i*>(parki + kHalf + at) + rnd) >> 4;
+            };
+            if (q8.pool) {
+                // 16 tiles x 2x2 pooled pixels = 64 pixels; thread: pixels px and px + 32
+    #pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int pp = px + 32 * e, tile = pp >> 2, pi = (pp >> 1) & 1, pj = pp & 1;
+                    v4i best = requantise(staged(4 * (2 * pi) + 2 * pj, tile), q8);
+                    best = __builtin_elementwise_max(best, requantise(staged(4 * (2 * pi) + 2 * pj + 1, tile), q8));
+                    best = __builtin_elementwise_max(best, requantise(staged(4 * (2 * pi + 1) + 2 * pj, tile), q8));
+                    best = __builtin_elementwise_max(best, requantise(staged(4 * (2 * pi + 1) + 2 * pj + 1, tile), q8));
+                    const int n = __shfl(my_n, tile), row = __shfl(my_row, tile), col = __shfl(my_col, tile);
+                    const bool ok = __shfl(my_origin, tile) >= 0 && row + 2 * pi < p.H && col + 2 * pj < p.W && kk < p.K;
+                    const size_t at = (((size_t)n * (p.H >> 1) + (row >> 1) + pi) * (p.W >> 1) + (col >> 1) + pj) * p.K + kk;
+                    if (ok) *reinterpret_cast<uint32_t*>(q8.out + at) = pack_bytes(best);
+                }
+                return;
+            }
+            {
+    #pragma unroll
+                for (int ps = 0; ps < 8; ++ps) {
+                    const int i = ps >> 1, tile = 8 * (ps & 1) + (px >> 2);
+                    const v4i v = requantise(staged(4 * i + j, tile), q8);
+                    const int origin = __shfl(my_origin, tile);
+                    const bool ok = origin >= 0 && __shfl(my_row, tile) + i < p.H && __shfl(my_col, tile) + j < p.W && kk < p.K;
+                    if (ok) *reinterpret_cast<uint32_t*>(q8.out + (size_t)origin + (size_t)(i * p.W + j) * p.K + kk) = pack_bytes(v);
+                }
+                return;
+            }
+            }
             int32_t* first[2];   // output row 0 of the thread's two tiles (e = 0, 1); null where nothing is stored
             int rows[2];         // output rows of that tile inside the image
     #pragma unroll
@@ -634,6 +681,35 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
     #pragma unroll
         for (int i = 0; i < 16; ++i) park[(wave * 16 + i) * 64 + lane] = Yp[i];
         __syncthreads();
+        if constexpr (Q8) {
+            // One byte per (tile, output pixel, filter), in the order of the output layout; lg = log2
+            // of the output pixels per tile side (4, or 2 after pooling).
+            const int lg = q8.pool ? 1 : 2, side = 1 << lg, span = q8.pool ? 2 : 1;
+            const int Ho = q8.pool ? p.H >> 1 : p.H, Wo = q8.pool ? p.W >> 1 : p.W;
+            const int items = (16 * 32) << (2 * lg);
+            for (int e = tid; e < items; e += 256) {
+                int kl, tile, pi, pj;
+                if constexpr (LAYOUT == WG_NHWC) {
+                    kl = e & 31; pj = (e >> 5) & (side - 1); pi = (e >> (5 + lg)) & (side - 1); tile = e >> (5 + 2 * lg);
+                } else {
+                    pj = e & (side - 1); tile = (e >> lg) & 15; pi = (e >> (lg + 4)) & (side - 1); kl = e >> (2 * lg + 4);
+                }
+                int best = -129;
+                for (int a = 0; a < span; ++a)
+                    for (int b = 0; b < span; ++b) {
+                        const int o = 4 * (span * pi + a) + span * pj + b;
+                        const int at = ((((kl >> 4) * 16 + o) * 64) + (tile >> 2) * 16 + (kl & 15)) * 4 + (tile & 3);
+                        best = max(best, requantise((parki[at] + parki[at + 2 * 16 * 64 * 4] + rnd) >> 4, q8));
+                    }
+                const int n = __shfl(my_n, tile), row = __shfl(my_row, tile), col = __shfl(my_col, tile);
+                const bool ok = __shfl(my_origin, tile) >= 0 && row + span * pi < p.H && col + span * pj < p.W && kbase + kl < p.K;
+                const int oh = (q8.pool ? row >> 1 : row) + pi, ow = (q8.pool ? col >> 1 : col) + pj;
+                const size_t at = LAYOUT == WG_NHWC ? (((size_t)n * Ho + oh) * Wo + ow) * p.K + kbase + kl
+                                                    : (((size_t)n * p.K + kbase + kl) * Ho + oh) * Wo + ow;
+                if (ok) q8.out[at] = (int8_t)best;
+            }
+            return;
+        }
         int v[32];
         if constexpr (LAYOUT == WG_NHWC) {
             // thread: filter kl and output column j fixed; iteration it: tile it/2, output row 2(it%2) + tid/128
@@ -678,6 +754,20 @@ __global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restric
     }
 }
 
+template <int LAYOUT, int LOAD, int MODE, bool SUMS, bool WIDE>
+__global__ __launch_bounds__(256) void fused_conv_kernel(const int8_t* __restrict__ x,
+                                                         const uint8_t* __restrict__ blob, size_t table_off,
+                                                         size_t planes_off, int32_t* __restrict__ y, Problem p) {
+    fused_conv_body<LAYOUT, LOAD, MODE, SUMS, WIDE, false>(x, blob, table_off, planes_off, y, p, Int8Epilogue{});
+}
+
+template <int LAYOUT, int LOAD, int MODE, bool SUMS, bool WIDE>
+__global__ __launch_bounds__(256) void fused_conv_int8_kernel(const int8_t* __restrict__ x,
+                                                              const uint8_t* __restrict__ blob, size_t table_off,
+                                                              size_t planes_off, Problem p, Int8Epilogue q8) {
+    fused_conv_body<LAYOUT, LOAD, MODE, SUMS, WIDE, true>(x, blob, table_off, planes_off, nullptr, p, q8);
+}
+
 // Compute units of the current device (256 on MI355X), asked once.
 int compute_units() {
     static int cus = 0;
@@ -692,52 +782,63 @@ int compute_units() {
     return cus;
 }
 
-template <int LAYOUT, int LOAD, int MODE, bool SUMS, bool WIDE>
+template <int LAYOUT, int LOAD, int MODE, bool SUMS, bool WIDE, bool Q8>
 hipError_t launch(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
-                  hipStream_t s) {
+                  const Int8Epilogue& q8, hipStream_t s) {
     constexpr int lds_bytes = kLdsBytes + (LOAD == kLoadDirect ? kRawBytes : 0);
+    const void* kernel = Q8 ? reinterpret_cast<const void*>(&fused_conv_int8_kernel<LAYOUT, LOAD, MODE, SUMS, WIDE>)
+                            : reinterpret_cast<const void*>(&fused_conv_kernel<LAYOUT, LOAD, MODE, SUMS, WIDE>);
     static bool configured = false;   // per template instance
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_conv_kernel<LAYOUT, LOAD, MODE, SUMS, WIDE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         configured = true;
     }
     dim3 grid(ceil_div(p.T, kFusedTiles), p.Kp / (kFusedFilters * (WIDE ? 2 : 1)));
-    fused_conv_kernel<LAYOUT, LOAD, MODE, SUMS, WIDE><<<grid, 256, lds_bytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p);
+    if constexpr (Q8)
+        fused_conv_int8_kernel<LAYOUT, LOAD, MODE, SUMS, WIDE><<<grid, 256, lds_bytes, s>>>(x, blob, bl.table_off, bl.planes_off, p, q8);
+    else
+        fused_conv_kernel<LAYOUT, LOAD, MODE, SUMS, WIDE><<<grid, 256, lds_bytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p);
     return hipGetLastError();
 }
 
-template <int LAYOUT, int LOAD>
+template <int LAYOUT, int LOAD, bool Q8>
 hipError_t launch_mode(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
-                       int mode, hipStream_t s) {
+                       int mode, const Int8Epilogue& q8, hipStream_t s) {
     // 64 filters per workgroup once the 32-filter grid would need more than one round of the
     // compute units (Kp is a multiple of 64).  Only the direct-transfer variants have the
     // registers for it (the others hold a patch in registers across the product phase).
     if constexpr (LOAD == kLoadDirect) {
         const long long workgroups = (long long)ceil_div(p.T, kFusedTiles) * (p.Kp / kFusedFilters);
         if (workgroups > compute_units()) {
-            if (mode == WG_LOSSLESS) return launch<LAYOUT, LOAD, WG_LOSSLESS, false, true>(x, blob, bl, y, p, s);
-            return p.CB == 1 ? launch<LAYOUT, LOAD, WG_SCALED, false, true>(x, blob, bl, y, p, s)
-                             : launch<LAYOUT, LOAD, WG_SCALED, true, true>(x, blob, bl, y, p, s);
+            if (mode == WG_LOSSLESS) return launch<LAYOUT, LOAD, WG_LOSSLESS, false, true, Q8>(x, blob, bl, y, p, q8, s);
+            return p.CB == 1 ? launch<LAYOUT, LOAD, WG_SCALED, false, true, Q8>(x, blob, bl, y, p, q8, s)
+                             : launch<LAYOUT, LOAD, WG_SCALED, true, true, Q8>(x, blob, bl, y, p, q8, s);
         }
     }
-    if (mode == WG_LOSSLESS) return launch<LAYOUT, LOAD, WG_LOSSLESS, false, false>(x, blob, bl, y, p, s);
-    if (p.CB == 1) return launch<LAYOUT, LOAD, WG_SCALED, false, false>(x, blob, bl, y, p, s);
-    return launch<LAYOUT, LOAD, WG_SCALED, true, false>(x, blob, bl, y, p, s);
+    if (mode == WG_LOSSLESS) return launch<LAYOUT, LOAD, WG_LOSSLESS, false, false, Q8>(x, blob, bl, y, p, q8, s);
+    if (p.CB == 1) return launch<LAYOUT, LOAD, WG_SCALED, false, false, Q8>(x, blob, bl, y, p, q8, s);
+    return launch<LAYOUT, LOAD, WG_SCALED, true, false, Q8>(x, blob, bl, y, p, q8, s);
+}
+
+template <bool Q8>
+hipError_t launch_layout(const int8_t* x, const uint8_t* b, const BlobLayout& bl, int32_t* y, const Problem& p,
+                         int layout, int mode, const Int8Epilogue& q8, hipStream_t s) {
+    if (layout == WG_NHWC && p.C % 16 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0)
+        return launch_mode<WG_NHWC, kLoadDirect, Q8>(x, b, bl, y, p, mode, q8, s);
+    if (layout == WG_NHWC && p.C % 4 == 0) return launch_mode<WG_NHWC, kLoadDwords, Q8>(x, b, bl, y, p, mode, q8, s);
+    if (layout == WG_NHWC) return launch_mode<WG_NHWC, kLoadBytes, Q8>(x, b, bl, y, p, mode, q8, s);
+    return launch_mode<WG_NCHW, kLoadBytes, Q8>(x, b, bl, y, p, mode, q8, s);
 }
 
 }  // namespace
 
 hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int layout, int mode,
-                             hipStream_t s) {
+                             const Int8Epilogue& q8, hipStream_t s) {
     const BlobLayout bl = blob_layout(p.Kp, p.CB, mode);
     const uint8_t* b = static_cast<const uint8_t*>(blob);
-    if (layout == WG_NHWC && p.C % 16 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0)
-        return launch_mode<WG_NHWC, kLoadDirect>(x, b, bl, y, p, mode, s);
-    if (layout == WG_NHWC && p.C % 4 == 0) return launch_mode<WG_NHWC, kLoadDwords>(x, b, bl, y, p, mode, s);
-    if (layout == WG_NHWC) return launch_mode<WG_NHWC, kLoadBytes>(x, b, bl, y, p, mode, s);
-    return launch_mode<WG_NCHW, kLoadBytes>(x, b, bl, y, p, mode, s);
+    return q8.out != nullptr ? launch_layout<true>(x, b, bl, y, p, layout, mode, q8, s)
+                             : launch_layout<false>(x, b, bl, y, p, layout, mode, q8, s);
 }
 
 }  // namespace wg

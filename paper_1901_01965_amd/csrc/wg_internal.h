@@ -150,9 +150,21 @@ hipError_t launch_contraction(const int8_t* V, const void* blob, int32_t* M, con
                               int mode, hipStream_t s);
 hipError_t launch_output_transform(const int32_t* M, const void* blob, int32_t* y, const Problem& p,
                                    int layout, int mode, hipStream_t s);
+// What the single-kernel path does with a finished int32 output.  out == nullptr: store it to y.
+// Otherwise y is unused and the kernel stores int8: v = (y + round) >> shift clamped to
+// [lo, 127], followed by a 2x2 stride-2 maximum when pool != 0 (H and W even; a 4x4 output tile
+// holds whole pooling windows).
+struct Int8Epilogue {
+    int8_t* out;
+    int shift, round, lo, pool;
+};
+inline Int8Epilogue no_int8_epilogue() { return Int8Epilogue{nullptr, 0, 0, 0, 0}; }
+inline Int8Epilogue make_int8_epilogue(int8_t* out, int shift, bool relu, bool pool) {
+    return Int8Epilogue{out, shift, shift > 0 ? 1 << (shift - 1) : 0, relu ? 0 : -128, pool ? 1 : 0};
+}
 // Single-kernel path (no workspace traffic).
 hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int layout,
-                             int mode, hipStream_t s);
+                             int mode, const Int8Epilogue& q8, hipStream_t s);
 hipError_t launch_direct_conv(const int8_t* x, const int8_t* w, int32_t* y, const Problem& p,
                               int layout, hipStream_t s);
 hipError_t launch_requant_relu_pool(const int32_t* y, int8_t* out, int N, int K, int H, int W,

@@ -113,6 +113,15 @@ def test_validation_errors_return_before_any_launch(lib):
     assert rq(good, good2, 1, 4, 8, 8, 0, 32, 1, 0, None) == EINVAL   # shift out of range
     assert rq(good, good2, 1, 4, 7, 8, 0, 3, 1, 1, None) == EUNSUPPORTED   # odd H with pooling
 
+    cq = lib.winograd_conv2d_int8_requant
+    assert cq(good, good2, None, 1, 4, 8, 8, 4, 0, 0, 3, 1, 0, None) == EINVAL
+    assert cq(good, good2, good3, 1, 4, 8, 8, 4, 0, 0, -1, 1, 0, None) == EINVAL     # shift out of range
+    assert cq(good, good2, good3, 1, 4, 8, 8, 4, 0, 0, 32, 1, 0, None) == EINVAL
+    assert cq(good, good2, good3, 1, 4, 8, 8, 4, 0, 2, 3, 1, 0, None) == EINVAL      # unknown mode
+    assert cq(good, good2, odd, 1, 4, 8, 8, 4, 0, 0, 3, 1, 0, None) == EINVAL        # misaligned output
+    assert cq(good, good2, good3, 1, 4, 8, 7, 4, 0, 0, 3, 1, 1, None) == EUNSUPPORTED   # odd W with pooling
+    assert cq(good, good2, good3, 1, 1000, 8, 8, 4, 0, 0, 3, 1, 0, None) == EUNSUPPORTED
+
     st = lib.winograd_conv2d_int8_stage_times
     assert st(good, good2, good3, 1, 4, 8, 8, 4, 0, 0, p(0x40000), ws_bytes, None, 0, good) == EINVAL
     assert st(good, good2, good3, 1, 4, 8, 8, 4, 0, 0, p(0x40000), ws_bytes, None, 1, None) == EINVAL

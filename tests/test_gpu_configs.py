@@ -83,6 +83,10 @@ def _vgg_stack_gpu(x, gs, mode, layers):
         packed = wg.winograd_filter_transform(gd, wg.NHWC, mode)
         y = wg.winograd_conv2d_int8(act, packed, wg.NHWC)
         nxt = wg.requant_relu_pool_int8(y, wl.VGG16_SHIFTS[i], True, pool, wg.NHWC)
+        # the same layer with the requantisation inside the convolution kernel; nxt itself is checked
+        # against the oracle by the callers
+        one_kernel = wg.winograd_conv2d_int8_requant(act, packed, wl.VGG16_SHIFTS[i], True, pool, wg.NHWC)
+        assert torch.equal(one_kernel, nxt), "layer %d: int8 epilogue differs from the two-kernel result" % i
         outs.append((wl.from_nhwc(y.cpu().numpy()), wl.from_nhwc(nxt.cpu().numpy())))
         act = nxt
     return outs

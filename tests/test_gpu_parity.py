@@ -260,6 +260,49 @@ def test_requant_relu_pool(layout):
                 assert np.array_equal(_y(got, layout), oracle.requant_relu_pool(y, shift, relu, pool))
 
 
+REQUANT_SHAPES = [  # N, C, K, H, W: every load variant, both store paths, ragged tiles and filters, 64-filter groups
+    (2, 16, 32, 8, 12), (1, 3, 5, 6, 10), (2, 20, 36, 10, 6), (1, 70, 33, 12, 8), (1, 64, 7, 4, 4),
+    (3, 32, 64, 18, 22), (1, 130, 68, 8, 8), (5, 16, 128, 40, 36), (1, 1, 1, 2, 2),
+]
+
+
+@pytest.mark.parametrize("mode", [wg.LOSSLESS, wg.SCALED])
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("shape", REQUANT_SHAPES)
+def test_conv_with_int8_epilogue_equals_oracle_conv_then_requantisation(shape, layout, mode):
+    """The int8 store of the single-kernel path against the oracle's convolution followed by the oracle's
+    requantisation, ReLU and pooling; the shift is chosen so that the outputs spread over the int8 range and some
+    saturate."""
+    N, C, K, H, W = shape
+    x, g = wl.make_custom(N, C, K, H, W, seed=58)
+    want32 = oracle.direct_conv2d(x, g) if mode == wg.LOSSLESS else oracle.winograd_conv2d(x, g, oracle.SCALED)[0]
+    top = max(1, int(np.abs(want32).max()))
+    shifts = sorted({0, max(0, top.bit_length() - 8), max(0, top.bit_length() - 6)})
+    packed = wg.winograd_filter_transform(_g(g, layout), layout, mode)
+    xd = _x(x, layout)
+    for shift in shifts:
+        for relu in (True, False):
+            for pool in (False, True):
+                got = wg.winograd_conv2d_int8_requant(xd, packed, shift, relu, pool, layout)
+                assert np.array_equal(_y(got, layout), oracle.requant_relu_pool(want32, shift, relu, pool)), (
+                    shift, relu, pool)
+
+
+def test_int8_epilogue_odd_sizes_without_pooling_and_fill():
+    """Odd H and W (ragged tiles) without pooling; the output buffer is pre-filled so that an element the kernel
+    skipped would show."""
+    x, g = wl.make_custom(2, 24, 40, 7, 13, seed=59)
+    want32 = oracle.direct_conv2d(x, g)
+    for layout in LAYOUTS:
+        packed = wg.winograd_filter_transform(_g(g, layout), layout, wg.LOSSLESS)
+        shape = (2, 40, 7, 13) if layout == wg.NCHW else (2, 7, 13, 40)
+        out = torch.full(shape, 77, dtype=torch.int8, device="cuda")
+        wg.winograd_conv2d_int8_requant(_x(x, layout), packed, 9, False, False, layout, out=out)
+        assert np.array_equal(_y(out, layout), oracle.requant_relu_pool(want32, 9, False, False))
+        with pytest.raises(wg.WinogradError):
+            wg.winograd_conv2d_int8_requant(_x(x, layout), packed, 9, True, True, layout)
+
+
 @pytest.mark.parametrize("path", PATHS, indirect=True)
 def test_results_do_not_depend_on_workspace_contents_and_repeat_exactly(path):
     x, g = wl.make_custom(2, 24, 40, 14, 9, seed=40)
