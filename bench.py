@@ -227,6 +227,30 @@ def main():
     direct_ms = (time.perf_counter() - t0) / direct_runs * 1e3
     same_as_direct = bool(torch.equal(y, yd)) if mode == wg.LOSSLESS else None
 
+    # the same convolution with requantisation and ReLU applied before the store (int8 output), for context
+    shift = max(0, int(y.abs().max().item()).bit_length() - 7)
+    y8 = torch.empty(out_shape, dtype=torch.int8, device=dev)
+
+    def int8_step():
+        wg.winograd_conv2d_int8_requant(xd, packed, shift, True, False, layout, out=y8)
+
+    for _ in range(3):
+        int8_step()
+    torch.cuda.synchronize()
+    qgraph = None if args.eager else capture_steps(torch, int8_step, args.steps)
+    if qgraph is not None:
+        qgraph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    if qgraph is not None:
+        qgraph.replay()
+    else:
+        for _ in range(args.steps):
+            int8_step()
+    torch.cuda.synchronize()
+    int8_ms = (time.perf_counter() - t0) / args.steps * 1e3
+    int8_matches = bool(torch.equal(y8, wg.requant_relu_pool_int8(y, shift, True, False, layout)))
+
     result = {
         "metric": "direct-equivalent int8 conv TOPS, 56x56x64 layer, 1 GPU" if args.case == "cfg2"
                   else "direct-equivalent int8 conv TOPS, %s, 1 GPU" % args.case,
@@ -242,6 +266,9 @@ def main():
         "kernels": kernels,
         "filter_transform_ms": round(filter_ms, 4),
         "direct_conv_ms": round(direct_ms, 4),
+        "int8_epilogue": {"ms_per_step": round(int8_ms, 5), "TOPS": round(case.direct_ops / (int8_ms * 1e-3) / 1e12, 2),
+                          "shift": shift, "relu": True, "pool": False,
+                          "equals_int32_path_then_requantisation": int8_matches},
         "gpu_lossless_equals_gpu_direct": same_as_direct,
     }
 

@@ -618,37 +618,49 @@ __device__ __forceinline__ void fused_conv_body(const int8_t* __restrict__ x, co
             const int k4 = tid & 7, px = tid >> 3, j = px & 3;
             const int kk = kbase + 4 * k4;
             if constexpr (Q8) {
-            auto staged = [&](int o, int tile) {   // finished int32 outputs of four filters
-                const int at = (o * 16 + tile) * kRow + 4 * k4;
-                return (*reinterpret_cast<const v4i*>(parki + at) + *reinterpret_cast<const v4i*>(parki + kHalf + at) + rnd) >> 4;
-            };
-            if (q8.pool) {
-                // 16 tiles x 2x2 pooled pixels = 64 pixels; thread: pixels px and px + 32
+                // finished int32 outputs of filters 4*g .. 4*g+3 of the block
+                auto staged = [&](int o, int tile, int g) {
+                    const int at = (o * 16 + tile) * kRow + 4 * g;
+                    return (*reinterpret_cast<const v4i*>(parki + at) + *reinterpret_cast<const v4i*>(parki + kHalf + at) + rnd) >> 4;
+                };
+                if (q8.pool) {
+                    // 16 tiles x 2x2 pooled pixels = 64 pixels; thread: four filters of pixels px and px + 32
+    #pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const int pp = px + 32 * e, tile = pp >> 2, pi = (pp >> 1) & 1, pj = pp & 1;
+                        v4i best = requantise(staged(4 * (2 * pi) + 2 * pj, tile, k4), q8);
+                        best = __builtin_elementwise_max(best, requantise(staged(4 * (2 * pi) + 2 * pj + 1, tile, k4), q8));
+                        best = __builtin_elementwise_max(best, requantise(staged(4 * (2 * pi + 1) + 2 * pj, tile, k4), q8));
+                        best = __builtin_elementwise_max(best, requantise(staged(4 * (2 * pi + 1) + 2 * pj + 1, tile, k4), q8));
+                        const int n = __shfl(my_n, tile), row = __shfl(my_row, tile), col = __shfl(my_col, tile);
+                        const bool ok = __shfl(my_origin, tile) >= 0 && row + 2 * pi < p.H && col + 2 * pj < p.W && kk < p.K;
+                        const size_t at = (((size_t)n * (p.H >> 1) + (row >> 1) + pi) * (p.W >> 1) + (col >> 1) + pj) * p.K + kk;
+                        if (ok) *reinterpret_cast<uint32_t*>(q8.out + at) = pack_bytes(best);
+                    }
+                    return;
+                }
+                // thread: 16 filters (half h16 of the block) of its own tile (lane & 15) at outputs
+                // tid/32 and tid/32 + 8: sixteen lanes read sixteen tiles' rows, which fall in
+                // different banks, and a thread stores 16 bytes where the alignment allows
+                const int h16 = (tid >> 4) & 1, kq = kbase + 16 * h16;
+                const bool vector_store = ((p.K & 15) | (reinterpret_cast<uintptr_t>(q8.out) & 15)) == 0;
     #pragma unroll
                 for (int e = 0; e < 2; ++e) {
-                    const int pp = px + 32 * e, tile = pp >> 2, pi = (pp >> 1) & 1, pj = pp & 1;
-                    v4i best = requantise(staged(4 * (2 * pi) + 2 * pj, tile), q8);
-                    best = __builtin_elementwise_max(best, requantise(staged(4 * (2 * pi) + 2 * pj + 1, tile), q8));
-                    best = __builtin_elementwise_max(best, requantise(staged(4 * (2 * pi + 1) + 2 * pj, tile), q8));
-                    best = __builtin_elementwise_max(best, requantise(staged(4 * (2 * pi + 1) + 2 * pj + 1, tile), q8));
-                    const int n = __shfl(my_n, tile), row = __shfl(my_row, tile), col = __shfl(my_col, tile);
-                    const bool ok = __shfl(my_origin, tile) >= 0 && row + 2 * pi < p.H && col + 2 * pj < p.W && kk < p.K;
-                    const size_t at = (((size_t)n * (p.H >> 1) + (row >> 1) + pi) * (p.W >> 1) + (col >> 1) + pj) * p.K + kk;
-                    if (ok) *reinterpret_cast<uint32_t*>(q8.out + at) = pack_bytes(best);
-                }
-                return;
-            }
-            {
+                    const int o = (tid >> 5) + 8 * e, i = o >> 2, jj = o & 3;
+                    uint32_t bytes[4];
     #pragma unroll
-                for (int ps = 0; ps < 8; ++ps) {
-                    const int i = ps >> 1, tile = 8 * (ps & 1) + (px >> 2);
-                    const v4i v = requantise(staged(4 * i + j, tile), q8);
-                    const int origin = __shfl(my_origin, tile);
-                    const bool ok = origin >= 0 && __shfl(my_row, tile) + i < p.H && __shfl(my_col, tile) + j < p.W && kk < p.K;
-                    if (ok) *reinterpret_cast<uint32_t*>(q8.out + (size_t)origin + (size_t)(i * p.W + j) * p.K + kk) = pack_bytes(v);
+                    for (int g = 0; g < 4; ++g) bytes[g] = pack_bytes(requantise(staged(o, lane & 15, 4 * h16 + g), q8));
+                    const bool ok = my_origin >= 0 && my_row + i < p.H && my_col + jj < p.W;
+                    int8_t* dst = q8.out + (size_t)my_origin + (size_t)(i * p.W + jj) * p.K + kq;
+                    if (ok && vector_store && kq < p.K) {
+                        *reinterpret_cast<uint4*>(dst) = make_uint4(bytes[0], bytes[1], bytes[2], bytes[3]);
+                    } else if (ok) {
+    #pragma unroll
+                        for (int g = 0; g < 4; ++g)
+                            if (kq + 4 * g < p.K) reinterpret_cast<uint32_t*>(dst)[g] = bytes[g];
+                    }
                 }
                 return;
-            }
             }
             int32_t* first[2];   // output row 0 of the thread's two tiles (e = 0, 1); null where nothing is stored
             int rows[2];         // output rows of that tile inside the image
