@@ -62,7 +62,7 @@ int winograd_num_filter_planes(int mode) { return valid_mode(mode) ? num_filter_
 
 size_t winograd_packed_filter_bytes(int K, int C, int mode) {
     if (check_filter_shape(K, C) != WG_OK || !valid_mode(mode)) return 0;
-    return blob_layout(ceil_div(K, kFilterPad) * kFilterPad, ceil_div(C, kCBlock), mode).total;
+    return blob_layout(ceil_div(K, kFilterPad) * kFilterPad, C, mode).total;
 }
 
 size_t winograd_workspace_bytes(int N, int C, int H, int W, int K, int mode) {

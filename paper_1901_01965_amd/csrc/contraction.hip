@@ -303,7 +303,7 @@ hipError_t launch_contraction(const int8_t* V, const void* blob, int32_t* M, con
                               hipStream_t s) {
     if (hipError_t e = mode == WG_LOSSLESS ? configure_contraction<WG_LOSSLESS>() : configure_contraction<WG_SCALED>())
         return e;
-    const BlobLayout bl = blob_layout(p.Kp, p.CB, mode);
+    const BlobLayout bl = blob_layout(p.Kp, p.C, mode);
     const unsigned blocks = ceil_div(p.T, kBlockTiles) * ceil_div(p.K, kBlockFilters);
     const unsigned grid = kXcds * (mode == WG_LOSSLESS ? units_per_xcd<WG_LOSSLESS>() : units_per_xcd<WG_SCALED>()) * blocks;
     const uint8_t* b = static_cast<const uint8_t*>(blob);

@@ -107,7 +107,8 @@ __device__ inline int scale_half_up(int v, int n, int p) { return (v * n + (1 <<
 // rows and channels beyond K, C are written as zeros so the contraction needs no masks.
 __global__ __launch_bounds__(256) void filter_pack_kernel(const int8_t* w, int K, int C, int layout,
                                                           int mode, int Kp, int CB,
-                                                          const ScaleEntry* table, int8_t* planes) {
+                                                          const ScaleEntry* table, int8_t* planes,
+                                                          int16_t* narrow) {
     int c = blockIdx.x * 64 + (threadIdx.x & 63);
     int k = blockIdx.y * 4 + (threadIdx.x >> 6);
     if (k >= Kp) return;
@@ -116,7 +117,17 @@ __global__ __launch_bounds__(256) void filter_pack_kernel(const int8_t* w, int K
     filter_entries(g, re, cr, ci);
     const size_t plane_stride = kFilterFragBytes;
     int8_t* base = planes + filter_plane_offset(0, c >> 6, k, c & 63, Kp, num_filter_planes(mode));
+    // narrow table (C <= 4 only): the same values, unsplit, int16 [k][36][4]
+    int16_t* wide = narrow != nullptr && c < kNarrowChannels ? narrow + (size_t)k * kNarrowValues * kNarrowChannels + c
+                                                             : nullptr;
     if (mode == WG_LOSSLESS) {
+        if (wide != nullptr) {
+            for (int e = 0; e < 16; ++e) wide[e * kNarrowChannels] = (int16_t)re[e];
+            for (int j = 0; j < 10; ++j) {
+                wide[(16 + 2 * j) * kNarrowChannels] = (int16_t)cr[j];
+                wide[(17 + 2 * j) * kNarrowChannels] = (int16_t)ci[j];
+            }
+        }
         // value v -> planes 3v: v>>6, 3v+1: v&63, 3v+2: their sum (Karatsuba's middle operand, Section 3.1)
         auto put = [&](int value_index, int v) {
             int hi = v >> 6, lo = v & 63;
@@ -136,6 +147,7 @@ __global__ __launch_bounds__(256) void filter_pack_kernel(const int8_t* w, int K
             ScaleEntry s = tk[e];
             int v = s.n ? scale_half_up(re[e], s.n, s.p) : re[e];
             base[(size_t)e * plane_stride] = (int8_t)v;
+            if (wide != nullptr) wide[e * kNarrowChannels] = (int16_t)v;
         }
         for (int j = 0; j < 10; ++j) {
             ScaleEntry s = tk[16 + j];
@@ -144,6 +156,10 @@ __global__ __launch_bounds__(256) void filter_pack_kernel(const int8_t* w, int K
             base[(size_t)(16 + 3 * j + 0) * plane_stride] = (int8_t)vr;
             base[(size_t)(16 + 3 * j + 1) * plane_stride] = (int8_t)vi;
             base[(size_t)(16 + 3 * j + 2) * plane_stride] = (int8_t)(-vi);
+            if (wide != nullptr) {
+                wide[(16 + 2 * j) * kNarrowChannels] = (int16_t)vr;
+                wide[(17 + 2 * j) * kNarrowChannels] = (int16_t)vi;
+            }
         }
     }
 }
@@ -171,7 +187,7 @@ hipError_t launch_filter_transform(const int8_t* w, int K, int C, int layout, in
                                    hipStream_t s) {
     uint8_t* blob = static_cast<uint8_t*>(blob_v);
     const int Kp = ceil_div(K, kFilterPad) * kFilterPad, CB = ceil_div(C, kCBlock);
-    const BlobLayout bl = blob_layout(Kp, CB, mode);
+    const BlobLayout bl = blob_layout(Kp, C, mode);
     uint32_t* maxmag = reinterpret_cast<uint32_t*>(blob + bl.maxmag_off);
     ScaleEntry* table = reinterpret_cast<ScaleEntry*>(blob + bl.table_off);
     int8_t* planes = reinterpret_cast<int8_t*>(blob + bl.planes_off);
@@ -180,7 +196,8 @@ hipError_t launch_filter_transform(const int8_t* w, int K, int C, int layout, in
     if (mode == WG_SCALED)
         filter_maxmag_kernel<<<dim3(K, CB), 64, 0, s>>>(w, K, C, layout, maxmag);
     filter_table_kernel<<<ceil_div(entries, 256), 256, 0, s>>>(maxmag, table, entries, mode);
-    filter_pack_kernel<<<dim3(CB, ceil_div(Kp, 4)), 256, 0, s>>>(w, K, C, layout, mode, Kp, CB, table, planes);
+    int16_t* narrow = C <= kNarrowChannels ? reinterpret_cast<int16_t*>(blob + bl.narrow_off) : nullptr;
+    filter_pack_kernel<<<dim3(CB, ceil_div(Kp, 4)), 256, 0, s>>>(w, K, C, layout, mode, Kp, CB, table, planes, narrow);
     return hipGetLastError();
 }
 
@@ -188,7 +205,7 @@ hipError_t launch_unpack_filter_planes(const void* blob_v, int8_t* dense, int32_
                                        int mode, hipStream_t s) {
     const uint8_t* blob = static_cast<const uint8_t*>(blob_v);
     const int Kp = ceil_div(K, kFilterPad) * kFilterPad, CB = ceil_div(C, kCBlock);
-    const BlobLayout bl = blob_layout(Kp, CB, mode);
+    const BlobLayout bl = blob_layout(Kp, C, mode);
     const int nplanes = num_filter_planes(mode);
     size_t total = (size_t)nplanes * K * C;
     size_t threads = total > (size_t)K * kEntries ? total : (size_t)K * kEntries;

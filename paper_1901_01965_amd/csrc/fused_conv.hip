@@ -847,7 +847,8 @@ hipError_t launch_layout(const int8_t* x, const uint8_t* b, const BlobLayout& bl
 
 hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int layout, int mode,
                              const Int8Epilogue& q8, hipStream_t s) {
-    const BlobLayout bl = blob_layout(p.Kp, p.CB, mode);
+    if (layout == WG_NHWC && p.C <= kNarrowChannels) return launch_narrow_conv(x, blob, y, p, mode, q8, s);
+    const BlobLayout bl = blob_layout(p.Kp, p.C, mode);
     const uint8_t* b = static_cast<const uint8_t*>(blob);
     return q8.out != nullptr ? launch_layout<true>(x, b, bl, y, p, layout, mode, q8, s)
                              : launch_layout<false>(x, b, bl, y, p, layout, mode, q8, s);

@@ -155,9 +155,10 @@ struct OperandSplitter {
     }
 };
 
-// Transforms one loaded patch (four channels) and emits every operand plane.
-template <int SPLIT, class Sink>
-__device__ inline void transform_patch(const uint32_t u[6][6], const OperandSplitter<SPLIT, Sink>& out) {
+// Transforms one loaded patch (four channels) and hands every free entry to `out`
+// (real_entry(p, v), complex_entry(j, re, im)): an OperandSplitter emits the operand planes.
+template <class Out>
+__device__ inline void transform_patch(const uint32_t u[6][6], const Out& out) {
     // column pass: d'[.][b] = B^T applied down each of the six tile columns
     Line col[6];
 #pragma unroll

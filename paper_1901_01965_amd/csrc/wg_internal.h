@@ -81,12 +81,13 @@ __host__ __device__ inline int num_filter_planes(int mode) { return mode == WG_L
 
 // ---- packed filter blob -------------------------------------------------------
 // [BlobHeader, 256 B][maxmag: uint32 [Kp][26]][table: ScaleEntry [Kp][26]]
-// [operand planes: int8 [CB][Kp/16][planes][16][64]], each section 256-byte aligned.
+// [operand planes: int8 [CB][Kp/16][planes][16][64]][narrow table, only when C <= 4:
+// int16 [Kp][36][4]], each section 256-byte aligned.
 // The operand planes are fragment-major: the 1 KB piece (16 filters x 64 channels) that one
 // matrix-core instruction consumes is contiguous, and all planes of a (channel block, filter
 // block) follow each other, so a kernel steps from plane to plane with constant offsets.
 constexpr uint32_t kBlobMagic = 0x33344757u;  // "WG43"
-constexpr uint32_t kBlobVersion = 2;
+constexpr uint32_t kBlobVersion = 3;
 
 struct BlobHeader {
     uint32_t magic, version;
@@ -116,15 +117,26 @@ struct ReverseScale {
     __device__ inline int operator()(int m) const { return (m >> q) * r + ((__mul24(m & mask, r) + rnd) >> q); }
 };
 
+// Layers with at most kNarrowChannels input channels (a network's first layer) are served by a
+// kernel that multiplies on the vector ALU; for them the blob also carries the Winograd-domain
+// filters (after the scaling, in scaled mode) as 16-bit values, four channel slots per value:
+// the 36 real numbers of the 26 free entries in the order 16 real entries, then (Re, Im) of
+// each complex entry.
+constexpr int kNarrowChannels = 4;
+constexpr int kNarrowValues = 36;
+constexpr int kNarrowFilterBytes = kNarrowValues * kNarrowChannels * 2;   // 288 per filter
+
 struct BlobLayout {
-    size_t maxmag_off, table_off, planes_off, total;
+    size_t maxmag_off, table_off, planes_off, narrow_off, total;
 };
-inline BlobLayout blob_layout(int Kp, int CB, int mode) {
+inline BlobLayout blob_layout(int Kp, int C, int mode) {
+    const int CB = (C + kCBlock - 1) / kCBlock;
     BlobLayout b;
     b.maxmag_off = sizeof(BlobHeader);
     b.table_off = round_up(b.maxmag_off + (size_t)Kp * kEntries * sizeof(uint32_t), 256);
     b.planes_off = round_up(b.table_off + (size_t)Kp * kEntries * sizeof(ScaleEntry), 256);
-    b.total = b.planes_off + (size_t)num_filter_planes(mode) * CB * Kp * kCBlock;
+    b.narrow_off = round_up(b.planes_off + (size_t)num_filter_planes(mode) * CB * Kp * kCBlock, 256);
+    b.total = b.narrow_off + (C <= kNarrowChannels ? (size_t)Kp * kNarrowFilterBytes : 0);
     return b;
 }
 
@@ -165,6 +177,9 @@ inline Int8Epilogue make_int8_epilogue(int8_t* out, int shift, bool relu, bool p
 // Single-kernel path (no workspace traffic).
 hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int layout,
                              int mode, const Int8Epilogue& q8, hipStream_t s);
+// Single-kernel path for channels-last inputs with C <= kNarrowChannels.
+hipError_t launch_narrow_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int mode,
+                              const Int8Epilogue& q8, hipStream_t s);
 hipError_t launch_direct_conv(const int8_t* x, const int8_t* w, int32_t* y, const Problem& p,
                               int layout, hipStream_t s);
 hipError_t launch_requant_relu_pool(const int32_t* y, int8_t* out, int N, int K, int H, int W,

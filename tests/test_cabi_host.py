@@ -49,7 +49,9 @@ def test_size_queries(lib):
     assert lossless > 138 * 64 * 64 and scaled > 46 * 64 * 64 and lossless > scaled
     assert lossless % 256 == 0
     # padding: K up to 64, C up to 64
-    assert wg.packed_filter_bytes(1, 1, 0) == wg.packed_filter_bytes(64, 64, 0)
+    assert wg.packed_filter_bytes(1, 5, 0) == wg.packed_filter_bytes(64, 64, 0)
+    # up to four input channels: the blob also carries the 36 values of each filter as int16 x 4 channel slots
+    assert wg.packed_filter_bytes(1, 1, 0) == wg.packed_filter_bytes(64, 4, 0) == wg.packed_filter_bytes(64, 64, 0) + 64 * 36 * 4 * 2
     assert wg.workspace_bytes(0, 1, 1, 1, 1, 0) == 0
     c = wl.CASES["cfg2"]
     ws = wg.workspace_bytes(c.N, c.C, c.H, c.W, c.K, wg.LOSSLESS)

@@ -303,6 +303,38 @@ def test_int8_epilogue_odd_sizes_without_pooling_and_fill():
             wg.winograd_conv2d_int8_requant(_x(x, layout), packed, 9, True, True, layout)
 
 
+NARROW_SHAPES = [  # N, C, K, H, W: at most four input channels, channels-last -> the vector-ALU kernel
+    (2, 3, 70, 30, 22), (1, 1, 64, 16, 16), (3, 2, 5, 9, 7), (1, 4, 130, 20, 36), (1, 3, 64, 4, 4),
+]
+
+
+@pytest.mark.parametrize("mode", [wg.LOSSLESS, wg.SCALED])
+@pytest.mark.parametrize("wgt", ["uniform", "gauss"])
+@pytest.mark.parametrize("shape", NARROW_SHAPES)
+def test_narrow_input_layers(shape, wgt, mode):
+    """First-layer shapes (C <= 4, channels-last): int32 output and the int8 epilogue, more than one wave's 64 tiles,
+    more than 64 filters, ragged tiles and filter counts; uniform weights make most locations need scaling."""
+    N, C, K, H, W = shape
+    x, g = wl.make_custom(N, C, K, H, W, wgt=wgt, seed=61)
+    want = oracle.direct_conv2d(x, g) if mode == wg.LOSSLESS else oracle.winograd_conv2d(x, g, oracle.SCALED)[0]
+    packed = wg.winograd_filter_transform(_g(g, wg.NHWC), wg.NHWC, mode)
+    xd = _x(x, wg.NHWC)
+    assert np.array_equal(_y(wg.winograd_conv2d_int8(xd, packed, wg.NHWC), wg.NHWC), want)
+    shift = max(0, int(np.abs(want).max()).bit_length() - 7)
+    for relu in (True, False):
+        for pool in (False, True):
+            if pool and (H % 2 or W % 2):
+                continue
+            got = wg.winograd_conv2d_int8_requant(xd, packed, shift, relu, pool, wg.NHWC)
+            assert np.array_equal(_y(got, wg.NHWC), oracle.requant_relu_pool(want, shift, relu, pool)), (relu, pool)
+    # the staged pipeline on the same blob gives the same int32 result
+    wg.force_path(wg.STAGED)
+    try:
+        assert np.array_equal(_y(wg.winograd_conv2d_int8(xd, packed, wg.NHWC), wg.NHWC), want)
+    finally:
+        wg.force_path(wg.AUTO)
+
+
 @pytest.mark.parametrize("path", PATHS, indirect=True)
 def test_results_do_not_depend_on_workspace_contents_and_repeat_exactly(path):
     x, g = wl.make_custom(2, 24, 40, 14, 9, seed=40)
