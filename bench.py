@@ -79,6 +79,100 @@ def read_profiled_traffic(kernel):
     return None
 
 
+def run_stack(args):
+    """--stack: the VGG-16-shaped stack (13 layers, batch 16, requantisation + ReLU after every layer, 2x2 max-pool
+    after layers 2, 4, 7, 10, 13).  A step is one pass of the batch through all 13 layers, each layer one launch of
+    the convolution with the int8 epilogue; filters are transformed once beforehand."""
+    import numpy as np
+    import torch
+    import paper_1901_01965_amd as wg
+    from paper_1901_01965_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    wg.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    mode = wg.LOSSLESS if args.mode == "lossless" else wg.SCALED
+    batch = args.batch or wl.VGG16_BATCH
+    x_np, gs = wl.make_vgg16(batch=batch)
+    x0 = torch.from_numpy(wl.to_nhwc(x_np)).to(dev)
+    gd = [torch.from_numpy(wl.to_krsc(g)).to(dev) for g in gs]
+    packed = [wg.winograd_filter_transform(g, wg.NHWC, mode) for g in gd]
+    acts, y32 = [x0], []
+    for cin, cout, hw, pool in wl.VGG16_LAYERS:
+        ho = hw // 2 if pool else hw
+        acts.append(torch.empty((batch, ho, ho, cout), dtype=torch.int8, device=dev))
+        y32.append(None)
+    ops = sum(2 * 9 * batch * cout * cin * hw * hw for cin, cout, hw, _ in wl.VGG16_LAYERS)
+
+    def layer(i):
+        wg.winograd_conv2d_int8_requant(acts[i], packed[i], wl.VGG16_SHIFTS[i], True, wl.VGG16_LAYERS[i][3], wg.NHWC,
+                                        out=acts[i + 1])
+
+    def step():
+        for i in range(13):
+            layer(i)
+
+    def timed(fn, count):
+        for _ in range(max(1, args.warmup // 4)):
+            fn()
+        torch.cuda.synchronize()
+        graph = None if args.eager else capture_steps(torch, fn, count)
+        if graph is not None:
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        if graph is not None:
+            graph.replay()
+        else:
+            for _ in range(count):
+                fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / count * 1e3, graph is not None
+
+    steps = min(args.steps, 50)
+    ms, graphed = timed(step, steps)
+    layers = []
+    for i, (cin, cout, hw, pool) in enumerate(wl.VGG16_LAYERS):
+        lms, _ = timed(lambda i=i: layer(i), 20)
+        lops = 2 * 9 * batch * cout * cin * hw * hw
+        layers.append({"layer": "%d->%d @%d%s" % (cin, cout, hw, " +pool" if pool else ""), "ms": round(lms, 4),
+                       "TOPS": round(lops / (lms * 1e-3) / 1e12, 1)})
+
+    # the same stack as 13 int32 convolutions + 13 requantisation launches, and with the direct convolution
+    outs32 = [torch.empty((batch, hw, hw, cout), dtype=torch.int32, device=dev) for _, cout, hw, _ in wl.VGG16_LAYERS]
+    wss = [wg.make_workspace(batch, cin, hw, hw, cout, mode, dev) for cin, cout, hw, _ in wl.VGG16_LAYERS]
+
+    def two_kernel_step():
+        for i in range(13):
+            wg.winograd_conv2d_int8(acts[i], packed[i], wg.NHWC, out=outs32[i], workspace=wss[i])
+            wg.requant_relu_pool_int8(outs32[i], wl.VGG16_SHIFTS[i], True, wl.VGG16_LAYERS[i][3], wg.NHWC, out=acts[i + 1])
+
+    def direct_step():
+        for i in range(13):
+            wg.direct_conv2d_int8(acts[i], gd[i], wg.NHWC, out=outs32[i])
+            wg.requant_relu_pool_int8(outs32[i], wl.VGG16_SHIFTS[i], True, wl.VGG16_LAYERS[i][3], wg.NHWC, out=acts[i + 1])
+
+    final = acts[13].clone()
+    two_ms, _ = timed(two_kernel_step, 10)
+    same = bool(torch.equal(final, acts[13]))
+    direct_ms, _ = timed(direct_step, 10)
+    same_direct = bool(torch.equal(final, acts[13])) if mode == wg.LOSSLESS else None
+    print(json.dumps({
+        "metric": "direct-equivalent int8 conv TOPS, VGG-16-shaped stack, 1 GPU", "value": round(ops / (ms * 1e-3) / 1e12, 2),
+        "unit": "TOPS", "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "cfg5: VGG-16-shaped stack of 13 3x3 convolutions, N=%d, NHWC, %s mode, int8 between layers "
+                               "(power-of-two requantisation, ReLU, 2x2 max-pool after layers 2,4,7,10,13)" % (batch, args.mode)},
+        "launch": "hip graph of %d steps, one replay" % steps if graphed else "eager",
+        "layers": layers,
+        "int32_conv_plus_requant_kernel_ms": round(two_ms, 4), "final_activations_equal": same,
+        "direct_conv_plus_requant_kernel_ms": round(direct_ms, 4), "final_activations_equal_direct": same_direct,
+        "nonzero_fraction_of_final_activations": round(float((final != 0).float().mean().item()), 3),
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -98,9 +192,13 @@ def main():
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 256 MiB device-to-device tensor copy, the known-size kernel that "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
+    ap.add_argument("--stack", action="store_true",
+                    help="time the VGG-16-shaped stack (cfg5) instead of one layer; prints its own JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (the path has no cross-GPU step); use --gpus 1")
+    if args.stack:
+        return run_stack(args)
 
     import numpy as np
     import torch

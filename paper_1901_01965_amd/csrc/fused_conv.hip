@@ -824,8 +824,9 @@ hipError_t launch_mode(const int8_t* x, const uint8_t* blob, const BlobLayout& b
         const long long workgroups = (long long)ceil_div(p.T, kFusedTiles) * (p.Kp / kFusedFilters);
         if (workgroups > compute_units()) {
             if (mode == WG_LOSSLESS) return launch<LAYOUT, LOAD, WG_LOSSLESS, false, true, Q8>(x, blob, bl, y, p, q8, s);
-            return p.CB == 1 ? launch<LAYOUT, LOAD, WG_SCALED, false, true, Q8>(x, blob, bl, y, p, q8, s)
-                             : launch<LAYOUT, LOAD, WG_SCALED, true, true, Q8>(x, blob, bl, y, p, q8, s);
+            // scaled mode keeps channel sums here also for a single channel block: the variant that
+            // reduces each entry at once needs more registers than a wave has when it covers 64 filters
+            return launch<LAYOUT, LOAD, WG_SCALED, true, true, Q8>(x, blob, bl, y, p, q8, s);
         }
     }
     if (mode == WG_LOSSLESS) return launch<LAYOUT, LOAD, WG_LOSSLESS, false, false, Q8>(x, blob, bl, y, p, q8, s);
