@@ -44,6 +44,20 @@ def algorithmic_bytes(case, mode):
     }
 
 
+def layout_bytes(case, mode):
+    """Bytes per launch that the kernels' own data layout moves when nothing is cached (same padding-free
+    counting): the staged pipeline stores 138 (lossless) or 72 (scaled) int8 operand planes per (tile, channel)
+    and 46 or 36 int32 accumulator planes per (tile, filter); the fused kernel has no intermediate arrays."""
+    T, C, K = case.tiles, case.C, case.K
+    vp, mp, fp = (138, 46, 138) if mode == "lossless" else (72, 36, 46)
+    return {
+        "input_transform": (16 + vp) * T * C,
+        "contraction": vp * T * C + fp * K * C + 4 * mp * T * K,
+        "output_transform": (4 * mp + 64) * T * K,
+        "fused_conv": 16 * T * C + fp * K * C + 64 * T * K,
+    }
+
+
 def contraction_int8_ops(case, mode):
     """int8 multiply-adds x2 the method needs on the matrix cores: 46 real products per tile and channel
     pair (Section 3.4), each three int8 limb products in lossless mode (138), 112 in scaled mode."""
@@ -285,8 +299,10 @@ def main():
             "hbm_frac": round(alg[s] / (stage[s] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         for s in STAGES if stage[s] > 0
     }
+    lay = layout_bytes(case, args.mode)
     for s in kernels:
         kernels[s]["on_timed_path"] = s in used
+        kernels[s]["layout_GBps"] = round(lay[s] / (stage[s] * 1e-3) / 1e9, 1)
     for s in ("contraction", "fused_conv"):
         if s in kernels:
             mfma_tops = contraction_int8_ops(case, args.mode) / (stage[s] * 1e-3) / 1e12

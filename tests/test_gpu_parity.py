@@ -223,6 +223,21 @@ def test_extreme_values_lossless(layout, path):
         assert np.array_equal(_y(y, layout), oracle.direct_conv2d(x, g))
 
 
+@pytest.mark.parametrize("mode", [wg.LOSSLESS, wg.SCALED])
+@pytest.mark.parametrize("C", [1, 3, 4])
+def test_extreme_values_narrow_input(C, mode):
+    """All-extreme data through the vector-ALU kernel (C <= 4, channels-last): its 16-bit operands and the
+    24-bit products summed over four channel slots are at their largest."""
+    for xv, gv in ((-128, -128), (127, -128), (-128, 127), (127, 127)):
+        x = np.full((1, C, 12, 8), xv, np.int8)
+        g = np.full((66, C, 3, 3), gv, np.int8)
+        g[1::2] = -gv if gv != -128 else 127
+        packed = wg.winograd_filter_transform(_g(g, wg.NHWC), wg.NHWC, mode)
+        y = wg.winograd_conv2d_int8(_x(x, wg.NHWC), packed, wg.NHWC)
+        want = oracle.direct_conv2d(x, g) if mode == wg.LOSSLESS else oracle.winograd_conv2d(x, g, oracle.SCALED)[0]
+        assert np.array_equal(_y(y, wg.NHWC), want), (xv, gv)
+
+
 @pytest.mark.parametrize("path", PATHS, indirect=True)
 def test_max_channels_lossless_wraparound_is_exact(path):
     """C = 896 with worst-case data: intermediate accumulators wrap modulo 2^32, the result is exact."""
