@@ -1,6 +1,6 @@
 """CPU ORACLE -- test infrastructure, not product code.
 
-ctypes front end of ``winograd_oracle.c`` (plain C, built with gcc).  Only
+ctypes front end of ``winograd_oracle.c`` and ``winograd_f2x2_oracle.c`` (plain C, built with gcc).  Only
 tests, the smoke check and the benchmark's cpu_baseline leg may import this
 package; the HIP library and its Python binding never do, and nothing here
 imports them.  Arrays are numpy; activations and outputs are NCHW, filters
@@ -17,15 +17,15 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "winograd_oracle.c")
+_SRCS = [os.path.join(_HERE, "winograd_oracle.c"), os.path.join(_HERE, "winograd_f2x2_oracle.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
 
 
 def build(force=False):
     """Compile the oracle with gcc -O2 (OpenMP over the outermost loops only)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(s) for s in _SRCS):
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-o", _LIB, _SRC]
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-o", _LIB] + _SRCS
         )
     return _LIB
 
@@ -221,3 +221,53 @@ def requant_relu_pool(y, shift, relu=True, pool=False):
     out = np.zeros((N, K, H // 2 if pool else H, W // 2 if pool else W), np.int8)
     lib().oracle_requant_relu_pool(_p(y), _p(out), N, K, H, W, shift, int(relu), int(pool))
     return out
+
+
+# ---- rational F(2x2,3x3) in integers (the running example of Sections 4.1-4.2) --------------------------------
+
+def f2_matrices():
+    """(B^T [4,4], G' = 2G [4,3], A^T [2,4]) as int64 arrays."""
+    bt, g2, at = np.zeros((4, 4), np.int8), np.zeros((4, 3), np.int8), np.zeros((2, 4), np.int8)
+    lib().oracle_f2_get_matrices(_p(bt), _p(g2), _p(at))
+    return bt.astype(np.int64), g2.astype(np.int64), at.astype(np.int64)
+
+
+def f2_filter_transform(g):
+    """G' g G'^T for [K,C,3,3] int8 filters -> int64 [K,C,4,4]."""
+    g = _i8(g)
+    K, C = g.shape[:2]
+    out = np.zeros((K, C, 4, 4), np.int64)
+    lib().oracle_f2_filter_transform(_p(g), K, C, _p(out))
+    return out
+
+
+def f2_input_transform(x):
+    """B^T d B for every 4x4 input tile (stride 2, pad 1) -> int64 [T,C,4,4], T = N*ceil(H/2)*ceil(W/2)."""
+    x = _i8(x)
+    N, C, H, W = x.shape
+    out = np.zeros((N * ((H + 1) // 2) * ((W + 1) // 2), C, 4, 4), np.int64)
+    lib().oracle_f2_input_transform(_p(x), N, C, H, W, _p(out))
+    return out
+
+
+def f2_scale_filters(Wt, weight_range=127):
+    """Section 4.2 on [K,C,4,4] Winograd-domain filters: (scaled copy, table [K,4,4,4] = (n,p,r,q), max [K,4,4])."""
+    Wt = np.ascontiguousarray(Wt, dtype=np.int64).copy()
+    K, C = Wt.shape[:2]
+    tab = np.zeros((K, 4, 4, 4), np.int32)
+    mx = np.zeros((K, 4, 4), np.int64)
+    lib().oracle_f2_scale_filters(_p(Wt), K, C, ctypes.c_int64(weight_range), _p(tab), _p(mx))
+    return Wt, tab, mx
+
+
+def f2_conv2d(x, g, mode=LOSSLESS, weight_range=127):
+    """Whole F(2x2,3x3) path.  Returns (y int32 NCHW, flags)."""
+    x, g = _i8(x), _i8(g)
+    N, C, H, W = x.shape
+    K = g.shape[0]
+    assert g.shape == (K, C, 3, 3)
+    y = np.zeros((N, K, H, W), np.int32)
+    flags = lib().oracle_f2_conv2d(_p(x), _p(g), _p(y), N, C, H, W, K, mode, ctypes.c_int64(weight_range))
+    if flags < 0:
+        raise MemoryError("oracle ran out of memory")
+    return y, int(flags)
