@@ -125,6 +125,39 @@ int winograd_conv2d_int8_requant(const int8_t* x_dev, const void* packed_dev, in
                                  int shift, int relu, int pool, void* hip_stream);
 
 /*
+ * The same convolution with the rational Winograd algorithm F(2x2,3x3) in
+ * integer arithmetic: the running example of Sections 4.1-4.2 and the variant
+ * the evaluation of Section 4.4 used.  G' = 2G is the filter transform matrix
+ * printed in Section 4.1; all 16 Winograd-domain entries are real.
+ *   WG_LOSSLESS: 12-bit transformed filters and 11-bit transformed activations
+ *                as exact int8 limbs; the result equals direct_conv2d_int8's bit
+ *                for bit.
+ *   WG_SCALED:   Section 4.2 with 16 factors per filter (one per X-Y location,
+ *                from the largest magnitude over the input channels): filters
+ *                scaled into +-127 by n/2^p with a 4-bit n, rounding half up;
+ *                the channel sums multiplied back by the 8-bit reciprocal r/2^q
+ *                before the output transform; the final division by 4 (G' = 2G
+ *                on both sides) rounds half up.
+ * winograd_f2x2_filter_transform fills a blob of at least
+ * winograd_f2x2_packed_filter_bytes(K, C, mode) bytes (256-byte aligned; 0 from
+ * the size query means invalid arguments); winograd_f2x2_conv2d_int8 consumes it
+ * (WG_EBLOB-style mismatches leave y untouched) and needs no workspace.  Layouts,
+ * limits and error codes are those of the F(4x4,3x3) entry points.
+ * winograd_f2x2_debug_filter_operands exports what the blob holds:
+ * planes_dev int8 [planes][K][C] (lossless: 32 planes, entry e = 4 row + column
+ * as high limb 2e and low limb 2e+1; scaled: 16 planes) and table_dev int32
+ * [K][16][4] = (n, p, r, q).
+ */
+size_t winograd_f2x2_packed_filter_bytes(int K, int C, int mode);
+int winograd_f2x2_filter_transform(const int8_t* w_dev, int K, int C, int layout, int mode,
+                                   void* packed_dev, size_t packed_bytes, void* hip_stream);
+int winograd_f2x2_conv2d_int8(const int8_t* x_dev, const void* packed_dev, int32_t* y_dev,
+                              int N, int C, int H, int W, int K, int layout, int mode,
+                              void* hip_stream);
+int winograd_f2x2_debug_filter_operands(const void* packed_dev, int K, int C, int mode,
+                                        int8_t* planes_dev, int32_t* table_dev, void* hip_stream);
+
+/*
  * Direct evaluation of the same convolution (the 144-multiplication method
  * that Section 3.4 compares against):
  *   y[n,k,h,w] = sum_{c,a,b} x[n,c,h+a-1,w+b-1] * g[k,c,a,b],  x = 0 outside.

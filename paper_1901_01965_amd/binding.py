@@ -51,6 +51,10 @@ def load_library():
         "winograd_packed_filter_check": (i, [vp, i, i, i, vp]),
         "winograd_conv2d_int8": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp, sz, vp]),
         "winograd_conv2d_int8_requant": (i, [vp, vp, vp, i, i, i, i, i, i, i, i, i, i, vp]),
+        "winograd_f2x2_packed_filter_bytes": (sz, [i, i, i]),
+        "winograd_f2x2_filter_transform": (i, [vp, i, i, i, i, vp, sz, vp]),
+        "winograd_f2x2_conv2d_int8": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp]),
+        "winograd_f2x2_debug_filter_operands": (i, [vp, i, i, i, vp, vp, vp]),
         "winograd_conv2d_int8_stage_times": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp, sz, vp, i, vp]),
         "direct_conv2d_int8": (i, [vp, vp, vp, i, i, i, i, i, i, vp]),
         "requant_relu_pool_int8": (i, [vp, vp, i, i, i, i, i, i, i, i, vp]),
@@ -73,6 +77,8 @@ EXPORTED_SYMBOLS = (
     "winograd_conv2d_int8_stage_times",
     "direct_conv2d_int8", "requant_relu_pool_int8",
     "winograd_debug_input_operands", "winograd_debug_filter_operands", "winograd_debug_contraction",
+    "winograd_f2x2_packed_filter_bytes", "winograd_f2x2_filter_transform", "winograd_f2x2_conv2d_int8",
+    "winograd_f2x2_debug_filter_operands",
 )
 
 
@@ -278,3 +284,50 @@ def debug_contraction(x, packed, layout=NCHW):
                                                      layout, packed.mode, _ptr(ws), ws.numel(), _stream()),
            "winograd_debug_contraction")
     return out
+
+
+# ---- rational F(2x2,3x3) --------------------------------------------------------------------------------------
+
+class F2x2PackedFilter:
+    """Winograd-domain filters of the F(2x2,3x3) path: device blob plus the (K, C, mode) it was made for."""
+
+    def __init__(self, blob, K, C, mode):
+        self.blob, self.K, self.C, self.mode = blob, K, C, mode
+
+
+def f2x2_filter_transform(w, layout=NCHW, mode=LOSSLESS):
+    layout = _LAYOUTS[layout]
+    _need(w, torch.int8, "w")
+    K = w.shape[0]
+    C = w.shape[1] if layout == NCHW else w.shape[3]
+    nbytes = load_library().winograd_f2x2_packed_filter_bytes(K, C, mode)
+    if nbytes == 0:
+        raise WinogradError(-1, "winograd_f2x2_packed_filter_bytes")
+    blob = torch.empty(nbytes, dtype=torch.uint8, device=w.device)
+    _check(load_library().winograd_f2x2_filter_transform(_ptr(w), K, C, layout, mode, _ptr(blob), nbytes, _stream()),
+           "winograd_f2x2_filter_transform")
+    return F2x2PackedFilter(blob, K, C, mode)
+
+
+def f2x2_conv2d_int8(x, packed, layout=NCHW, out=None):
+    layout = _LAYOUTS[layout]
+    _need(x, torch.int8, "x")
+    N, C, H, W = _dims(x, layout)
+    K = packed.K
+    if out is None:
+        shape = (N, K, H, W) if layout == NCHW else (N, H, W, K)
+        out = torch.empty(shape, dtype=torch.int32, device=x.device)
+    _check(load_library().winograd_f2x2_conv2d_int8(_ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout,
+                                                    packed.mode, _stream()), "winograd_f2x2_conv2d_int8")
+    return out
+
+
+def f2x2_debug_filter_operands(packed):
+    """(planes int8 [planes, K, C], table int32 [K, 16, 4] = (n, p, r, q)) as the blob holds them."""
+    planes = 32 if packed.mode == LOSSLESS else 16
+    dense = torch.empty((planes, packed.K, packed.C), dtype=torch.int8, device=packed.blob.device)
+    table = torch.empty((packed.K, 16, 4), dtype=torch.int32, device=packed.blob.device)
+    _check(load_library().winograd_f2x2_debug_filter_operands(_ptr(packed.blob), packed.K, packed.C, packed.mode,
+                                                              _ptr(dense), _ptr(table), _stream()),
+           "winograd_f2x2_debug_filter_operands")
+    return dense, table

@@ -1,0 +1,411 @@
+// The rational Winograd algorithm F(2x2,3x3) in integer arithmetic, the running example of
+// Sections 4.1-4.2 and the variant the paper's evaluation used (Section 4.4): filter transform
+// W = G' g G'^T with G' = 2G (the matrix printed in Section 4.1), the filter precision scaling of
+// Section 4.2 per output channel and X-Y location (16 factors per filter), and one kernel for
+// input transform, Winograd-domain products on the int8 matrix cores and output transform.
+//
+// All 16 entries are real.  For int8 data the transformed activations need 11 bits and the
+// transformed filters 12, so both travel as two int8 limbs v = 64 h + l (l in 0..63); in scaled
+// mode the filters are back in int8 and are a single operand.  Per entry the matrix cores form
+//   lossless: hh, hl + lh, ll  (value = 4096 hh + 64 mid + ll)      scaled: h w, l w  (64 hw + lw)
+// and, unlike in the F(4x4,3x3) kernel, every accumulator of a wave (16 entries x 3) fits its
+// registers for the whole kernel: the matrix cores sum over all input channels and the limbs
+// are joined, unscaled (Section 4.2, scaled mode) and run through A^T . A once, at the end.
+#include <type_traits>
+#include <utility>
+
+#include "input_transform_core.h"
+#include "wg_internal.h"
+
+namespace wg {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+constexpr int kF2Tiles = 32;      // tiles per workgroup: two row blocks of the 16x16x64 matrix-core product
+constexpr int kF2Filters = 32;    // filters per workgroup: two 16-wide column blocks
+constexpr int kF2ActPlanes = 2 * kF2Entries;
+constexpr int kF2PlaneBytes = kF2Tiles * kCBlock;            // one operand plane of the tile block in LDS
+constexpr int kF2LdsBytes = kF2ActPlanes * kF2PlaneBytes;    // 64 KB
+
+// ---- filter transform -----------------------------------------------------------------------
+// W = G' g G'^T in the row-major order of the matrix printed in Section 4.1.
+__device__ inline void f2_filter_entries(const int g[9], int w[16]) {
+    int u[4][3];   // G' g
+    for (int c = 0; c < 3; ++c) {
+        const int g0 = g[c], g1 = g[3 + c], g2 = g[6 + c];
+        u[0][c] = 2 * g0;
+        u[1][c] = g0 + g1 + g2;
+        u[2][c] = g0 - g1 + g2;
+        u[3][c] = 2 * g2;
+    }
+    for (int r = 0; r < 4; ++r) {
+        w[4 * r + 0] = 2 * u[r][0];
+        w[4 * r + 1] = u[r][0] + u[r][1] + u[r][2];
+        w[4 * r + 2] = u[r][0] - u[r][1] + u[r][2];
+        w[4 * r + 3] = 2 * u[r][2];
+    }
+}
+
+__device__ inline void f2_load_filter(const int8_t* w, int k, int c, int K, int C, int layout, int g[9]) {
+    for (int i = 0; i < 9; ++i)
+        g[i] = (k >= K || c >= C) ? 0 : (layout == WG_NCHW ? w[((size_t)k * C + c) * 9 + i] : w[((size_t)k * 9 + i) * C + c]);
+}
+
+__global__ void f2_blob_init_kernel(uint8_t* blob, int K, int C, int mode, int Kp, int CB, size_t maxmag_off) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0) {
+        BlobHeader* h = reinterpret_cast<BlobHeader*>(blob);
+        h->magic = kF2BlobMagic; h->version = kBlobVersion;
+        h->K = K; h->C = C; h->mode = mode; h->range = kWeightRange;
+        h->Kp = Kp; h->CB = CB; h->planes = f2_filter_planes(mode);
+        for (int j = 0; j < 55; ++j) h->reserved[j] = 0;
+    }
+    if (i < Kp * kF2Entries) reinterpret_cast<uint32_t*>(blob + maxmag_off)[i] = 0;
+}
+
+// Step 2 of Section 4.2: the largest magnitude over the input channels at each of a filter's 16
+// locations.  One wave per (filter, 64-channel block).
+__global__ __launch_bounds__(64) void f2_maxmag_kernel(const int8_t* w, int K, int C, int layout, uint32_t* maxmag) {
+    const int k = blockIdx.x, c = blockIdx.y * 64 + threadIdx.x;
+    int g[9], v[16];
+    f2_load_filter(w, k, c, K, C, layout, g);
+    f2_filter_entries(g, v);
+    for (int e = 0; e < kF2Entries; ++e) {
+        int m = abs(v[e]);
+        for (int off = 32; off > 0; off >>= 1) m = max(m, __shfl_xor(m, off));
+        if (threadIdx.x == 0) atomicMax(&maxmag[k * kF2Entries + e], (uint32_t)m);
+    }
+}
+
+// Steps 3-4 of Section 4.2 and the reciprocal of its last paragraph (same rule as for the
+// complex algorithm): largest n/2^p with a 4-bit n that brings the maximum within the range.
+__global__ void f2_table_kernel(const uint32_t* maxmag, ScaleEntry* table, int count, int mode) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    ScaleEntry s = {0, 0, 1, 0};
+    const int mx = (int)maxmag[i];
+    if (mode == WG_SCALED && mx > kWeightRange) {
+        const int num = kWeightRange * 128;
+        int y = 0;
+        while ((mx << (y + 1)) <= num) ++y;
+        s.n = (num * 8) / (mx << y);
+        s.p = 10 - y;
+        for (int q = 7; q >= 0; --q) {
+            const int r = ((2 << (s.p + q)) + s.n) / (2 * s.n);
+            if (r <= 255) { s.r = r; s.q = q; break; }
+        }
+    }
+    table[i] = s;
+}
+
+// One thread per (filter row k < Kp, channel c < 64*CB); padding rows and channels are zeros.
+__global__ __launch_bounds__(256) void f2_pack_kernel(const int8_t* w, int K, int C, int layout, int mode, int Kp,
+                                                      const ScaleEntry* table, int8_t* planes) {
+    const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int k = blockIdx.y * 4 + (threadIdx.x >> 6);
+    if (k >= Kp) return;
+    int g[9], v[16];
+    f2_load_filter(w, k, c, K, C, layout, g);
+    f2_filter_entries(g, v);
+    int8_t* base = planes + filter_plane_offset(0, c >> 6, k, c & 63, Kp, f2_filter_planes(mode));
+    for (int e = 0; e < kF2Entries; ++e) {
+        if (mode == WG_LOSSLESS) {
+            base[(size_t)(2 * e) * kFilterFragBytes] = (int8_t)(v[e] >> 6);
+            base[(size_t)(2 * e + 1) * kFilterFragBytes] = (int8_t)(v[e] & 63);
+        } else {
+            const ScaleEntry s = table[(size_t)k * kF2Entries + e];
+            const int scaled = s.n ? (v[e] * s.n + (1 << (s.p - 1))) >> s.p : v[e];   // round half up
+            base[(size_t)e * kFilterFragBytes] = (int8_t)scaled;
+        }
+    }
+}
+
+__global__ void f2_unpack_kernel(const int8_t* planes, const ScaleEntry* table, int8_t* dense, int32_t* table_out,
+                                 int K, int C, int Kp, int nplanes) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t total = (size_t)nplanes * K * C;
+    if (i < total) {
+        const int c = (int)(i % C), k = (int)((i / C) % K), pl = (int)(i / ((size_t)C * K));
+        dense[i] = planes[filter_plane_offset(pl, c >> 6, k, c & 63, Kp, nplanes)];
+    }
+    if (i < (size_t)K * kF2Entries) {
+        const ScaleEntry s = table[i];
+        table_out[4 * i + 0] = s.n; table_out[4 * i + 1] = s.p;
+        table_out[4 * i + 2] = s.r; table_out[4 * i + 3] = s.q;
+    }
+}
+
+// ---- convolution kernel -----------------------------------------------------------------------
+// LDS operand plane: the 16-byte piece holding channels 16 c16 .. 16 c16 + 15 of tile `tile` of
+// row block `rb` (rotated by 4 c16 within the row block, so that 4-byte writes and 16-byte
+// reads both spread over the banks).
+__device__ inline int f2_lds_slot(int rb, int c16, int tile) { return rb * 64 + c16 * 16 + ((tile + 4 * c16) & 15); }
+
+// The 4x4 input patch of one tile (rows 2ty-1 .. 2ty+2, columns 2tx-1 .. 2tx+2), four
+// consecutive channels per pixel packed into a dword, biased to u = x + 128; pixels outside the
+// image and channels beyond C hold the bias itself (x = 0).  Addresses are clamped into the
+// image, so no load sits behind a branch.
+template <int LAYOUT, bool VEC4>
+__device__ inline void f2_load_patch(const int8_t* __restrict__ x, const Problem& p, int n, int ty, int tx, int c0,
+                                     uint32_t u[4][4]) {
+    const int h0 = 2 * ty - 1, w0 = 2 * tx - 1;
+    const uint32_t pixel_stride = LAYOUT == WG_NHWC ? (uint32_t)p.C : 1u;
+    uint32_t row_off[4], col_off[4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        row_off[a] = (uint32_t)min(max(h0 + a, 0), p.H - 1) * (uint32_t)p.W * pixel_stride;
+        col_off[a] = (uint32_t)min(max(w0 + a, 0), p.W - 1) * pixel_stride;
+    }
+    const int8_t* img = x + (size_t)n * p.C * p.H * p.W;
+    if constexpr (VEC4) {
+        const int8_t* src = img + (c0 < p.C ? c0 : 0);
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) u[a][b] = *reinterpret_cast<const uint32_t*>(src + (row_off[a] + col_off[b]));
+    } else {
+        const uint32_t cstride = LAYOUT == WG_NHWC ? 1u : (uint32_t)p.H * (uint32_t)p.W;
+        uint32_t chan_off[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) chan_off[i] = (uint32_t)min(c0 + i, p.C - 1) * cstride;
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                uint32_t word = 0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t e = (uint8_t)img[row_off[a] + col_off[b] + chan_off[i]];
+                    word |= (c0 + i < p.C ? e : 0u) << (8 * i);   // zero = no contribution beyond C
+                }
+                u[a][b] = word;
+            }
+    }
+    const bool have = c0 < p.C;
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const bool inside = have && (unsigned)(h0 + a) < (unsigned)p.H && (unsigned)(w0 + b) < (unsigned)p.W;
+            u[a][b] = inside ? (u[a][b] ^ kBiasBytes) : kBiasBytes;
+        }
+}
+
+// The 1-D rule of B^T for F(2,3): t0 = v0 - v2, t1 = v1 + v2, t2 = v2 - v1, t3 = v1 - v3.
+__device__ inline void f2_bt_rule(Quad v0, Quad v1, Quad v2, Quad v3, Quad t[4]) {
+    t[0] = v0 - v2;
+    t[1] = v1 + v2;
+    t[2] = v2 - v1;
+    t[3] = v1 - v3;
+}
+
+// D = B^T d B of one patch (four channels); entry e = 4 r + c goes to planes 2e (high limb) and
+// 2e + 1 (low limb).  A constant patch transforms to zero everywhere except entry (1,1), where
+// the four +1 coefficients add up: the bias leaves 4 * 128 there and is removed by one subtraction.
+__device__ inline void f2_transform_patch(const uint32_t u[4][4], int8_t* lds_piece) {
+    Quad col[4][4];   // col[b][r]: row r of B^T d, column b
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+        f2_bt_rule(unpack_u8x4(u[0][b]), unpack_u8x4(u[1][b]), unpack_u8x4(u[2][b]), unpack_u8x4(u[3][b]), col[b]);
+    const s16x2 bias11 = {512, 512};
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        Quad d[4];
+        f2_bt_rule(col[0][r], col[1][r], col[2][r], col[3][r], d);
+        if (r == 1) d[1] = Quad{d[1].a - bias11, d[1].b - bias11};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int e = 4 * r + c;
+            const Quad hi = Quad{d[c].a >> 6, d[c].b >> 6};
+            *reinterpret_cast<uint32_t*>(lds_piece + (2 * e) * kF2PlaneBytes) = pack_low_bytes(hi);
+            *reinterpret_cast<uint32_t*>(lds_piece + (2 * e + 1) * kF2PlaneBytes) = pack_low_bytes(d[c]) & 0x3f3f3f3fu;
+        }
+    }
+}
+
+template <class F, int... Is>
+__device__ inline void f2_static_for_impl(F&& f, std::integer_sequence<int, Is...>) {
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ inline void f2_static_for(F&& f) {
+    f2_static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// grid: (ceil(T/32), Kp/32), 256 threads.  Transform phase: thread = (tile, four channels), two
+// items per thread.  Product phase: wave w owns row block w & 1 (16 tiles) and filter block
+// w >> 1 (16 filters) for all 16 entries.
+template <int LAYOUT, bool VEC4, int MODE>
+__global__ __launch_bounds__(256) void f2_conv_kernel(const int8_t* __restrict__ x, const uint8_t* __restrict__ blob,
+                                                      size_t table_off, size_t planes_off, int32_t* __restrict__ y,
+                                                      Problem p) {
+    extern __shared__ __attribute__((aligned(16))) int8_t lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int rb = wave & 1, kb = wave >> 1;
+    const int tile0 = blockIdx.x * kF2Tiles;
+    const int k = blockIdx.y * kF2Filters + kb * 16 + (lane & 15);   // this lane's filter (< Kp)
+    const BlobHeader* hdr = reinterpret_cast<const BlobHeader*>(blob);
+    if (!(hdr->magic == kF2BlobMagic && hdr->version == kBlobVersion && hdr->K == p.K && hdr->C == p.C && hdr->mode == MODE))
+        return;
+
+    constexpr int NA = MODE == WG_LOSSLESS ? 3 : 2;          // accumulators per entry
+    constexpr int NBP = MODE == WG_LOSSLESS ? 2 : 1;         // filter planes per entry
+    constexpr int NP = MODE == WG_LOSSLESS ? 2 * kF2Entries : kF2Entries;
+    v4i acc[kF2Entries][NA];
+#pragma unroll
+    for (int e = 0; e < kF2Entries; ++e)
+#pragma unroll
+        for (int i = 0; i < NA; ++i) acc[e][i] = (v4i){0, 0, 0, 0};
+
+    // transform-phase identity: items (tile = tid / 16 + 16 it, channel quad = tid % 16)
+    int t_n[2] = {0, 0}, t_ty[2] = {0, 0}, t_tx[2] = {0, 0};
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int t = tile0 + (tid >> 4) + 16 * it;
+        if (t < p.T) decode_tile(p, t, t_n[it], t_ty[it], t_tx[it]);
+    }
+    const int cq = tid & 15;
+    const int8_t* a_lds = lds + f2_lds_slot(rb, lane >> 4, lane & 15) * 16;
+    const int8_t* b_lane = reinterpret_cast<const int8_t*>(blob + planes_off) +
+                           filter_plane_offset(0, 0, k, (lane >> 4) * 16, p.Kp, NP);
+    const size_t b_block_stride = (size_t)(p.Kp >> 4) * NP * kFilterFragBytes;
+
+    for (int cb = 0; cb < p.CB; ++cb) {
+        if (cb > 0) __syncthreads();   // the previous block's operand planes have been consumed
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            uint32_t u[4][4];
+            f2_load_patch<LAYOUT, VEC4>(x, p, t_n[it], t_ty[it], t_tx[it], cb * kCBlock + 4 * cq, u);
+            f2_transform_patch(u, lds + f2_lds_slot(it, cq >> 2, tid >> 4) * 16 + (cq & 3) * 4);
+        }
+        __syncthreads();
+        const int8_t* b_cb = b_lane + cb * b_block_stride;
+        f2_static_for<kF2Entries>([&](auto E) {
+            constexpr int e = E;
+            const v4i ah = *reinterpret_cast<const v4i*>(a_lds + (2 * e) * kF2PlaneBytes);
+            const v4i al = *reinterpret_cast<const v4i*>(a_lds + (2 * e + 1) * kF2PlaneBytes);
+            const v4i b0 = *reinterpret_cast<const v4i*>(b_cb + (NBP * e) * kFilterFragBytes);
+            if constexpr (MODE == WG_LOSSLESS) {
+                const v4i b1 = *reinterpret_cast<const v4i*>(b_cb + (2 * e + 1) * kFilterFragBytes);
+                acc[e][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ah, b0, acc[e][0], 0, 0, 0);
+                acc[e][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ah, b1, acc[e][1], 0, 0, 0);
+                acc[e][2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(al, b1, acc[e][2], 0, 0, 0);
+                acc[e][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(al, b0, acc[e][1], 0, 0, 0);
+            } else {
+                acc[e][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ah, b0, acc[e][0], 0, 0, 0);
+                acc[e][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(al, b0, acc[e][1], 0, 0, 0);
+            }
+        });
+    }
+
+    // ---- join the limbs, undo the filter scaling, output transform --------------------------
+    v4i m[kF2Entries];
+#pragma unroll
+    for (int e = 0; e < kF2Entries; ++e) {
+        if constexpr (MODE == WG_LOSSLESS) {
+            m[e] = (((acc[e][0] << 6) + acc[e][1]) << 6) + acc[e][2];
+        } else {
+            m[e] = (acc[e][0] << 6) + acc[e][1];
+            const ReverseScale unscale(reinterpret_cast<const ScaleEntry*>(blob + table_off)[(size_t)k * kF2Entries + e]);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) m[e][q] = unscale(m[e][q]);
+        }
+    }
+    // Y = A^T M A with A^T = [1 1 1 0; 0 1 -1 -1]: rows first, then columns; the rescale by 2^-2
+    // undoes G' = 2G on both sides (exact in lossless mode, round half up in scaled mode).
+    v4i z[2][4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        z[0][c] = m[c] + m[4 + c] + m[8 + c];
+        z[1][c] = m[4 + c] - m[8 + c] - m[12 + c];
+    }
+    const int rnd = MODE == WG_SCALED ? 2 : 0;
+    v4i out[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        out[i][0] = (z[i][0] + z[i][1] + z[i][2] + rnd) >> 2;
+        out[i][1] = (z[i][1] - z[i][2] - z[i][3] + rnd) >> 2;
+    }
+    // register q of a lane: tile 4 (lane / 16) + q of the wave's row block, filter k
+    if (k >= p.K) return;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int t = tile0 + rb * 16 + 4 * (lane >> 4) + q;
+        if (t >= p.T) continue;
+        int n, ty, tx;
+        decode_tile(p, t, n, ty, tx);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int h = 2 * ty + i, w = 2 * tx + j;
+                if (h >= p.H || w >= p.W) continue;
+                if (LAYOUT == WG_NHWC) y[(((size_t)n * p.H + h) * p.W + w) * p.K + k] = out[i][j][q];
+                else                   y[(((size_t)n * p.K + k) * p.H + h) * p.W + w] = out[i][j][q];
+            }
+    }
+}
+
+template <int LAYOUT, bool VEC4, int MODE>
+hipError_t launch(const int8_t* x, const uint8_t* blob, const F2BlobLayout& bl, int32_t* y, const Problem& p, hipStream_t s) {
+    static bool configured = false;   // per template instance
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&f2_conv_kernel<LAYOUT, VEC4, MODE>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kF2LdsBytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    dim3 grid(ceil_div(p.T, kF2Tiles), p.Kp / kF2Filters);
+    f2_conv_kernel<LAYOUT, VEC4, MODE><<<grid, 256, kF2LdsBytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p);
+    return hipGetLastError();
+}
+
+template <int LAYOUT, bool VEC4>
+hipError_t launch_mode(const int8_t* x, const uint8_t* blob, const F2BlobLayout& bl, int32_t* y, const Problem& p, int mode,
+                       hipStream_t s) {
+    return mode == WG_LOSSLESS ? launch<LAYOUT, VEC4, WG_LOSSLESS>(x, blob, bl, y, p, s)
+                               : launch<LAYOUT, VEC4, WG_SCALED>(x, blob, bl, y, p, s);
+}
+
+}  // namespace
+
+hipError_t launch_f2_filter_transform(const int8_t* w, int K, int C, int layout, int mode, void* blob_v, hipStream_t s) {
+    uint8_t* blob = static_cast<uint8_t*>(blob_v);
+    const int Kp = ceil_div(K, kFilterPad) * kFilterPad, CB = ceil_div(C, kCBlock);
+    const F2BlobLayout bl = f2_blob_layout(Kp, C, mode);
+    uint32_t* maxmag = reinterpret_cast<uint32_t*>(blob + bl.maxmag_off);
+    ScaleEntry* table = reinterpret_cast<ScaleEntry*>(blob + bl.table_off);
+    const int entries = Kp * kF2Entries;
+    f2_blob_init_kernel<<<ceil_div(entries, 256), 256, 0, s>>>(blob, K, C, mode, Kp, CB, bl.maxmag_off);
+    if (mode == WG_SCALED) f2_maxmag_kernel<<<dim3(K, CB), 64, 0, s>>>(w, K, C, layout, maxmag);
+    f2_table_kernel<<<ceil_div(entries, 256), 256, 0, s>>>(maxmag, table, entries, mode);
+    f2_pack_kernel<<<dim3(CB, ceil_div(Kp, 4)), 256, 0, s>>>(w, K, C, layout, mode, Kp, table,
+                                                             reinterpret_cast<int8_t*>(blob + bl.planes_off));
+    return hipGetLastError();
+}
+
+hipError_t launch_f2_unpack_filter_planes(const void* blob_v, int8_t* dense, int32_t* table_out, int K, int C, int mode,
+                                          hipStream_t s) {
+    const uint8_t* blob = static_cast<const uint8_t*>(blob_v);
+    const int Kp = ceil_div(K, kFilterPad) * kFilterPad;
+    const F2BlobLayout bl = f2_blob_layout(Kp, C, mode);
+    const int nplanes = f2_filter_planes(mode);
+    const size_t total = (size_t)nplanes * K * C;
+    const size_t threads = total > (size_t)K * kF2Entries ? total : (size_t)K * kF2Entries;
+    f2_unpack_kernel<<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(
+        reinterpret_cast<const int8_t*>(blob + bl.planes_off), reinterpret_cast<const ScaleEntry*>(blob + bl.table_off), dense,
+        table_out, K, C, Kp, nplanes);
+    return hipGetLastError();
+}
+
+hipError_t launch_f2_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int layout, int mode, hipStream_t s) {
+    const F2BlobLayout bl = f2_blob_layout(p.Kp, p.C, mode);
+    const uint8_t* b = static_cast<const uint8_t*>(blob);
+    if (layout == WG_NHWC && p.C % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 4 == 0)
+        return launch_mode<WG_NHWC, true>(x, b, bl, y, p, mode, s);
+    if (layout == WG_NHWC) return launch_mode<WG_NHWC, false>(x, b, bl, y, p, mode, s);
+    return launch_mode<WG_NCHW, false>(x, b, bl, y, p, mode, s);
+}
+
+}  // namespace wg

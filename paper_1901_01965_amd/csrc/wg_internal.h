@@ -140,6 +140,40 @@ inline BlobLayout blob_layout(int Kp, int C, int mode) {
     return b;
 }
 
+// ---- rational F(2x2,3x3) (Sections 4.1-4.2) ----------------------------------------
+// Its packed filter blob: [BlobHeader][maxmag: uint32 [Kp][16]][table: ScaleEntry [Kp][16]]
+// [operand planes: int8 [CB][Kp/16][planes][16][64]] with planes = 32 (lossless: entry e as limbs
+// 2e, 2e+1) or 16 (scaled).  Tiles are 2x2 outputs: a Problem made by make_problem_f2 counts them.
+constexpr int kF2Entries = 16;
+constexpr uint32_t kF2BlobMagic = 0x32324757u;  // "WG22"
+__host__ __device__ inline int f2_filter_planes(int mode) { return mode == WG_LOSSLESS ? 2 * kF2Entries : kF2Entries; }
+struct F2BlobLayout {
+    size_t maxmag_off, table_off, planes_off, total;
+};
+inline F2BlobLayout f2_blob_layout(int Kp, int C, int mode) {
+    const int CB = (C + kCBlock - 1) / kCBlock;
+    F2BlobLayout b;
+    b.maxmag_off = sizeof(BlobHeader);
+    b.table_off = round_up(b.maxmag_off + (size_t)Kp * kF2Entries * sizeof(uint32_t), 256);
+    b.planes_off = round_up(b.table_off + (size_t)Kp * kF2Entries * sizeof(ScaleEntry), 256);
+    b.total = b.planes_off + (size_t)f2_filter_planes(mode) * CB * Kp * kCBlock;
+    return b;
+}
+inline Problem make_problem_f2(int N, int C, int H, int W, int K) {
+    Problem p = make_problem(N, C, H, W, K);
+    p.TH = ceil_div(H, 2); p.TW = ceil_div(W, 2);
+    p.T = N * p.TH * p.TW;
+    p.Tp = ceil_div(p.T, kTilePad) * kTilePad;
+    p.div_tw = make_fast_div((uint32_t)p.TW);
+    p.div_th = make_fast_div((uint32_t)p.TH);
+    return p;
+}
+hipError_t launch_f2_filter_transform(const int8_t* w, int K, int C, int layout, int mode, void* blob, hipStream_t s);
+hipError_t launch_f2_unpack_filter_planes(const void* blob, int8_t* dense, int32_t* table, int K, int C, int mode,
+                                          hipStream_t s);
+hipError_t launch_f2_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int layout, int mode,
+                          hipStream_t s);
+
 // ---- workspace ------------------------------------------------------------------
 // [V: int8 [planes][CB][Tp][64]][M: int32 [46 lossless | 36 scaled][Tp][Kp]]
 struct WorkspaceLayout {

@@ -1,0 +1,110 @@
+"""GPU parity of the rational F(2x2,3x3) path, through the C ABI, bit for bit against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1901_01965_amd as wg
+from paper_1901_01965_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+LAYOUTS = [wg.NHWC, wg.NCHW]
+SHAPES = [  # N, C, K, H, W: ragged tiles, odd channel counts, several channel blocks, more than 32 tiles and filters
+    (1, 1, 1, 1, 1), (1, 4, 4, 4, 4), (1, 3, 5, 7, 9), (2, 16, 16, 16, 16), (1, 70, 33, 10, 6), (3, 8, 100, 5, 13),
+    (1, 130, 65, 8, 8), (2, 64, 64, 14, 14), (1, 200, 40, 6, 10),
+]
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _x(x, layout):
+    return _dev(x if layout == wg.NCHW else wl.to_nhwc(x))
+
+
+def _g(g, layout):
+    return _dev(g if layout == wg.NCHW else wl.to_krsc(g))
+
+
+def _y(y, layout):
+    y = y.cpu().numpy()
+    return y if layout == wg.NCHW else wl.from_nhwc(y)
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("kc,wgt", [((4, 4), "uniform"), ((5, 3), "gauss"), ((64, 64), "gauss"), ((33, 70), "uniform")])
+def test_filter_operands_and_scaling_table(kc, wgt, layout):
+    """The blob's operand planes and (n, p, r, q) table against the oracle's G' g G'^T and Section 4.2 routine."""
+    K, C = kc
+    _, g = wl.make_custom(1, C, K, 4, 4, wgt=wgt, seed=70)
+    Wt = oracle.f2_filter_transform(g)                      # [K, C, 4, 4]
+    flat = Wt.reshape(K, C, 16).transpose(2, 0, 1)          # [16, K, C]
+    planes, _ = wg.f2x2_debug_filter_operands(wg.f2x2_filter_transform(_g(g, layout), layout, wg.LOSSLESS))
+    planes = planes.cpu().numpy().astype(np.int64)
+    assert np.array_equal(planes[0::2], flat >> 6) and np.array_equal(planes[1::2], flat & 63)
+    scaled, tab, _ = oracle.f2_scale_filters(Wt, 127)
+    planes, table = wg.f2x2_debug_filter_operands(wg.f2x2_filter_transform(_g(g, layout), layout, wg.SCALED))
+    assert np.array_equal(planes.cpu().numpy().astype(np.int64), scaled.reshape(K, C, 16).transpose(2, 0, 1))
+    want = tab.reshape(K, 16, 4).copy()
+    want[want[..., 0] == 0] = (0, 0, 1, 0)                  # the library stores "no scaling" as r/2^q = 1/1
+    assert np.array_equal(table.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("shape", SHAPES)
+def test_lossless_equals_oracle_direct(shape, layout):
+    N, C, K, H, W = shape
+    x, g = wl.make_custom(N, C, K, H, W, seed=71)
+    packed = wg.f2x2_filter_transform(_g(g, layout), layout, wg.LOSSLESS)
+    y = wg.f2x2_conv2d_int8(_x(x, layout), packed, layout)
+    assert np.array_equal(_y(y, layout), oracle.direct_conv2d(x, g))
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("wgt", ["uniform", "gauss"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_scaled_equals_oracle_scaled(shape, wgt, layout):
+    N, C, K, H, W = shape
+    x, g = wl.make_custom(N, C, K, H, W, wgt=wgt, seed=72)
+    want, flags = oracle.f2_conv2d(x, g, oracle.SCALED, 127)
+    assert (flags & 4) == 0
+    packed = wg.f2x2_filter_transform(_g(g, layout), layout, wg.SCALED)
+    y = wg.f2x2_conv2d_int8(_x(x, layout), packed, layout)
+    assert np.array_equal(_y(y, layout), want)
+
+
+def test_extreme_values_and_many_channels():
+    """All-extreme data at the largest supported channel count: every limb product and the joins at their limits."""
+    C = wg.MAX_CHANNELS
+    for xv, gv in ((-128, -128), (127, -128), (-128, 127)):
+        x = np.full((1, C, 4, 6), xv, np.int8)
+        g = np.full((2, C, 3, 3), gv, np.int8)
+        g[1] = 127
+        packed = wg.f2x2_filter_transform(_g(g, wg.NHWC), wg.NHWC, wg.LOSSLESS)
+        y = wg.f2x2_conv2d_int8(_x(x, wg.NHWC), packed, wg.NHWC)
+        assert np.array_equal(_y(y, wg.NHWC), oracle.direct_conv2d(x, g))
+
+
+def test_cfg2_full_size_lossless_and_agreement_with_the_complex_algorithm():
+    x, g = wl.make_case("cfg2")
+    xd, gd = _x(x, wg.NHWC), _g(g, wg.NHWC)
+    y2 = wg.f2x2_conv2d_int8(xd, wg.f2x2_filter_transform(gd, wg.NHWC, wg.LOSSLESS), wg.NHWC)
+    y4 = wg.winograd_conv2d_int8(xd, wg.winograd_filter_transform(gd, wg.NHWC, wg.LOSSLESS), wg.NHWC)
+    assert torch.equal(y2, y4)
+    assert np.array_equal(_y(y2[:1], wg.NHWC), oracle.direct_conv2d(x[:1], g))
+
+
+def test_mismatched_blob_is_rejected_and_output_untouched():
+    x, g = wl.make_custom(1, 8, 8, 6, 6, seed=73)
+    packed = wg.f2x2_filter_transform(_g(g, wg.NHWC), wg.NHWC, wg.LOSSLESS)
+    other = wg.F2x2PackedFilter(packed.blob, packed.K, packed.C, wg.SCALED)     # blob made for the other mode
+    out = torch.full((1, 6, 6, 8), 1234567, dtype=torch.int32, device="cuda")
+    wg.f2x2_conv2d_int8(_x(x, wg.NHWC), other, wg.NHWC, out=out)
+    assert bool((out == 1234567).all())
+    # a blob of the F(4x4,3x3) path is not accepted either
+    p4 = wg.winograd_filter_transform(_g(g, wg.NHWC), wg.NHWC, wg.LOSSLESS)
+    if p4.blob.numel() >= packed.blob.numel():
+        wg.f2x2_conv2d_int8(_x(x, wg.NHWC), wg.F2x2PackedFilter(p4.blob, 8, 8, wg.LOSSLESS), wg.NHWC, out=out)
+        assert bool((out == 1234567).all())
