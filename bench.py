@@ -187,6 +187,69 @@ def run_stack(args):
     }))
 
 
+def run_f2x2(args):
+    """--algorithm f2x2: the same layer through the rational F(2x2,3x3) integer path (one kernel per step)."""
+    import torch
+    import paper_1901_01965_amd as wg
+    from paper_1901_01965_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    wg.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    case = wl.CASES[args.case]
+    if args.batch is not None:
+        import dataclasses
+        case = dataclasses.replace(case, name="%s@N=%d" % (case.name, args.batch), N=args.batch)
+    layout = wg.NHWC if args.layout == "nhwc" else wg.NCHW
+    mode = wg.LOSSLESS if args.mode == "lossless" else wg.SCALED
+    x_np, g_np = wl.make_case(case)
+    xd = torch.from_numpy(wl.to_nhwc(x_np) if layout == wg.NHWC else x_np).to(dev)
+    gd = torch.from_numpy(wl.to_krsc(g_np) if layout == wg.NHWC else g_np).to(dev)
+    out_shape = (case.N, case.H, case.W, case.K) if layout == wg.NHWC else (case.N, case.K, case.H, case.W)
+    y = torch.empty(out_shape, dtype=torch.int32, device=dev)
+    packed = wg.f2x2_filter_transform(gd, layout, mode)
+
+    def step():
+        wg.f2x2_conv2d_int8(xd, packed, layout, out=y)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    graph = None if args.eager else capture_steps(torch, step, args.steps)
+    if graph is not None:
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    if graph is not None:
+        graph.replay()
+    else:
+        for _ in range(args.steps):
+            step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    yd = wg.direct_conv2d_int8(xd, gd, layout)
+    tiles2 = case.N * ((case.H + 1) // 2) * ((case.W + 1) // 2)
+    alg = 4 * tiles2 * case.C + (32 if mode == wg.LOSSLESS else 16) * case.K * case.C + 16 * tiles2 * case.K
+    mfma_ops = 2 * (64 if mode == wg.LOSSLESS else 32) * tiles2 * case.C * case.K   # int8 limb products per tile and channel pair
+    print(json.dumps({
+        "metric": "direct-equivalent int8 conv TOPS, %s, 1 GPU, F(2x2,3x3)" % args.case,
+        "value": round(case.direct_ops / (ms * 1e-3) / 1e12, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "%s: 3x3 s1 p1 conv N=%d C=%d K=%d H=W=%d, %s, %s mode, rational F(2x2,3x3)" % (
+            case.name, case.N, case.C, case.K, case.H, args.layout.upper(), args.mode)},
+        "launch": "hip graph of %d steps, one replay" % args.steps if graph is not None else "eager",
+        "roofline": {"kernel": "f2_conv", "bound": "hbm", "achieved": round(alg / (ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes": alg, "kernel_ms": round(ms, 5)},
+        "int8_mfma_TOPS": round(mfma_ops / (ms * 1e-3) / 1e12, 1),
+        "mfma_frac": round(mfma_ops / (ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, 4),
+        "gpu_lossless_equals_gpu_direct": bool(torch.equal(y, yd)) if mode == wg.LOSSLESS else None,
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -206,6 +269,8 @@ def main():
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 256 MiB device-to-device tensor copy, the known-size kernel that "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
+    ap.add_argument("--algorithm", default="f4x4", choices=("f4x4", "f2x2"),
+                    help="f4x4: the complex F(4x4,3x3) path (the headline); f2x2: the rational F(2x2,3x3) path")
     ap.add_argument("--stack", action="store_true",
                     help="time the VGG-16-shaped stack (cfg5) instead of one layer; prints its own JSON line")
     args = ap.parse_args()
@@ -213,6 +278,8 @@ def main():
         sys.exit("bench.py: this build measures one GPU only (the path has no cross-GPU step); use --gpus 1")
     if args.stack:
         return run_stack(args)
+    if args.algorithm == "f2x2":
+        return run_f2x2(args)
 
     import numpy as np
     import torch

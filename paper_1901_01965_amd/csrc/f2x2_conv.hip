@@ -22,11 +22,11 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-constexpr int kF2Tiles = 32;      // tiles per workgroup: two row blocks of the 16x16x64 matrix-core product
-constexpr int kF2Filters = 32;    // filters per workgroup: two 16-wide column blocks
+constexpr int kF2Tiles = 16;      // tiles per workgroup: the rows of the 16x16x64 matrix-core product
+constexpr int kF2Filters = 64;    // filters per workgroup: four 16-wide column blocks, one per wave
 constexpr int kF2ActPlanes = 2 * kF2Entries;
 constexpr int kF2PlaneBytes = kF2Tiles * kCBlock;            // one operand plane of the tile block in LDS
-constexpr int kF2LdsBytes = kF2ActPlanes * kF2PlaneBytes;    // 64 KB
+constexpr int kF2LdsBytes = kF2ActPlanes * kF2PlaneBytes;    // 32 KB
 
 // ---- filter transform -----------------------------------------------------------------------
 // W = G' g G'^T in the row-major order of the matrix printed in Section 4.1.
@@ -137,10 +137,9 @@ __global__ void f2_unpack_kernel(const int8_t* planes, const ScaleEntry* table, 
 }
 
 // ---- convolution kernel -----------------------------------------------------------------------
-// LDS operand plane: the 16-byte piece holding channels 16 c16 .. 16 c16 + 15 of tile `tile` of
-// row block `rb` (rotated by 4 c16 within the row block, so that 4-byte writes and 16-byte
-// reads both spread over the banks).
-__device__ inline int f2_lds_slot(int rb, int c16, int tile) { return rb * 64 + c16 * 16 + ((tile + 4 * c16) & 15); }
+// LDS operand plane: the 16-byte piece holding channels 16 c16 .. 16 c16 + 15 of tile `tile`
+// (rotated by 4 c16, so that 4-byte writes and 16-byte reads both spread over the banks).
+__device__ inline int f2_lds_slot(int c16, int tile) { return c16 * 16 + ((tile + 4 * c16) & 15); }
 
 // The 4x4 input patch of one tile (rows 2ty-1 .. 2ty+2, columns 2tx-1 .. 2tx+2), four
 // consecutive channels per pixel packed into a dword, biased to u = x + 128; pixels outside the
@@ -233,18 +232,18 @@ __device__ inline void f2_static_for(F&& f) {
     f2_static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-// grid: (ceil(T/32), Kp/32), 256 threads.  Transform phase: thread = (tile, four channels), two
-// items per thread.  Product phase: wave w owns row block w & 1 (16 tiles) and filter block
-// w >> 1 (16 filters) for all 16 entries.
+// grid: (ceil(T/16), Kp/64), 256 threads.  Transform phase: thread = (tile, four channels).
+// Product phase: wave w owns filter block w (16 filters) of the 16 tiles for all 16 entries; the
+// activation and filter fragments of entry e + 2 are requested while entry e multiplies.
 template <int LAYOUT, bool VEC4, int MODE>
 __global__ __launch_bounds__(256) void f2_conv_kernel(const int8_t* __restrict__ x, const uint8_t* __restrict__ blob,
                                                       size_t table_off, size_t planes_off, int32_t* __restrict__ y,
                                                       Problem p) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int rb = wave & 1, kb = wave >> 1;
     const int tile0 = blockIdx.x * kF2Tiles;
-    const int k = blockIdx.y * kF2Filters + kb * 16 + (lane & 15);   // this lane's filter (< Kp)
+    const int kbase = blockIdx.y * kF2Filters;
+    const int k = kbase + wave * 16 + (lane & 15);   // this lane's filter (< Kp)
     const BlobHeader* hdr = reinterpret_cast<const BlobHeader*>(blob);
     if (!(hdr->magic == kF2BlobMagic && hdr->version == kBlobVersion && hdr->K == p.K && hdr->C == p.C && hdr->mode == MODE))
         return;
@@ -258,44 +257,60 @@ __global__ __launch_bounds__(256) void f2_conv_kernel(const int8_t* __restrict__
 #pragma unroll
         for (int i = 0; i < NA; ++i) acc[e][i] = (v4i){0, 0, 0, 0};
 
-    // transform-phase identity: items (tile = tid / 16 + 16 it, channel quad = tid % 16)
-    int t_n[2] = {0, 0}, t_ty[2] = {0, 0}, t_tx[2] = {0, 0};
-#pragma unroll
-    for (int it = 0; it < 2; ++it) {
-        const int t = tile0 + (tid >> 4) + 16 * it;
-        if (t < p.T) decode_tile(p, t, t_n[it], t_ty[it], t_tx[it]);
-    }
-    const int cq = tid & 15;
-    const int8_t* a_lds = lds + f2_lds_slot(rb, lane >> 4, lane & 15) * 16;
+    // every lane decodes tile (lane & 15) of the block once; the transform phase fetches the
+    // coordinates of its own tile (tid / 16) from that lane
+    int my_n = 0, my_ty = 0, my_tx = 0;
+    if (tile0 + (lane & 15) < p.T) decode_tile(p, tile0 + (lane & 15), my_n, my_ty, my_tx);
+    const int a_tile = tid >> 4, cq = tid & 15;
+    const int a_n = __shfl(my_n, a_tile), a_ty = __shfl(my_ty, a_tile), a_tx = __shfl(my_tx, a_tile);
+    int8_t* put = lds + f2_lds_slot(cq >> 2, a_tile) * 16 + (cq & 3) * 4;
+    const int8_t* a_lds = lds + f2_lds_slot(lane >> 4, lane & 15) * 16;
     const int8_t* b_lane = reinterpret_cast<const int8_t*>(blob + planes_off) +
                            filter_plane_offset(0, 0, k, (lane >> 4) * 16, p.Kp, NP);
     const size_t b_block_stride = (size_t)(p.Kp >> 4) * NP * kFilterFragBytes;
 
+    uint32_t u[4][4];
+    f2_load_patch<LAYOUT, VEC4>(x, p, a_n, a_ty, a_tx, 4 * cq, u);
     for (int cb = 0; cb < p.CB; ++cb) {
         if (cb > 0) __syncthreads();   // the previous block's operand planes have been consumed
-#pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            uint32_t u[4][4];
-            f2_load_patch<LAYOUT, VEC4>(x, p, t_n[it], t_ty[it], t_tx[it], cb * kCBlock + 4 * cq, u);
-            f2_transform_patch(u, lds + f2_lds_slot(it, cq >> 2, tid >> 4) * 16 + (cq & 3) * 4);
-        }
-        __syncthreads();
+        f2_transform_patch(u, put);
+        // the next channel block's patch travels while this one multiplies
+        if (cb + 1 < p.CB) f2_load_patch<LAYOUT, VEC4>(x, p, a_n, a_ty, a_tx, (cb + 1) * kCBlock + 4 * cq, u);
         const int8_t* b_cb = b_lane + cb * b_block_stride;
+        v4i bf[3][NBP], af[3][2];
+        auto request_b = [&](auto E) {
+            constexpr int e = E;
+#pragma unroll
+            for (int i = 0; i < NBP; ++i)
+                bf[e % 3][i] = *reinterpret_cast<const v4i*>(b_cb + (NBP * e + i) * kFilterFragBytes);
+        };
+        auto request_a = [&](auto E) {
+            constexpr int e = E;
+            af[e % 3][0] = *reinterpret_cast<const v4i*>(a_lds + (2 * e) * kF2PlaneBytes);
+            af[e % 3][1] = *reinterpret_cast<const v4i*>(a_lds + (2 * e + 1) * kF2PlaneBytes);
+        };
+        request_b(std::integral_constant<int, 0>{});
+        request_b(std::integral_constant<int, 1>{});
+        __syncthreads();               // the operand planes are complete
+        request_a(std::integral_constant<int, 0>{});
+        request_a(std::integral_constant<int, 1>{});
         f2_static_for<kF2Entries>([&](auto E) {
             constexpr int e = E;
-            const v4i ah = *reinterpret_cast<const v4i*>(a_lds + (2 * e) * kF2PlaneBytes);
-            const v4i al = *reinterpret_cast<const v4i*>(a_lds + (2 * e + 1) * kF2PlaneBytes);
-            const v4i b0 = *reinterpret_cast<const v4i*>(b_cb + (NBP * e) * kFilterFragBytes);
-            if constexpr (MODE == WG_LOSSLESS) {
-                const v4i b1 = *reinterpret_cast<const v4i*>(b_cb + (2 * e + 1) * kFilterFragBytes);
-                acc[e][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ah, b0, acc[e][0], 0, 0, 0);
-                acc[e][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ah, b1, acc[e][1], 0, 0, 0);
-                acc[e][2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(al, b1, acc[e][2], 0, 0, 0);
-                acc[e][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(al, b0, acc[e][1], 0, 0, 0);
-            } else {
-                acc[e][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ah, b0, acc[e][0], 0, 0, 0);
-                acc[e][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(al, b0, acc[e][1], 0, 0, 0);
+            if constexpr (e + 2 < kF2Entries) {
+                request_b(std::integral_constant<int, e + 2>{});
+                request_a(std::integral_constant<int, e + 2>{});
             }
+            const v4i ah = af[e % 3][0], al = af[e % 3][1];
+            if constexpr (MODE == WG_LOSSLESS) {
+                acc[e][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ah, bf[e % 3][0], acc[e][0], 0, 0, 0);
+                acc[e][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ah, bf[e % 3][1], acc[e][1], 0, 0, 0);
+                acc[e][2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(al, bf[e % 3][1], acc[e][2], 0, 0, 0);
+                acc[e][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(al, bf[e % 3][0], acc[e][1], 0, 0, 0);
+            } else {
+                acc[e][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ah, bf[e % 3][0], acc[e][0], 0, 0, 0);
+                acc[e][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(al, bf[e % 3][0], acc[e][1], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         });
     }
 
@@ -321,29 +336,52 @@ __global__ __launch_bounds__(256) void f2_conv_kernel(const int8_t* __restrict__
         z[1][c] = m[4 + c] - m[8 + c] - m[12 + c];
     }
     const int rnd = MODE == WG_SCALED ? 2 : 0;
-    v4i out[2][2];
+    v4i out[4];   // output pixel 2 i + j
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-        out[i][0] = (z[i][0] + z[i][1] + z[i][2] + rnd) >> 2;
-        out[i][1] = (z[i][1] - z[i][2] - z[i][3] + rnd) >> 2;
+        out[2 * i + 0] = (z[i][0] + z[i][1] + z[i][2] + rnd) >> 2;
+        out[2 * i + 1] = (z[i][1] - z[i][2] - z[i][3] + rnd) >> 2;
     }
-    // register q of a lane: tile 4 (lane / 16) + q of the wave's row block, filter k
-    if (k >= p.K) return;
+    // register q of a lane: tile 4 (lane / 16) + q, filter k
+    if (LAYOUT == WG_NHWC && (p.K & 3) == 0) {
+        // Channels-last with K a multiple of four: staged filter-fastest, stage[pixel][tile][68]
+        // (64 filters, rows padded to 68 dwords), then a thread stores four consecutive filters
+        // and sixteen lanes cover the 256 contiguous bytes this block owns of a pixel.
+        constexpr int kRow = 68;
+        static_assert(4 * 16 * kRow * 4 <= kF2LdsBytes, "staging fits the operand planes' LDS");
+        __syncthreads();   // the operand planes are dead
+        int* stage = reinterpret_cast<int*>(lds);
+#pragma unroll
+        for (int o = 0; o < 4; ++o)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) stage[(o * 16 + 4 * (lane >> 4) + q) * kRow + wave * 16 + (lane & 15)] = out[o][q];
+        __syncthreads();
+        const int k4 = tid & 15, tile = tid >> 4;   // thread: filters 4 k4 .. 4 k4 + 3 of tile `tile`, all four pixels
+        const int n = __shfl(my_n, tile), ty = __shfl(my_ty, tile), tx = __shfl(my_tx, tile);
+        const int kk = kbase + 4 * k4;
+        if (tile0 + tile < p.T && kk < p.K) {
+#pragma unroll
+            for (int o = 0; o < 4; ++o) {
+                const int h = 2 * ty + (o >> 1), w = 2 * tx + (o & 1);
+                if (h < p.H && w < p.W)
+                    *reinterpret_cast<v4i*>(y + (((size_t)n * p.H + h) * p.W + w) * p.K + kk) =
+                        *reinterpret_cast<const v4i*>(stage + (o * 16 + tile) * kRow + 4 * k4);
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        const int t = tile0 + rb * 16 + 4 * (lane >> 4) + q;
-        if (t >= p.T) continue;
-        int n, ty, tx;
-        decode_tile(p, t, n, ty, tx);
+        const int tl = 4 * (lane >> 4) + q;
+        const int n = __shfl(my_n, tl), ty = __shfl(my_ty, tl), tx = __shfl(my_tx, tl);   // all lanes take part
+        if (tile0 + tl >= p.T || k >= p.K) continue;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int h = 2 * ty + i, w = 2 * tx + j;
-                if (h >= p.H || w >= p.W) continue;
-                if (LAYOUT == WG_NHWC) y[(((size_t)n * p.H + h) * p.W + w) * p.K + k] = out[i][j][q];
-                else                   y[(((size_t)n * p.K + k) * p.H + h) * p.W + w] = out[i][j][q];
-            }
+        for (int o = 0; o < 4; ++o) {
+            const int h = 2 * ty + (o >> 1), w = 2 * tx + (o & 1);
+            if (h >= p.H || w >= p.W) continue;
+            if (LAYOUT == WG_NHWC) y[(((size_t)n * p.H + h) * p.W + w) * p.K + k] = out[o][q];
+            else                   y[(((size_t)n * p.K + k) * p.H + h) * p.W + w] = out[o][q];
+        }
     }
 }
 
