@@ -468,9 +468,24 @@ __device__ __forceinline__ void fused_conv_body(const int8_t* __restrict__ x, co
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kblock = wave & 1, half = wave >> 1;
-    const int tile0 = blockIdx.x * kFusedTiles;
+    // Workgroups are handed to the eight XCDs (each with its own L2) round-robin in launch order.
+    // With eight or more filter blocks, the blocks are dealt out so that all tile blocks of one
+    // filter block run on the same XCD at the same time: a filter block's operand planes (up to
+    // several hundred KB per channel block) are then fetched into that L2 once instead of into
+    // every L2.
+    int bx = blockIdx.x, by = blockIdx.y;
+    {
+        const int total = gridDim.x * gridDim.y;
+        if (gridDim.y >= 8 && (total & 7) == 0) {
+            const int launch = blockIdx.y * gridDim.x + blockIdx.x;
+            const int w = (launch & 7) * (total >> 3) + (launch >> 3);   // XCD-major position
+            by = w / (int)gridDim.x;
+            bx = w - by * (int)gridDim.x;
+        }
+    }
+    const int tile0 = bx * kFusedTiles;
     constexpr int NPASS = WIDE ? 2 : 1;
-    const int k0 = blockIdx.y * (kFusedFilters * NPASS);
+    const int k0 = by * (kFusedFilters * NPASS);
     const int k = k0 + kblock * 16 + (lane & 15);
 
     // The activation patch of the first channel block does not depend on the blob and is the
