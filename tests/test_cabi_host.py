@@ -124,6 +124,24 @@ def test_validation_errors_return_before_any_launch(lib):
     assert cq(good, good2, good3, 1, 4, 8, 7, 4, 0, 0, 3, 1, 1, None) == EUNSUPPORTED   # odd W with pooling
     assert cq(good, good2, good3, 1, 1000, 8, 8, 4, 0, 0, 3, 1, 0, None) == EUNSUPPORTED
 
+    # rational F(2x2,3x3) entry points
+    assert lib.winograd_f2x2_packed_filter_bytes(0, 4, 0) == 0 and lib.winograd_f2x2_packed_filter_bytes(4, 4, 5) == 0
+    f2_bytes = lib.winograd_f2x2_packed_filter_bytes(4, 4, 0)
+    assert f2_bytes > 32 * 64 * 64 and f2_bytes % 256 == 0
+    assert lib.winograd_f2x2_packed_filter_bytes(4, 4, 1) < f2_bytes          # one operand plane per entry instead of two
+    f2t = lib.winograd_f2x2_filter_transform
+    assert f2t(None, 4, 4, 0, 0, good2, f2_bytes, None) == EINVAL
+    assert f2t(good, 4, 4, 0, 0, good2, f2_bytes - 1, None) == ESMALLBUF
+    assert f2t(good, 4, 1000, 0, 0, good2, big, None) == EUNSUPPORTED
+    assert f2t(good, 4, 4, 0, 0, p(0x20010), big, None) == EINVAL             # misaligned blob
+    f2c = lib.winograd_f2x2_conv2d_int8
+    assert f2c(good, good2, None, 1, 4, 8, 8, 4, 0, 0, None) == EINVAL
+    assert f2c(good, good2, good3, 1, 4, 8, 8, 4, 7, 0, None) == EINVAL       # unknown layout
+    assert f2c(good, good2, good3, 0, 4, 8, 8, 4, 0, 0, None) == EINVAL
+    assert f2c(odd, good2, good3, 1, 4, 8, 8, 4, 0, 0, None) == EINVAL
+    assert f2c(good, good2, good3, 1, 1000, 8, 8, 4, 0, 0, None) == EUNSUPPORTED
+    assert lib.winograd_f2x2_debug_filter_operands(good2, 4, 4, 0, None, good3, None) == EINVAL
+
     st = lib.winograd_conv2d_int8_stage_times
     assert st(good, good2, good3, 1, 4, 8, 8, 4, 0, 0, p(0x40000), ws_bytes, None, 0, good) == EINVAL
     assert st(good, good2, good3, 1, 4, 8, 8, 4, 0, 0, p(0x40000), ws_bytes, None, 1, None) == EINVAL
