@@ -451,11 +451,12 @@ __device__ inline uint32_t pack_bytes(v4i v) {
     return (uint32_t)(v[0] & 0xff) | ((uint32_t)(v[1] & 0xff) << 8) | ((uint32_t)(v[2] & 0xff) << 16) | ((uint32_t)v[3] << 24);
 }
 
-// grid: (ceil(T/16), Kp/32).  256 threads: in the transform phase one thread per (tile,
+// grid: (ceil(T/16), Kp/32), or Kp/64 for WIDE.  256 threads: in the transform phase one thread per (tile,
 // four channels); in the product phase wave w owns filter block (w & 1) and half of the
 // rows of M (w >> 1: rows 0,1,2 or rows 5,3); all four waves stage their partial outputs
 // in LDS and the block stores the sums with full-line writes.
-// SUMS: scaled mode with more than one channel block (see ScaledSums).
+// SUMS: scaled mode keeps channel sums and scales them at the end (see ScaledSums): needed with
+// more than one channel block, and used for every scaled WIDE workgroup.
 // WIDE: the workgroup covers 64 filters instead of 32: the transform of a
 // channel block is followed by two passes over the entries, one per 32 filters, each with its own
 // outputs; used when there are more workgroups than compute units, where halving the number of
