@@ -96,6 +96,23 @@ def test_cfg2_full_size_lossless_and_agreement_with_the_complex_algorithm():
     assert np.array_equal(_y(y2[:1], wg.NHWC), oracle.direct_conv2d(x[:1], g))
 
 
+@pytest.mark.parametrize("name", ["cfg3", "cfg4a", "cfg4b"])
+def test_full_size_scaled_configs(name):
+    """The benchmark configurations at full size in the launch configuration bench.py --algorithm f2x2 times; the
+    oracle checks the first and the last two images (tiles at both ends of the grid), the lossless result the whole
+    batch against the direct kernel."""
+    x, g = wl.make_case(name)
+    xd, gd = _x(x, wg.NHWC), _g(g, wg.NHWC)
+    y = _y(wg.f2x2_conv2d_int8(xd, wg.f2x2_filter_transform(gd, wg.NHWC, wg.SCALED), wg.NHWC), wg.NHWC)
+    for sl in (slice(0, 1), slice(x.shape[0] - 2, x.shape[0])):
+        want, flags = oracle.f2_conv2d(x[sl], g, oracle.SCALED, 127)
+        assert (flags & 4) == 0
+        assert np.array_equal(y[sl], want)
+    lossless = wg.f2x2_conv2d_int8(xd, wg.f2x2_filter_transform(gd, wg.NHWC, wg.LOSSLESS), wg.NHWC)
+    assert torch.equal(lossless, wg.direct_conv2d_int8(xd, gd, wg.NHWC))
+    assert np.array_equal(_y(lossless[:1], wg.NHWC), oracle.direct_conv2d(x[:1], g))
+
+
 def test_mismatched_blob_is_rejected_and_output_untouched():
     x, g = wl.make_custom(1, 8, 8, 6, 6, seed=73)
     packed = wg.f2x2_filter_transform(_g(g, wg.NHWC), wg.NHWC, wg.LOSSLESS)
