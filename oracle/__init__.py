@@ -271,3 +271,42 @@ def f2_conv2d(x, g, mode=LOSSLESS, weight_range=127):
     if flags < 0:
         raise MemoryError("oracle ran out of memory")
     return y, int(flags)
+
+
+def _i16(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.int16, a.dtype
+    return a
+
+
+def direct_conv2d_i16(x, g):
+    """Direct 3x3 stride-1 pad-1 correlation of int16 arrays (e.g. uint8 minus zero point) -> int32 NCHW."""
+    x, g = _i16(x), _i16(g)
+    N, C, H, W = x.shape
+    K = g.shape[0]
+    assert g.shape == (K, C, 3, 3)
+    y = np.zeros((N, K, H, W), np.int32)
+    flags = lib().oracle_direct_conv2d_i16(_p(x), _p(g), _p(y), N, C, H, W, K)
+    assert flags == 0, "output does not fit int32"
+    return y
+
+
+def f2_filter_transform_i16(g):
+    g = _i16(g)
+    K, C = g.shape[:2]
+    out = np.zeros((K, C, 4, 4), np.int64)
+    lib().oracle_f2_filter_transform_i16(_p(g), K, C, _p(out))
+    return out
+
+
+def f2_conv2d_i16(x, g, mode=LOSSLESS, weight_range=127):
+    """F(2x2,3x3) path on int16 inputs (int9 values).  Returns (y int32 NCHW, flags)."""
+    x, g = _i16(x), _i16(g)
+    N, C, H, W = x.shape
+    K = g.shape[0]
+    assert g.shape == (K, C, 3, 3)
+    y = np.zeros((N, K, H, W), np.int32)
+    flags = lib().oracle_f2_conv2d_i16(_p(x), _p(g), _p(y), N, C, H, W, K, mode, ctypes.c_int64(weight_range))
+    if flags < 0:
+        raise MemoryError("oracle ran out of memory")
+    return y, int(flags)

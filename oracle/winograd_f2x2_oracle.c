@@ -19,6 +19,9 @@
  *   oracle_f2_input_transform, oracle_f2_conv2d (lossless)
  *                               pinned: exact equality with the direct convolution,
  *                               1-D F(2,3) against brute force
+ *   *_i16 variants              the same code on 16-bit inputs (uint8 minus zero point = int9,
+ *                               Section 4.1); oracle_direct_conv2d_i16 pinned against the int8
+ *                               direct convolution and a numpy einsum
  *   oracle_f2_conv2d (scaled)   special cases pinned (no location needs scaling
  *                               => equals lossless; scaled weights within the range;
  *                               table entries from the pinned factor routines);
@@ -51,10 +54,19 @@ void oracle_f2_get_matrices(int8_t* bt /*[4][4]*/, int8_t* g2 /*[4][3]*/, int8_t
 
 static int cdiv(int a, int b) { return (a + b - 1) / b; }
 
+/* The arithmetic below takes 16-bit inputs, so that it also covers the paper's own setting
+   (Section 4.1): uint8 quantised values minus their zero point, i.e. int9 in [-255, 255].  The
+   int8 entry points widen their arguments and call the same code. */
+static int16_t* widen(const int8_t* a, size_t n) {
+    int16_t* w = (int16_t*)malloc((n ? n : 1) * sizeof(int16_t));
+    if (w) for (size_t i = 0; i < n; ++i) w[i] = a[i];
+    return w;
+}
+
 /* W = G' g G'^T, [K][C][4][4] */
-void oracle_f2_filter_transform(const int8_t* g, int K, int C, int64_t* out) {
+void oracle_f2_filter_transform_i16(const int16_t* g, int K, int C, int64_t* out) {
     for (int64_t kc = 0; kc < (int64_t)K * C; ++kc) {
-        const int8_t* f = g + kc * 9;
+        const int16_t* f = g + kc * 9;
         int64_t u[4][3];
         for (int r = 0; r < 4; ++r)
             for (int c = 0; c < 3; ++c) {
@@ -70,8 +82,14 @@ void oracle_f2_filter_transform(const int8_t* g, int K, int C, int64_t* out) {
     }
 }
 
+void oracle_f2_filter_transform(const int8_t* g, int K, int C, int64_t* out) {
+    int16_t* w = widen(g, (size_t)K * C * 9);
+    if (w) oracle_f2_filter_transform_i16(w, K, C, out);
+    free(w);
+}
+
 /* D = B^T d B for every tile and channel of one batch, [T][C][4][4] */
-void oracle_f2_input_transform(const int8_t* x, int N, int C, int H, int W, int64_t* out) {
+void oracle_f2_input_transform_i16(const int16_t* x, int N, int C, int H, int W, int64_t* out) {
     int TH = cdiv(H, 2), TW = cdiv(W, 2);
     #pragma omp parallel for collapse(2)
     for (int n = 0; n < N; ++n)
@@ -99,6 +117,12 @@ void oracle_f2_input_transform(const int8_t* x, int N, int C, int H, int W, int6
                         }
                 }
             }
+}
+
+void oracle_f2_input_transform(const int8_t* x, int N, int C, int H, int W, int64_t* out) {
+    int16_t* w = widen(x, (size_t)N * C * H * W);
+    if (w) oracle_f2_input_transform_i16(w, N, C, H, W, out);
+    free(w);
 }
 
 /* Section 4.2, steps 1-4, for one 4x4xC Winograd-domain filter per output channel: the
@@ -133,8 +157,8 @@ void oracle_f2_scale_filters(int64_t* Wt, int K, int C, int64_t range, int32_t* 
    the output transform, and the final A^T M A / 4 rounded half up.
    Returns a bit mask: 2 = a lossless A^T M A was not divisible by 4, 4 = an output did not
    fit int32; -1 when memory runs out. */
-int oracle_f2_conv2d(const int8_t* x, const int8_t* g, int32_t* y, int N, int C, int H, int W,
-                     int K, int mode, int64_t range) {
+int oracle_f2_conv2d_i16(const int16_t* x, const int16_t* g, int32_t* y, int N, int C, int H, int W,
+                         int K, int mode, int64_t range) {
     int TH = cdiv(H, 2), TW = cdiv(W, 2);
     int64_t Timg = (int64_t)TH * TW;
     int64_t* Wt = (int64_t*)malloc((size_t)K * C * 16 * sizeof(int64_t));
@@ -143,10 +167,10 @@ int oracle_f2_conv2d(const int8_t* x, const int8_t* g, int32_t* y, int N, int C,
     int64_t* D = (int64_t*)malloc((size_t)Timg * C * 16 * sizeof(int64_t));
     int flags = 0;
     if (!Wt || !tab || !mx || !D) { flags = -1; goto done; }
-    oracle_f2_filter_transform(g, K, C, Wt);
+    oracle_f2_filter_transform_i16(g, K, C, Wt);
     if (mode == 1) oracle_f2_scale_filters(Wt, K, C, range, tab, mx);
     for (int n = 0; n < N; ++n) {
-        oracle_f2_input_transform(x + (size_t)n * C * H * W, 1, C, H, W, D);
+        oracle_f2_input_transform_i16(x + (size_t)n * C * H * W, 1, C, H, W, D);
         #pragma omp parallel for reduction(|:flags)
         for (int64_t t = 0; t < Timg; ++t) {
             int ty = (int)(t / TW), tx = (int)(t % TW);
@@ -182,5 +206,38 @@ int oracle_f2_conv2d(const int8_t* x, const int8_t* g, int32_t* y, int N, int C,
     }
 done:
     free(Wt); free(tab); free(mx); free(D);
+    return flags;
+}
+
+int oracle_f2_conv2d(const int8_t* x, const int8_t* g, int32_t* y, int N, int C, int H, int W,
+                     int K, int mode, int64_t range) {
+    int16_t* xw = widen(x, (size_t)N * C * H * W);
+    int16_t* gw = widen(g, (size_t)K * C * 9);
+    int flags = (xw && gw) ? oracle_f2_conv2d_i16(xw, gw, y, N, C, H, W, K, mode, range) : -1;
+    free(xw); free(gw);
+    return flags;
+}
+
+/* Direct 3x3 stride-1 pad-1 correlation of 16-bit inputs (the definition the int9 path is
+   checked against); returns 4 if an output did not fit int32, else 0. */
+int oracle_direct_conv2d_i16(const int16_t* x, const int16_t* g, int32_t* y, int N, int C, int H, int W, int K) {
+    int flags = 0;
+    #pragma omp parallel for collapse(2) reduction(|:flags)
+    for (int n = 0; n < N; ++n)
+        for (int k = 0; k < K; ++k)
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w) {
+                    int64_t s = 0;
+                    for (int c = 0; c < C; ++c)
+                        for (int a = 0; a < 3; ++a)
+                            for (int b = 0; b < 3; ++b) {
+                                int hh = h + a - 1, ww = w + b - 1;
+                                if (hh < 0 || hh >= H || ww < 0 || ww >= W) continue;
+                                s += (int64_t)x[(((size_t)n * C + c) * H + hh) * W + ww] *
+                                     g[(((size_t)k * C + c) * 3 + a) * 3 + b];
+                            }
+                    if (s > INT32_MAX || s < INT32_MIN) flags |= 4;
+                    y[(((size_t)n * K + k) * H + h) * W + w] = (int32_t)s;
+                }
     return flags;
 }

@@ -129,3 +129,45 @@ def test_scaled_error_is_small_relative_to_signal():
     err = np.abs(y.astype(np.int64) - want)
     assert err.max() > 0                          # gaussian sigma-32 filters do get scaled
     assert err.mean() < 0.02 * np.abs(want).mean()
+
+
+# ---- the paper's own setting: uint8 values minus their zero point (int9), Section 4.1 ---------------------------
+
+def test_int16_direct_convolution_against_int8_and_einsum():
+    x, g = wl.make_custom(2, 3, 4, 5, 6, seed=10)
+    assert np.array_equal(oracle.direct_conv2d_i16(x.astype(np.int16), g.astype(np.int16)), oracle.direct_conv2d(x, g))
+    rng = np.random.default_rng(11)
+    x9 = rng.integers(-255, 256, (2, 3, 5, 6)).astype(np.int16)
+    g9 = rng.integers(-255, 256, (4, 3, 3, 3)).astype(np.int16)
+    xp = np.pad(x9.astype(np.int64), ((0, 0), (0, 0), (1, 1), (1, 1)))
+    want = sum(np.einsum("nchw,kc->nkhw", xp[:, :, a:a + 5, b:b + 6], g9[:, :, a, b].astype(np.int64))
+               for a in range(3) for b in range(3))
+    assert np.array_equal(oracle.direct_conv2d_i16(x9, g9), want.astype(np.int32))
+
+
+def test_int9_filters_reach_the_printed_worst_case_entries():
+    """All taps at +255 (uint8 255, zero point 0) give 4, 6 and 9 times 255 at the corner, edge and centre entries:
+    the 1020 / 1530 / 2295 of the printed table, which need 11 / 12 / 13 bits."""
+    gold = golden_io.sections("f2x2_3x3_worstcase.txt")
+    Wt = oracle.f2_filter_transform_i16(np.full((1, 1, 3, 3), 255, np.int16))[0, 0]
+    mag = np.real(gold["MAG"]).astype(np.int64)
+    for (r, c) in ((0, 0), (0, 1), (1, 0), (1, 1), (3, 3), (0, 3), (3, 1)):
+        assert Wt[r, c] == mag[r, c]
+    assert np.all(np.abs(Wt) <= mag)
+    corners = np.array(list(itertools.product([-255, 255], repeat=9)), np.int16).reshape(-1, 1, 3, 3)
+    assert np.array_equal(np.abs(oracle.f2_filter_transform_i16(corners)).max(axis=(0, 1)), mag)
+
+
+def test_int9_lossless_equals_direct_and_scaling_to_the_papers_range():
+    rng = np.random.default_rng(12)
+    x9 = (rng.integers(0, 256, (2, 5, 7, 6)) - 117).astype(np.int16)        # uint8 activations, zero point 117
+    g9 = (rng.integers(0, 256, (3, 5, 3, 3)) - 131).astype(np.int16)        # uint8 weights, zero point 131
+    want = oracle.direct_conv2d_i16(x9, g9)
+    y, flags = oracle.f2_conv2d_i16(x9, g9, oracle.LOSSLESS)
+    assert flags == 0 and np.array_equal(y, want)
+    for rng_ in (127, 255):                                                 # int8 operands / the paper's int9
+        scaled, tab, mx = oracle.f2_scale_filters(oracle.f2_filter_transform_i16(g9), rng_)
+        assert np.abs(scaled).max() <= rng_ and (tab[..., 0] != 0).any()
+        y, flags = oracle.f2_conv2d_i16(x9, g9, oracle.SCALED, rng_)
+        err = np.abs(y.astype(np.int64) - want)
+        assert (flags & 4) == 0 and err.mean() < 0.02 * np.abs(want).mean()
