@@ -149,11 +149,25 @@ int winograd_conv2d_int8_requant(const int8_t* x_dev, const void* packed_dev, in
  * [K][16][4] = (n, p, r, q).
  */
 size_t winograd_f2x2_packed_filter_bytes(int K, int C, int mode);
+/*
+ * The *_u8 variants take the quantised tensors of Section 4.1: unsigned int8
+ * bytes with a zero point (0..255), i.e. the integers byte - zero_point in
+ * [-255, 255] (int9).  y = sum (x - zx) (w - zw) in int32, exact in
+ * WG_LOSSLESS mode (G' g G'^T then reaches the 1020/1530/2295 of the
+ * section's table and travels as two int8 limbs); WG_SCALED brings the
+ * 13-bit Winograd-domain filters into +-127, the operand range of the
+ * matrix cores.  Blobs are interchangeable: either convolution entry point
+ * accepts a blob made by either filter transform.
+ */
 int winograd_f2x2_filter_transform(const int8_t* w_dev, int K, int C, int layout, int mode,
                                    void* packed_dev, size_t packed_bytes, void* hip_stream);
 int winograd_f2x2_conv2d_int8(const int8_t* x_dev, const void* packed_dev, int32_t* y_dev,
                               int N, int C, int H, int W, int K, int layout, int mode,
                               void* hip_stream);
+int winograd_f2x2_filter_transform_u8(const uint8_t* w_dev, int zero_point, int K, int C, int layout,
+                                      int mode, void* packed_dev, size_t packed_bytes, void* hip_stream);
+int winograd_f2x2_conv2d_u8(const uint8_t* x_dev, int zero_point, const void* packed_dev, int32_t* y_dev,
+                            int N, int C, int H, int W, int K, int layout, int mode, void* hip_stream);
 int winograd_f2x2_debug_filter_operands(const void* packed_dev, int K, int C, int mode,
                                         int8_t* planes_dev, int32_t* table_dev, void* hip_stream);
 

@@ -55,6 +55,8 @@ def load_library():
         "winograd_f2x2_filter_transform": (i, [vp, i, i, i, i, vp, sz, vp]),
         "winograd_f2x2_conv2d_int8": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp]),
         "winograd_f2x2_debug_filter_operands": (i, [vp, i, i, i, vp, vp, vp]),
+        "winograd_f2x2_filter_transform_u8": (i, [vp, i, i, i, i, i, vp, sz, vp]),
+        "winograd_f2x2_conv2d_u8": (i, [vp, i, vp, vp, i, i, i, i, i, i, i, vp]),
         "winograd_conv2d_int8_stage_times": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp, sz, vp, i, vp]),
         "direct_conv2d_int8": (i, [vp, vp, vp, i, i, i, i, i, i, vp]),
         "requant_relu_pool_int8": (i, [vp, vp, i, i, i, i, i, i, i, i, vp]),
@@ -78,7 +80,7 @@ EXPORTED_SYMBOLS = (
     "direct_conv2d_int8", "requant_relu_pool_int8",
     "winograd_debug_input_operands", "winograd_debug_filter_operands", "winograd_debug_contraction",
     "winograd_f2x2_packed_filter_bytes", "winograd_f2x2_filter_transform", "winograd_f2x2_conv2d_int8",
-    "winograd_f2x2_debug_filter_operands",
+    "winograd_f2x2_debug_filter_operands", "winograd_f2x2_filter_transform_u8", "winograd_f2x2_conv2d_u8",
 )
 
 
@@ -295,30 +297,40 @@ class F2x2PackedFilter:
         self.blob, self.K, self.C, self.mode = blob, K, C, mode
 
 
-def f2x2_filter_transform(w, layout=NCHW, mode=LOSSLESS):
+def f2x2_filter_transform(w, layout=NCHW, mode=LOSSLESS, zero_point=None):
+    """w: int8 filters, or uint8 filters with their zero point (values w - zero_point)."""
     layout = _LAYOUTS[layout]
-    _need(w, torch.int8, "w")
+    _need(w, torch.int8 if zero_point is None else torch.uint8, "w")
     K = w.shape[0]
     C = w.shape[1] if layout == NCHW else w.shape[3]
     nbytes = load_library().winograd_f2x2_packed_filter_bytes(K, C, mode)
     if nbytes == 0:
         raise WinogradError(-1, "winograd_f2x2_packed_filter_bytes")
     blob = torch.empty(nbytes, dtype=torch.uint8, device=w.device)
-    _check(load_library().winograd_f2x2_filter_transform(_ptr(w), K, C, layout, mode, _ptr(blob), nbytes, _stream()),
-           "winograd_f2x2_filter_transform")
+    if zero_point is None:
+        _check(load_library().winograd_f2x2_filter_transform(_ptr(w), K, C, layout, mode, _ptr(blob), nbytes, _stream()),
+               "winograd_f2x2_filter_transform")
+    else:
+        _check(load_library().winograd_f2x2_filter_transform_u8(_ptr(w), int(zero_point), K, C, layout, mode, _ptr(blob),
+                                                                nbytes, _stream()), "winograd_f2x2_filter_transform_u8")
     return F2x2PackedFilter(blob, K, C, mode)
 
 
-def f2x2_conv2d_int8(x, packed, layout=NCHW, out=None):
+def f2x2_conv2d_int8(x, packed, layout=NCHW, out=None, zero_point=None):
+    """x: int8 activations, or uint8 activations with their zero point (values x - zero_point)."""
     layout = _LAYOUTS[layout]
-    _need(x, torch.int8, "x")
+    _need(x, torch.int8 if zero_point is None else torch.uint8, "x")
     N, C, H, W = _dims(x, layout)
     K = packed.K
     if out is None:
         shape = (N, K, H, W) if layout == NCHW else (N, H, W, K)
         out = torch.empty(shape, dtype=torch.int32, device=x.device)
-    _check(load_library().winograd_f2x2_conv2d_int8(_ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout,
-                                                    packed.mode, _stream()), "winograd_f2x2_conv2d_int8")
+    if zero_point is None:
+        _check(load_library().winograd_f2x2_conv2d_int8(_ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout,
+                                                        packed.mode, _stream()), "winograd_f2x2_conv2d_int8")
+    else:
+        _check(load_library().winograd_f2x2_conv2d_u8(_ptr(x), int(zero_point), _ptr(packed.blob), _ptr(out), N, C, H, W, K,
+                                                      layout, packed.mode, _stream()), "winograd_f2x2_conv2d_u8")
     return out
 
 

@@ -136,25 +136,47 @@ size_t winograd_f2x2_packed_filter_bytes(int K, int C, int mode) {
     return f2_blob_layout(ceil_div(K, kFilterPad) * kFilterPad, C, mode).total;
 }
 
-int winograd_f2x2_filter_transform(const int8_t* w_dev, int K, int C, int layout, int mode, void* packed_dev,
-                                   size_t packed_bytes, void* hip_stream) {
+static int f2_filter_transform(const void* w_dev, int is_unsigned, int zero_point, int K, int C, int layout, int mode,
+                               void* packed_dev, size_t packed_bytes, void* hip_stream) {
     if (!w_dev || !packed_dev || !valid_layout(layout) || !valid_mode(mode)) return WG_EINVAL;
+    if (is_unsigned && (zero_point < 0 || zero_point > 255)) return WG_EINVAL;
     if (int st = check_filter_shape(K, C)) return st;
     if (!aligned(w_dev, 4) || !aligned(packed_dev, 256)) return WG_EINVAL;
     if (packed_bytes < winograd_f2x2_packed_filter_bytes(K, C, mode)) return WG_ESMALLBUF;
-    return status_of(launch_f2_filter_transform(w_dev, K, C, layout, mode, packed_dev,
-                                                static_cast<hipStream_t>(hip_stream)));
+    return status_of(launch_f2_filter_transform(static_cast<const int8_t*>(w_dev), is_unsigned, zero_point, K, C, layout,
+                                                mode, packed_dev, static_cast<hipStream_t>(hip_stream)));
 }
 
-int winograd_f2x2_conv2d_int8(const int8_t* x_dev, const void* packed_dev, int32_t* y_dev, int N, int C, int H,
-                              int W, int K, int layout, int mode, void* hip_stream) {
+static int f2_conv2d(const void* x_dev, int is_unsigned, int zero_point, const void* packed_dev, int32_t* y_dev, int N,
+                     int C, int H, int W, int K, int layout, int mode, void* hip_stream) {
     if (!x_dev || !packed_dev || !y_dev || !valid_layout(layout) || !valid_mode(mode)) return WG_EINVAL;
+    if (is_unsigned && (zero_point < 0 || zero_point > 255)) return WG_EINVAL;
     if (int st = check_shape(N, C, H, W, K)) return st;
     const long long tiles = (long long)N * ((H + 1) / 2) * ((W + 1) / 2);   // 2x2 tiles: four times as many
     if (tiles + kTilePad > kIndexLimit / 64) return WG_EUNSUPPORTED;
     if (!aligned(x_dev, 4) || !aligned(y_dev, 4) || !aligned(packed_dev, 256)) return WG_EINVAL;
-    return status_of(launch_f2_conv(x_dev, packed_dev, y_dev, make_problem_f2(N, C, H, W, K), layout, mode,
-                                    static_cast<hipStream_t>(hip_stream)));
+    return status_of(launch_f2_conv(static_cast<const int8_t*>(x_dev), is_unsigned, zero_point, packed_dev, y_dev,
+                                    make_problem_f2(N, C, H, W, K), layout, mode, static_cast<hipStream_t>(hip_stream)));
+}
+
+int winograd_f2x2_filter_transform(const int8_t* w_dev, int K, int C, int layout, int mode, void* packed_dev,
+                                   size_t packed_bytes, void* hip_stream) {
+    return f2_filter_transform(w_dev, 0, 0, K, C, layout, mode, packed_dev, packed_bytes, hip_stream);
+}
+
+int winograd_f2x2_filter_transform_u8(const uint8_t* w_dev, int zero_point, int K, int C, int layout, int mode,
+                                      void* packed_dev, size_t packed_bytes, void* hip_stream) {
+    return f2_filter_transform(w_dev, 1, zero_point, K, C, layout, mode, packed_dev, packed_bytes, hip_stream);
+}
+
+int winograd_f2x2_conv2d_int8(const int8_t* x_dev, const void* packed_dev, int32_t* y_dev, int N, int C, int H,
+                              int W, int K, int layout, int mode, void* hip_stream) {
+    return f2_conv2d(x_dev, 0, 0, packed_dev, y_dev, N, C, H, W, K, layout, mode, hip_stream);
+}
+
+int winograd_f2x2_conv2d_u8(const uint8_t* x_dev, int zero_point, const void* packed_dev, int32_t* y_dev, int N, int C,
+                            int H, int W, int K, int layout, int mode, void* hip_stream) {
+    return f2_conv2d(x_dev, 1, zero_point, packed_dev, y_dev, N, C, H, W, K, layout, mode, hip_stream);
 }
 
 int winograd_f2x2_debug_filter_operands(const void* packed_dev, int K, int C, int mode, int8_t* planes_dev,

@@ -47,9 +47,17 @@ __device__ inline void f2_filter_entries(const int g[9], int w[16]) {
     }
 }
 
-__device__ inline void f2_load_filter(const int8_t* w, int k, int c, int K, int C, int layout, int g[9]) {
+// Quantised values as the integers the arithmetic works on: signed int8 as they are, or unsigned
+// uint8 minus the zero point (the int9 of Section 4.1).
+struct Quantisation {
+    int is_unsigned, zero_point;
+    __device__ inline int value(int8_t raw) const { return is_unsigned ? (int)(uint8_t)raw - zero_point : (int)raw; }
+};
+
+__device__ inline void f2_load_filter(const int8_t* w, Quantisation qn, int k, int c, int K, int C, int layout, int g[9]) {
     for (int i = 0; i < 9; ++i)
-        g[i] = (k >= K || c >= C) ? 0 : (layout == WG_NCHW ? w[((size_t)k * C + c) * 9 + i] : w[((size_t)k * 9 + i) * C + c]);
+        g[i] = (k >= K || c >= C) ? 0
+                                  : qn.value(layout == WG_NCHW ? w[((size_t)k * C + c) * 9 + i] : w[((size_t)k * 9 + i) * C + c]);
 }
 
 __global__ void f2_blob_init_kernel(uint8_t* blob, int K, int C, int mode, int Kp, int CB, size_t maxmag_off) {
@@ -66,10 +74,11 @@ __global__ void f2_blob_init_kernel(uint8_t* blob, int K, int C, int mode, int K
 
 // Step 2 of Section 4.2: the largest magnitude over the input channels at each of a filter's 16
 // locations.  One wave per (filter, 64-channel block).
-__global__ __launch_bounds__(64) void f2_maxmag_kernel(const int8_t* w, int K, int C, int layout, uint32_t* maxmag) {
+__global__ __launch_bounds__(64) void f2_maxmag_kernel(const int8_t* w, Quantisation qn, int K, int C, int layout,
+                                                       uint32_t* maxmag) {
     const int k = blockIdx.x, c = blockIdx.y * 64 + threadIdx.x;
     int g[9], v[16];
-    f2_load_filter(w, k, c, K, C, layout, g);
+    f2_load_filter(w, qn, k, c, K, C, layout, g);
     f2_filter_entries(g, v);
     for (int e = 0; e < kF2Entries; ++e) {
         int m = abs(v[e]);
@@ -100,13 +109,13 @@ __global__ void f2_table_kernel(const uint32_t* maxmag, ScaleEntry* table, int c
 }
 
 // One thread per (filter row k < Kp, channel c < 64*CB); padding rows and channels are zeros.
-__global__ __launch_bounds__(256) void f2_pack_kernel(const int8_t* w, int K, int C, int layout, int mode, int Kp,
-                                                      const ScaleEntry* table, int8_t* planes) {
+__global__ __launch_bounds__(256) void f2_pack_kernel(const int8_t* w, Quantisation qn, int K, int C, int layout, int mode,
+                                                      int Kp, const ScaleEntry* table, int8_t* planes) {
     const int c = blockIdx.x * 64 + (threadIdx.x & 63);
     const int k = blockIdx.y * 4 + (threadIdx.x >> 6);
     if (k >= Kp) return;
     int g[9], v[16];
-    f2_load_filter(w, k, c, K, C, layout, g);
+    f2_load_filter(w, qn, k, c, K, C, layout, g);
     f2_filter_entries(g, v);
     int8_t* base = planes + filter_plane_offset(0, c >> 6, k, c & 63, Kp, f2_filter_planes(mode));
     for (int e = 0; e < kF2Entries; ++e) {
@@ -141,13 +150,22 @@ __global__ void f2_unpack_kernel(const int8_t* planes, const ScaleEntry* table, 
 // (rotated by 4 c16, so that 4-byte writes and 16-byte reads both spread over the banks).
 __device__ inline int f2_lds_slot(int c16, int tile) { return c16 * 16 + ((tile + 4 * c16) & 15); }
 
+// How activation bytes become the unsigned u = x + bias the transform works on (so that unpacking
+// is a zero extension): signed int8: flip the sign bit, bias 128; uint8 with zero point z: the
+// byte itself, bias z.  A pixel that does not exist (padding, channels beyond C) is the bias.
+struct ActivationBias {
+    uint32_t flip;    // XOR mask on the four packed bytes
+    uint32_t bytes;   // the bias in each of the four bytes
+    int entry11;      // what the bias leaves at entry (1,1) of B^T d B: 4 * bias
+};
+
 // The 4x4 input patch of one tile (rows 2ty-1 .. 2ty+2, columns 2tx-1 .. 2tx+2), four
-// consecutive channels per pixel packed into a dword, biased to u = x + 128; pixels outside the
-// image and channels beyond C hold the bias itself (x = 0).  Addresses are clamped into the
-// image, so no load sits behind a branch.
+// consecutive channels per pixel packed into a dword, biased; pixels outside the image and
+// channels beyond C hold the bias itself (x = 0).  Addresses are clamped into the image, so no
+// load sits behind a branch.
 template <int LAYOUT, bool VEC4>
-__device__ inline void f2_load_patch(const int8_t* __restrict__ x, const Problem& p, int n, int ty, int tx, int c0,
-                                     uint32_t u[4][4]) {
+__device__ inline void f2_load_patch(const int8_t* __restrict__ x, const Problem& p, const ActivationBias& ab, int n, int ty,
+                                     int tx, int c0, uint32_t u[4][4]) {
     const int h0 = 2 * ty - 1, w0 = 2 * tx - 1;
     const uint32_t pixel_stride = LAYOUT == WG_NHWC ? (uint32_t)p.C : 1u;
     uint32_t row_off[4], col_off[4];
@@ -176,7 +194,7 @@ __device__ inline void f2_load_patch(const int8_t* __restrict__ x, const Problem
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const uint32_t e = (uint8_t)img[row_off[a] + col_off[b] + chan_off[i]];
-                    word |= (c0 + i < p.C ? e : 0u) << (8 * i);   // zero = no contribution beyond C
+                    word |= (c0 + i < p.C ? e : ((ab.bytes ^ ab.flip) & 0xffu)) << (8 * i);   // beyond C: x = 0
                 }
                 u[a][b] = word;
             }
@@ -187,7 +205,7 @@ __device__ inline void f2_load_patch(const int8_t* __restrict__ x, const Problem
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             const bool inside = have && (unsigned)(h0 + a) < (unsigned)p.H && (unsigned)(w0 + b) < (unsigned)p.W;
-            u[a][b] = inside ? (u[a][b] ^ kBiasBytes) : kBiasBytes;
+            u[a][b] = inside ? (u[a][b] ^ ab.flip) : ab.bytes;
         }
 }
 
@@ -201,13 +219,13 @@ __device__ inline void f2_bt_rule(Quad v0, Quad v1, Quad v2, Quad v3, Quad t[4])
 
 // D = B^T d B of one patch (four channels); entry e = 4 r + c goes to planes 2e (high limb) and
 // 2e + 1 (low limb).  A constant patch transforms to zero everywhere except entry (1,1), where
-// the four +1 coefficients add up: the bias leaves 4 * 128 there and is removed by one subtraction.
-__device__ inline void f2_transform_patch(const uint32_t u[4][4], int8_t* lds_piece) {
+// the four +1 coefficients add up: the bias leaves 4 * bias there and is removed by one subtraction.
+__device__ inline void f2_transform_patch(const uint32_t u[4][4], int entry11, int8_t* lds_piece) {
     Quad col[4][4];   // col[b][r]: row r of B^T d, column b
 #pragma unroll
     for (int b = 0; b < 4; ++b)
         f2_bt_rule(unpack_u8x4(u[0][b]), unpack_u8x4(u[1][b]), unpack_u8x4(u[2][b]), unpack_u8x4(u[3][b]), col[b]);
-    const s16x2 bias11 = {512, 512};
+    const s16x2 bias11 = {(short)entry11, (short)entry11};
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         Quad d[4];
@@ -238,7 +256,7 @@ __device__ inline void f2_static_for(F&& f) {
 template <int LAYOUT, bool VEC4, int MODE>
 __global__ __launch_bounds__(256) void f2_conv_kernel(const int8_t* __restrict__ x, const uint8_t* __restrict__ blob,
                                                       size_t table_off, size_t planes_off, int32_t* __restrict__ y,
-                                                      Problem p) {
+                                                      Problem p, ActivationBias ab) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int tile0 = blockIdx.x * kF2Tiles;
@@ -270,12 +288,12 @@ __global__ __launch_bounds__(256) void f2_conv_kernel(const int8_t* __restrict__
     const size_t b_block_stride = (size_t)(p.Kp >> 4) * NP * kFilterFragBytes;
 
     uint32_t u[4][4];
-    f2_load_patch<LAYOUT, VEC4>(x, p, a_n, a_ty, a_tx, 4 * cq, u);
+    f2_load_patch<LAYOUT, VEC4>(x, p, ab, a_n, a_ty, a_tx, 4 * cq, u);
     for (int cb = 0; cb < p.CB; ++cb) {
         if (cb > 0) __syncthreads();   // the previous block's operand planes have been consumed
-        f2_transform_patch(u, put);
+        f2_transform_patch(u, ab.entry11, put);
         // the next channel block's patch travels while this one multiplies
-        if (cb + 1 < p.CB) f2_load_patch<LAYOUT, VEC4>(x, p, a_n, a_ty, a_tx, (cb + 1) * kCBlock + 4 * cq, u);
+        if (cb + 1 < p.CB) f2_load_patch<LAYOUT, VEC4>(x, p, ab, a_n, a_ty, a_tx, (cb + 1) * kCBlock + 4 * cq, u);
         const int8_t* b_cb = b_lane + cb * b_block_stride;
         v4i bf[3][NBP], af[3][2];
         auto request_b = [&](auto E) {
@@ -386,7 +404,8 @@ __global__ __launch_bounds__(256) void f2_conv_kernel(const int8_t* __restrict__
 }
 
 template <int LAYOUT, bool VEC4, int MODE>
-hipError_t launch(const int8_t* x, const uint8_t* blob, const F2BlobLayout& bl, int32_t* y, const Problem& p, hipStream_t s) {
+hipError_t launch(const int8_t* x, const uint8_t* blob, const F2BlobLayout& bl, int32_t* y, const Problem& p,
+                  const ActivationBias& ab, hipStream_t s) {
     static bool configured = false;   // per template instance
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&f2_conv_kernel<LAYOUT, VEC4, MODE>),
@@ -395,20 +414,22 @@ hipError_t launch(const int8_t* x, const uint8_t* blob, const F2BlobLayout& bl, 
         configured = true;
     }
     dim3 grid(ceil_div(p.T, kF2Tiles), p.Kp / kF2Filters);
-    f2_conv_kernel<LAYOUT, VEC4, MODE><<<grid, 256, kF2LdsBytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p);
+    f2_conv_kernel<LAYOUT, VEC4, MODE><<<grid, 256, kF2LdsBytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p, ab);
     return hipGetLastError();
 }
 
 template <int LAYOUT, bool VEC4>
 hipError_t launch_mode(const int8_t* x, const uint8_t* blob, const F2BlobLayout& bl, int32_t* y, const Problem& p, int mode,
-                       hipStream_t s) {
-    return mode == WG_LOSSLESS ? launch<LAYOUT, VEC4, WG_LOSSLESS>(x, blob, bl, y, p, s)
-                               : launch<LAYOUT, VEC4, WG_SCALED>(x, blob, bl, y, p, s);
+                       const ActivationBias& ab, hipStream_t s) {
+    return mode == WG_LOSSLESS ? launch<LAYOUT, VEC4, WG_LOSSLESS>(x, blob, bl, y, p, ab, s)
+                               : launch<LAYOUT, VEC4, WG_SCALED>(x, blob, bl, y, p, ab, s);
 }
 
 }  // namespace
 
-hipError_t launch_f2_filter_transform(const int8_t* w, int K, int C, int layout, int mode, void* blob_v, hipStream_t s) {
+hipError_t launch_f2_filter_transform(const int8_t* w, int is_unsigned, int zero_point, int K, int C, int layout, int mode,
+                                      void* blob_v, hipStream_t s) {
+    const Quantisation qn = {is_unsigned, zero_point};
     uint8_t* blob = static_cast<uint8_t*>(blob_v);
     const int Kp = ceil_div(K, kFilterPad) * kFilterPad, CB = ceil_div(C, kCBlock);
     const F2BlobLayout bl = f2_blob_layout(Kp, C, mode);
@@ -416,9 +437,9 @@ hipError_t launch_f2_filter_transform(const int8_t* w, int K, int C, int layout,
     ScaleEntry* table = reinterpret_cast<ScaleEntry*>(blob + bl.table_off);
     const int entries = Kp * kF2Entries;
     f2_blob_init_kernel<<<ceil_div(entries, 256), 256, 0, s>>>(blob, K, C, mode, Kp, CB, bl.maxmag_off);
-    if (mode == WG_SCALED) f2_maxmag_kernel<<<dim3(K, CB), 64, 0, s>>>(w, K, C, layout, maxmag);
+    if (mode == WG_SCALED) f2_maxmag_kernel<<<dim3(K, CB), 64, 0, s>>>(w, qn, K, C, layout, maxmag);
     f2_table_kernel<<<ceil_div(entries, 256), 256, 0, s>>>(maxmag, table, entries, mode);
-    f2_pack_kernel<<<dim3(CB, ceil_div(Kp, 4)), 256, 0, s>>>(w, K, C, layout, mode, Kp, table,
+    f2_pack_kernel<<<dim3(CB, ceil_div(Kp, 4)), 256, 0, s>>>(w, qn, K, C, layout, mode, Kp, table,
                                                              reinterpret_cast<int8_t*>(blob + bl.planes_off));
     return hipGetLastError();
 }
@@ -437,13 +458,16 @@ hipError_t launch_f2_unpack_filter_planes(const void* blob_v, int8_t* dense, int
     return hipGetLastError();
 }
 
-hipError_t launch_f2_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int layout, int mode, hipStream_t s) {
+hipError_t launch_f2_conv(const int8_t* x, int is_unsigned, int zero_point, const void* blob, int32_t* y, const Problem& p,
+                          int layout, int mode, hipStream_t s) {
+    const uint32_t bias = is_unsigned ? (uint32_t)zero_point : 128u;
+    const ActivationBias ab = {is_unsigned ? 0u : 0x80808080u, bias * 0x01010101u, (int)(4 * bias)};
     const F2BlobLayout bl = f2_blob_layout(p.Kp, p.C, mode);
     const uint8_t* b = static_cast<const uint8_t*>(blob);
     if (layout == WG_NHWC && p.C % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 4 == 0)
-        return launch_mode<WG_NHWC, true>(x, b, bl, y, p, mode, s);
-    if (layout == WG_NHWC) return launch_mode<WG_NHWC, false>(x, b, bl, y, p, mode, s);
-    return launch_mode<WG_NCHW, false>(x, b, bl, y, p, mode, s);
+        return launch_mode<WG_NHWC, true>(x, b, bl, y, p, mode, ab, s);
+    if (layout == WG_NHWC) return launch_mode<WG_NHWC, false>(x, b, bl, y, p, mode, ab, s);
+    return launch_mode<WG_NCHW, false>(x, b, bl, y, p, mode, ab, s);
 }
 
 }  // namespace wg

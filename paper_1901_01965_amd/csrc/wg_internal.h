@@ -168,11 +168,14 @@ inline Problem make_problem_f2(int N, int C, int H, int W, int K) {
     p.div_th = make_fast_div((uint32_t)p.TH);
     return p;
 }
-hipError_t launch_f2_filter_transform(const int8_t* w, int K, int C, int layout, int mode, void* blob, hipStream_t s);
+// is_unsigned: the bytes are uint8 with the given zero point (values = byte - zero_point, the int9
+// of Section 4.1); otherwise signed int8 and zero_point is ignored.
+hipError_t launch_f2_filter_transform(const int8_t* w, int is_unsigned, int zero_point, int K, int C, int layout, int mode,
+                                      void* blob, hipStream_t s);
 hipError_t launch_f2_unpack_filter_planes(const void* blob, int8_t* dense, int32_t* table, int K, int C, int mode,
                                           hipStream_t s);
-hipError_t launch_f2_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int layout, int mode,
-                          hipStream_t s);
+hipError_t launch_f2_conv(const int8_t* x, int is_unsigned, int zero_point, const void* blob, int32_t* y, const Problem& p,
+                          int layout, int mode, hipStream_t s);
 
 // ---- workspace ------------------------------------------------------------------
 // [V: int8 [planes][CB][Tp][64]][M: int32 [46 lossless | 36 scaled][Tp][Kp]]

@@ -141,6 +141,12 @@ def test_validation_errors_return_before_any_launch(lib):
     assert f2c(odd, good2, good3, 1, 4, 8, 8, 4, 0, 0, None) == EINVAL
     assert f2c(good, good2, good3, 1, 1000, 8, 8, 4, 0, 0, None) == EUNSUPPORTED
     assert lib.winograd_f2x2_debug_filter_operands(good2, 4, 4, 0, None, good3, None) == EINVAL
+    f2tu, f2cu = lib.winograd_f2x2_filter_transform_u8, lib.winograd_f2x2_conv2d_u8
+    assert f2tu(good, 256, 4, 4, 0, 0, good2, f2_bytes, None) == EINVAL      # zero point beyond a byte
+    assert f2tu(good, -1, 4, 4, 0, 0, good2, f2_bytes, None) == EINVAL
+    assert f2tu(None, 3, 4, 4, 0, 0, good2, f2_bytes, None) == EINVAL
+    assert f2cu(good, 300, good2, good3, 1, 4, 8, 8, 4, 0, 0, None) == EINVAL
+    assert f2cu(good, 3, good2, None, 1, 4, 8, 8, 4, 0, 0, None) == EINVAL
 
     st = lib.winograd_conv2d_int8_stage_times
     assert st(good, good2, good3, 1, 4, 8, 8, 4, 0, 0, p(0x40000), ws_bytes, None, 0, good) == EINVAL

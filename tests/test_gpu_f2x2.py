@@ -125,3 +125,67 @@ def test_mismatched_blob_is_rejected_and_output_untouched():
     if p4.blob.numel() >= packed.blob.numel():
         wg.f2x2_conv2d_int8(_x(x, wg.NHWC), wg.F2x2PackedFilter(p4.blob, 8, 8, wg.LOSSLESS), wg.NHWC, out=out)
         assert bool((out == 1234567).all())
+
+
+# ---- the paper's own setting: uint8 tensors with zero points (int9 values), Section 4.1 ------------------------
+
+def _u8_case(N, C, K, H, W, zx, zw, seed):
+    rng = np.random.default_rng(9000 + seed)
+    xq = rng.integers(0, 256, (N, C, H, W)).astype(np.uint8)
+    gq = rng.integers(0, 256, (K, C, 3, 3)).astype(np.uint8)
+    return xq, gq, (xq.astype(np.int16) - zx), (gq.astype(np.int16) - zw)
+
+
+def test_int9_filters_reach_the_printed_worst_case_table():
+    """All taps 255 with zero point 0: the blob's limbs reassemble to 4, 6 and 9 times 255 at the corner, edge and
+    centre entries — the 1020 / 1530 / 2295 of the printed table."""
+    gq = np.full((2, 3, 3, 3), 255, np.uint8)
+    packed = wg.f2x2_filter_transform(_dev(gq), wg.NCHW, wg.LOSSLESS, zero_point=0)
+    planes, _ = wg.f2x2_debug_filter_operands(packed)
+    planes = planes.cpu().numpy().astype(np.int64)
+    Wt = (64 * planes[0::2] + planes[1::2]).reshape(4, 4, 2, 3)
+    assert np.all(Wt[0, 0] == 1020) and np.all(Wt[0, 1] == 1530) and np.all(Wt[1, 1] == 2295) and np.all(Wt[3, 3] == 1020)
+    assert np.array_equal(Wt[..., 0, 0], oracle.f2_filter_transform_i16(np.full((1, 1, 3, 3), 255, np.int16))[0, 0])
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("shape,zx,zw", [((1, 3, 5, 7, 9), 0, 255), ((2, 16, 16, 16, 16), 117, 131), ((1, 70, 33, 10, 6), 255, 0),
+                                         ((1, 200, 72, 6, 10), 128, 128)])
+def test_uint8_with_zero_points(shape, zx, zw, layout):
+    N, C, K, H, W = shape
+    xq, gq, x9, g9 = _u8_case(N, C, K, H, W, zx, zw, seed=C)
+    xd = _dev(xq if layout == wg.NCHW else wl.to_nhwc(xq))
+    gd = _dev(gq if layout == wg.NCHW else wl.to_krsc(gq))
+    want = oracle.direct_conv2d_i16(x9, g9)
+    y = wg.f2x2_conv2d_int8(xd, wg.f2x2_filter_transform(gd, layout, wg.LOSSLESS, zero_point=zw), layout, zero_point=zx)
+    assert np.array_equal(_y(y, layout), want)
+    packed = wg.f2x2_filter_transform(gd, layout, wg.SCALED, zero_point=zw)
+    scaled, tab, _ = oracle.f2_scale_filters(oracle.f2_filter_transform_i16(g9), 127)
+    planes, table = wg.f2x2_debug_filter_operands(packed)
+    assert np.array_equal(planes.cpu().numpy().astype(np.int64), scaled.reshape(K, C, 16).transpose(2, 0, 1))
+    y = wg.f2x2_conv2d_int8(xd, packed, layout, zero_point=zx)
+    want_scaled, flags = oracle.f2_conv2d_i16(x9, g9, oracle.SCALED, 127)
+    assert (flags & 4) == 0 and np.array_equal(_y(y, layout), want_scaled)
+
+
+def test_uint8_extremes_at_the_largest_channel_count():
+    C = wg.MAX_CHANNELS
+    for xv, zx, gv, zw in ((255, 0, 255, 0), (0, 255, 255, 0), (0, 255, 0, 255)):
+        xq = np.full((1, C, 4, 6), xv, np.uint8)
+        gq = np.full((2, C, 3, 3), gv, np.uint8)
+        gq[1] = 255 - gv
+        y = wg.f2x2_conv2d_int8(_dev(wl.to_nhwc(xq)), wg.f2x2_filter_transform(_dev(wl.to_krsc(gq)), wg.NHWC, wg.LOSSLESS,
+                                                                             zero_point=zw), wg.NHWC, zero_point=zx)
+        assert np.array_equal(_y(y, wg.NHWC), oracle.direct_conv2d_i16(xq.astype(np.int16) - zx, gq.astype(np.int16) - zw))
+
+
+def test_blobs_of_both_filter_transforms_serve_both_convolutions():
+    """int8 activations with int9 filters and uint8 activations with int8 filters."""
+    xq, gq, x9, g9 = _u8_case(1, 24, 20, 8, 8, 100, 140, seed=3)
+    x8, g8 = wl.make_custom(1, 24, 20, 8, 8, seed=74)
+    p9 = wg.f2x2_filter_transform(_dev(gq), wg.NCHW, wg.LOSSLESS, zero_point=140)
+    p8 = wg.f2x2_filter_transform(_dev(g8), wg.NCHW, wg.LOSSLESS)
+    y = wg.f2x2_conv2d_int8(_dev(x8), p9, wg.NCHW)
+    assert np.array_equal(y.cpu().numpy(), oracle.direct_conv2d_i16(x8.astype(np.int16), g9))
+    y = wg.f2x2_conv2d_int8(_dev(xq), p8, wg.NCHW, zero_point=100)
+    assert np.array_equal(y.cpu().numpy(), oracle.direct_conv2d_i16(x9, g8.astype(np.int16)))
