@@ -259,8 +259,20 @@ __global__ __launch_bounds__(256) void f2_conv_kernel(const int8_t* __restrict__
                                                       Problem p, ActivationBias ab) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int tile0 = blockIdx.x * kF2Tiles;
-    const int kbase = blockIdx.y * kF2Filters;
+    // With eight or more filter blocks, workgroups are dealt to the eight XCDs (round-robin in
+    // launch order) so that all tile blocks of a filter block share one L2.
+    int bx = blockIdx.x, by = blockIdx.y;
+    {
+        const int total = gridDim.x * gridDim.y;
+        if (gridDim.y >= 8 && (total & 7) == 0) {
+            const int launch = blockIdx.y * gridDim.x + blockIdx.x;
+            const int w = (launch & 7) * (total >> 3) + (launch >> 3);
+            by = w / (int)gridDim.x;
+            bx = w - by * (int)gridDim.x;
+        }
+    }
+    const int tile0 = bx * kF2Tiles;
+    const int kbase = by * kF2Filters;
     const int k = kbase + wave * 16 + (lane & 15);   // this lane's filter (< Kp)
     const BlobHeader* hdr = reinterpret_cast<const BlobHeader*>(blob);
     if (!(hdr->magic == kF2BlobMagic && hdr->version == kBlobVersion && hdr->K == p.K && hdr->C == p.C && hdr->mode == MODE))
