@@ -470,14 +470,15 @@ __device__ __forceinline__ void fused_conv_body(const int8_t* __restrict__ x, co
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kblock = wave & 1, half = wave >> 1;
     // Workgroups are handed to the eight XCDs (each with its own L2) round-robin in launch order.
-    // With eight or more filter blocks, the blocks are dealt out so that all tile blocks of one
-    // filter block run on the same XCD at the same time: a filter block's operand planes (up to
-    // several hundred KB per channel block) are then fetched into that L2 once instead of into
-    // every L2.
+    // With several filter blocks and channel blocks, the grid is dealt out XCD-major instead, so
+    // that an XCD runs consecutive tile blocks of as few filter blocks as possible at the same
+    // time: a filter block's operand planes (46-138 KB per channel block) are then fetched into
+    // one or two L2s instead of into all eight.  (With a single channel block the planes are
+    // small and the order made no difference.)
     int bx = blockIdx.x, by = blockIdx.y;
     {
         const int total = gridDim.x * gridDim.y;
-        if (gridDim.y >= 8 && (total & 7) == 0) {
+        if (gridDim.y >= 2 && p.CB >= 2 && (total & 7) == 0) {
             const int launch = blockIdx.y * gridDim.x + blockIdx.x;
             const int w = (launch & 7) * (total >> 3) + (launch >> 3);   // XCD-major position
             by = w / (int)gridDim.x;
