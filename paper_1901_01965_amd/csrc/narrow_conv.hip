@@ -6,9 +6,8 @@
 // lanes (no limb split, Section 3.1 is not needed) and one `v_dot2_i32_i16` multiplies two
 // channels at a time.
 //
-// One wave per workgroup and 32 tiles per wave (more, smaller workgroups than 64 tiles would
-// give: several waves share a SIMD and cover each other's LDS and memory waits).  Phase 1:
-// lane = tile (half of the lanes); the lane loads its 6x6
+// One wave per workgroup and 8 to 32 tiles per wave (chosen on the host so that the waves fill
+// the SIMDs evenly, two per SIMD).  Phase 1: lane = tile (the first lanes); the lane loads its 6x6
 // patch (all channels packed in one dword per pixel), runs the input transform of Section 3.3
 // and leaves the 36 real numbers of the 26 free entries in LDS.  Phase 2: lane = filter; the
 // lane holds its filter's 36 Winograd-domain numbers (from the blob's narrow table) in
@@ -20,13 +19,12 @@
 #include "output_transform_core.h"
 #include "wg_internal.h"
 
-#ifndef WG_NARROW_TILES
-#define WG_NARROW_TILES 32
-#endif
+#include <algorithm>
 
 namespace wg {
 namespace {
 
+constexpr int kNarrowTiles = 32;                   // most tiles a wave takes
 constexpr int kNarrowPieces = kNarrowValues / 2;   // 16-byte pieces per tile or filter: two values x four channels
 
 // Receives the free entries from the input transform: value index = real entry p, or
@@ -46,22 +44,27 @@ __device__ inline int dot4(uint32_t a01, uint32_t a23, uint32_t b01, uint32_t b2
                                   false);
 }
 
-__device__ inline int requantise_one(int y, const Int8Epilogue& q) { return min(max((y + q.round) >> q.shift, q.lo), 127); }
+// The int8 epilogue on the output transform's 16 Y (before its rescale by 2^-4): the two nested
+// floor divisions ((Y + rnd) >> 4, then (. + round) >> shift) are one, floor((Y + rnd + 16 round) /
+// 2^(4 + shift)); then the clamp to [lo, 127].
+__device__ inline int requantise_y16(int y16, int add, int shift, int lo) {
+    return min(max((y16 + add) >> shift, lo), 127);   // the compiler picks v_med3_i32
+}
 
-// grid: (ceil(T/kNarrowTiles), Kp/64), 64 threads.
-template <int MODE, bool Q8, int kNarrowTiles>
+// grid: (ceil(T/tiles_per_wave), Kp/64), 64 threads.
+template <int MODE, bool Q8>
 __global__ __launch_bounds__(64) void narrow_conv_kernel(const int8_t* __restrict__ x, const uint8_t* __restrict__ blob,
                                                          size_t table_off, size_t narrow_off, int32_t* __restrict__ y,
-                                                         Problem p, Int8Epilogue q8) {
+                                                         Problem p, Int8Epilogue q8, int tiles_per_wave) {
     __shared__ uint4 values[kNarrowPieces * kNarrowTiles];   // [piece][tile]
     const int lane = threadIdx.x;
-    const int tile0 = blockIdx.x * kNarrowTiles;
+    const int tile0 = blockIdx.x * tiles_per_wave;
     if (!blob_matches(reinterpret_cast<const BlobHeader*>(blob), p.K, p.C, MODE)) return;
 
     // ---- phase 1: lane = tile -----------------------------------------------------------------
     int my_n = 0, my_ty = 0, my_tx = 0;
     if (tile0 + lane < p.T) decode_tile(p, tile0 + lane, my_n, my_ty, my_tx);   // else tile (0,0,0): loaded, never used
-    if (lane < kNarrowTiles) {
+    if (lane < tiles_per_wave) {
         uint32_t u[6][6];
         load_patch<WG_NHWC, false>(x, p, my_n, my_ty, my_tx, 0, u);
         bias_patch(p, my_ty, my_tx, 0, u);
@@ -103,7 +106,7 @@ __global__ __launch_bounds__(64) void narrow_conv_kernel(const int8_t* __restric
     __shared__ __attribute__((aligned(16))) int8_t staging[Q8 ? 2 : 1][Q8 ? 16 * 64 : 16];
     const bool vector_store = Q8 && ((p.K & 15) | (reinterpret_cast<uintptr_t>(q8.out) & 15)) == 0;
 
-    const int count = min(kNarrowTiles, p.T - tile0);
+    const int count = min(tiles_per_wave, p.T - tile0);
     const int rnd = MODE == WG_SCALED ? 8 : 0;
     for (int t = 0; t < count; ++t) {
         // all of the tile's numbers are requested before the first one is used, so the wave waits
@@ -142,6 +145,7 @@ __global__ __launch_bounds__(64) void narrow_conv_kernel(const int8_t* __restric
             const int Ho = p.H >> (q8.pool ? 1 : 0), Wo = p.W >> (q8.pool ? 1 : 0);
             const int orow = q8.pool ? row >> 1 : row, ocol = q8.pool ? col >> 1 : col;
             int8_t* tile_out = q8.out + (((size_t)n * Ho + orow) * Wo + ocol) * p.K;
+            const int add = rnd + 16 * q8.round, shift = 4 + q8.shift;
             int8_t bytes[16];   // pixel (i, j) of the tile at 4 i + j; pooled: (pi, pj) at 2 pi + pj
             if (q8.pool) {
 #pragma unroll
@@ -153,14 +157,14 @@ __global__ __launch_bounds__(64) void narrow_conv_kernel(const int8_t* __restric
                         for (int a = 0; a < 2; ++a)
 #pragma unroll
                             for (int b = 0; b < 2; ++b)
-                                best = max(best, requantise_one((out[2 * pj + b][2 * pi + a] + rnd) >> 4, q8));
+                                best = max(best, requantise_y16(out[2 * pj + b][2 * pi + a], add, shift, q8.lo));
                         bytes[2 * pi + pj] = (int8_t)best;
                     }
             } else {
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) bytes[4 * i + j] = (int8_t)requantise_one((out[j][i] + rnd) >> 4, q8);
+                    for (int j = 0; j < 4; ++j) bytes[4 * i + j] = (int8_t)requantise_y16(out[j][i], add, shift, q8.lo);
             }
             if (vector_store) {
                 // through LDS, so that a lane stores 16 consecutive filters of one pixel: stage[pixel][filter]
@@ -188,9 +192,13 @@ __global__ __launch_bounds__(64) void narrow_conv_kernel(const int8_t* __restric
 template <int MODE, bool Q8>
 hipError_t launch(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
                   const Int8Epilogue& q8, hipStream_t s) {
-    constexpr int tiles = WG_NARROW_TILES;
+    // Tiles per wave: the kernel is bound by vector instructions, so the waves should fill every
+    // SIMD evenly: two waves on each of the 1,024 SIMDs (two cover each other's LDS and memory
+    // waits; a third would only add transform phases with mostly idle lanes).
+    const long long work = (long long)p.T * (p.Kp / 64);
+    const int tiles = (int)std::min<long long>(kNarrowTiles, std::max<long long>(8, (work + 2047) / 2048));
     dim3 grid(ceil_div(p.T, tiles), p.Kp / 64);
-    narrow_conv_kernel<MODE, Q8, tiles><<<grid, 64, 0, s>>>(x, blob, bl.table_off, bl.narrow_off, y, p, q8);
+    narrow_conv_kernel<MODE, Q8><<<grid, 64, 0, s>>>(x, blob, bl.table_off, bl.narrow_off, y, p, q8, tiles);
     return hipGetLastError();
 }
 
