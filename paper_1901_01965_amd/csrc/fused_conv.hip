@@ -451,6 +451,188 @@ __device__ inline uint32_t pack_bytes(v4i v) {
     return (uint32_t)(v[0] & 0xff) | ((uint32_t)(v[1] & 0xff) << 8) | ((uint32_t)(v[2] & 0xff) << 16) | ((uint32_t)v[3] << 24);
 }
 
+// Who a thread is when the four product waves store their outputs, and where its tile lies.
+struct StoreContext {
+    int8_t* lds;
+    int tid, lane, wave, half, kblock;          // within the four waves that hold the outputs
+    int my_n, my_row, my_col, my_origin;        // of tile (lane & 15): image, first output row and column, offset in y (-1: none)
+    int rnd;                                    // rounding added before the final >> 4
+    int32_t* y;
+};
+
+// Adds the two row halves and stores the 16 tiles x 32 filters (from kbase) whose partial outputs
+// the four waves hold in Yp.  All four waves call it together (it contains one barrier).
+template <int LAYOUT, bool Q8>
+__device__ __forceinline__ void store_block(const StoreContext& sc, const Problem& p, const Int8Epilogue& q8,
+                                            const v4i (&Yp)[16], int kbase) {
+    int8_t* const lds = sc.lds;
+    const int tid = sc.tid, lane = sc.lane, wave = sc.wave, half = sc.half, kblock = sc.kblock;
+    const int my_n = sc.my_n, my_row = sc.my_row, my_col = sc.my_col, my_origin = sc.my_origin, rnd = sc.rnd;
+    int32_t* const y = sc.y;
+    int* parki = reinterpret_cast<int*>(lds);
+    (void)wave; (void)my_n;
+    if (LAYOUT == WG_NHWC && (p.K & 3) == 0) {
+        // Channels-last with K a multiple of four: outputs are staged filter-fastest,
+        // stage[half][output 4i+j][tile][36] (32 filters, rows padded to 36 dwords so that the
+        // four 16-lane groups of a wave land in different banks), then every thread adds the
+        // halves for four consecutive filters and stores 16 bytes; eight lanes cover the 128
+        // contiguous bytes this block owns of a pixel.
+        constexpr int kRow = 36, kHalf = 16 * 16 * kRow;
+        static_assert(2 * kHalf * 4 <= kLdsBytes, "staging fits the operand planes' LDS");
+        {
+            int* dst = parki + half * kHalf + (4 * (lane >> 4)) * kRow + kblock * 16 + (lane & 15);
+#pragma unroll
+            for (int o = 0; o < 16; ++o)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) dst[(o * 16 + q) * kRow] = Yp[o][q];
+        }
+        __syncthreads();
+        // thread: filters 4*k4..4*k4+3; pass ps: output row i = ps/2, tile = 8*(ps%2) + px/4, column j = px%4
+        const int k4 = tid & 7, px = tid >> 3, j = px & 3;
+        const int kk = kbase + 4 * k4;
+        if constexpr (Q8) {
+            // finished int32 outputs of filters 4*g .. 4*g+3 of the block
+            auto staged = [&](int o, int tile, int g) {
+                const int at = (o * 16 + tile) * kRow + 4 * g;
+                return (*reinterpret_cast<const v4i*>(parki + at) + *reinterpret_cast<const v4i*>(parki + kHalf + at) + rnd) >> 4;
+            };
+            if (q8.pool) {
+                // 16 tiles x 2x2 pooled pixels = 64 pixels; thread: four filters of pixels px and px + 32
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int pp = px + 32 * e, tile = pp >> 2, pi = (pp >> 1) & 1, pj = pp & 1;
+                    v4i best = requantise(staged(4 * (2 * pi) + 2 * pj, tile, k4), q8);
+                    best = __builtin_elementwise_max(best, requantise(staged(4 * (2 * pi) + 2 * pj + 1, tile, k4), q8));
+                    best = __builtin_elementwise_max(best, requantise(staged(4 * (2 * pi + 1) + 2 * pj, tile, k4), q8));
+                    best = __builtin_elementwise_max(best, requantise(staged(4 * (2 * pi + 1) + 2 * pj + 1, tile, k4), q8));
+                    const int n = __shfl(my_n, tile), row = __shfl(my_row, tile), col = __shfl(my_col, tile);
+                    const bool ok = __shfl(my_origin, tile) >= 0 && row + 2 * pi < p.H && col + 2 * pj < p.W && kk < p.K;
+                    const size_t at = (((size_t)n * (p.H >> 1) + (row >> 1) + pi) * (p.W >> 1) + (col >> 1) + pj) * p.K + kk;
+                    if (ok) *reinterpret_cast<uint32_t*>(q8.out + at) = pack_bytes(best);
+                }
+                return;
+            }
+            // thread: 16 filters (half h16 of the block) of its own tile (lane & 15) at outputs
+            // tid/32 and tid/32 + 8: sixteen lanes read sixteen tiles' rows, which fall in
+            // different banks, and a thread stores 16 bytes where the alignment allows
+            const int h16 = (tid >> 4) & 1, kq = kbase + 16 * h16;
+            const bool vector_store = ((p.K & 15) | (reinterpret_cast<uintptr_t>(q8.out) & 15)) == 0;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int o = (tid >> 5) + 8 * e, i = o >> 2, jj = o & 3;
+                uint32_t bytes[4];
+#pragma unroll
+                for (int g = 0; g < 4; ++g) bytes[g] = pack_bytes(requantise(staged(o, lane & 15, 4 * h16 + g), q8));
+                const bool ok = my_origin >= 0 && my_row + i < p.H && my_col + jj < p.W;
+                int8_t* dst = q8.out + (size_t)my_origin + (size_t)(i * p.W + jj) * p.K + kq;
+                if (ok && vector_store && kq < p.K) {
+                    *reinterpret_cast<uint4*>(dst) = make_uint4(bytes[0], bytes[1], bytes[2], bytes[3]);
+                } else if (ok) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        if (kq + 4 * g < p.K) reinterpret_cast<uint32_t*>(dst)[g] = bytes[g];
+                }
+            }
+            return;
+        }
+        int32_t* first[2];   // output row 0 of the thread's two tiles (e = 0, 1); null where nothing is stored
+        int rows[2];         // output rows of that tile inside the image
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int origin = __shfl(my_origin, 8 * e + (px >> 2));
+            const bool ok = origin >= 0 && __shfl(my_col, 8 * e + (px >> 2)) + j < p.W && kk < p.K;
+            first[e] = ok ? y + (size_t)origin + j * p.K + kk : nullptr;
+            rows[e] = p.H - __shfl(my_row, 8 * e + (px >> 2));
+        }
+        const size_t row_pitch = (size_t)p.W * p.K;
+        v4i v[8];
+#pragma unroll
+        for (int ps = 0; ps < 8; ++ps) {
+            const int i = ps >> 1, tile = 8 * (ps & 1) + (px >> 2);
+            const int at = ((4 * i + j) * 16 + tile) * kRow + 4 * k4;
+            v[ps] = (*reinterpret_cast<const v4i*>(parki + at) + *reinterpret_cast<const v4i*>(parki + kHalf + at) + rnd) >> 4;
+        }
+#pragma unroll
+        for (int ps = 0; ps < 8; ++ps) {
+            const int i = ps >> 1, e = ps & 1;
+            if (first[e] != nullptr && i < rows[e]) *reinterpret_cast<v4i*>(first[e] + i * row_pitch) = v[ps];
+        }
+        return;
+    }
+    // General path: park[wave][output 0..15][lane] (four registers = four tiles each); the value
+    // of (tile, output 4i+j, filter kl) sits in waves kl/16 and 2 + kl/16 at output 4i+j, lane
+    // (tile/4)*16 + kl%16, register tile%4.  16 x 16 x 32 = 8192 results, 32 per thread.
+    v4i* park = reinterpret_cast<v4i*>(lds);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) park[(wave * 16 + i) * 64 + lane] = Yp[i];
+    __syncthreads();
+    if constexpr (Q8) {
+        // One byte per (tile, output pixel, filter), in the order of the output layout; lg = log2
+        // of the output pixels per tile side (4, or 2 after pooling).
+        const int lg = q8.pool ? 1 : 2, side = 1 << lg, span = q8.pool ? 2 : 1;
+        const int Ho = q8.pool ? p.H >> 1 : p.H, Wo = q8.pool ? p.W >> 1 : p.W;
+        const int items = (16 * 32) << (2 * lg);
+        for (int e = tid; e < items; e += 256) {
+            int kl, tile, pi, pj;
+            if constexpr (LAYOUT == WG_NHWC) {
+                kl = e & 31; pj = (e >> 5) & (side - 1); pi = (e >> (5 + lg)) & (side - 1); tile = e >> (5 + 2 * lg);
+            } else {
+                pj = e & (side - 1); tile = (e >> lg) & 15; pi = (e >> (lg + 4)) & (side - 1); kl = e >> (2 * lg + 4);
+            }
+            int best = -129;
+            for (int a = 0; a < span; ++a)
+                for (int b = 0; b < span; ++b) {
+                    const int o = 4 * (span * pi + a) + span * pj + b;
+                    const int at = ((((kl >> 4) * 16 + o) * 64) + (tile >> 2) * 16 + (kl & 15)) * 4 + (tile & 3);
+                    best = max(best, requantise((parki[at] + parki[at + 2 * 16 * 64 * 4] + rnd) >> 4, q8));
+                }
+            const int n = __shfl(my_n, tile), row = __shfl(my_row, tile), col = __shfl(my_col, tile);
+            const bool ok = __shfl(my_origin, tile) >= 0 && row + span * pi < p.H && col + span * pj < p.W && kbase + kl < p.K;
+            const int oh = (q8.pool ? row >> 1 : row) + pi, ow = (q8.pool ? col >> 1 : col) + pj;
+            const size_t at = LAYOUT == WG_NHWC ? (((size_t)n * Ho + oh) * Wo + ow) * p.K + kbase + kl
+                                                : (((size_t)n * p.K + kbase + kl) * Ho + oh) * Wo + ow;
+            if (ok) q8.out[at] = (int8_t)best;
+        }
+        return;
+    }
+    int v[32];
+    if constexpr (LAYOUT == WG_NHWC) {
+        // thread: filter kl and output column j fixed; iteration it: tile it/2, output row 2(it%2) + tid/128
+        const int kl = tid & 31, j = (tid >> 5) & 3, ih = tid >> 7;
+        const int kk = kbase + kl;
+        const int at0 = (((kl >> 4) * 16 + j) * 64 + (kl & 15)) * 4;
+#pragma unroll
+        for (int it = 0; it < 32; ++it) {
+            const int tile = it >> 1, i = 2 * (it & 1) + ih;
+            const int at = at0 + (4 * i * 64 + (tile >> 2) * 16) * 4 + (tile & 3);
+            v[it] = (parki[at] + parki[at + 2 * 16 * 64 * 4] + rnd) >> 4;
+        }
+#pragma unroll
+        for (int it = 0; it < 32; ++it) {
+            const int tile = it >> 1, i = 2 * (it & 1) + ih;
+            const int origin = __builtin_amdgcn_readlane(my_origin, tile);
+            const int h = __builtin_amdgcn_readlane(my_row, tile) + i, w = __builtin_amdgcn_readlane(my_col, tile) + j;
+            if (origin >= 0 && h < p.H && w < p.W && kk < p.K) y[(size_t)origin + (i * p.W + j) * p.K + kk] = v[it];
+        }
+    } else {
+        // thread: tile, output row i and column j fixed; iteration it: filter it.  A wave writes one
+        // output row of 16 consecutive tiles = 256 contiguous bytes.
+        const int j = tid & 3, tile = (tid >> 2) & 15, i = tid >> 6;
+        const int origin = __shfl(my_origin, tile), h = __shfl(my_row, tile) + i, w = __shfl(my_col, tile) + j;
+        const bool ok = origin >= 0 && h < p.H && w < p.W;
+        const int at0 = ((4 * i + j) * 64 + (tile >> 2) * 16) * 4 + (tile & 3);
+#pragma unroll
+        for (int it = 0; it < 32; ++it) {
+            const int at = at0 + ((it >> 4) * 16 * 64 + (it & 15)) * 4;
+            v[it] = (parki[at] + parki[at + 2 * 16 * 64 * 4] + rnd) >> 4;
+        }
+#pragma unroll
+        for (int it = 0; it < 32; ++it)
+            if (ok && kbase + it < p.K) y[(size_t)origin + ((size_t)(kbase + it) * p.H + i) * p.W + j] = v[it];
+    }
+
+}
+
 // grid: (ceil(T/16), Kp/32), or Kp/64 for WIDE.  256 threads: in the transform phase one thread per (tile,
 // four channels); in the product phase wave w owns filter block (w & 1) and half of the
 // rows of M (w >> 1: rows 0,1,2 or rows 5,3); all four waves stage their partial outputs
@@ -612,174 +794,11 @@ __device__ __forceinline__ void fused_conv_body(const int8_t* __restrict__ x, co
         my_origin = LAYOUT == WG_NHWC ? ((my_n * p.H + my_row) * p.W + my_col) * p.K
                                       : (my_n * p.K * p.H + my_row) * p.W + my_col;
     const int rnd = MODE == WG_SCALED ? 8 : 0;
-    int* parki = reinterpret_cast<int*>(lds);
-    // stores the 16 tiles x 32 filters (from kbase) whose partial outputs the four waves hold in Yp
-    auto store_block = [&](const v4i (&Yp)[16], int kbase) {
-        if (LAYOUT == WG_NHWC && (p.K & 3) == 0) {
-            // Channels-last with K a multiple of four: outputs are staged filter-fastest,
-            // stage[half][output 4i+j][tile][36] (32 filters, rows padded to 36 dwords so that the
-            // four 16-lane groups of a wave land in different banks), then every thread adds the
-            // halves for four consecutive filters and stores 16 bytes; eight lanes cover the 128
-            // contiguous bytes this block owns of a pixel.
-            constexpr int kRow = 36, kHalf = 16 * 16 * kRow;
-            static_assert(2 * kHalf * 4 <= kLdsBytes, "staging fits the operand planes' LDS");
-            {
-                int* dst = parki + half * kHalf + (4 * (lane >> 4)) * kRow + kblock * 16 + (lane & 15);
-    #pragma unroll
-                for (int o = 0; o < 16; ++o)
-    #pragma unroll
-                    for (int q = 0; q < 4; ++q) dst[(o * 16 + q) * kRow] = Yp[o][q];
-            }
-            __syncthreads();
-            // thread: filters 4*k4..4*k4+3; pass ps: output row i = ps/2, tile = 8*(ps%2) + px/4, column j = px%4
-            const int k4 = tid & 7, px = tid >> 3, j = px & 3;
-            const int kk = kbase + 4 * k4;
-            if constexpr (Q8) {
-                // finished int32 outputs of filters 4*g .. 4*g+3 of the block
-                auto staged = [&](int o, int tile, int g) {
-                    const int at = (o * 16 + tile) * kRow + 4 * g;
-                    return (*reinterpret_cast<const v4i*>(parki + at) + *reinterpret_cast<const v4i*>(parki + kHalf + at) + rnd) >> 4;
-                };
-                if (q8.pool) {
-                    // 16 tiles x 2x2 pooled pixels = 64 pixels; thread: four filters of pixels px and px + 32
-    #pragma unroll
-                    for (int e = 0; e < 2; ++e) {
-                        const int pp = px + 32 * e, tile = pp >> 2, pi = (pp >> 1) & 1, pj = pp & 1;
-                        v4i best = requantise(staged(4 * (2 * pi) + 2 * pj, tile, k4), q8);
-                        best = __builtin_elementwise_max(best, requantise(staged(4 * (2 * pi) + 2 * pj + 1, tile, k4), q8));
-                        best = __builtin_elementwise_max(best, requantise(staged(4 * (2 * pi + 1) + 2 * pj, tile, k4), q8));
-                        best = __builtin_elementwise_max(best, requantise(staged(4 * (2 * pi + 1) + 2 * pj + 1, tile, k4), q8));
-                        const int n = __shfl(my_n, tile), row = __shfl(my_row, tile), col = __shfl(my_col, tile);
-                        const bool ok = __shfl(my_origin, tile) >= 0 && row + 2 * pi < p.H && col + 2 * pj < p.W && kk < p.K;
-                        const size_t at = (((size_t)n * (p.H >> 1) + (row >> 1) + pi) * (p.W >> 1) + (col >> 1) + pj) * p.K + kk;
-                        if (ok) *reinterpret_cast<uint32_t*>(q8.out + at) = pack_bytes(best);
-                    }
-                    return;
-                }
-                // thread: 16 filters (half h16 of the block) of its own tile (lane & 15) at outputs
-                // tid/32 and tid/32 + 8: sixteen lanes read sixteen tiles' rows, which fall in
-                // different banks, and a thread stores 16 bytes where the alignment allows
-                const int h16 = (tid >> 4) & 1, kq = kbase + 16 * h16;
-                const bool vector_store = ((p.K & 15) | (reinterpret_cast<uintptr_t>(q8.out) & 15)) == 0;
-    #pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    const int o = (tid >> 5) + 8 * e, i = o >> 2, jj = o & 3;
-                    uint32_t bytes[4];
-    #pragma unroll
-                    for (int g = 0; g < 4; ++g) bytes[g] = pack_bytes(requantise(staged(o, lane & 15, 4 * h16 + g), q8));
-                    const bool ok = my_origin >= 0 && my_row + i < p.H && my_col + jj < p.W;
-                    int8_t* dst = q8.out + (size_t)my_origin + (size_t)(i * p.W + jj) * p.K + kq;
-                    if (ok && vector_store && kq < p.K) {
-                        *reinterpret_cast<uint4*>(dst) = make_uint4(bytes[0], bytes[1], bytes[2], bytes[3]);
-                    } else if (ok) {
-    #pragma unroll
-                        for (int g = 0; g < 4; ++g)
-                            if (kq + 4 * g < p.K) reinterpret_cast<uint32_t*>(dst)[g] = bytes[g];
-                    }
-                }
-                return;
-            }
-            int32_t* first[2];   // output row 0 of the thread's two tiles (e = 0, 1); null where nothing is stored
-            int rows[2];         // output rows of that tile inside the image
-    #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const int origin = __shfl(my_origin, 8 * e + (px >> 2));
-                const bool ok = origin >= 0 && __shfl(my_col, 8 * e + (px >> 2)) + j < p.W && kk < p.K;
-                first[e] = ok ? y + (size_t)origin + j * p.K + kk : nullptr;
-                rows[e] = p.H - __shfl(my_row, 8 * e + (px >> 2));
-            }
-            const size_t row_pitch = (size_t)p.W * p.K;
-            v4i v[8];
-    #pragma unroll
-            for (int ps = 0; ps < 8; ++ps) {
-                const int i = ps >> 1, tile = 8 * (ps & 1) + (px >> 2);
-                const int at = ((4 * i + j) * 16 + tile) * kRow + 4 * k4;
-                v[ps] = (*reinterpret_cast<const v4i*>(parki + at) + *reinterpret_cast<const v4i*>(parki + kHalf + at) + rnd) >> 4;
-            }
-    #pragma unroll
-            for (int ps = 0; ps < 8; ++ps) {
-                const int i = ps >> 1, e = ps & 1;
-                if (first[e] != nullptr && i < rows[e]) *reinterpret_cast<v4i*>(first[e] + i * row_pitch) = v[ps];
-            }
-            return;
-        }
-        // General path: park[wave][output 0..15][lane] (four registers = four tiles each); the value
-        // of (tile, output 4i+j, filter kl) sits in waves kl/16 and 2 + kl/16 at output 4i+j, lane
-        // (tile/4)*16 + kl%16, register tile%4.  16 x 16 x 32 = 8192 results, 32 per thread.
-        v4i* park = reinterpret_cast<v4i*>(lds);
-    #pragma unroll
-        for (int i = 0; i < 16; ++i) park[(wave * 16 + i) * 64 + lane] = Yp[i];
-        __syncthreads();
-        if constexpr (Q8) {
-            // One byte per (tile, output pixel, filter), in the order of the output layout; lg = log2
-            // of the output pixels per tile side (4, or 2 after pooling).
-            const int lg = q8.pool ? 1 : 2, side = 1 << lg, span = q8.pool ? 2 : 1;
-            const int Ho = q8.pool ? p.H >> 1 : p.H, Wo = q8.pool ? p.W >> 1 : p.W;
-            const int items = (16 * 32) << (2 * lg);
-            for (int e = tid; e < items; e += 256) {
-                int kl, tile, pi, pj;
-                if constexpr (LAYOUT == WG_NHWC) {
-                    kl = e & 31; pj = (e >> 5) & (side - 1); pi = (e >> (5 + lg)) & (side - 1); tile = e >> (5 + 2 * lg);
-                } else {
-                    pj = e & (side - 1); tile = (e >> lg) & 15; pi = (e >> (lg + 4)) & (side - 1); kl = e >> (2 * lg + 4);
-                }
-                int best = -129;
-                for (int a = 0; a < span; ++a)
-                    for (int b = 0; b < span; ++b) {
-                        const int o = 4 * (span * pi + a) + span * pj + b;
-                        const int at = ((((kl >> 4) * 16 + o) * 64) + (tile >> 2) * 16 + (kl & 15)) * 4 + (tile & 3);
-                        best = max(best, requantise((parki[at] + parki[at + 2 * 16 * 64 * 4] + rnd) >> 4, q8));
-                    }
-                const int n = __shfl(my_n, tile), row = __shfl(my_row, tile), col = __shfl(my_col, tile);
-                const bool ok = __shfl(my_origin, tile) >= 0 && row + span * pi < p.H && col + span * pj < p.W && kbase + kl < p.K;
-                const int oh = (q8.pool ? row >> 1 : row) + pi, ow = (q8.pool ? col >> 1 : col) + pj;
-                const size_t at = LAYOUT == WG_NHWC ? (((size_t)n * Ho + oh) * Wo + ow) * p.K + kbase + kl
-                                                    : (((size_t)n * p.K + kbase + kl) * Ho + oh) * Wo + ow;
-                if (ok) q8.out[at] = (int8_t)best;
-            }
-            return;
-        }
-        int v[32];
-        if constexpr (LAYOUT == WG_NHWC) {
-            // thread: filter kl and output column j fixed; iteration it: tile it/2, output row 2(it%2) + tid/128
-            const int kl = tid & 31, j = (tid >> 5) & 3, ih = tid >> 7;
-            const int kk = kbase + kl;
-            const int at0 = (((kl >> 4) * 16 + j) * 64 + (kl & 15)) * 4;
-    #pragma unroll
-            for (int it = 0; it < 32; ++it) {
-                const int tile = it >> 1, i = 2 * (it & 1) + ih;
-                const int at = at0 + (4 * i * 64 + (tile >> 2) * 16) * 4 + (tile & 3);
-                v[it] = (parki[at] + parki[at + 2 * 16 * 64 * 4] + rnd) >> 4;
-            }
-    #pragma unroll
-            for (int it = 0; it < 32; ++it) {
-                const int tile = it >> 1, i = 2 * (it & 1) + ih;
-                const int origin = __builtin_amdgcn_readlane(my_origin, tile);
-                const int h = __builtin_amdgcn_readlane(my_row, tile) + i, w = __builtin_amdgcn_readlane(my_col, tile) + j;
-                if (origin >= 0 && h < p.H && w < p.W && kk < p.K) y[(size_t)origin + (i * p.W + j) * p.K + kk] = v[it];
-            }
-        } else {
-            // thread: tile, output row i and column j fixed; iteration it: filter it.  A wave writes one
-            // output row of 16 consecutive tiles = 256 contiguous bytes.
-            const int j = tid & 3, tile = (tid >> 2) & 15, i = tid >> 6;
-            const int origin = __shfl(my_origin, tile), h = __shfl(my_row, tile) + i, w = __shfl(my_col, tile) + j;
-            const bool ok = origin >= 0 && h < p.H && w < p.W;
-            const int at0 = ((4 * i + j) * 64 + (tile >> 2) * 16) * 4 + (tile & 3);
-    #pragma unroll
-            for (int it = 0; it < 32; ++it) {
-                const int at = at0 + ((it >> 4) * 16 * 64 + (it & 15)) * 4;
-                v[it] = (parki[at] + parki[at + 2 * 16 * 64 * 4] + rnd) >> 4;
-            }
-    #pragma unroll
-            for (int it = 0; it < 32; ++it)
-                if (ok && kbase + it < p.K) y[(size_t)origin + ((size_t)(kbase + it) * p.H + i) * p.W + j] = v[it];
-        }
-
-    };
+    const StoreContext sc = {lds, tid, lane, wave, half, kblock, my_n, my_row, my_col, my_origin, rnd, y};
 #pragma unroll
     for (int pass = 0; pass < NPASS; ++pass) {
         __syncthreads();   // the operand planes (or the previous pass's staged outputs) are dead
-        store_block(Yall[pass], k0 + pass * kFusedFilters);
+        store_block<LAYOUT, Q8>(sc, p, q8, Yall[pass], k0 + pass * kFusedFilters);
     }
 }
 
@@ -795,6 +814,213 @@ __global__ __launch_bounds__(256) void fused_conv_int8_kernel(const int8_t* __re
                                                               const uint8_t* __restrict__ blob, size_t table_off,
                                                               size_t planes_off, Problem p, Int8Epilogue q8) {
     fused_conv_body<LAYOUT, LOAD, MODE, SUMS, WIDE, true>(x, blob, table_off, planes_off, nullptr, p, q8);
+}
+
+// Product phase of the role-specialised kernel: the same arithmetic as ProductPhase / ScaledSums
+// without their software pipelining (one set of fragments and accumulators, an eight-deep filter
+// ring), because a product wave there has 256 registers and its waits are covered by the
+// transform wave on the same SIMD.
+template <int MODE, int HALF, bool SUMS>
+struct LeanProducts {
+    using Phase = ProductPhase<MODE, HALF>;
+    static constexpr int NE = Phase::NE, NB = Phase::NB;
+    static constexpr int kRing = 8;
+    v4i ring[kRing];
+
+    __device__ inline void prefetch(const LaneContext& cx) {
+        static_for<(NB < kRing ? NB : kRing)>([&](auto I) { ring[I] = Phase::template load_b<I>(cx); });
+    }
+
+    // sums: the 18 channel sums of ScaledSums (SUMS), else unused; Y: the outputs (not SUMS)
+    __device__ inline void run(const LaneContext& cx, v4i (&sums)[SUMS ? kChannelSums : 1], v4i (&Y)[16]) {
+        v4i er[6], ei[6];
+        static_for<NE>([&](auto S) {
+            constexpr int s = S;
+            constexpr Slot sl = half_slot(HALF, s);
+            constexpr int entry = sl.entry;
+            constexpr int b0 = b_start<MODE>(HALF, s);
+            v4i afr[4], acc[9];
+            static_for<num_a<MODE>(entry)>([&](auto I) { afr[I] = Phase::template load_a<s, I>(cx); });
+            static_for<num_ops<MODE>(entry)>([&](auto I) {
+                constexpr Op op = entry_op<MODE>(entry, I);
+                constexpr v4i zero = {0, 0, 0, 0};
+                acc[op.acc] = __builtin_amdgcn_mfma_i32_16x16x64_i8(afr[op.a], ring[(b0 + op.b) % kRing],
+                                                                    op.init ? zero : acc[op.acc], 0, 0, 0);
+            });
+            static_for<num_b<MODE>(entry)>([&](auto I) {
+                if constexpr (b0 + I + kRing < NB) ring[(b0 + I) % kRing] = Phase::template load_b<b0 + I + kRing>(cx);
+            });
+            if constexpr (SUMS) {
+                constexpr int v = ScaledSums<HALF>::sum_start(s);
+                sums[v] += (acc[0] << 6) + acc[1];
+                if constexpr (!is_real(entry)) sums[v + 1] += (acc[2] << 6) + acc[3];
+            } else {
+                v4i re, im = {0, 0, 0, 0};
+                if constexpr (MODE == WG_LOSSLESS) {
+                    if constexpr (is_real(entry)) {
+                        re = join_limbs(acc[0], acc[1], acc[2]);
+                    } else {   // Re = Dr Wr - Di Wi,  Im = Dr Wi + Di Wr
+                        re = join_limbs(acc[0] - acc[3], acc[1] - acc[4], acc[2] - acc[5]);
+                        im = join_limbs(acc[6], acc[7], acc[8]);
+                    }
+                } else {
+                    re = (acc[0] << 6) + acc[1];
+                    if constexpr (!is_real(entry)) im = (acc[2] << 6) + acc[3];
+                    const ReverseScale unscale(cx.table_k[entry]);   // Section 4.2
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        re[q] = unscale(re[q]);
+                        if constexpr (!is_real(entry)) im[q] = unscale(im[q]);
+                    }
+                }
+                er[sl.pos] = re;
+                ei[sl.pos] = im;
+                if constexpr (sl.last_in_row) finish_row<sl.row>(er, ei, Y);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    }
+};
+
+// The same computation for layers with several channel blocks, with the two kinds of work on
+// different waves.  Eight waves: waves 0-3 only transform (vector ALU), waves 4-7 only multiply
+// (matrix cores, joins, output transform); each SIMD hosts one of each, so the transform of
+// channel block cb + 1 runs under the products of block cb instead of before them, and a
+// product wave's waits are filled with the transform wave's work.  The operand planes are
+// double-buffered in LDS (2 x 72 KB); patches come through 4-byte or byte loads into the
+// transform threads' registers, one channel block ahead.  One barrier per channel block:
+// barrier j (j = 1..CB) publishes the planes of block j - 1 and frees the buffer that the
+// products of block j - 2 were reading.  32 filters per workgroup (a second pass would not fit
+// the 256 registers a wave has when two share a SIMD).
+template <int LAYOUT, bool VEC4, int MODE, bool SUMS, bool Q8>
+__global__ __launch_bounds__(512) void fused_conv_roles_kernel(const int8_t* __restrict__ x, const uint8_t* __restrict__ blob,
+                                                               size_t table_off, size_t planes_off, int32_t* __restrict__ y,
+                                                               Problem p, Int8Epilogue q8) {
+    extern __shared__ __attribute__((aligned(16))) int8_t lds[];
+    const int lane = threadIdx.x & 63, wave8 = threadIdx.x >> 6;
+    const bool transforms = wave8 < 4;
+    const int tid = threadIdx.x & 255, wave = wave8 & 3;   // within the role
+    int bx = blockIdx.x, by = blockIdx.y;
+    {
+        const int total = gridDim.x * gridDim.y;
+        if (gridDim.y >= 2 && (total & 7) == 0) {   // XCD-major order, as in fused_conv_body
+            const int launch = blockIdx.y * gridDim.x + blockIdx.x;
+            const int w = (launch & 7) * (total >> 3) + (launch >> 3);
+            by = w / (int)gridDim.x;
+            bx = w - by * (int)gridDim.x;
+        }
+    }
+    const int tile0 = bx * kFusedTiles, k0 = by * kFusedFilters;
+    if (!blob_matches(reinterpret_cast<const BlobHeader*>(blob), p.K, p.C, MODE)) return;
+    int my_n = 0, my_ty = 0, my_tx = 0;
+    if (tile0 + (lane & 15) < p.T) decode_tile(p, tile0 + (lane & 15), my_n, my_ty, my_tx);
+
+    if (transforms) {
+        const int a_tile = tid >> 4, a_cq = tid & 15;
+        const int a_t = tile0 + a_tile;
+        const int a_tx = __shfl(my_tx, a_tile), a_ty = __shfl(my_ty, a_tile), a_n = __shfl(my_n, a_tile);
+        OperandSplitter<kSplitTwoLimb, LdsPlaneSink> out;
+        int8_t* const slot = lds + lds_slot(a_cq >> 2, a_tile) * 16 + (a_cq & 3) * 4;
+        uint32_t patch[6][6];
+        // 4-byte pixel loads: the 36 offsets of the patch (clamped into the image, relative to x:
+        // they fit 32 bits) are formed once; a channel block is then a uniform base plus these.
+        uint32_t pixel[VEC4 ? 36 : 1];
+        auto request = [&](int cb) {
+            if constexpr (VEC4) {
+                const int c0 = cb * kCBlock + 4 * a_cq;
+                const int8_t* base = x + (c0 < p.C ? c0 : 0);
+#pragma unroll
+                for (int i = 0; i < 36; ++i) patch[i / 6][i % 6] = *reinterpret_cast<const uint32_t*>(base + pixel[i]);
+            } else {
+                load_patch<LAYOUT, false>(x, p, a_n, a_ty, a_tx, cb * kCBlock + 4 * a_cq, patch);
+            }
+        };
+        if constexpr (VEC4) {
+            const int h0 = 4 * a_ty - 1, w0 = 4 * a_tx - 1;
+            const uint32_t image = (uint32_t)a_n * (uint32_t)p.H * (uint32_t)p.W * (uint32_t)p.C;
+#pragma unroll
+            for (int a = 0; a < 6; ++a)
+#pragma unroll
+                for (int b = 0; b < 6; ++b)
+                    pixel[6 * a + b] = image + ((uint32_t)min(max(h0 + a, 0), p.H - 1) * (uint32_t)p.W +
+                                                (uint32_t)min(max(w0 + b, 0), p.W - 1)) * (uint32_t)p.C;
+        }
+        if (a_t < p.T) request(0);
+        for (int cb = 0; cb < p.CB; ++cb) {
+            if (cb > 0) {   // barrier cb
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+            }
+            out.sink.base = slot + (cb & 1) * kLdsBytes;
+            if (a_t < p.T) {
+                bias_patch(p, a_ty, a_tx, cb * kCBlock + 4 * a_cq, patch);
+                transform_patch(patch, out);
+                if (cb + 1 < p.CB) request(cb + 1);
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();   // barrier CB: the last block's planes are published
+        __syncthreads();                // the two barriers of the product waves' store
+        __syncthreads();
+        return;
+    }
+
+    const int kblock = wave & 1, half = wave >> 1;
+    const int k = k0 + kblock * 16 + (lane & 15);
+    LaneContext cx;
+    cx.table_k = reinterpret_cast<const ScaleEntry*>(blob + table_off) + (size_t)k * kEntries;
+    constexpr int NP = MODE == WG_LOSSLESS ? 138 : 46;
+    const int8_t* b_lane = reinterpret_cast<const int8_t*>(blob + planes_off) +
+                           filter_plane_offset(0, 0, k, (lane >> 4) * 16, p.Kp, NP);
+    const size_t b_block_stride = (size_t)(p.Kp >> 4) * NP * kFilterFragBytes;
+    v4i Y[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) Y[i] = (v4i){0, 0, 0, 0};
+    LeanProducts<MODE, 0, SUMS> phase0;
+    LeanProducts<MODE, 1, SUMS> phase1;
+    static_assert(!SUMS || MODE == WG_SCALED, "channel sums are kept apart in scaled mode only");
+    v4i sums[SUMS ? kChannelSums : 1];
+    if constexpr (SUMS) {
+#pragma unroll
+        for (int i = 0; i < kChannelSums; ++i) sums[i] = (v4i){0, 0, 0, 0};
+    }
+    for (int cb = 0; cb < p.CB; ++cb) {
+        cx.b_glob = b_lane + cb * b_block_stride;
+        if (half == 0) phase0.prefetch(cx); else phase1.prefetch(cx);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();   // barrier cb + 1
+        cx.a_lds = lds + (cb & 1) * kLdsBytes + lds_slot(lane >> 4, lane & 15) * 16;
+        if (half == 0) phase0.run(cx, sums, Y); else phase1.run(cx, sums, Y);
+    }
+    if constexpr (SUMS) {
+        if (half == 0) ScaledSums<0>::template finish<0>(cx, sums, Y);
+        else           ScaledSums<1>::template finish<0>(cx, sums, Y);
+    }
+    const int my_row = 4 * my_ty, my_col = 4 * my_tx;
+    int my_origin = -1;
+    if (tile0 + (lane & 15) < p.T)
+        my_origin = LAYOUT == WG_NHWC ? ((my_n * p.H + my_row) * p.W + my_col) * p.K
+                                      : (my_n * p.K * p.H + my_row) * p.W + my_col;
+    const StoreContext sc = {lds, tid, lane, wave, half, kblock, my_n, my_row, my_col, my_origin,
+                             MODE == WG_SCALED ? 8 : 0, y};
+    __syncthreads();   // the operand planes are dead
+    store_block<LAYOUT, Q8>(sc, p, q8, Y, k0);
+}
+
+template <int LAYOUT, bool VEC4, int MODE, bool SUMS, bool Q8>
+hipError_t launch_roles(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
+                        const Int8Epilogue& q8, hipStream_t s) {
+    constexpr int lds_bytes = 2 * kLdsBytes;
+    static bool configured = false;   // per template instance
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_conv_roles_kernel<LAYOUT, VEC4, MODE, SUMS, Q8>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    dim3 grid(ceil_div(p.T, kFusedTiles), p.Kp / kFusedFilters);
+    fused_conv_roles_kernel<LAYOUT, VEC4, MODE, SUMS, Q8><<<grid, 512, lds_bytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p, q8);
+    return hipGetLastError();
 }
 
 // Compute units of the current device (256 on MI355X), asked once.
@@ -852,6 +1078,13 @@ hipError_t launch_mode(const int8_t* x, const uint8_t* blob, const BlobLayout& b
 }
 
 template <bool Q8>
+hipError_t launch_roles_mode(const int8_t* x, const uint8_t* b, const BlobLayout& bl, int32_t* y, const Problem& p,
+                             int mode, const Int8Epilogue& q8, hipStream_t s) {
+    if (mode == WG_LOSSLESS) return launch_roles<WG_NHWC, true, WG_LOSSLESS, false, Q8>(x, b, bl, y, p, q8, s);
+    return launch_roles<WG_NHWC, true, WG_SCALED, true, Q8>(x, b, bl, y, p, q8, s);
+}
+
+template <bool Q8>
 hipError_t launch_layout(const int8_t* x, const uint8_t* b, const BlobLayout& bl, int32_t* y, const Problem& p,
                          int layout, int mode, const Int8Epilogue& q8, hipStream_t s) {
     if (layout == WG_NHWC && p.C % 16 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0)
@@ -868,6 +1101,13 @@ hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, cons
     if (layout == WG_NHWC && p.C <= kNarrowChannels) return launch_narrow_conv(x, blob, y, p, mode, q8, s);
     const BlobLayout bl = blob_layout(p.Kp, p.C, mode);
     const uint8_t* b = static_cast<const uint8_t*>(blob);
+    // Several channel blocks and no more 32-filter workgroups than compute units (so the 64-filter
+    // variant would leave units idle), channels-last with 4-byte pixel loads: transform and
+    // products on separate waves.
+    if (layout == WG_NHWC && p.C % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 4 == 0 && p.CB >= 2 &&
+        (long long)ceil_div(p.T, kFusedTiles) * (p.Kp / kFusedFilters) <= compute_units())
+        return q8.out != nullptr ? launch_roles_mode<true>(x, b, bl, y, p, mode, q8, s)
+                                 : launch_roles_mode<false>(x, b, bl, y, p, mode, q8, s);
     return q8.out != nullptr ? launch_layout<true>(x, b, bl, y, p, layout, mode, q8, s)
                              : launch_layout<false>(x, b, bl, y, p, layout, mode, q8, s);
 }
