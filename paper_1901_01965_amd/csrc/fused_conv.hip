@@ -882,6 +882,68 @@ struct LeanProducts {
     }
 };
 
+// Scaled mode in the role-specialised kernel: every limb product of every entry a wave owns has
+// its own matrix-core accumulator for the whole kernel (two per real entry: high and low
+// activation limb; four per complex entry: Re and Im, each high and low; 36 per wave), so a
+// channel block costs a product wave nothing but fragment loads and matrix-core instructions
+// and the vector ALU is left to the transform wave.  The limbs are joined, the reverse scaling
+// applied and the output transform run once, on the finished channel sums.
+template <int HALF>
+struct ResidentScaled {
+    static constexpr int MODE = WG_SCALED;
+    using Phase = ProductPhase<MODE, HALF>;
+    static constexpr int NE = Phase::NE, NB = Phase::NB;
+    static constexpr int kRing = 8;
+    static constexpr int acc_start(int slot) {
+        int n = 0;
+        for (int s = 0; s < slot; ++s) n += is_real(half_slot(HALF, s).entry) ? 2 : 4;
+        return n;
+    }
+    static constexpr int kAcc = acc_start(NE);
+    v4i ring[kRing];
+
+    __device__ inline void prefetch(const LaneContext& cx) {
+        static_for<(NB < kRing ? NB : kRing)>([&](auto I) { ring[I] = Phase::template load_b<I>(cx); });
+    }
+    __device__ inline void run(const LaneContext& cx, v4i (&acc)[kAcc]) {
+        static_for<NE>([&](auto S) {
+            constexpr int s = S;
+            constexpr int entry = half_slot(HALF, s).entry;
+            constexpr int b0 = b_start<MODE>(HALF, s);
+            constexpr int v = acc_start(s);
+            v4i afr[4];
+            static_for<num_a<MODE>(entry)>([&](auto I) { afr[I] = Phase::template load_a<s, I>(cx); });
+            static_for<num_ops<MODE>(entry)>([&](auto I) {
+                constexpr Op op = entry_op<MODE>(entry, I);
+                acc[v + op.acc] = __builtin_amdgcn_mfma_i32_16x16x64_i8(afr[op.a], ring[(b0 + op.b) % kRing], acc[v + op.acc], 0, 0, 0);
+            });
+            static_for<num_b<MODE>(entry)>([&](auto I) {
+                if constexpr (b0 + I + kRing < NB) ring[(b0 + I) % kRing] = Phase::template load_b<b0 + I + kRing>(cx);
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    }
+    __device__ inline static void finish(const LaneContext& cx, const v4i (&acc)[kAcc], v4i (&Y)[16]) {
+        v4i er[6], ei[6];
+        static_for<NE>([&](auto S) {
+            constexpr Slot sl = half_slot(HALF, S);
+            constexpr int v = acc_start(S);
+            v4i re = (acc[v] << 6) + acc[v + 1], im = {0, 0, 0, 0};
+            if constexpr (!is_real(sl.entry)) im = (acc[v + 2] << 6) + acc[v + 3];
+            const ReverseScale unscale(cx.table_k[sl.entry]);   // Section 4.2
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                re[q] = unscale(re[q]);
+                if constexpr (!is_real(sl.entry)) im[q] = unscale(im[q]);
+            }
+            er[sl.pos] = re;
+            ei[sl.pos] = im;
+            if constexpr (sl.last_in_row) finish_row<sl.row>(er, ei, Y);
+        });
+    }
+};
+static_assert(ResidentScaled<0>::kAcc == 36 && ResidentScaled<1>::kAcc == 36, "both halves keep 36 accumulators");
+
 // The same computation for layers with several channel blocks, with the two kinds of work on
 // different waves.  Eight waves: waves 0-3 only transform (vector ALU), waves 4-7 only multiply
 // (matrix cores, joins, output transform); each SIMD hosts one of each, so the transform of
@@ -976,13 +1038,13 @@ __global__ __launch_bounds__(512) void fused_conv_roles_kernel(const int8_t* __r
     v4i Y[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) Y[i] = (v4i){0, 0, 0, 0};
-    LeanProducts<MODE, 0, SUMS> phase0;
-    LeanProducts<MODE, 1, SUMS> phase1;
-    static_assert(!SUMS || MODE == WG_SCALED, "channel sums are kept apart in scaled mode only");
-    v4i sums[SUMS ? kChannelSums : 1];
+    static_assert(!SUMS || MODE == WG_SCALED, "accumulators stay resident in scaled mode only");
+    std::conditional_t<SUMS, ResidentScaled<0>, LeanProducts<MODE, 0, false>> phase0;
+    std::conditional_t<SUMS, ResidentScaled<1>, LeanProducts<MODE, 1, false>> phase1;
+    v4i sums[SUMS ? 36 : 1];
     if constexpr (SUMS) {
 #pragma unroll
-        for (int i = 0; i < kChannelSums; ++i) sums[i] = (v4i){0, 0, 0, 0};
+        for (int i = 0; i < 36; ++i) sums[i] = (v4i){0, 0, 0, 0};
     }
     for (int cb = 0; cb < p.CB; ++cb) {
         cx.b_glob = b_lane + cb * b_block_stride;
@@ -990,11 +1052,16 @@ __global__ __launch_bounds__(512) void fused_conv_roles_kernel(const int8_t* __r
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();   // barrier cb + 1
         cx.a_lds = lds + (cb & 1) * kLdsBytes + lds_slot(lane >> 4, lane & 15) * 16;
-        if (half == 0) phase0.run(cx, sums, Y); else phase1.run(cx, sums, Y);
+        if constexpr (SUMS) {
+            if (half == 0) phase0.run(cx, sums); else phase1.run(cx, sums);
+        } else {
+            v4i unused[1];
+            if (half == 0) phase0.run(cx, unused, Y); else phase1.run(cx, unused, Y);
+        }
     }
     if constexpr (SUMS) {
-        if (half == 0) ScaledSums<0>::template finish<0>(cx, sums, Y);
-        else           ScaledSums<1>::template finish<0>(cx, sums, Y);
+        if (half == 0) ResidentScaled<0>::finish(cx, sums, Y);
+        else           ResidentScaled<1>::finish(cx, sums, Y);
     }
     const int my_row = 4 * my_ty, my_col = 4 * my_tx;
     int my_origin = -1;
