@@ -851,9 +851,17 @@ struct LeanProducts {
                 if constexpr (b0 + I + kRing < NB) ring[(b0 + I) % kRing] = Phase::template load_b<b0 + I + kRing>(cx);
             });
             if constexpr (SUMS) {
+                // joined values only; scaling (scaled mode) and the output transform wait for finish()
                 constexpr int v = ScaledSums<HALF>::sum_start(s);
-                sums[v] += (acc[0] << 6) + acc[1];
-                if constexpr (!is_real(entry)) sums[v + 1] += (acc[2] << 6) + acc[3];
+                if constexpr (MODE == WG_SCALED) {
+                    sums[v] += (acc[0] << 6) + acc[1];
+                    if constexpr (!is_real(entry)) sums[v + 1] += (acc[2] << 6) + acc[3];
+                } else if constexpr (is_real(entry)) {
+                    sums[v] += join_limbs(acc[0], acc[1], acc[2]);
+                } else {
+                    sums[v] += join_limbs(acc[0] - acc[3], acc[1] - acc[4], acc[2] - acc[5]);
+                    sums[v + 1] += join_limbs(acc[6], acc[7], acc[8]);
+                }
             } else {
                 v4i re, im = {0, 0, 0, 0};
                 if constexpr (MODE == WG_LOSSLESS) {
@@ -878,6 +886,21 @@ struct LeanProducts {
                 if constexpr (sl.last_in_row) finish_row<sl.row>(er, ei, Y);
             }
             __builtin_amdgcn_sched_barrier(0);
+        });
+    }
+
+    // SUMS, lossless mode, after the last channel block: the output transform of the channel sums
+    // (it is linear, so it may as well run once on the sums as once per block).
+    __device__ inline static void finish_lossless(const v4i (&sums)[SUMS ? kChannelSums : 1], v4i (&Y)[16]) {
+        static_assert(!SUMS || kChannelSums == ScaledSums<HALF>::kSums, "same sum layout as ScaledSums");
+        v4i er[6], ei[6];
+        static_for<NE>([&](auto S) {
+            constexpr Slot sl = half_slot(HALF, S);
+            constexpr int v = ScaledSums<HALF>::sum_start(S);
+            er[sl.pos] = sums[v];
+            if constexpr (!is_real(sl.entry)) ei[sl.pos] = sums[v + 1];
+            else                              ei[sl.pos] = (v4i){0, 0, 0, 0};
+            if constexpr (sl.last_in_row) finish_row<sl.row>(er, ei, Y);
         });
     }
 };
@@ -1038,13 +1061,16 @@ __global__ __launch_bounds__(512) void fused_conv_roles_kernel(const int8_t* __r
     v4i Y[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) Y[i] = (v4i){0, 0, 0, 0};
-    static_assert(!SUMS || MODE == WG_SCALED, "accumulators stay resident in scaled mode only");
-    std::conditional_t<SUMS, ResidentScaled<0>, LeanProducts<MODE, 0, false>> phase0;
-    std::conditional_t<SUMS, ResidentScaled<1>, LeanProducts<MODE, 1, false>> phase1;
-    v4i sums[SUMS ? 36 : 1];
+    // SUMS: the product waves do no output transform per block.  Scaled: all 36 limb-product
+    // accumulators stay resident; lossless: 18 joined channel sums (54 accumulators would not fit).
+    constexpr bool RESIDENT = SUMS && MODE == WG_SCALED;
+    std::conditional_t<RESIDENT, ResidentScaled<0>, LeanProducts<MODE, 0, SUMS>> phase0;
+    std::conditional_t<RESIDENT, ResidentScaled<1>, LeanProducts<MODE, 1, SUMS>> phase1;
+    constexpr int kSumRegs = RESIDENT ? 36 : (SUMS ? kChannelSums : 1);
+    v4i sums[kSumRegs];
     if constexpr (SUMS) {
 #pragma unroll
-        for (int i = 0; i < 36; ++i) sums[i] = (v4i){0, 0, 0, 0};
+        for (int i = 0; i < kSumRegs; ++i) sums[i] = (v4i){0, 0, 0, 0};
     }
     for (int cb = 0; cb < p.CB; ++cb) {
         cx.b_glob = b_lane + cb * b_block_stride;
@@ -1052,16 +1078,18 @@ __global__ __launch_bounds__(512) void fused_conv_roles_kernel(const int8_t* __r
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();   // barrier cb + 1
         cx.a_lds = lds + (cb & 1) * kLdsBytes + lds_slot(lane >> 4, lane & 15) * 16;
-        if constexpr (SUMS) {
+        if constexpr (RESIDENT) {
             if (half == 0) phase0.run(cx, sums); else phase1.run(cx, sums);
         } else {
-            v4i unused[1];
-            if (half == 0) phase0.run(cx, unused, Y); else phase1.run(cx, unused, Y);
+            if (half == 0) phase0.run(cx, sums, Y); else phase1.run(cx, sums, Y);
         }
     }
-    if constexpr (SUMS) {
+    if constexpr (RESIDENT) {
         if (half == 0) ResidentScaled<0>::finish(cx, sums, Y);
         else           ResidentScaled<1>::finish(cx, sums, Y);
+    } else if constexpr (SUMS) {
+        if (half == 0) LeanProducts<MODE, 0, true>::finish_lossless(sums, Y);
+        else           LeanProducts<MODE, 1, true>::finish_lossless(sums, Y);
     }
     const int my_row = 4 * my_ty, my_col = 4 * my_tx;
     int my_origin = -1;
@@ -1147,7 +1175,7 @@ hipError_t launch_mode(const int8_t* x, const uint8_t* blob, const BlobLayout& b
 template <bool Q8>
 hipError_t launch_roles_mode(const int8_t* x, const uint8_t* b, const BlobLayout& bl, int32_t* y, const Problem& p,
                              int mode, const Int8Epilogue& q8, hipStream_t s) {
-    if (mode == WG_LOSSLESS) return launch_roles<WG_NHWC, true, WG_LOSSLESS, false, Q8>(x, b, bl, y, p, q8, s);
+    if (mode == WG_LOSSLESS) return launch_roles<WG_NHWC, true, WG_LOSSLESS, true, Q8>(x, b, bl, y, p, q8, s);
     return launch_roles<WG_NHWC, true, WG_SCALED, true, Q8>(x, b, bl, y, p, q8, s);
 }
 
