@@ -238,6 +238,12 @@ int winograd_num_activation_planes(int mode);
    Process-wide; for tests and benchmarks.  Returns WG_EINVAL for any other
    value. */
 int winograd_debug_force_path(int path);
+/* Test hook for the single-kernel path's streaming variant (one workgroup walks over many tile
+   blocks of a 32-filter block; the library picks it by itself only for large layers): n > 0
+   makes every call whose layout allows it (channels-last, C % 4 = 0, K % 4 = 0) use it with n
+   workgroups per filter block; 0 restores the library's own choice.  Process-wide, not
+   thread-safe, like winograd_debug_force_path. */
+int winograd_debug_stream_workgroups(int n);
 int winograd_num_filter_planes(int mode);
 
 /* Host-only: the (n, ty, tx) the kernels derive from tile index t = (n*TH + ty)*TW + tx for

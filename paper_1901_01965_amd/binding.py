@@ -43,6 +43,7 @@ def load_library():
         "winograd_num_activation_planes": (i, [i]),
         "winograd_num_filter_planes": (i, [i]),
         "winograd_debug_force_path": (i, [i]),
+        "winograd_debug_stream_workgroups": (i, [i]),
         "winograd_conv2d_path": (i, [i, i, i, i, i, i]),
         "winograd_debug_tile_decode": (i, [i, i, i, i, i, i, vp]),
         "winograd_packed_filter_bytes": (sz, [i, i, i]),
@@ -73,7 +74,7 @@ def load_library():
 
 EXPORTED_SYMBOLS = (
     "winograd_status_string", "winograd_num_activation_planes", "winograd_num_filter_planes",
-    "winograd_debug_force_path", "winograd_conv2d_path", "winograd_debug_tile_decode",
+    "winograd_debug_force_path", "winograd_debug_stream_workgroups", "winograd_conv2d_path", "winograd_debug_tile_decode",
     "winograd_packed_filter_bytes", "winograd_workspace_bytes", "winograd_filter_transform",
     "winograd_packed_filter_check", "winograd_conv2d_int8", "winograd_conv2d_int8_requant",
     "winograd_conv2d_int8_stage_times",
@@ -120,6 +121,11 @@ AUTO, STAGED, FUSED = 0, 1, 2
 def force_path(path):
     """0: library's choice (the fused kernel), 1: staged three-kernel pipeline, 2: fused kernel."""
     _check(load_library().winograd_debug_force_path(int(path)), "winograd_debug_force_path")
+
+
+def stream_workgroups(n):
+    """Test hook: n > 0 = use the streaming variant of the single-kernel path with n workgroups per filter block."""
+    _check(load_library().winograd_debug_stream_workgroups(int(n)), "winograd_debug_stream_workgroups")
 
 
 def conv2d_path(N, C, H, W, K, mode):

@@ -202,6 +202,12 @@ int winograd_debug_tile_decode(int N, int C, int H, int W, int K, int t, int* ou
     return WG_OK;
 }
 
+int winograd_debug_stream_workgroups(int n) {
+    if (n < 0) return WG_EINVAL;
+    set_stream_workgroups(n);
+    return WG_OK;
+}
+
 int winograd_debug_force_path(int path) {
     if (path < 0 || path > 2) return WG_EINVAL;
     g_forced_path = path;

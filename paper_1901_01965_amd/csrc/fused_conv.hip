@@ -462,7 +462,10 @@ struct StoreContext {
 
 // Adds the two row halves and stores the 16 tiles x 32 filters (from kbase) whose partial outputs
 // the four waves hold in Yp.  All four waves call it together (it contains one barrier).
-template <int LAYOUT, bool Q8>
+// PART 1 / PART 2 (channels-last with K % 4 = 0 only): just the staging of Yp into LDS / just
+// the adding and storing of what was staged, for callers that put their own barrier between
+// the two and may run them on different waves.
+template <int LAYOUT, bool Q8, int PART = 0>
 __device__ __forceinline__ void store_block(const StoreContext& sc, const Problem& p, const Int8Epilogue& q8,
                                             const v4i (&Yp)[16], int kbase) {
     int8_t* const lds = sc.lds;
@@ -479,14 +482,15 @@ __device__ __forceinline__ void store_block(const StoreContext& sc, const Proble
         // contiguous bytes this block owns of a pixel.
         constexpr int kRow = 36, kHalf = 16 * 16 * kRow;
         static_assert(2 * kHalf * 4 <= kLdsBytes, "staging fits the operand planes' LDS");
-        {
+        if constexpr (PART != 2) {
             int* dst = parki + half * kHalf + (4 * (lane >> 4)) * kRow + kblock * 16 + (lane & 15);
 #pragma unroll
             for (int o = 0; o < 16; ++o)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) dst[(o * 16 + q) * kRow] = Yp[o][q];
         }
-        __syncthreads();
+        if constexpr (PART == 1) return;
+        if constexpr (PART == 0) __syncthreads();
         // thread: filters 4*k4..4*k4+3; pass ps: output row i = ps/2, tile = 8*(ps%2) + px/4, column j = px%4
         const int k4 = tid & 7, px = tid >> 3, j = px & 3;
         const int kk = kbase + 4 * k4;
@@ -1132,6 +1136,184 @@ int compute_units() {
     return cus;
 }
 
+// The role-specialised kernel as a stream over tile blocks: a workgroup owns one 32-filter block
+// and walks over many tile blocks (grid: about one workgroup per compute unit), so that the two
+// roles also overlap across tile blocks and layers with a single channel block are pipelined
+// too.  A unit u is one (tile block, channel block); the transform waves are one unit ahead of
+// the product waves, and they also take over the second half of the store: at the end of a
+// tile block the product waves only stage their outputs in LDS (in the buffer whose planes
+// they have just consumed), and the transform waves add the halves and write them out while
+// the product waves already multiply the next unit.
+// Barriers, in the same order on both roles: U_u (u = 1..U) publishes the planes of unit u - 1 and
+// frees the buffer of unit u - 2; after the last channel block of a tile block, D_u (every product
+// wave has finished reading the planes) and S_u (the outputs are staged).
+// Channels-last, C % 4 = 0 (4-byte pixel loads), K % 4 = 0 (16-byte stores).
+template <int MODE, bool Q8>
+__global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __restrict__ x, const uint8_t* __restrict__ blob,
+                                                                size_t table_off, size_t planes_off, int32_t* __restrict__ y,
+                                                                Problem p, Int8Epilogue q8, int tile_blocks) {
+    extern __shared__ __attribute__((aligned(16))) int8_t lds[];
+    const int lane = threadIdx.x & 63, wave8 = threadIdx.x >> 6;
+    const bool transforms = wave8 < 4;
+    const int tid = threadIdx.x & 255, wave = wave8 & 3;   // within the role
+    const int k0 = blockIdx.y * kFusedFilters;
+    if (!blob_matches(reinterpret_cast<const BlobHeader*>(blob), p.K, p.C, MODE)) return;
+    // this workgroup's tile blocks: blockIdx.x, blockIdx.x + gridDim.x, ...
+    const int my_blocks = (tile_blocks - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int units = my_blocks * p.CB;
+    const int rnd = MODE == WG_SCALED ? 8 : 0;
+
+    if (transforms) {
+        const int a_tile = tid >> 4, a_cq = tid & 15;
+        OperandSplitter<kSplitTwoLimb, LdsPlaneSink> out;
+        int8_t* const slot = lds + lds_slot(a_cq >> 2, a_tile) * 16 + (a_cq & 3) * 4;
+        uint32_t patch[6][6], pixel[36];
+        int a_t = 0, a_ty = 0, a_tx = 0;
+        // identity of the thread's tile in tile block tb, and the 36 clamped pixel offsets of its patch
+        auto enter_tile_block = [&](int tb) {
+            a_t = tb * kFusedTiles + a_tile;
+            int a_n = 0;
+            a_ty = 0; a_tx = 0;
+            if (a_t < p.T) decode_tile(p, a_t, a_n, a_ty, a_tx);
+            const int h0 = 4 * a_ty - 1, w0 = 4 * a_tx - 1;
+            const uint32_t image = (uint32_t)a_n * (uint32_t)p.H * (uint32_t)p.W * (uint32_t)p.C;
+#pragma unroll
+            for (int a = 0; a < 6; ++a)
+#pragma unroll
+                for (int b = 0; b < 6; ++b)
+                    pixel[6 * a + b] = image + ((uint32_t)min(max(h0 + a, 0), p.H - 1) * (uint32_t)p.W +
+                                                (uint32_t)min(max(w0 + b, 0), p.W - 1)) * (uint32_t)p.C;
+        };
+        auto request = [&](int cb) {
+            const int c0 = cb * kCBlock + 4 * a_cq;
+            const int8_t* base = x + (c0 < p.C ? c0 : 0);
+#pragma unroll
+            for (int i = 0; i < 36; ++i) patch[i / 6][i % 6] = *reinterpret_cast<const uint32_t*>(base + pixel[i]);
+        };
+        // adds the two halves staged in `buffer` for tile block tb and writes them out
+        auto flush = [&](int tb, int buffer) {
+            int n = 0, ty = 0, tx = 0;
+            const int t = tb * kFusedTiles + (lane & 15);
+            if (t < p.T) decode_tile(p, t, n, ty, tx);
+            const int row = 4 * ty, col = 4 * tx;
+            const int origin = t < p.T ? ((n * p.H + row) * p.W + col) * p.K : -1;
+            const StoreContext sc = {lds + buffer * kLdsBytes, tid, lane, wave, 0, 0, n, row, col, origin, rnd, y};
+            v4i none[16];
+            store_block<WG_NHWC, Q8, 2>(sc, p, q8, none, k0);
+        };
+        int cb = 0, jb = 0;   // unit u = (tile block number jb of this workgroup, channel block cb)
+        if (units > 0) {
+            enter_tile_block(blockIdx.x);
+            request(0);
+        }
+        // was unit v the last channel block of its tile block?  v % CB == CB - 1, tracked without division:
+        // last1 = for unit u - 1, last2 = for unit u - 2; tb1 / tb2 = their tile blocks
+        bool last1 = false, last2 = false;
+        int tb1 = 0, tb2 = 0;
+        for (int u = 0; u <= units; ++u) {
+            if (u > 0) {   // U_u
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+            }
+            if (last2) flush(tb2, u & 1);   // staged in the buffer of unit u - 2, which unit u is about to overwrite
+            const int tb = (int)blockIdx.x + jb * (int)gridDim.x;
+            if (u < units) {
+                out.sink.base = slot + (u & 1) * kLdsBytes;
+                if (a_t < p.T) {
+                    bias_patch(p, a_ty, a_tx, cb * kCBlock + 4 * a_cq, patch);
+                    transform_patch(patch, out);
+                }
+            }
+            if (last1) {   // D_{u-1}, S_{u-1}
+                __syncthreads();
+                __syncthreads();
+            }
+            last2 = last1; tb2 = tb1;
+            last1 = u < units && cb == p.CB - 1; tb1 = tb;
+            if (u < units) {   // next unit's patch
+                if (++cb == p.CB) { cb = 0; ++jb; }
+                if (u + 1 < units) {
+                    if (cb == 0) enter_tile_block((int)blockIdx.x + jb * (int)gridDim.x);
+                    if (a_t < p.T) request(cb);
+                }
+            }
+        }
+        if (last2) flush(tb2, (units + 1) & 1);   // the last tile block, staged in the buffer of unit U - 1
+        return;
+    }
+
+    const int kblock = wave & 1, half = wave >> 1;
+    const int k = k0 + kblock * 16 + (lane & 15);
+    LaneContext cx;
+    cx.table_k = reinterpret_cast<const ScaleEntry*>(blob + table_off) + (size_t)k * kEntries;
+    constexpr int NP = MODE == WG_LOSSLESS ? 138 : 46;
+    const int8_t* b_lane = reinterpret_cast<const int8_t*>(blob + planes_off) +
+                           filter_plane_offset(0, 0, k, (lane >> 4) * 16, p.Kp, NP);
+    const size_t b_block_stride = (size_t)(p.Kp >> 4) * NP * kFilterFragBytes;
+    // 18 joined channel sums per wave in both modes (36 resident accumulators plus the outputs
+    // would not fit the 256 registers here)
+    LeanProducts<MODE, 0, true> phase0;
+    LeanProducts<MODE, 1, true> phase1;
+    constexpr int kSumRegs = kChannelSums;
+    v4i sums[kSumRegs];
+    v4i Y[16];
+    int cb = 0;
+    for (int u = 0; u < units; ++u) {
+        if (cb == 0) {
+#pragma unroll
+            for (int i = 0; i < kSumRegs; ++i) sums[i] = (v4i){0, 0, 0, 0};
+        }
+        cx.b_glob = b_lane + cb * b_block_stride;
+        if (half == 0) phase0.prefetch(cx); else phase1.prefetch(cx);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();   // U_{u+1}
+        cx.a_lds = lds + (u & 1) * kLdsBytes + lds_slot(lane >> 4, lane & 15) * 16;
+        if (half == 0) phase0.run(cx, sums, Y); else phase1.run(cx, sums, Y);
+        if (++cb == p.CB) {
+            cb = 0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) Y[i] = (v4i){0, 0, 0, 0};
+            if constexpr (MODE == WG_SCALED) {
+                if (half == 0) ScaledSums<0>::template finish<0>(cx, sums, Y);
+                else           ScaledSums<1>::template finish<0>(cx, sums, Y);
+            } else {
+                if (half == 0) LeanProducts<MODE, 0, true>::finish_lossless(sums, Y);
+                else           LeanProducts<MODE, 1, true>::finish_lossless(sums, Y);
+            }
+            __syncthreads();   // D_u: every product wave has finished reading this unit's planes
+            const StoreContext sc = {lds + (u & 1) * kLdsBytes, tid, lane, wave, half, kblock, 0, 0, 0, -1, rnd, y};
+            store_block<WG_NHWC, Q8, 1>(sc, p, q8, Y, k0);
+            __syncthreads();   // S_u: staged
+        }
+    }
+}
+
+// Workgroups per filter block of the streaming kernel: about one workgroup per compute unit in
+// total (a test hook can set a smaller number, so that small problems stream, too).
+int g_stream_workgroups = 0;
+int stream_workgroups(int tile_blocks, int filter_blocks) {
+    const int wanted = g_stream_workgroups > 0 ? g_stream_workgroups : compute_units() / filter_blocks;
+    return std::max(1, std::min(tile_blocks, wanted));
+}
+
+template <int MODE, bool Q8>
+hipError_t launch_stream(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
+                         const Int8Epilogue& q8, hipStream_t s) {
+    constexpr int lds_bytes = 2 * kLdsBytes;
+    static bool configured = false;   // per template instance
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_conv_stream_kernel<MODE, Q8>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int tile_blocks = ceil_div(p.T, kFusedTiles), filter_blocks = p.Kp / kFusedFilters;
+    const int gx = stream_workgroups(tile_blocks, filter_blocks);
+    fused_conv_stream_kernel<MODE, Q8><<<dim3(gx, filter_blocks), 512, lds_bytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p,
+                                                                                     q8, tile_blocks);
+    return hipGetLastError();
+}
+
 template <int LAYOUT, int LOAD, int MODE, bool SUMS, bool WIDE, bool Q8>
 hipError_t launch(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
                   const Int8Epilogue& q8, hipStream_t s) {
@@ -1191,11 +1373,23 @@ hipError_t launch_layout(const int8_t* x, const uint8_t* b, const BlobLayout& bl
 
 }  // namespace
 
+void set_stream_workgroups(int n) { g_stream_workgroups = n > 0 ? n : 0; }
+
 hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int layout, int mode,
                              const Int8Epilogue& q8, hipStream_t s) {
     if (layout == WG_NHWC && p.C <= kNarrowChannels) return launch_narrow_conv(x, blob, y, p, mode, q8, s);
     const BlobLayout bl = blob_layout(p.Kp, p.C, mode);
     const uint8_t* b = static_cast<const uint8_t*>(blob);
+    // The streaming variant of the role-specialised kernel when every workgroup gets at least six
+    // tile blocks to stream over (measured: +10-17 % on the large layers; with fewer, the fill
+    // and drain of its pipeline cost more than the overlap saves), or when a test asks for it.
+    const bool can_stream = layout == WG_NHWC && p.C % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 4 == 0 && (p.K & 3) == 0;
+    const int tile_blocks = ceil_div(p.T, kFusedTiles), filter_blocks = p.Kp / kFusedFilters;
+    if (can_stream && (g_stream_workgroups > 0 || tile_blocks >= 6 * stream_workgroups(tile_blocks, filter_blocks))) {
+        if (mode == WG_LOSSLESS)
+            return q8.out ? launch_stream<WG_LOSSLESS, true>(x, b, bl, y, p, q8, s) : launch_stream<WG_LOSSLESS, false>(x, b, bl, y, p, q8, s);
+        return q8.out ? launch_stream<WG_SCALED, true>(x, b, bl, y, p, q8, s) : launch_stream<WG_SCALED, false>(x, b, bl, y, p, q8, s);
+    }
     // Transform and products on separate waves (channels-last with 4-byte pixel loads): with
     // several channel blocks and no more 32-filter workgroups than compute units (where the
     // 64-filter variant would leave units idle), and in scaled mode from four channel blocks on

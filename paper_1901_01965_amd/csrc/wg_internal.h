@@ -214,6 +214,9 @@ inline Int8Epilogue make_int8_epilogue(int8_t* out, int shift, bool relu, bool p
 // Single-kernel path (no workspace traffic).
 hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int layout,
                              int mode, const Int8Epilogue& q8, hipStream_t s);
+// Test hook: n > 0 makes the single-kernel path use its streaming variant wherever the layout
+// allows, with n workgroups per filter block; 0 restores the library's own choice.
+void set_stream_workgroups(int n);
 // Single-kernel path for channels-last inputs with C <= kNarrowChannels.
 hipError_t launch_narrow_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int mode,
                               const Int8Epilogue& q8, hipStream_t s);

@@ -350,6 +350,53 @@ def test_narrow_input_layers(shape, wgt, mode):
         wg.force_path(wg.AUTO)
 
 
+STREAM_CASES = [  # (N, C, K, H, W), workgroups per filter block: tile blocks per workgroup 1, several, uneven;
+    # one to three channel blocks; ragged last tile block; filters beyond K in the last block
+    ((1, 16, 32, 16, 16), 1), ((2, 16, 32, 20, 16), 3), ((3, 64, 40, 18, 22), 4), ((2, 80, 72, 14, 14), 2),
+    ((1, 132, 36, 26, 10), 5), ((4, 32, 64, 8, 8), 7), ((1, 200, 32, 9, 7), 1),
+]
+
+
+@pytest.mark.parametrize("mode", [wg.LOSSLESS, wg.SCALED])
+@pytest.mark.parametrize("case", STREAM_CASES)
+def test_streaming_variant_of_the_single_kernel_path(case, mode):
+    """The role-specialised streaming kernel (a workgroup walks over several tile blocks; transform waves one unit
+    ahead of product waves and storing the previous tile block), forced through the test hook on small problems:
+    int32 output and the int8 epilogue with and without pooling."""
+    (N, C, K, H, W), slots = case
+    x, g = wl.make_custom(N, C, K, H, W, act="relu", wgt="gauss", seed=63)
+    want = oracle.direct_conv2d(x, g) if mode == wg.LOSSLESS else oracle.winograd_conv2d(x, g, oracle.SCALED)[0]
+    packed = wg.winograd_filter_transform(_g(g, wg.NHWC), wg.NHWC, mode)
+    xd = _x(x, wg.NHWC)
+    shift = max(0, int(np.abs(want).max()).bit_length() - 7)
+    wg.stream_workgroups(slots)
+    try:
+        out = torch.full((N, H, W, K), 1357911, dtype=torch.int32, device="cuda")
+        wg.winograd_conv2d_int8(xd, packed, wg.NHWC, out=out)
+        assert np.array_equal(_y(out, wg.NHWC), want)
+        for pool in (False, True):
+            if pool and (H % 2 or W % 2):
+                continue
+            got = wg.winograd_conv2d_int8_requant(xd, packed, shift, True, pool, wg.NHWC)
+            assert np.array_equal(_y(got, wg.NHWC), oracle.requant_relu_pool(want, shift, True, pool)), pool
+    finally:
+        wg.stream_workgroups(0)
+
+
+def test_streaming_variant_is_what_large_layers_run():
+    """A layer large enough for the library to choose the streaming kernel by itself (six or more tile blocks per
+    workgroup): equal to the direct kernel everywhere, and to the oracle on the first and the last image."""
+    N, C, K, H, W = 6, 16, 32, 224, 224
+    x, g = wl.make_custom(N, C, K, H, W, act="relu", wgt="gauss", seed=64)
+    xd, gd = _x(x, wg.NHWC), _g(g, wg.NHWC)
+    y = wg.winograd_conv2d_int8(xd, wg.winograd_filter_transform(gd, wg.NHWC, wg.LOSSLESS), wg.NHWC)
+    assert torch.equal(y, wg.direct_conv2d_int8(xd, gd, wg.NHWC))
+    for sl in (slice(0, 1), slice(N - 1, N)):
+        assert np.array_equal(_y(y[sl], wg.NHWC), oracle.direct_conv2d(x[sl], g))
+    ys = _y(wg.winograd_conv2d_int8(xd, wg.winograd_filter_transform(gd, wg.NHWC, wg.SCALED), wg.NHWC)[N - 1:], wg.NHWC)
+    assert np.array_equal(ys, oracle.winograd_conv2d(x[N - 1:], g, oracle.SCALED)[0])
+
+
 @pytest.mark.parametrize("path", PATHS, indirect=True)
 def test_results_do_not_depend_on_workspace_contents_and_repeat_exactly(path):
     x, g = wl.make_custom(2, 24, 40, 14, 9, seed=40)
