@@ -260,6 +260,20 @@ def f2_scale_filters(Wt, weight_range=127):
     return Wt, tab, mx
 
 
+BOTH_SCALED = 2   # F(2x2,3x3) only: filters and activations scaled
+
+
+def f2_scale_activations(D, value_range=127):
+    """The rule of Section 4.2 applied per tile to [T,C,4,4] transformed activations: (scaled copy, table [T,4,4,4] =
+    (n,p,r,q), max [T,4,4])."""
+    D = np.ascontiguousarray(D, dtype=np.int64).copy()
+    T, C = D.shape[:2]
+    tab = np.zeros((T, 4, 4, 4), np.int32)
+    mx = np.zeros((T, 4, 4), np.int64)
+    lib().oracle_f2_scale_activations(_p(D), ctypes.c_int64(T), C, ctypes.c_int64(value_range), _p(tab), _p(mx))
+    return D, tab, mx
+
+
 def f2_conv2d(x, g, mode=LOSSLESS, weight_range=127):
     """Whole F(2x2,3x3) path.  Returns (y int32 NCHW, flags)."""
     x, g = _i8(x), _i8(g)

@@ -27,6 +27,15 @@
  *                               table entries from the pinned factor routines);
  *                               the general lossy result is PARITY UNPINNED (the
  *                               paper prints no worked example of it).
+ *   oracle_f2_scale_activations, oracle_f2_conv2d mode 2 (activations scaled as well)
+ *                               Section 4.1 only remarks that the analysis of Section 4.2
+ *                               carries over to B^T d B; the rule here is that section's
+ *                               with the roles of filter and tile exchanged (see the
+ *                               function).  Special cases pinned (no tile needs scaling
+ *                               => equals mode 1; scaled activations within the range;
+ *                               table entries from the pinned factor routines; the
+ *                               operand a tile sees does not depend on the other tiles);
+ *                               the general lossy result is PARITY UNPINNED.
  *
  * Tile t = (n*TH + ty)*TW + tx with TH = ceil(H/2), TW = ceil(W/2); tile (ty,tx)
  * reads input rows 2ty-1 .. 2ty+2, columns 2tx-1 .. 2tx+2 (zero outside: pad 1)
@@ -152,9 +161,40 @@ void oracle_f2_scale_filters(int64_t* Wt, int K, int C, int64_t range, int32_t* 
         }
 }
 
+/* The same steps applied to the activations, which Section 4.1 says the analysis covers as
+   well (11-bit B^T d B for int8 data) but which cannot be prepared offline: what an output
+   feature map is for the filters, a tile is for the activations.  For every tile and each of
+   its 16 X-Y locations the largest magnitude over the channels decides one factor n/2^p (none
+   if it is within the range); every channel's value there is multiplied by it, rounding half
+   up.  D [T][C][4][4] in place; tab [T][16][4] = (n,p,r,q); mx_out [T][16]. */
+void oracle_f2_scale_activations(int64_t* D, int64_t T, int C, int64_t range, int32_t* tab, int64_t* mx_out) {
+    for (int64_t t = 0; t < T; ++t)
+        for (int e = 0; e < 16; ++e) {
+            int64_t mx = 0;
+            for (int c = 0; c < C; ++c) {
+                int64_t a = llabs(D[((size_t)t * C + c) * 16 + e]);
+                if (a > mx) mx = a;
+            }
+            int32_t n, p, r, q;
+            oracle_scale_factor(mx, range, &n, &p);
+            oracle_inverse_factor(n, p, &r, &q);
+            if (n != 0)
+                for (int c = 0; c < C; ++c) {
+                    int64_t* d = D + ((size_t)t * C + c) * 16 + e;
+                    *d = oracle_scale_round(*d, n, p);
+                }
+            int32_t* tb = tab + ((size_t)t * 16 + e) * 4;
+            tb[0] = n; tb[1] = p; tb[2] = r; tb[3] = q;
+            if (mx_out) mx_out[(size_t)t * 16 + e] = mx;
+        }
+}
+
 /* Whole path.  mode 0: lossless (y equals the direct convolution); mode 1: filters scaled
    into [-range, range], the channel sums multiplied back by r/2^q (round half up) before
-   the output transform, and the final A^T M A / 4 rounded half up.
+   the output transform, and the final A^T M A / 4 rounded half up; mode 2: mode 1 with the
+   activations of every tile scaled into the same range too (oracle_f2_scale_activations); a
+   channel sum is multiplied back first by the filter's reciprocal, then by the tile's, each
+   step rounding half up.
    Returns a bit mask: 2 = a lossless A^T M A was not divisible by 4, 4 = an output did not
    fit int32; -1 when memory runs out. */
 int oracle_f2_conv2d_i16(const int16_t* x, const int16_t* g, int32_t* y, int N, int C, int H, int W,
@@ -165,12 +205,14 @@ int oracle_f2_conv2d_i16(const int16_t* x, const int16_t* g, int32_t* y, int N, 
     int32_t* tab = (int32_t*)malloc((size_t)K * 16 * 4 * sizeof(int32_t));
     int64_t* mx = (int64_t*)malloc((size_t)K * 16 * sizeof(int64_t));
     int64_t* D = (int64_t*)malloc((size_t)Timg * C * 16 * sizeof(int64_t));
+    int32_t* atab = (int32_t*)malloc((size_t)Timg * 16 * 4 * sizeof(int32_t));
     int flags = 0;
-    if (!Wt || !tab || !mx || !D) { flags = -1; goto done; }
+    if (!Wt || !tab || !mx || !D || !atab) { flags = -1; goto done; }
     oracle_f2_filter_transform_i16(g, K, C, Wt);
-    if (mode == 1) oracle_f2_scale_filters(Wt, K, C, range, tab, mx);
+    if (mode >= 1) oracle_f2_scale_filters(Wt, K, C, range, tab, mx);
     for (int n = 0; n < N; ++n) {
         oracle_f2_input_transform_i16(x + (size_t)n * C * H * W, 1, C, H, W, D);
+        if (mode == 2) oracle_f2_scale_activations(D, Timg, C, range, atab, NULL);
         #pragma omp parallel for reduction(|:flags)
         for (int64_t t = 0; t < Timg; ++t) {
             int ty = (int)(t / TW), tx = (int)(t % TW);
@@ -180,9 +222,13 @@ int oracle_f2_conv2d_i16(const int16_t* x, const int16_t* g, int32_t* y, int N, 
                     int64_t s = 0;
                     for (int c = 0; c < C; ++c)
                         s += Wt[((size_t)k * C + c) * 16 + e] * D[((size_t)t * C + c) * 16 + e];
-                    if (mode == 1) {
+                    if (mode >= 1) {
                         const int32_t* tb = tab + ((size_t)k * 16 + e) * 4;
                         if (tb[0] != 0) s = oracle_scale_round(s, tb[2], tb[3]);
+                    }
+                    if (mode == 2) {
+                        const int32_t* ta = atab + ((size_t)t * 16 + e) * 4;
+                        if (ta[0] != 0) s = oracle_scale_round(s, ta[2], ta[3]);
                     }
                     M[e / 4][e % 4] = s;
                 }
@@ -196,7 +242,7 @@ int oracle_f2_conv2d_i16(const int16_t* x, const int16_t* g, int32_t* y, int N, 
                         int64_t s = 0;
                         for (int c = 0; c < 4; ++c) s += Z[i][c] * A2T[j][c];
                         if (mode == 0 && (s & 3) != 0) flags |= 2;
-                        int64_t v = (s + (mode == 1 ? 2 : 0)) >> 2;   /* arithmetic shift */
+                        int64_t v = (s + (mode >= 1 ? 2 : 0)) >> 2;   /* arithmetic shift */
                         if (v > INT32_MAX || v < INT32_MIN) flags |= 4;
                         int h = 2 * ty + i, w = 2 * tx + j;
                         if (h < H && w < W) y[(((size_t)n * K + k) * H + h) * W + w] = (int32_t)v;
@@ -205,7 +251,7 @@ int oracle_f2_conv2d_i16(const int16_t* x, const int16_t* g, int32_t* y, int N, 
         }
     }
 done:
-    free(Wt); free(tab); free(mx); free(D);
+    free(Wt); free(tab); free(mx); free(D); free(atab);
     return flags;
 }
 

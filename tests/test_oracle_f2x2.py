@@ -171,3 +171,74 @@ def test_int9_lossless_equals_direct_and_scaling_to_the_papers_range():
         y, flags = oracle.f2_conv2d_i16(x9, g9, oracle.SCALED, rng_)
         err = np.abs(y.astype(np.int64) - want)
         assert (flags & 4) == 0 and err.mean() < 0.02 * np.abs(want).mean()
+
+
+# ---- activations scaled as well (the remark that closes Section 4.1; rule of Section 4.2 per tile) ---------------
+
+def test_activation_scaling_follows_the_rule_per_tile_and_location():
+    x, _ = wl.make_custom(2, 10, 1, 7, 6, seed=13)
+    D = oracle.f2_input_transform(x)
+    assert np.abs(D).max() <= 4 * 128                     # the 11 bits Section 4.1 states for int8 data
+    scaled, tab, mx = oracle.f2_scale_activations(D, 127)
+    assert np.array_equal(mx, np.abs(D).max(axis=1)) and np.abs(scaled).max() <= 127
+    for t in range(D.shape[0]):
+        for r in range(4):
+            for c in range(4):
+                n, p = oracle.scale_factor(int(mx[t, r, c]), 127)
+                rr, q = oracle.inverse_factor(n, p)
+                assert tuple(tab[t, r, c]) == (n, p, rr, q)
+                want = D[t, :, r, c] if n == 0 else (D[t, :, r, c] * n + (1 << (p - 1))) >> p
+                assert np.array_equal(scaled[t, :, r, c], want)
+    assert (tab[..., 0] != 0).any() and (tab[..., 0] == 0).any()
+    # a tile's operands depend on that tile alone
+    one, tab1, _ = oracle.f2_scale_activations(D[5:6], 127)
+    assert np.array_equal(one[0], scaled[5]) and np.array_equal(tab1[0], tab[5])
+
+
+def test_both_scaled_equals_filter_scaled_when_no_tile_needs_scaling():
+    """|x| <= 31 keeps |B^T d B| <= 4 * 31 within the range, so no activation factor is applied."""
+    rng = np.random.default_rng(14)
+    x = rng.integers(-31, 32, (2, 9, 6, 7)).astype(np.int8)
+    _, g = wl.make_custom(1, 9, 5, 6, 7, seed=15)
+    assert np.abs(oracle.f2_input_transform(x)).max() <= 127
+    y1, _ = oracle.f2_conv2d(x, g, oracle.SCALED, 127)
+    y2, flags = oracle.f2_conv2d(x, g, oracle.BOTH_SCALED, 127)
+    assert (flags & 4) == 0 and np.array_equal(y1, y2)
+    assert not np.array_equal(y1, oracle.direct_conv2d(x, g))       # the filters were scaled
+    # with a range nothing exceeds, both reduce to the direct convolution
+    x, g = wl.make_custom(1, 6, 3, 6, 6, seed=16)
+    y, _ = oracle.f2_conv2d(x, g, oracle.BOTH_SCALED, 1 << 20)
+    assert np.array_equal(y, oracle.direct_conv2d(x, g))
+
+
+def test_both_scaled_reverses_the_activation_factor_after_the_filter_factor():
+    """One channel, one tile: the result can be followed by hand from the two tables."""
+    x = np.zeros((1, 1, 2, 2), np.int8)
+    x[0, 0] = [[127, -128], [90, 127]]
+    g = np.full((1, 1, 3, 3), 100, np.int8)
+    D = oracle.f2_input_transform(x)
+    Wt = oracle.f2_filter_transform(g)
+    Ds, ta, _ = oracle.f2_scale_activations(D, 127)
+    Ws, tf, _ = oracle.f2_scale_filters(Wt, 127)
+    assert (ta[..., 0] != 0).any() and (tf[..., 0] != 0).any()
+    M = np.zeros((4, 4), np.int64)
+    for r in range(4):
+        for c in range(4):
+            s = int(Ws[0, 0, r, c] * Ds[0, 0, r, c])
+            for n, p, rr, q in (tf[0, r, c], ta[0, r, c]):
+                if n != 0:
+                    s = (s * int(rr) + (1 << (int(q) - 1) if q else 0)) >> int(q)
+            M[r, c] = s
+    _, _, at = oracle.f2_matrices()
+    want = ((at @ M @ at.T) + 2) >> 2
+    y, _ = oracle.f2_conv2d(x, g, oracle.BOTH_SCALED, 127)
+    assert np.array_equal(y[0, 0], want)
+
+
+def test_both_scaled_error_is_small_relative_to_signal():
+    x, g = wl.make_custom(2, 32, 8, 12, 12, act="relu", wgt="gauss", seed=9)
+    want = oracle.direct_conv2d(x, g).astype(np.int64)
+    y1, _ = oracle.f2_conv2d(x, g, oracle.SCALED, 127)
+    y2, flags = oracle.f2_conv2d(x, g, oracle.BOTH_SCALED, 127)
+    assert (flags & 4) == 0 and not np.array_equal(y1, y2)          # post-ReLU activations do get scaled
+    assert np.abs(y2.astype(np.int64) - want).mean() < 0.03 * np.abs(want).mean()
