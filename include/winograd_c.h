@@ -172,6 +172,29 @@ int winograd_f2x2_debug_filter_operands(const void* packed_dev, int K, int C, in
                                         int8_t* planes_dev, int32_t* table_dev, void* hip_stream);
 
 /*
+ * F(2x2,3x3) with the activations scaled as well.  Section 4.1 ends with the
+ * remark that the analysis of Section 4.2 carries over to the activation
+ * transform B^T d B (11 bits for int8 data) and leaves it out because it cannot
+ * be prepared offline; here it runs inside the convolution kernel.  The rule is
+ * that section's with a tile in the place of an output feature map: for each
+ * tile and each of its 16 X-Y locations the largest magnitude over the input
+ * channels decides n/2^p (4-bit n; nothing if the maximum is within +-127),
+ * every channel's value there is multiplied by it, rounding half up, and a
+ * channel sum is multiplied back first by the filter's reciprocal r/2^q, then
+ * by the tile's (each step rounds half up).  Both operands of the
+ * Winograd-domain products are then single int8 values.
+ * packed_dev: a WG_SCALED blob of winograd_f2x2_filter_transform (signed int8
+ * filters; WG_EBLOB-style mismatches leave y untouched).  x_dev, y_dev, layout,
+ * limits and error codes as for winograd_f2x2_conv2d_int8.  act_table_dev: NULL,
+ * or int32 [T][16][4] = (n, p, r, q) per tile t = (n*ceil(H/2) + ty)*ceil(W/2)
+ * + tx and location 4 row + column ((0,0,1,0) where nothing was scaled), which
+ * the kernel fills for tests (DEVICE memory, 16-byte aligned).
+ */
+int winograd_f2x2_conv2d_int8_act_scaled(const int8_t* x_dev, const void* packed_dev, int32_t* y_dev,
+                                         int N, int C, int H, int W, int K, int layout,
+                                         int32_t* act_table_dev, void* hip_stream);
+
+/*
  * Direct evaluation of the same convolution (the 144-multiplication method
  * that Section 3.4 compares against):
  *   y[n,k,h,w] = sum_{c,a,b} x[n,c,h+a-1,w+b-1] * g[k,c,a,b],  x = 0 outside.

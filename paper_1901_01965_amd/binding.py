@@ -58,6 +58,7 @@ def load_library():
         "winograd_f2x2_debug_filter_operands": (i, [vp, i, i, i, vp, vp, vp]),
         "winograd_f2x2_filter_transform_u8": (i, [vp, i, i, i, i, i, vp, sz, vp]),
         "winograd_f2x2_conv2d_u8": (i, [vp, i, vp, vp, i, i, i, i, i, i, i, vp]),
+        "winograd_f2x2_conv2d_int8_act_scaled": (i, [vp, vp, vp, i, i, i, i, i, i, vp, vp]),
         "winograd_conv2d_int8_stage_times": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp, sz, vp, i, vp]),
         "direct_conv2d_int8": (i, [vp, vp, vp, i, i, i, i, i, i, vp]),
         "requant_relu_pool_int8": (i, [vp, vp, i, i, i, i, i, i, i, i, vp]),
@@ -82,6 +83,7 @@ EXPORTED_SYMBOLS = (
     "winograd_debug_input_operands", "winograd_debug_filter_operands", "winograd_debug_contraction",
     "winograd_f2x2_packed_filter_bytes", "winograd_f2x2_filter_transform", "winograd_f2x2_conv2d_int8",
     "winograd_f2x2_debug_filter_operands", "winograd_f2x2_filter_transform_u8", "winograd_f2x2_conv2d_u8",
+    "winograd_f2x2_conv2d_int8_act_scaled",
 )
 
 
@@ -338,6 +340,25 @@ def f2x2_conv2d_int8(x, packed, layout=NCHW, out=None, zero_point=None):
         _check(load_library().winograd_f2x2_conv2d_u8(_ptr(x), int(zero_point), _ptr(packed.blob), _ptr(out), N, C, H, W, K,
                                                       layout, packed.mode, _stream()), "winograd_f2x2_conv2d_u8")
     return out
+
+
+def f2x2_conv2d_int8_act_scaled(x, packed, layout=NCHW, out=None, want_table=False):
+    """F(2x2,3x3) with the activations of every tile scaled into +-127 as well; packed: a SCALED blob of signed int8
+    filters.  want_table: also return the int32 [T, 16, 4] = (n, p, r, q) table the kernel derived per tile."""
+    layout = _LAYOUTS[layout]
+    _need(x, torch.int8, "x")
+    N, C, H, W = _dims(x, layout)
+    K = packed.K
+    if out is None:
+        shape = (N, K, H, W) if layout == NCHW else (N, H, W, K)
+        out = torch.empty(shape, dtype=torch.int32, device=x.device)
+    table = None
+    if want_table:
+        table = torch.empty((N * ((H + 1) // 2) * ((W + 1) // 2), 16, 4), dtype=torch.int32, device=x.device)
+    _check(load_library().winograd_f2x2_conv2d_int8_act_scaled(
+        _ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout,
+        _ptr(table) if table is not None else ctypes.c_void_p(0), _stream()), "winograd_f2x2_conv2d_int8_act_scaled")
+    return (out, table) if want_table else out
 
 
 def f2x2_debug_filter_operands(packed):

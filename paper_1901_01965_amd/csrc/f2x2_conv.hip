@@ -27,6 +27,7 @@ constexpr int kF2Filters = 64;    // filters per workgroup: four 16-wide column 
 constexpr int kF2ActPlanes = 2 * kF2Entries;
 constexpr int kF2PlaneBytes = kF2Tiles * kCBlock;            // one operand plane of the tile block in LDS
 constexpr int kF2LdsBytes = kF2ActPlanes * kF2PlaneBytes;    // 32 KB
+constexpr int kF2StageBytes = 24 * 1024;                     // the output staging's share of it
 
 // ---- filter transform -----------------------------------------------------------------------
 // W = G' g G'^T in the row-major order of the matrix printed in Section 4.1.
@@ -217,10 +218,10 @@ __device__ inline void f2_bt_rule(Quad v0, Quad v1, Quad v2, Quad v3, Quad t[4])
     t[3] = v1 - v3;
 }
 
-// D = B^T d B of one patch (four channels); entry e = 4 r + c goes to planes 2e (high limb) and
-// 2e + 1 (low limb).  A constant patch transforms to zero everywhere except entry (1,1), where
-// the four +1 coefficients add up: the bias leaves 4 * bias there and is removed by one subtraction.
-__device__ inline void f2_transform_patch(const uint32_t u[4][4], int entry11, int8_t* lds_piece) {
+// D = B^T d B of one patch (four channels), entry e = 4 r + c.  A constant patch transforms to
+// zero everywhere except entry (1,1), where the four +1 coefficients add up: the bias leaves
+// 4 * bias there and is removed by one subtraction.
+__device__ inline void f2_patch_entries(const uint32_t u[4][4], int entry11, Quad d[kF2Entries]) {
     Quad col[4][4];   // col[b][r]: row r of B^T d, column b
 #pragma unroll
     for (int b = 0; b < 4; ++b)
@@ -228,16 +229,20 @@ __device__ inline void f2_transform_patch(const uint32_t u[4][4], int entry11, i
     const s16x2 bias11 = {(short)entry11, (short)entry11};
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        Quad d[4];
-        f2_bt_rule(col[0][r], col[1][r], col[2][r], col[3][r], d);
-        if (r == 1) d[1] = Quad{d[1].a - bias11, d[1].b - bias11};
+        f2_bt_rule(col[0][r], col[1][r], col[2][r], col[3][r], d + 4 * r);
+        if (r == 1) d[5] = Quad{d[5].a - bias11, d[5].b - bias11};
+    }
+}
+
+// Entry e as two limbs: planes 2e (high) and 2e + 1 (low).
+__device__ inline void f2_transform_patch(const uint32_t u[4][4], int entry11, int8_t* lds_piece) {
+    Quad d[kF2Entries];
+    f2_patch_entries(u, entry11, d);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int e = 4 * r + c;
-            const Quad hi = Quad{d[c].a >> 6, d[c].b >> 6};
-            *reinterpret_cast<uint32_t*>(lds_piece + (2 * e) * kF2PlaneBytes) = pack_low_bytes(hi);
-            *reinterpret_cast<uint32_t*>(lds_piece + (2 * e + 1) * kF2PlaneBytes) = pack_low_bytes(d[c]) & 0x3f3f3f3fu;
-        }
+    for (int e = 0; e < kF2Entries; ++e) {
+        const Quad hi = Quad{d[e].a >> 6, d[e].b >> 6};
+        *reinterpret_cast<uint32_t*>(lds_piece + (2 * e) * kF2PlaneBytes) = pack_low_bytes(hi);
+        *reinterpret_cast<uint32_t*>(lds_piece + (2 * e + 1) * kF2PlaneBytes) = pack_low_bytes(d[e]) & 0x3f3f3f3fu;
     }
 }
 
@@ -250,6 +255,89 @@ __device__ inline void f2_static_for(F&& f) {
     f2_static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
+// With eight or more filter blocks, workgroups are dealt to the eight XCDs (round-robin in
+// launch order) so that all tile blocks of a filter block share one L2.
+__device__ inline void f2_block_coordinates(int& bx, int& by) {
+    bx = blockIdx.x;
+    by = blockIdx.y;
+    const int total = gridDim.x * gridDim.y;
+    if (gridDim.y >= 8 && (total & 7) == 0) {
+        const int launch = blockIdx.y * gridDim.x + blockIdx.x;
+        const int w = (launch & 7) * (total >> 3) + (launch >> 3);
+        by = w / (int)gridDim.x;
+        bx = w - by * (int)gridDim.x;
+    }
+}
+
+// Where a workgroup's tiles and filters sit, as every phase of the kernels below needs it.
+struct F2Block {
+    int tid, lane, wave;
+    int tile0, kbase, k;          // first tile, first filter, this lane's filter (< Kp)
+    int my_n, my_ty, my_tx;       // coordinates of tile tile0 + (lane & 15)
+};
+
+// Y = A^T M A with A^T = [1 1 1 0; 0 1 -1 -1]: rows first, then columns; the rescale by 2^-2
+// undoes G' = 2G on both sides (rnd = 0: exact, lossless mode; rnd = 2: round half up).  Register
+// q of m[e] belongs to tile 4 (lane / 16) + q and filter k.  The operand planes in LDS must be
+// dead for all waves' products when this is called (it synchronises before it overwrites them).
+template <int LAYOUT>
+__device__ __forceinline__ void f2_output_transform_store(const v4i (&m)[kF2Entries], int rnd, const F2Block& b,
+                                                          const Problem& p, int8_t* lds, int32_t* __restrict__ y) {
+    const int lane = b.lane;
+    v4i z[2][4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        z[0][c] = m[c] + m[4 + c] + m[8 + c];
+        z[1][c] = m[4 + c] - m[8 + c] - m[12 + c];
+    }
+    v4i out[4];   // output pixel 2 i + j
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        out[2 * i + 0] = (z[i][0] + z[i][1] + z[i][2] + rnd) >> 2;
+        out[2 * i + 1] = (z[i][1] - z[i][2] - z[i][3] + rnd) >> 2;
+    }
+    if (LAYOUT == WG_NHWC && (p.K & 3) == 0) {
+        // Channels-last with K a multiple of four: staged filter-fastest, stage[pixel][tile][68]
+        // (64 filters, rows padded to 68 dwords), then a thread stores four consecutive filters
+        // and sixteen lanes cover the 256 contiguous bytes this block owns of a pixel.
+        constexpr int kRow = 68;
+        static_assert(4 * 16 * kRow * 4 <= kF2StageBytes, "staging fits its share of the LDS");
+        __syncthreads();   // the operand planes are dead
+        int* stage = reinterpret_cast<int*>(lds);
+#pragma unroll
+        for (int o = 0; o < 4; ++o)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) stage[(o * 16 + 4 * (lane >> 4) + q) * kRow + b.wave * 16 + (lane & 15)] = out[o][q];
+        __syncthreads();
+        const int k4 = b.tid & 15, tile = b.tid >> 4;   // thread: filters 4 k4 .. 4 k4 + 3 of tile `tile`, all four pixels
+        const int n = __shfl(b.my_n, tile), ty = __shfl(b.my_ty, tile), tx = __shfl(b.my_tx, tile);
+        const int kk = b.kbase + 4 * k4;
+        if (b.tile0 + tile < p.T && kk < p.K) {
+#pragma unroll
+            for (int o = 0; o < 4; ++o) {
+                const int h = 2 * ty + (o >> 1), w = 2 * tx + (o & 1);
+                if (h < p.H && w < p.W)
+                    *reinterpret_cast<v4i*>(y + (((size_t)n * p.H + h) * p.W + w) * p.K + kk) =
+                        *reinterpret_cast<const v4i*>(stage + (o * 16 + tile) * kRow + 4 * k4);
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int tl = 4 * (lane >> 4) + q;
+        const int n = __shfl(b.my_n, tl), ty = __shfl(b.my_ty, tl), tx = __shfl(b.my_tx, tl);   // all lanes take part
+        if (b.tile0 + tl >= p.T || b.k >= p.K) continue;
+#pragma unroll
+        for (int o = 0; o < 4; ++o) {
+            const int h = 2 * ty + (o >> 1), w = 2 * tx + (o & 1);
+            if (h >= p.H || w >= p.W) continue;
+            if (LAYOUT == WG_NHWC) y[(((size_t)n * p.H + h) * p.W + w) * p.K + b.k] = out[o][q];
+            else                   y[(((size_t)n * p.K + b.k) * p.H + h) * p.W + w] = out[o][q];
+        }
+    }
+}
+
 // grid: (ceil(T/16), Kp/64), 256 threads.  Transform phase: thread = (tile, four channels).
 // Product phase: wave w owns filter block w (16 filters) of the 16 tiles for all 16 entries; the
 // activation and filter fragments of entry e + 2 are requested while entry e multiplies.
@@ -259,18 +347,8 @@ __global__ __launch_bounds__(256) void f2_conv_kernel(const int8_t* __restrict__
                                                       Problem p, ActivationBias ab) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // With eight or more filter blocks, workgroups are dealt to the eight XCDs (round-robin in
-    // launch order) so that all tile blocks of a filter block share one L2.
-    int bx = blockIdx.x, by = blockIdx.y;
-    {
-        const int total = gridDim.x * gridDim.y;
-        if (gridDim.y >= 8 && (total & 7) == 0) {
-            const int launch = blockIdx.y * gridDim.x + blockIdx.x;
-            const int w = (launch & 7) * (total >> 3) + (launch >> 3);
-            by = w / (int)gridDim.x;
-            bx = w - by * (int)gridDim.x;
-        }
-    }
+    int bx, by;
+    f2_block_coordinates(bx, by);
     const int tile0 = bx * kF2Tiles;
     const int kbase = by * kF2Filters;
     const int k = kbase + wave * 16 + (lane & 15);   // this lane's filter (< Kp)
@@ -357,63 +435,193 @@ __global__ __launch_bounds__(256) void f2_conv_kernel(const int8_t* __restrict__
             for (int q = 0; q < 4; ++q) m[e][q] = unscale(m[e][q]);
         }
     }
-    // Y = A^T M A with A^T = [1 1 1 0; 0 1 -1 -1]: rows first, then columns; the rescale by 2^-2
-    // undoes G' = 2G on both sides (exact in lossless mode, round half up in scaled mode).
-    v4i z[2][4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        z[0][c] = m[c] + m[4 + c] + m[8 + c];
-        z[1][c] = m[4 + c] - m[8 + c] - m[12 + c];
-    }
-    const int rnd = MODE == WG_SCALED ? 2 : 0;
-    v4i out[4];   // output pixel 2 i + j
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        out[2 * i + 0] = (z[i][0] + z[i][1] + z[i][2] + rnd) >> 2;
-        out[2 * i + 1] = (z[i][1] - z[i][2] - z[i][3] + rnd) >> 2;
-    }
-    // register q of a lane: tile 4 (lane / 16) + q, filter k
-    if (LAYOUT == WG_NHWC && (p.K & 3) == 0) {
-        // Channels-last with K a multiple of four: staged filter-fastest, stage[pixel][tile][68]
-        // (64 filters, rows padded to 68 dwords), then a thread stores four consecutive filters
-        // and sixteen lanes cover the 256 contiguous bytes this block owns of a pixel.
-        constexpr int kRow = 68;
-        static_assert(4 * 16 * kRow * 4 <= kF2LdsBytes, "staging fits the operand planes' LDS");
-        __syncthreads();   // the operand planes are dead
-        int* stage = reinterpret_cast<int*>(lds);
-#pragma unroll
-        for (int o = 0; o < 4; ++o)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) stage[(o * 16 + 4 * (lane >> 4) + q) * kRow + wave * 16 + (lane & 15)] = out[o][q];
-        __syncthreads();
-        const int k4 = tid & 15, tile = tid >> 4;   // thread: filters 4 k4 .. 4 k4 + 3 of tile `tile`, all four pixels
-        const int n = __shfl(my_n, tile), ty = __shfl(my_ty, tile), tx = __shfl(my_tx, tile);
-        const int kk = kbase + 4 * k4;
-        if (tile0 + tile < p.T && kk < p.K) {
-#pragma unroll
-            for (int o = 0; o < 4; ++o) {
-                const int h = 2 * ty + (o >> 1), w = 2 * tx + (o & 1);
-                if (h < p.H && w < p.W)
-                    *reinterpret_cast<v4i*>(y + (((size_t)n * p.H + h) * p.W + w) * p.K + kk) =
-                        *reinterpret_cast<const v4i*>(stage + (o * 16 + tile) * kRow + 4 * k4);
+    const F2Block blk = {tid, lane, wave, tile0, kbase, k, my_n, my_ty, my_tx};
+    f2_output_transform_store<LAYOUT>(m, MODE == WG_SCALED ? 2 : 0, blk, p, lds, y);
+}
+
+// ---- activations scaled as well -------------------------------------------------------------------
+// Section 4.1 closes with the remark that the analysis of Section 4.2 applies to B^T d B too
+// (11 bits for int8 data).  The rule here is that section's with a tile in the place of an output
+// feature map: the largest magnitude over the input channels at each of a tile's 16 X-Y locations
+// decides one factor n/2^p, every channel's value there is multiplied by it (round half up), and
+// the channel sums are multiplied back by its reciprocal r/2^q after the filter's.  Both operands
+// are then single int8 values: one matrix-core instruction per entry and channel block.
+//
+// (n, p, r, q) for every possible maximum of int8 data, one byte each (n = 0: within the range,
+// nothing applied).
+constexpr int kF2ActMax = 4 * 128;
+struct F2ActScaleTable {
+    uint32_t v[kF2ActMax + 1];
+};
+constexpr F2ActScaleTable f2_make_act_scale_table() {
+    F2ActScaleTable t = {};
+    for (int mx = 0; mx <= kF2ActMax; ++mx) {
+        uint32_t n = 0, p = 0, r = 1, q = 0;
+        if (mx > kWeightRange) {
+            const int num = kWeightRange * 128;
+            int y = 0;
+            while ((mx << (y + 1)) <= num) ++y;
+            n = (uint32_t)((num * 8) / (mx << y));
+            p = (uint32_t)(10 - y);
+            for (int qq = 7; qq >= 0; --qq) {
+                const uint32_t rr = ((2u << (p + qq)) + n) / (2 * n);
+                if (rr <= 255) { r = rr; q = (uint32_t)qq; break; }
             }
         }
-        return;
+        t.v[mx] = n | (p << 8) | (r << 16) | (q << 24);
     }
+    return t;
+}
+__device__ const F2ActScaleTable kF2ActScale = f2_make_act_scale_table();
+
+constexpr int kF2NpOff = 28 * 1024;   // LDS: packed table entries [tile][entry], read by the transform threads
+constexpr int kF2RqOff = 29 * 1024;   // the same entries [entry][tile], read by the finishing lanes
+static_assert(kF2StageBytes <= kF2NpOff && kF2RqOff + 1024 <= kF2LdsBytes, "LDS regions");
+
+// grid and roles as in f2_conv_kernel; the blob is a WG_SCALED one.  Pass 1 transforms every
+// channel block of the workgroup's 16 tiles and keeps the running maxima; the 256 threads then
+// look up one (tile, location) each; pass 2 transforms again (the patches now come from the
+// caches), scales, and multiplies.  act_table (may be null) receives int32 [T][16][4] = (n,p,r,q).
+template <int LAYOUT, bool VEC4>
+__global__ __launch_bounds__(256) void f2_conv_act_scaled_kernel(const int8_t* __restrict__ x,
+                                                                 const uint8_t* __restrict__ blob, size_t table_off,
+                                                                 size_t planes_off, int32_t* __restrict__ y,
+                                                                 int32_t* __restrict__ act_table, Problem p,
+                                                                 ActivationBias ab) {
+    extern __shared__ __attribute__((aligned(16))) int8_t lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int bx, by;
+    f2_block_coordinates(bx, by);
+    const int tile0 = bx * kF2Tiles;
+    const int kbase = by * kF2Filters;
+    const int k = kbase + wave * 16 + (lane & 15);
+    const BlobHeader* hdr = reinterpret_cast<const BlobHeader*>(blob);
+    if (!(hdr->magic == kF2BlobMagic && hdr->version == kBlobVersion && hdr->K == p.K && hdr->C == p.C &&
+          hdr->mode == WG_SCALED))
+        return;
+
+    int my_n = 0, my_ty = 0, my_tx = 0;
+    if (tile0 + (lane & 15) < p.T) decode_tile(p, tile0 + (lane & 15), my_n, my_ty, my_tx);
+    const int a_tile = tid >> 4, cq = tid & 15;
+    const int a_n = __shfl(my_n, a_tile), a_ty = __shfl(my_ty, a_tile), a_tx = __shfl(my_tx, a_tile);
+    uint32_t* np_tab = reinterpret_cast<uint32_t*>(lds + kF2NpOff);
+    uint32_t* rq_tab = reinterpret_cast<uint32_t*>(lds + kF2RqOff);
+
+    // ---- pass 1: largest magnitude per (tile, location) over all channels ------------------------
+    uint32_t u[4][4];
+    f2_load_patch<LAYOUT, VEC4>(x, p, ab, a_n, a_ty, a_tx, 4 * cq, u);
+    s16x2 mx[kF2Entries];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int tl = 4 * (lane >> 4) + q;
-        const int n = __shfl(my_n, tl), ty = __shfl(my_ty, tl), tx = __shfl(my_tx, tl);   // all lanes take part
-        if (tile0 + tl >= p.T || k >= p.K) continue;
+    for (int e = 0; e < kF2Entries; ++e) mx[e] = (s16x2){0, 0};
+    for (int cb = 0; cb < p.CB; ++cb) {
+        Quad d[kF2Entries];
+        f2_patch_entries(u, ab.entry11, d);
+        if (cb + 1 < p.CB) f2_load_patch<LAYOUT, VEC4>(x, p, ab, a_n, a_ty, a_tx, (cb + 1) * kCBlock + 4 * cq, u);
 #pragma unroll
-        for (int o = 0; o < 4; ++o) {
-            const int h = 2 * ty + (o >> 1), w = 2 * tx + (o & 1);
-            if (h >= p.H || w >= p.W) continue;
-            if (LAYOUT == WG_NHWC) y[(((size_t)n * p.H + h) * p.W + w) * p.K + k] = out[o][q];
-            else                   y[(((size_t)n * p.K + k) * p.H + h) * p.W + w] = out[o][q];
+        for (int e = 0; e < kF2Entries; ++e) {
+            const s16x2 zero = {0, 0};
+            const s16x2 ma = __builtin_elementwise_max(d[e].a, zero - d[e].a);
+            const s16x2 mb = __builtin_elementwise_max(d[e].b, zero - d[e].b);
+            mx[e] = __builtin_elementwise_max(mx[e], __builtin_elementwise_max(ma, mb));
         }
     }
+    // the first patch of pass 2 travels during the reduction
+    f2_load_patch<LAYOUT, VEC4>(x, p, ab, a_n, a_ty, a_tx, 4 * cq, u);
+    // over the sixteen threads of a tile (consecutive lanes), two locations per register
+    s16x2 pm[kF2Entries / 2];
+#pragma unroll
+    for (int j = 0; j < kF2Entries / 2; ++j) {
+        pm[j] = (s16x2){max(mx[2 * j].x, mx[2 * j].y), max(mx[2 * j + 1].x, mx[2 * j + 1].y)};
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1)
+            pm[j] = __builtin_elementwise_max(pm[j], as_s16x2((uint32_t)__shfl_xor((int)as_u32(pm[j]), off)));
+    }
+    {   // thread (tile, cq) looks up location cq of its tile
+        int mine = 0;
+#pragma unroll
+        for (int e = 0; e < kF2Entries; ++e)
+            if (cq == e) mine = (e & 1) ? pm[e / 2].y : pm[e / 2].x;
+        const uint32_t entry = kF2ActScale.v[min(mine, kF2ActMax)];
+        np_tab[a_tile * 16 + cq] = entry;
+        rq_tab[cq * 16 + a_tile] = entry;
+        if (act_table != nullptr && by == 0 && tile0 + a_tile < p.T)
+            *reinterpret_cast<v4i*>(act_table + ((size_t)(tile0 + a_tile) * kF2Entries + cq) * 4) =
+                (v4i){(int)(entry & 255u), (int)((entry >> 8) & 255u), (int)((entry >> 16) & 255u), (int)(entry >> 24)};
+    }
+    __syncthreads();
+    s16x2 mul[kF2Entries], shift[kF2Entries], half[kF2Entries];
+#pragma unroll
+    for (int e = 0; e < kF2Entries; ++e) {
+        const uint32_t t = np_tab[a_tile * 16 + e];
+        const short n = (short)max((int)(t & 255u), 1), sh = (short)((t >> 8) & 255u);
+        const short h = (short)((1 << sh) >> 1);
+        mul[e] = (s16x2){n, n};
+        shift[e] = (s16x2){sh, sh};
+        half[e] = (s16x2){h, h};
+    }
+
+    // ---- pass 2: scaled operands, products ----------------------------------------------------------
+    v4i acc[kF2Entries];
+#pragma unroll
+    for (int e = 0; e < kF2Entries; ++e) acc[e] = (v4i){0, 0, 0, 0};
+    int8_t* put = lds + f2_lds_slot(cq >> 2, a_tile) * 16 + (cq & 3) * 4;
+    const int8_t* a_lds = lds + f2_lds_slot(lane >> 4, lane & 15) * 16;
+    const int8_t* b_lane = reinterpret_cast<const int8_t*>(blob + planes_off) +
+                           filter_plane_offset(0, 0, k, (lane >> 4) * 16, p.Kp, kF2Entries);
+    const size_t b_block_stride = (size_t)(p.Kp >> 4) * kF2Entries * kFilterFragBytes;
+    for (int cb = 0; cb < p.CB; ++cb) {
+        if (cb > 0) __syncthreads();   // the previous block's operand planes have been consumed
+        {
+            Quad d[kF2Entries];
+            f2_patch_entries(u, ab.entry11, d);
+#pragma unroll
+            for (int e = 0; e < kF2Entries; ++e) {
+                const Quad v = Quad{(d[e].a * mul[e] + half[e]) >> shift[e], (d[e].b * mul[e] + half[e]) >> shift[e]};
+                *reinterpret_cast<uint32_t*>(put + e * kF2PlaneBytes) = pack_low_bytes(v);
+            }
+        }
+        if (cb + 1 < p.CB) f2_load_patch<LAYOUT, VEC4>(x, p, ab, a_n, a_ty, a_tx, (cb + 1) * kCBlock + 4 * cq, u);
+        const int8_t* b_cb = b_lane + cb * b_block_stride;
+        v4i bf[3], af[3];
+        auto request_b = [&](auto E) {
+            constexpr int e = E;
+            bf[e % 3] = *reinterpret_cast<const v4i*>(b_cb + e * kFilterFragBytes);
+        };
+        auto request_a = [&](auto E) {
+            constexpr int e = E;
+            af[e % 3] = *reinterpret_cast<const v4i*>(a_lds + e * kF2PlaneBytes);
+        };
+        request_b(std::integral_constant<int, 0>{});
+        request_b(std::integral_constant<int, 1>{});
+        __syncthreads();               // the operand planes are complete
+        request_a(std::integral_constant<int, 0>{});
+        request_a(std::integral_constant<int, 1>{});
+        f2_static_for<kF2Entries>([&](auto E) {
+            constexpr int e = E;
+            if constexpr (e + 2 < kF2Entries) {
+                request_b(std::integral_constant<int, e + 2>{});
+                request_a(std::integral_constant<int, e + 2>{});
+            }
+            acc[e] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[e % 3], bf[e % 3], acc[e], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    }
+
+    // ---- undo the filter's factor, then the tile's; output transform ---------------------------------
+#pragma unroll
+    for (int e = 0; e < kF2Entries; ++e) {
+        const ReverseScale filter_side(reinterpret_cast<const ScaleEntry*>(blob + table_off)[(size_t)k * kF2Entries + e]);
+        const v4i rq = *reinterpret_cast<const v4i*>(rq_tab + e * 16 + 4 * (lane >> 4));
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const ReverseScale tile_side((int)(((uint32_t)rq[q] >> 16) & 255u), (int)((uint32_t)rq[q] >> 24));
+            acc[e][q] = tile_side(filter_side(acc[e][q]));
+        }
+    }
+    const F2Block blk = {tid, lane, wave, tile0, kbase, k, my_n, my_ty, my_tx};
+    f2_output_transform_store<LAYOUT>(acc, 2, blk, p, lds, y);
 }
+
 
 template <int LAYOUT, bool VEC4, int MODE>
 hipError_t launch(const int8_t* x, const uint8_t* blob, const F2BlobLayout& bl, int32_t* y, const Problem& p,
@@ -435,6 +643,22 @@ hipError_t launch_mode(const int8_t* x, const uint8_t* blob, const F2BlobLayout&
                        const ActivationBias& ab, hipStream_t s) {
     return mode == WG_LOSSLESS ? launch<LAYOUT, VEC4, WG_LOSSLESS>(x, blob, bl, y, p, ab, s)
                                : launch<LAYOUT, VEC4, WG_SCALED>(x, blob, bl, y, p, ab, s);
+}
+
+template <int LAYOUT, bool VEC4>
+hipError_t launch_act_scaled(const int8_t* x, const uint8_t* blob, const F2BlobLayout& bl, int32_t* y, int32_t* act_table,
+                             const Problem& p, const ActivationBias& ab, hipStream_t s) {
+    static bool configured = false;   // per template instance
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&f2_conv_act_scaled_kernel<LAYOUT, VEC4>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kF2LdsBytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    dim3 grid(ceil_div(p.T, kF2Tiles), p.Kp / kF2Filters);
+    f2_conv_act_scaled_kernel<LAYOUT, VEC4><<<grid, 256, kF2LdsBytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, act_table,
+                                                                          p, ab);
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -480,6 +704,17 @@ hipError_t launch_f2_conv(const int8_t* x, int is_unsigned, int zero_point, cons
         return launch_mode<WG_NHWC, true>(x, b, bl, y, p, mode, ab, s);
     if (layout == WG_NHWC) return launch_mode<WG_NHWC, false>(x, b, bl, y, p, mode, ab, s);
     return launch_mode<WG_NCHW, false>(x, b, bl, y, p, mode, ab, s);
+}
+
+hipError_t launch_f2_conv_act_scaled(const int8_t* x, const void* blob, int32_t* y, int32_t* act_table, const Problem& p,
+                                     int layout, hipStream_t s) {
+    const ActivationBias ab = {0x80808080u, 128u * 0x01010101u, 4 * 128};
+    const F2BlobLayout bl = f2_blob_layout(p.Kp, p.C, WG_SCALED);
+    const uint8_t* b = static_cast<const uint8_t*>(blob);
+    if (layout == WG_NHWC && p.C % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 4 == 0)
+        return launch_act_scaled<WG_NHWC, true>(x, b, bl, y, act_table, p, ab, s);
+    if (layout == WG_NHWC) return launch_act_scaled<WG_NHWC, false>(x, b, bl, y, act_table, p, ab, s);
+    return launch_act_scaled<WG_NCHW, false>(x, b, bl, y, act_table, p, ab, s);
 }
 
 }  // namespace wg

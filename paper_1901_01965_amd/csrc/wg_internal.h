@@ -114,6 +114,7 @@ struct ReverseScale {
     int r, q, mask, rnd;
     __device__ inline explicit ReverseScale(const ScaleEntry& se)
         : r(se.r), q(se.q), mask((1 << se.q) - 1), rnd(se.q > 0 ? 1 << (se.q - 1) : 0) {}
+    __device__ inline ReverseScale(int r_, int q_) : r(r_), q(q_), mask((1 << q_) - 1), rnd(q_ > 0 ? 1 << (q_ - 1) : 0) {}
     __device__ inline int operator()(int m) const { return (m >> q) * r + ((__mul24(m & mask, r) + rnd) >> q); }
 };
 
@@ -174,6 +175,8 @@ hipError_t launch_f2_filter_transform(const int8_t* w, int is_unsigned, int zero
                                       void* blob, hipStream_t s);
 hipError_t launch_f2_unpack_filter_planes(const void* blob, int8_t* dense, int32_t* table, int K, int C, int mode,
                                           hipStream_t s);
+hipError_t launch_f2_conv_act_scaled(const int8_t* x, const void* blob, int32_t* y, int32_t* act_table, const Problem& p,
+                                     int layout, hipStream_t s);
 hipError_t launch_f2_conv(const int8_t* x, int is_unsigned, int zero_point, const void* blob, int32_t* y, const Problem& p,
                           int layout, int mode, hipStream_t s);
 

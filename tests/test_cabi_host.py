@@ -147,6 +147,12 @@ def test_validation_errors_return_before_any_launch(lib):
     assert f2tu(None, 3, 4, 4, 0, 0, good2, f2_bytes, None) == EINVAL
     assert f2cu(good, 300, good2, good3, 1, 4, 8, 8, 4, 0, 0, None) == EINVAL
     assert f2cu(good, 3, good2, None, 1, 4, 8, 8, 4, 0, 0, None) == EINVAL
+    f2a = lib.winograd_f2x2_conv2d_int8_act_scaled
+    assert f2a(good, good2, None, 1, 4, 8, 8, 4, 0, None, None) == EINVAL
+    assert f2a(good, None, good3, 1, 4, 8, 8, 4, 0, None, None) == EINVAL
+    assert f2a(good, good2, good3, 1, 4, 8, 8, 4, 9, None, None) == EINVAL       # unknown layout
+    assert f2a(good, good2, good3, 1, 4, 8, 8, 4, 0, odd, None) == EINVAL        # misaligned table export
+    assert f2a(good, good2, good3, 1, 1000, 8, 8, 4, 0, None, None) == EUNSUPPORTED
 
     st = lib.winograd_conv2d_int8_stage_times
     assert st(good, good2, good3, 1, 4, 8, 8, 4, 0, 0, p(0x40000), ws_bytes, None, 0, good) == EINVAL

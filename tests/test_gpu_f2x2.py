@@ -189,3 +189,72 @@ def test_blobs_of_both_filter_transforms_serve_both_convolutions():
     assert np.array_equal(y.cpu().numpy(), oracle.direct_conv2d_i16(x8.astype(np.int16), g9))
     y = wg.f2x2_conv2d_int8(_dev(xq), p8, wg.NCHW, zero_point=100)
     assert np.array_equal(y.cpu().numpy(), oracle.direct_conv2d_i16(x9, g8.astype(np.int16)))
+
+
+# ---- activations scaled per tile as well (the remark that closes Section 4.1) ---------------------------------
+
+def _oracle_act_table(x):
+    """[T, 16, 4] in the library's convention ("no scaling" stored as (0, 0, 1, 0))."""
+    _, tab, _ = oracle.f2_scale_activations(oracle.f2_input_transform(x), 127)
+    tab = tab.reshape(-1, 16, 4).copy()
+    tab[tab[..., 0] == 0] = (0, 0, 1, 0)
+    return tab
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("act", ["uniform", "relu"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_both_sides_scaled_equals_oracle(shape, act, layout):
+    N, C, K, H, W = shape
+    x, g = wl.make_custom(N, C, K, H, W, act=act, wgt="gauss", seed=75)
+    want, flags = oracle.f2_conv2d(x, g, oracle.BOTH_SCALED, 127)
+    assert (flags & 4) == 0
+    packed = wg.f2x2_filter_transform(_g(g, layout), layout, wg.SCALED)
+    y, table = wg.f2x2_conv2d_int8_act_scaled(_x(x, layout), packed, layout, want_table=True)
+    assert np.array_equal(table.cpu().numpy(), _oracle_act_table(x))
+    assert np.array_equal(_y(y, layout), want)
+    y2 = wg.f2x2_conv2d_int8_act_scaled(_x(x, layout), packed, layout)          # without the table export
+    assert torch.equal(y, y2)
+
+
+def test_both_sides_scaled_extremes_and_small_activations():
+    """All-extreme activations at the largest channel count (every tile location at its largest magnitude), and
+    activations small enough that no tile is scaled (the result is then the filter-scaled one)."""
+    C = wg.MAX_CHANNELS
+    for xv in (-128, 127):
+        x = np.full((1, C, 5, 6), xv, np.int8)
+        _, g = wl.make_custom(1, C, 3, 5, 6, wgt="uniform", seed=76)
+        g[1] = 127
+        want, flags = oracle.f2_conv2d(x, g, oracle.BOTH_SCALED, 127)
+        assert (flags & 4) == 0
+        packed = wg.f2x2_filter_transform(_g(g, wg.NHWC), wg.NHWC, wg.SCALED)
+        y, table = wg.f2x2_conv2d_int8_act_scaled(_x(x, wg.NHWC), packed, wg.NHWC, want_table=True)
+        assert np.array_equal(table.cpu().numpy(), _oracle_act_table(x))
+        assert np.array_equal(_y(y, wg.NHWC), want)
+    x = np.random.default_rng(77).integers(-31, 32, (2, 40, 9, 7)).astype(np.int8)
+    _, g = wl.make_custom(2, 40, 24, 9, 7, wgt="gauss", seed=78)
+    packed = wg.f2x2_filter_transform(_g(g, wg.NCHW), wg.NCHW, wg.SCALED)
+    y, table = wg.f2x2_conv2d_int8_act_scaled(_dev(x), packed, wg.NCHW, want_table=True)
+    assert bool((table[..., 0] == 0).all())
+    assert torch.equal(y, wg.f2x2_conv2d_int8(_dev(x), packed, wg.NCHW))
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg4a", "cfg4b"])
+def test_full_size_both_sides_scaled(name):
+    """Benchmark configurations at full size in the launch configuration bench.py times; the oracle checks the first
+    image and the last two."""
+    x, g = wl.make_case(name)
+    xd, gd = _x(x, wg.NHWC), _g(g, wg.NHWC)
+    y = _y(wg.f2x2_conv2d_int8_act_scaled(xd, wg.f2x2_filter_transform(gd, wg.NHWC, wg.SCALED), wg.NHWC), wg.NHWC)
+    for sl in (slice(0, 1), slice(x.shape[0] - 2, x.shape[0])):
+        want, flags = oracle.f2_conv2d(x[sl], g, oracle.BOTH_SCALED, 127)
+        assert (flags & 4) == 0
+        assert np.array_equal(y[sl], want)
+
+
+def test_act_scaled_rejects_a_lossless_blob():
+    x, g = wl.make_custom(1, 8, 8, 6, 6, seed=79)
+    packed = wg.f2x2_filter_transform(_g(g, wg.NHWC), wg.NHWC, wg.LOSSLESS)
+    out = torch.full((1, 6, 6, 8), 1234567, dtype=torch.int32, device="cuda")
+    wg.f2x2_conv2d_int8_act_scaled(_x(x, wg.NHWC), packed, wg.NHWC, out=out)
+    assert bool((out == 1234567).all())
