@@ -204,6 +204,7 @@ def run_f2x2(args):
         case = dataclasses.replace(case, name="%s@N=%d" % (case.name, args.batch), N=args.batch)
     layout = wg.NHWC if args.layout == "nhwc" else wg.NCHW
     mode = wg.LOSSLESS if args.mode == "lossless" else wg.SCALED
+    both = args.mode == "both-scaled"
     x_np, g_np = wl.make_case(case)
     xd = torch.from_numpy(wl.to_nhwc(x_np) if layout == wg.NHWC else x_np).to(dev)
     gd = torch.from_numpy(wl.to_krsc(g_np) if layout == wg.NHWC else g_np).to(dev)
@@ -212,7 +213,10 @@ def run_f2x2(args):
     packed = wg.f2x2_filter_transform(gd, layout, mode)
 
     def step():
-        wg.f2x2_conv2d_int8(xd, packed, layout, out=y)
+        if both:
+            wg.f2x2_conv2d_int8_act_scaled(xd, packed, layout, out=y)
+        else:
+            wg.f2x2_conv2d_int8(xd, packed, layout, out=y)
 
     for _ in range(args.warmup):
         step()
@@ -232,7 +236,8 @@ def run_f2x2(args):
     yd = wg.direct_conv2d_int8(xd, gd, layout)
     tiles2 = case.N * ((case.H + 1) // 2) * ((case.W + 1) // 2)
     alg = 4 * tiles2 * case.C + (32 if mode == wg.LOSSLESS else 16) * case.K * case.C + 16 * tiles2 * case.K
-    mfma_ops = 2 * (64 if mode == wg.LOSSLESS else 32) * tiles2 * case.C * case.K   # int8 limb products per tile and channel pair
+    # int8 products per tile and channel pair: two limbs on both sides, on the activations only, on neither
+    mfma_ops = 2 * (64 if mode == wg.LOSSLESS else 16 if both else 32) * tiles2 * case.C * case.K
     print(json.dumps({
         "metric": "direct-equivalent int8 conv TOPS, %s, 1 GPU, F(2x2,3x3)" % args.case,
         "value": round(case.direct_ops / (ms * 1e-3) / 1e12, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
@@ -256,7 +261,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--case", default="cfg2", help="workload (default: the 56x56x64 layer the metric is quoted on)")
-    ap.add_argument("--mode", default="lossless", choices=("lossless", "scaled"))
+    ap.add_argument("--mode", default="lossless", choices=("lossless", "scaled", "both-scaled"),
+                    help="both-scaled (filters and activations scaled): --algorithm f2x2 only")
     ap.add_argument("--layout", default="nhwc", choices=("nhwc", "nchw"))
     ap.add_argument("--batch", type=int, default=None,
                     help="override the workload's batch size N (batch sweeps; the default is the quoted configuration)")
@@ -276,6 +282,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (the path has no cross-GPU step); use --gpus 1")
+    if args.mode == "both-scaled" and (args.stack or args.algorithm != "f2x2"):
+        sys.exit("bench.py: --mode both-scaled exists for --algorithm f2x2 only")
     if args.stack:
         return run_stack(args)
     if args.algorithm == "f2x2":

@@ -161,11 +161,12 @@ struct ActivationBias {
 };
 
 // The 4x4 input patch of one tile (rows 2ty-1 .. 2ty+2, columns 2tx-1 .. 2tx+2), four
-// consecutive channels per pixel packed into a dword, biased; pixels outside the image and
-// channels beyond C hold the bias itself (x = 0).  Addresses are clamped into the image, so no
-// load sits behind a branch.
+// consecutive channels per pixel packed into a dword.  Addresses are clamped into the image, so no
+// load sits behind a branch, and nothing here uses the loaded data (with 4-byte loads): the
+// requests travel until f2_bias_patch() turns them into biased values, where pixels outside the
+// image and channels beyond C become the bias itself (x = 0).
 template <int LAYOUT, bool VEC4>
-__device__ inline void f2_load_patch(const int8_t* __restrict__ x, const Problem& p, const ActivationBias& ab, int n, int ty,
+__device__ inline void f2_request_patch(const int8_t* __restrict__ x, const Problem& p, const ActivationBias& ab, int n, int ty,
                                      int tx, int c0, uint32_t u[4][4]) {
     const int h0 = 2 * ty - 1, w0 = 2 * tx - 1;
     const uint32_t pixel_stride = LAYOUT == WG_NHWC ? (uint32_t)p.C : 1u;
@@ -200,6 +201,10 @@ __device__ inline void f2_load_patch(const int8_t* __restrict__ x, const Problem
                 u[a][b] = word;
             }
     }
+}
+
+__device__ inline void f2_bias_patch(const Problem& p, const ActivationBias& ab, int ty, int tx, int c0, uint32_t u[4][4]) {
+    const int h0 = 2 * ty - 1, w0 = 2 * tx - 1;
     const bool have = c0 < p.C;
 #pragma unroll
     for (int a = 0; a < 4; ++a)
@@ -377,46 +382,52 @@ __global__ __launch_bounds__(256) void f2_conv_kernel(const int8_t* __restrict__
                            filter_plane_offset(0, 0, k, (lane >> 4) * 16, p.Kp, NP);
     const size_t b_block_stride = (size_t)(p.Kp >> 4) * NP * kFilterFragBytes;
 
+    // Workgroups that run side by side on an XCD read the same filter fragments; each starts at a
+    // channel block of its own (the integer sums do not depend on the order) so that they do not
+    // all ask the same L2 channels for the same lines at the same time.
+    int cb = bx % p.CB;
     uint32_t u[4][4];
-    f2_load_patch<LAYOUT, VEC4>(x, p, ab, a_n, a_ty, a_tx, 4 * cq, u);
-    for (int cb = 0; cb < p.CB; ++cb) {
-        if (cb > 0) __syncthreads();   // the previous block's operand planes have been consumed
-        f2_transform_patch(u, ab.entry11, put);
-        // the next channel block's patch travels while this one multiplies
-        if (cb + 1 < p.CB) f2_load_patch<LAYOUT, VEC4>(x, p, ab, a_n, a_ty, a_tx, (cb + 1) * kCBlock + 4 * cq, u);
+    f2_request_patch<LAYOUT, VEC4>(x, p, ab, a_n, a_ty, a_tx, cb * kCBlock + 4 * cq, u);
+    // filter fragments in flight: requested before the transform, they arrive under it
+    constexpr int kRing = MODE == WG_LOSSLESS ? 4 : 6;
+    for (int step = 0; step < p.CB; ++step) {
         const int8_t* b_cb = b_lane + cb * b_block_stride;
-        v4i bf[3][NBP], af[3][2];
+        v4i bf[kRing][NBP], af[3][2];
         auto request_b = [&](auto E) {
             constexpr int e = E;
 #pragma unroll
             for (int i = 0; i < NBP; ++i)
-                bf[e % 3][i] = *reinterpret_cast<const v4i*>(b_cb + (NBP * e + i) * kFilterFragBytes);
+                bf[e % kRing][i] = *reinterpret_cast<const v4i*>(b_cb + (NBP * e + i) * kFilterFragBytes);
         };
         auto request_a = [&](auto E) {
             constexpr int e = E;
             af[e % 3][0] = *reinterpret_cast<const v4i*>(a_lds + (2 * e) * kF2PlaneBytes);
             af[e % 3][1] = *reinterpret_cast<const v4i*>(a_lds + (2 * e + 1) * kF2PlaneBytes);
         };
-        request_b(std::integral_constant<int, 0>{});
-        request_b(std::integral_constant<int, 1>{});
+        f2_static_for<kRing - 1>([&](auto E) { request_b(E); });
+        __builtin_amdgcn_sched_barrier(0);
+        if (step > 0) __syncthreads();   // the previous block's operand planes have been consumed
+        f2_bias_patch(p, ab, a_ty, a_tx, cb * kCBlock + 4 * cq, u);
+        f2_transform_patch(u, ab.entry11, put);
+        cb = cb + 1 == p.CB ? 0 : cb + 1;
+        // the next channel block's patch travels while this one multiplies
+        if (step + 1 < p.CB) f2_request_patch<LAYOUT, VEC4>(x, p, ab, a_n, a_ty, a_tx, cb * kCBlock + 4 * cq, u);
         __syncthreads();               // the operand planes are complete
         request_a(std::integral_constant<int, 0>{});
         request_a(std::integral_constant<int, 1>{});
         f2_static_for<kF2Entries>([&](auto E) {
             constexpr int e = E;
-            if constexpr (e + 2 < kF2Entries) {
-                request_b(std::integral_constant<int, e + 2>{});
-                request_a(std::integral_constant<int, e + 2>{});
-            }
+            if constexpr (e + kRing - 1 < kF2Entries) request_b(std::integral_constant<int, e + kRing - 1>{});
+            if constexpr (e + 2 < kF2Entries) request_a(std::integral_constant<int, e + 2>{});
             const v4i ah = af[e % 3][0], al = af[e % 3][1];
             if constexpr (MODE == WG_LOSSLESS) {
-                acc[e][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ah, bf[e % 3][0], acc[e][0], 0, 0, 0);
-                acc[e][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ah, bf[e % 3][1], acc[e][1], 0, 0, 0);
-                acc[e][2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(al, bf[e % 3][1], acc[e][2], 0, 0, 0);
-                acc[e][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(al, bf[e % 3][0], acc[e][1], 0, 0, 0);
+                acc[e][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ah, bf[e % kRing][0], acc[e][0], 0, 0, 0);
+                acc[e][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ah, bf[e % kRing][1], acc[e][1], 0, 0, 0);
+                acc[e][2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(al, bf[e % kRing][1], acc[e][2], 0, 0, 0);
+                acc[e][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(al, bf[e % kRing][0], acc[e][1], 0, 0, 0);
             } else {
-                acc[e][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ah, bf[e % 3][0], acc[e][0], 0, 0, 0);
-                acc[e][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(al, bf[e % 3][0], acc[e][1], 0, 0, 0);
+                acc[e][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ah, bf[e % kRing][0], acc[e][0], 0, 0, 0);
+                acc[e][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(al, bf[e % kRing][0], acc[e][1], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
         });
@@ -508,15 +519,19 @@ __global__ __launch_bounds__(256) void f2_conv_act_scaled_kernel(const int8_t* _
     uint32_t* rq_tab = reinterpret_cast<uint32_t*>(lds + kF2RqOff);
 
     // ---- pass 1: largest magnitude per (tile, location) over all channels ------------------------
+    const int first_cb = bx % p.CB;   // see f2_conv_kernel: neighbours start at different channel blocks
+    int cb = first_cb;
     uint32_t u[4][4];
-    f2_load_patch<LAYOUT, VEC4>(x, p, ab, a_n, a_ty, a_tx, 4 * cq, u);
+    f2_request_patch<LAYOUT, VEC4>(x, p, ab, a_n, a_ty, a_tx, cb * kCBlock + 4 * cq, u);
     s16x2 mx[kF2Entries];
 #pragma unroll
     for (int e = 0; e < kF2Entries; ++e) mx[e] = (s16x2){0, 0};
-    for (int cb = 0; cb < p.CB; ++cb) {
+    for (int step = 0; step < p.CB; ++step) {
         Quad d[kF2Entries];
+        f2_bias_patch(p, ab, a_ty, a_tx, cb * kCBlock + 4 * cq, u);
         f2_patch_entries(u, ab.entry11, d);
-        if (cb + 1 < p.CB) f2_load_patch<LAYOUT, VEC4>(x, p, ab, a_n, a_ty, a_tx, (cb + 1) * kCBlock + 4 * cq, u);
+        cb = cb + 1 == p.CB ? 0 : cb + 1;
+        if (step + 1 < p.CB) f2_request_patch<LAYOUT, VEC4>(x, p, ab, a_n, a_ty, a_tx, cb * kCBlock + 4 * cq, u);
 #pragma unroll
         for (int e = 0; e < kF2Entries; ++e) {
             const s16x2 zero = {0, 0};
@@ -526,7 +541,8 @@ __global__ __launch_bounds__(256) void f2_conv_act_scaled_kernel(const int8_t* _
         }
     }
     // the first patch of pass 2 travels during the reduction
-    f2_load_patch<LAYOUT, VEC4>(x, p, ab, a_n, a_ty, a_tx, 4 * cq, u);
+    cb = first_cb;
+    f2_request_patch<LAYOUT, VEC4>(x, p, ab, a_n, a_ty, a_tx, cb * kCBlock + 4 * cq, u);
     // over the sixteen threads of a tile (consecutive lanes), two locations per register
     s16x2 pm[kF2Entries / 2];
 #pragma unroll
@@ -569,10 +585,26 @@ __global__ __launch_bounds__(256) void f2_conv_act_scaled_kernel(const int8_t* _
     const int8_t* b_lane = reinterpret_cast<const int8_t*>(blob + planes_off) +
                            filter_plane_offset(0, 0, k, (lane >> 4) * 16, p.Kp, kF2Entries);
     const size_t b_block_stride = (size_t)(p.Kp >> 4) * kF2Entries * kFilterFragBytes;
-    for (int cb = 0; cb < p.CB; ++cb) {
-        if (cb > 0) __syncthreads();   // the previous block's operand planes have been consumed
+    constexpr int kRing = 8;   // filter fragments in flight: requested before the transform, they arrive under it
+    for (int step = 0; step < p.CB; ++step) {
+        const int8_t* b_cb = b_lane + cb * b_block_stride;
+        const int c0 = cb * kCBlock + 4 * cq;
+        cb = cb + 1 == p.CB ? 0 : cb + 1;
+        v4i bf[kRing], af[3];
+        auto request_b = [&](auto E) {
+            constexpr int e = E;
+            bf[e % kRing] = *reinterpret_cast<const v4i*>(b_cb + e * kFilterFragBytes);
+        };
+        auto request_a = [&](auto E) {
+            constexpr int e = E;
+            af[e % 3] = *reinterpret_cast<const v4i*>(a_lds + e * kF2PlaneBytes);
+        };
+        f2_static_for<kRing - 1>([&](auto E) { request_b(E); });
+        __builtin_amdgcn_sched_barrier(0);
+        if (step > 0) __syncthreads();   // the previous block's operand planes have been consumed
         {
             Quad d[kF2Entries];
+            f2_bias_patch(p, ab, a_ty, a_tx, c0, u);
             f2_patch_entries(u, ab.entry11, d);
 #pragma unroll
             for (int e = 0; e < kF2Entries; ++e) {
@@ -580,29 +612,15 @@ __global__ __launch_bounds__(256) void f2_conv_act_scaled_kernel(const int8_t* _
                 *reinterpret_cast<uint32_t*>(put + e * kF2PlaneBytes) = pack_low_bytes(v);
             }
         }
-        if (cb + 1 < p.CB) f2_load_patch<LAYOUT, VEC4>(x, p, ab, a_n, a_ty, a_tx, (cb + 1) * kCBlock + 4 * cq, u);
-        const int8_t* b_cb = b_lane + cb * b_block_stride;
-        v4i bf[3], af[3];
-        auto request_b = [&](auto E) {
-            constexpr int e = E;
-            bf[e % 3] = *reinterpret_cast<const v4i*>(b_cb + e * kFilterFragBytes);
-        };
-        auto request_a = [&](auto E) {
-            constexpr int e = E;
-            af[e % 3] = *reinterpret_cast<const v4i*>(a_lds + e * kF2PlaneBytes);
-        };
-        request_b(std::integral_constant<int, 0>{});
-        request_b(std::integral_constant<int, 1>{});
+        if (step + 1 < p.CB) f2_request_patch<LAYOUT, VEC4>(x, p, ab, a_n, a_ty, a_tx, cb * kCBlock + 4 * cq, u);
         __syncthreads();               // the operand planes are complete
         request_a(std::integral_constant<int, 0>{});
         request_a(std::integral_constant<int, 1>{});
         f2_static_for<kF2Entries>([&](auto E) {
             constexpr int e = E;
-            if constexpr (e + 2 < kF2Entries) {
-                request_b(std::integral_constant<int, e + 2>{});
-                request_a(std::integral_constant<int, e + 2>{});
-            }
-            acc[e] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[e % 3], bf[e % 3], acc[e], 0, 0, 0);
+            if constexpr (e + kRing - 1 < kF2Entries) request_b(std::integral_constant<int, e + kRing - 1>{});
+            if constexpr (e + 2 < kF2Entries) request_a(std::integral_constant<int, e + 2>{});
+            acc[e] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[e % 3], bf[e % kRing], acc[e], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         });
     }
