@@ -344,8 +344,8 @@ struct ProductPhase {
                         im = join_limbs(a[6], a[7], a[8]);
                     }
                 } else {
-                    re = (a[0] << 6) + a[1];
-                    if constexpr (!is_real(sl.entry)) im = (a[2] << 6) + a[3];
+                    re = (a[0] << kByteLimbShift) + a[1];
+                    if constexpr (!is_real(sl.entry)) im = (a[2] << kByteLimbShift) + a[3];
                     const ReverseScale unscale(cx.table_k[PASS * kFusedFilters * kEntries + sl.entry]);   // Section 4.2
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
@@ -378,7 +378,7 @@ struct ScaledSums {
     static constexpr int kSums = sum_start(NE);
 
     // One channel block: each entry's limb products are formed from zero, and its value
-    // 64 * high + low joins the entry's running sum one entry later.
+    // 256 * high + low (byte limbs) joins the entry's running sum one entry later.
     template <int PASS = 0, int NPASS = 1>
     __device__ inline static void run(const LaneContext& cx, v4i (&bring)[kFilterPrefetch], v4i (&sums)[kSums]) {
         constexpr int F0 = PASS * NB, FEND = NPASS * NB;   // this pass's place in the fragment stream
@@ -407,8 +407,8 @@ struct ScaledSums {
             if constexpr (s > 0) {
                 constexpr int v = sum_start(s - 1);
                 const v4i(&a)[4] = acc[(s - 1) & 1];
-                sums[v] += (a[0] << 6) + a[1];
-                if constexpr (!is_real(half_slot(HALF, s - 1).entry)) sums[v + 1] += (a[2] << 6) + a[3];
+                sums[v] += (a[0] << kByteLimbShift) + a[1];
+                if constexpr (!is_real(half_slot(HALF, s - 1).entry)) sums[v + 1] += (a[2] << kByteLimbShift) + a[3];
             }
             __builtin_amdgcn_sched_barrier(0);
         });
@@ -696,7 +696,7 @@ __device__ __forceinline__ void fused_conv_body(const int8_t* __restrict__ x, co
     const int a_tile = tid >> 4, a_cq = tid & 15;
     const int a_t = tile0 + a_tile;
     const int a_tx = __shfl(my_tx, a_tile), a_ty = __shfl(my_ty, a_tile), a_n = __shfl(my_n, a_tile);
-    OperandSplitter<kSplitTwoLimb, LdsPlaneSink> out;
+    OperandSplitter<MODE == WG_SCALED ? kSplitByteLimbs : kSplitTwoLimb, LdsPlaneSink> out;
     out.sink.base = lds + lds_slot(a_cq >> 2, a_tile) * 16 + (a_cq & 3) * 4;
 
     LaneContext cx;
@@ -858,8 +858,8 @@ struct LeanProducts {
                 // joined values only; scaling (scaled mode) and the output transform wait for finish()
                 constexpr int v = ScaledSums<HALF>::sum_start(s);
                 if constexpr (MODE == WG_SCALED) {
-                    sums[v] += (acc[0] << 6) + acc[1];
-                    if constexpr (!is_real(entry)) sums[v + 1] += (acc[2] << 6) + acc[3];
+                    sums[v] += (acc[0] << kByteLimbShift) + acc[1];
+                    if constexpr (!is_real(entry)) sums[v + 1] += (acc[2] << kByteLimbShift) + acc[3];
                 } else if constexpr (is_real(entry)) {
                     sums[v] += join_limbs(acc[0], acc[1], acc[2]);
                 } else {
@@ -876,8 +876,8 @@ struct LeanProducts {
                         im = join_limbs(acc[6], acc[7], acc[8]);
                     }
                 } else {
-                    re = (acc[0] << 6) + acc[1];
-                    if constexpr (!is_real(entry)) im = (acc[2] << 6) + acc[3];
+                    re = (acc[0] << kByteLimbShift) + acc[1];
+                    if constexpr (!is_real(entry)) im = (acc[2] << kByteLimbShift) + acc[3];
                     const ReverseScale unscale(cx.table_k[entry]);   // Section 4.2
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
@@ -955,8 +955,8 @@ struct ResidentScaled {
         static_for<NE>([&](auto S) {
             constexpr Slot sl = half_slot(HALF, S);
             constexpr int v = acc_start(S);
-            v4i re = (acc[v] << 6) + acc[v + 1], im = {0, 0, 0, 0};
-            if constexpr (!is_real(sl.entry)) im = (acc[v + 2] << 6) + acc[v + 3];
+            v4i re = (acc[v] << kByteLimbShift) + acc[v + 1], im = {0, 0, 0, 0};
+            if constexpr (!is_real(sl.entry)) im = (acc[v + 2] << kByteLimbShift) + acc[v + 3];
             const ReverseScale unscale(cx.table_k[sl.entry]);   // Section 4.2
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -1008,7 +1008,7 @@ __global__ __launch_bounds__(512) void fused_conv_roles_kernel(const int8_t* __r
         const int a_tile = tid >> 4, a_cq = tid & 15;
         const int a_t = tile0 + a_tile;
         const int a_tx = __shfl(my_tx, a_tile), a_ty = __shfl(my_ty, a_tile), a_n = __shfl(my_n, a_tile);
-        OperandSplitter<kSplitTwoLimb, LdsPlaneSink> out;
+        OperandSplitter<MODE == WG_SCALED ? kSplitByteLimbs : kSplitTwoLimb, LdsPlaneSink> out;
         int8_t* const slot = lds + lds_slot(a_cq >> 2, a_tile) * 16 + (a_cq & 3) * 4;
         uint32_t patch[6][6];
         // 4-byte pixel loads: the 36 offsets of the patch (clamped into the image, relative to x:
@@ -1165,7 +1165,7 @@ __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __
 
     if (transforms) {
         const int a_tile = tid >> 4, a_cq = tid & 15;
-        OperandSplitter<kSplitTwoLimb, LdsPlaneSink> out;
+        OperandSplitter<MODE == WG_SCALED ? kSplitByteLimbs : kSplitTwoLimb, LdsPlaneSink> out;
         int8_t* const slot = lds + lds_slot(a_cq >> 2, a_tile) * 16 + (a_cq & 3) * 4;
         uint32_t patch[6][6], pixel[36];
         int a_t = 0, a_ty = 0, a_tx = 0;

@@ -31,6 +31,8 @@ __device__ inline Quad unpack_u8x4(uint32_t u) {
 }
 // low bytes of the four 16-bit lanes -> one dword (c0,c1,c2,c3)
 __device__ inline uint32_t pack_low_bytes(Quad v) { return __builtin_amdgcn_perm(as_u32(v.b), as_u32(v.a), 0x06040200u); }
+// their high bytes
+__device__ inline uint32_t pack_high_bytes(Quad v) { return __builtin_amdgcn_perm(as_u32(v.b), as_u32(v.a), 0x07050301u); }
 
 constexpr uint32_t kBiasBytes = 0x80808080u;
 
@@ -120,8 +122,14 @@ __device__ inline Line bt_rule(Quad v0, Quad v1, Quad v2, Quad v3, Quad v4, Quad
 //                    complex entry (the extra operand of the three-multiplication complex
 //                    product): 138 planes, the lossless staged layout;
 //   kSplitTwoLimb:   two planes per value, h and l: real entry p -> 2p, 2p+1; complex entry j
-//                    -> 32+4j + {Re h, Re l, Im h, Im l}: 72 planes.
-constexpr int kSplitKaratsuba = 0, kSplitTwoLimb = 1;
+//                    -> 32+4j + {Re h, Re l, Im h, Im l}: 72 planes;
+//   kSplitByteLimbs: the same 72 planes with v = 256 h + l, l the low byte of v read as a signed
+//                    int8 and h = (v + 128) >> 8 in [-8, 8]: both limbs are bytes of a register
+//                    already, so the split costs one addition instead of a shift and a mask.  Used
+//                    where the other operand is a single int8 (scaled mode inside one kernel): the
+//                    two limb products then simply carry the weights 256 and 1.
+constexpr int kSplitKaratsuba = 0, kSplitTwoLimb = 1, kSplitByteLimbs = 2;
+constexpr int kByteLimbShift = 8;
 
 template <int SPLIT, class Sink>
 struct OperandSplitter {
@@ -137,8 +145,14 @@ struct OperandSplitter {
         sink.put(3 * q + 2, pack_low_bytes(hi + lo));
     }
     __device__ inline void limbs(int first, Quad v) const {
-        sink.put(first, pack_low_bytes(high(v)));
-        sink.put(first + 1, pack_low_bytes(v) & 0x3f3f3f3fu);   // v & 63 on all four channels at once
+        if (SPLIT == kSplitByteLimbs) {
+            const s16x2 half = {128, 128};
+            sink.put(first, pack_high_bytes(Quad{v.a + half, v.b + half}));
+            sink.put(first + 1, pack_low_bytes(v));
+        } else {
+            sink.put(first, pack_low_bytes(high(v)));
+            sink.put(first + 1, pack_low_bytes(v) & 0x3f3f3f3fu);   // v & 63 on all four channels at once
+        }
     }
     __device__ inline void real_entry(int p, Quad v) const {
         if (SPLIT == kSplitKaratsuba) value(p, v); else limbs(2 * p, v);
