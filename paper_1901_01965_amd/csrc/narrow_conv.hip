@@ -93,8 +93,11 @@ __global__ __launch_bounds__(64) void narrow_conv_kernel(const int8_t* __restric
     }
     auto unscale = [&](int e, int m) {
         if constexpr (MODE == WG_SCALED) {
+            // at most four channels: |m| <= 4 * 2047 * 127 < 2^21, so m * r + 2^(q-1) fits 32 bits and
+            // the product is a 24-bit multiply
             const int r = (int)(rq[e] & 0xff), q = (int)(rq[e] >> 8);
-            return (m >> q) * r + ((__mul24((int)__builtin_amdgcn_ubfe((uint32_t)m, 0u, (uint32_t)q), r) + ((1 << q) >> 1)) >> q);
+            static_assert(2LL * kNarrowChannels * 2047 * 127 * 255 + 64 < (1LL << 31), "m * r + rnd fits int32");
+            return (__mul24(m, r) + ((1 << q) >> 1)) >> q;
         } else {
             return m;
         }
