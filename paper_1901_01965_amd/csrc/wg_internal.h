@@ -106,16 +106,17 @@ __host__ __device__ inline size_t filter_plane_offset(int plane, int cb, int k, 
 }
 
 // Reverse scaling of Section 4.2 for a 32-bit channel sum m: (m * r + 2^(q-1)) >> q with an
-// arithmetic shift (q = 0: m * r), r <= 255, q <= 7.  No 64-bit product is needed: with
-// m = a 2^q + b, 0 <= b < 2^q, the value is a r + ((b r + 2^(q-1)) >> q) exactly, and since the
-// result fits 32 bits, wrap-around in a r is harmless.  Entries that were not scaled carry
-// (r, q) = (1, 0), for which this returns m.
+// arithmetic shift (q = 0: m * r), r <= 255, q <= 7: one multiply-add with a 64-bit result and
+// one funnel shift that takes the 32 bits from bit q on (the result fits 32 bits).  Entries that
+// were not scaled carry (r, q) = (1, 0), for which this returns m.
 struct ReverseScale {
-    int r, q, mask, rnd;
-    __device__ inline explicit ReverseScale(const ScaleEntry& se)
-        : r(se.r), q(se.q), mask((1 << se.q) - 1), rnd(se.q > 0 ? 1 << (se.q - 1) : 0) {}
-    __device__ inline ReverseScale(int r_, int q_) : r(r_), q(q_), mask((1 << q_) - 1), rnd(q_ > 0 ? 1 << (q_ - 1) : 0) {}
-    __device__ inline int operator()(int m) const { return (m >> q) * r + ((__mul24(m & mask, r) + rnd) >> q); }
+    int r, q, rnd;
+    __device__ inline explicit ReverseScale(const ScaleEntry& se) : ReverseScale(se.r, se.q) {}
+    __device__ inline ReverseScale(int r_, int q_) : r(r_), q(q_), rnd(q_ > 0 ? 1 << (q_ - 1) : 0) {}
+    __device__ inline int operator()(int m) const {
+        const long long t = (long long)m * r + rnd;
+        return (int)__builtin_amdgcn_alignbit((uint32_t)(t >> 32), (uint32_t)t, (uint32_t)q);
+    }
 };
 
 // Layers with at most kNarrowChannels input channels (a network's first layer) are served by a
