@@ -20,6 +20,13 @@
  *     [K][3][3][C], outputs [N][H][W][K].  All dense, no strides.
  *   - 1 <= C <= WG_MAX_CHANNELS keeps every int32 accumulator exact for any
  *     int8 data (16 * 9 * C * 128 * 128 < 2^31).
+ *   - Threads and devices: launches go to the device that is current in the
+ *     calling thread.  The first call of a kernel variant sets that kernel's
+ *     shared-memory limit once per process without locking, so the first call
+ *     of each entry point should not race with another call of the same entry
+ *     point, and a process should drive one device through this library (the
+ *     build targets one GPU).  The winograd_debug_* switches are process-wide
+ *     and not thread-safe.
  */
 #ifndef WINOGRAD_C_H
 #define WINOGRAD_C_H
