@@ -22,6 +22,12 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+# Kernel arguments in device memory rather than in host memory: the waves' first scalar loads then
+# stay on the GPU.  Launches replayed from a HIP graph (the timed path) are unaffected; launches
+# made one by one (--eager) take 8.7 instead of 9.8 us per step on the default workload.  Has to be
+# in the environment before the HIP runtime starts.
+os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
+
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8
 
