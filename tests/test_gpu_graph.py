@@ -24,12 +24,15 @@ def test_graph_replays_equal_eager_results(mode):
     y = torch.empty((N, H, W, K), dtype=torch.int32, device="cuda")
     q = torch.empty((N, H // 2, W // 2, K), dtype=torch.int8, device="cuda")
     y2 = torch.empty_like(y)
+    y3 = torch.empty_like(y)
     yd = torch.empty_like(y)
 
     def work():
         wg.winograd_conv2d_int8(xd, packed, wg.NHWC, out=y, workspace=ws)
         wg.winograd_conv2d_int8_requant(xd, packed, 10, True, True, wg.NHWC, out=q)
         wg.f2x2_conv2d_int8(xd, packed2, wg.NHWC, out=y2)
+        if mode == wg.SCALED:
+            wg.f2x2_conv2d_int8_act_scaled(xd, packed2, wg.NHWC, out=y3)
         wg.direct_conv2d_int8(xd, gd, wg.NHWC, out=yd)
 
     work()
@@ -40,7 +43,7 @@ def test_graph_replays_equal_eager_results(mode):
     inputs = [x, x2, x]
     for xin in inputs:
         xd.copy_(torch.from_numpy(wl.to_nhwc(xin)).cuda())       # eager work between the replays
-        for t in (y, y2, yd):
+        for t in (y, y2, y3, yd):
             t.fill_(-7)
         q.fill_(-7)
         torch.cuda.synchronize()
@@ -55,4 +58,6 @@ def test_graph_replays_equal_eager_results(mode):
         assert np.array_equal(wl.from_nhwc(y.cpu().numpy()), want)
         assert np.array_equal(wl.from_nhwc(q.cpu().numpy()), oracle.requant_relu_pool(want, 10, True, True))
         assert np.array_equal(wl.from_nhwc(y2.cpu().numpy()), want2)
+        if mode == wg.SCALED:
+            assert np.array_equal(wl.from_nhwc(y3.cpu().numpy()), oracle.f2_conv2d(xin, g, oracle.BOTH_SCALED, 127)[0])
         assert np.array_equal(wl.from_nhwc(yd.cpu().numpy()), oracle.direct_conv2d(xin, g))
