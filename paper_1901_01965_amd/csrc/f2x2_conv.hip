@@ -345,7 +345,8 @@ __device__ __forceinline__ void f2_output_transform_store(const v4i (&m)[kF2Entr
 
 // grid: (ceil(T/16), Kp/64), 256 threads.  Transform phase: thread = (tile, four channels).
 // Product phase: wave w owns filter block w (16 filters) of the 16 tiles for all 16 entries; the
-// activation and filter fragments of entry e + 2 are requested while entry e multiplies.
+// filter fragments travel through a ring that is filled before the transform, the activation
+// fragments of entry e + 2 are read from LDS while entry e multiplies.
 template <int LAYOUT, bool VEC4, int MODE>
 __global__ __launch_bounds__(256) void f2_conv_kernel(const int8_t* __restrict__ x, const uint8_t* __restrict__ blob,
                                                       size_t table_off, size_t planes_off, int32_t* __restrict__ y,
