@@ -67,6 +67,28 @@ def test_complex_filter_transform_widens_int8_by_four_bits():
     assert round(100 * ((3.13 / 12) / (2.25 / 10) - 1), 2) == CONST["efficiency_gain_vs_rational_f2"]
 
 
+def test_rational_f4x4_needs_eighteen_bits_where_the_complex_algorithm_needs_twelve():
+    """Section 3.2: the rational F(4x4,3x3) matrix G (points 0, +-1, +-2) has the denominator 24, so exact integer
+    arithmetic needs G' = 24 G and widens an int8 filter by ceil(log2(24^2)) = 10 bits.  The oracle's worst-case routine
+    (pinned to the printed 1020/1530/2295 table) on that G' and on the complex G' = 4 G gives the two bit widths the
+    33.33 % of Section 3.4 compares."""
+    g_rat = np.real(golden_io.sections("rational_f4x4_3x3_filter_matrix.txt")["G"])
+    g24 = np.rint(24 * g_rat)
+    assert np.allclose(24 * g_rat, g24) and not np.allclose(12 * g_rat, np.rint(12 * g_rat))   # 24 is the least multiplier
+    re, im = oracle.worstcase_magnitude(g24.astype(np.complex128), 127, 128)
+    assert not im.any()
+    assert re.max() == 24 * 24 * 128 and re[5, 5] == re.max()         # the corner entry passes a tap through (24 * 1)^2
+    bits_rational = int(re.max()).bit_length() + 1                     # signed
+    corners = np.array(list(itertools.product([-128, 127], repeat=9)), np.float64).reshape(-1, 3, 3)
+    assert np.abs(np.einsum("ra,nab,sb->nrs", g24, corners, g24)).max() == re.max()   # reached by a box corner
+    _, g4, _ = oracle.matrices()
+    re_c, im_c = oracle.worstcase_magnitude(g4, 127, 128)
+    bits_complex = int(max(re_c.max(), im_c.max()) - 1).bit_length() + 1   # -2048 itself still fits 12 bits
+    assert (bits_rational, bits_complex) == (8 + int(CONST["filter_widening_bits_rational"]),
+                                             8 + int(CONST["filter_widening_bits_complex"])) == (18, 12)
+    assert round(100 * (1 - bits_complex / bits_rational), 2) == CONST["bitwidth_reduction_vs_rational"]
+
+
 def test_transformed_activations_fit_twelve_bits():
     """B^T d B of int8 data, and the real+imaginary sum the 3-mult product needs, fit 12 bits."""
     re, im = oracle.worstcase_input_magnitude(127, 128)
