@@ -177,6 +177,18 @@ int winograd_f2x2_conv2d_u8(const uint8_t* x_dev, int zero_point, const void* pa
                             int N, int C, int H, int W, int K, int layout, int mode, void* hip_stream);
 int winograd_f2x2_debug_filter_operands(const void* packed_dev, int K, int C, int mode,
                                         int8_t* planes_dev, int32_t* table_dev, void* hip_stream);
+/*
+ * winograd_f2x2_conv2d_int8 with the requantisation that follows a quantised
+ * convolution in a network (Section 4.4) applied before the store, as in
+ * winograd_conv2d_int8_requant: out = clamp((y + 2^(shift-1)) >> shift, lo, 127)
+ * with lo = 0 if relu else -128, then an optional 2x2 stride-2 maximum (pool != 0:
+ * H and W even; a 2x2 output tile is exactly one pooling window).  out_dev: int8
+ * in `layout` with K channels, [N][K][H/2][W/2] or [N][H/2][W/2][K] when pooling,
+ * every element written, 4-byte aligned.  0 <= shift <= 31.  Signed int8 inputs.
+ */
+int winograd_f2x2_conv2d_int8_requant(const int8_t* x_dev, const void* packed_dev, int8_t* out_dev,
+                                      int N, int C, int H, int W, int K, int layout, int mode,
+                                      int shift, int relu, int pool, void* hip_stream);
 
 /*
  * F(2x2,3x3) with the activations scaled as well.  Section 4.1 ends with the

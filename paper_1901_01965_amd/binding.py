@@ -59,6 +59,7 @@ def load_library():
         "winograd_f2x2_filter_transform_u8": (i, [vp, i, i, i, i, i, vp, sz, vp]),
         "winograd_f2x2_conv2d_u8": (i, [vp, i, vp, vp, i, i, i, i, i, i, i, vp]),
         "winograd_f2x2_conv2d_int8_act_scaled": (i, [vp, vp, vp, i, i, i, i, i, i, vp, vp]),
+        "winograd_f2x2_conv2d_int8_requant": (i, [vp, vp, vp, i, i, i, i, i, i, i, i, i, i, vp]),
         "winograd_conv2d_int8_stage_times": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp, sz, vp, i, vp]),
         "direct_conv2d_int8": (i, [vp, vp, vp, i, i, i, i, i, i, vp]),
         "requant_relu_pool_int8": (i, [vp, vp, i, i, i, i, i, i, i, i, vp]),
@@ -83,7 +84,7 @@ EXPORTED_SYMBOLS = (
     "winograd_debug_input_operands", "winograd_debug_filter_operands", "winograd_debug_contraction",
     "winograd_f2x2_packed_filter_bytes", "winograd_f2x2_filter_transform", "winograd_f2x2_conv2d_int8",
     "winograd_f2x2_debug_filter_operands", "winograd_f2x2_filter_transform_u8", "winograd_f2x2_conv2d_u8",
-    "winograd_f2x2_conv2d_int8_act_scaled",
+    "winograd_f2x2_conv2d_int8_act_scaled", "winograd_f2x2_conv2d_int8_requant",
 )
 
 
@@ -339,6 +340,22 @@ def f2x2_conv2d_int8(x, packed, layout=NCHW, out=None, zero_point=None):
     else:
         _check(load_library().winograd_f2x2_conv2d_u8(_ptr(x), int(zero_point), _ptr(packed.blob), _ptr(out), N, C, H, W, K,
                                                       layout, packed.mode, _stream()), "winograd_f2x2_conv2d_u8")
+    return out
+
+
+def f2x2_conv2d_int8_requant(x, packed, shift, relu=True, pool=False, layout=NCHW, out=None):
+    """F(2x2,3x3) convolution with requantisation, ReLU and optional 2x2 max-pool before the store: int8 output."""
+    layout = _LAYOUTS[layout]
+    _need(x, torch.int8, "x")
+    N, C, H, W = _dims(x, layout)
+    K = packed.K
+    Ho, Wo = (H // 2, W // 2) if pool else (H, W)
+    if out is None:
+        shape = (N, K, Ho, Wo) if layout == NCHW else (N, Ho, Wo, K)
+        out = torch.empty(shape, dtype=torch.int8, device=x.device)
+    _check(load_library().winograd_f2x2_conv2d_int8_requant(_ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout,
+                                                            packed.mode, int(shift), int(bool(relu)), int(bool(pool)),
+                                                            _stream()), "winograd_f2x2_conv2d_int8_requant")
     return out
 
 

@@ -156,7 +156,23 @@ static int f2_conv2d(const void* x_dev, int is_unsigned, int zero_point, const v
     if (tiles + kTilePad > kIndexLimit / 64) return WG_EUNSUPPORTED;
     if (!aligned(x_dev, 4) || !aligned(y_dev, 4) || !aligned(packed_dev, 256)) return WG_EINVAL;
     return status_of(launch_f2_conv(static_cast<const int8_t*>(x_dev), is_unsigned, zero_point, packed_dev, y_dev,
-                                    make_problem_f2(N, C, H, W, K), layout, mode, static_cast<hipStream_t>(hip_stream)));
+                                    make_problem_f2(N, C, H, W, K), layout, mode, no_int8_epilogue(),
+                                    static_cast<hipStream_t>(hip_stream)));
+}
+
+int winograd_f2x2_conv2d_int8_requant(const int8_t* x_dev, const void* packed_dev, int8_t* out_dev, int N, int C, int H,
+                                      int W, int K, int layout, int mode, int shift, int relu, int pool,
+                                      void* hip_stream) {
+    if (!x_dev || !packed_dev || !out_dev || !valid_layout(layout) || !valid_mode(mode)) return WG_EINVAL;
+    if (shift < 0 || shift > 31) return WG_EINVAL;
+    if (int st = check_shape(N, C, H, W, K)) return st;
+    const long long tiles = (long long)N * ((H + 1) / 2) * ((W + 1) / 2);
+    if (tiles + kTilePad > kIndexLimit / 64) return WG_EUNSUPPORTED;
+    if (!aligned(x_dev, 4) || !aligned(out_dev, 4) || !aligned(packed_dev, 256)) return WG_EINVAL;
+    if (pool && ((H | W) & 1)) return WG_EUNSUPPORTED;
+    return status_of(launch_f2_conv(x_dev, 0, 0, packed_dev, nullptr, make_problem_f2(N, C, H, W, K), layout, mode,
+                                    make_int8_epilogue(out_dev, shift, relu != 0, pool != 0),
+                                    static_cast<hipStream_t>(hip_stream)));
 }
 
 int winograd_f2x2_filter_transform(const int8_t* w_dev, int K, int C, int layout, int mode, void* packed_dev,

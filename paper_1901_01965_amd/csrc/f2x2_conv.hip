@@ -285,9 +285,17 @@ struct F2Block {
 // undoes G' = 2G on both sides (rnd = 0: exact, lossless mode; rnd = 2: round half up).  Register
 // q of m[e] belongs to tile 4 (lane / 16) + q and filter k.  The operand planes in LDS must be
 // dead for all waves' products when this is called (it synchronises before it overwrites them).
-template <int LAYOUT>
+// Q8: instead of the int32 store, v = (y + round) >> shift clamped to [lo, 127] goes to q8.out as
+// int8; with q8.pool the tile's four outputs (one 2x2 pooling window) are reduced to their maximum.
+__device__ inline v4i f2_requantise(v4i v, const Int8Epilogue& q) {
+    v = (v + q.round) >> q.shift;
+    const v4i lo = {q.lo, q.lo, q.lo, q.lo}, hi = {127, 127, 127, 127};
+    return __builtin_elementwise_min(__builtin_elementwise_max(v, lo), hi);
+}
+template <int LAYOUT, bool Q8 = false>
 __device__ __forceinline__ void f2_output_transform_store(const v4i (&m)[kF2Entries], int rnd, const F2Block& b,
-                                                          const Problem& p, int8_t* lds, int32_t* __restrict__ y) {
+                                                          const Problem& p, int8_t* lds, int32_t* __restrict__ y,
+                                                          const Int8Epilogue& q8 = Int8Epilogue{nullptr, 0, 0, 0, 0}) {
     const int lane = b.lane;
     v4i z[2][4];
 #pragma unroll
@@ -301,6 +309,15 @@ __device__ __forceinline__ void f2_output_transform_store(const v4i (&m)[kF2Entr
         out[2 * i + 0] = (z[i][0] + z[i][1] + z[i][2] + rnd) >> 2;
         out[2 * i + 1] = (z[i][1] - z[i][2] - z[i][3] + rnd) >> 2;
     }
+    // int8 epilogue: NO outputs per tile (one after pooling), on a grid of Ho x Wo pixels
+    const bool pooled = Q8 && q8.pool != 0;
+    const int NO = pooled ? 1 : 4, Ho = pooled ? p.H >> 1 : p.H, Wo = pooled ? p.W >> 1 : p.W;
+    if constexpr (Q8) {
+#pragma unroll
+        for (int o = 0; o < 4; ++o) out[o] = f2_requantise(out[o], q8);
+        if (pooled)
+            out[0] = __builtin_elementwise_max(__builtin_elementwise_max(out[0], out[1]), __builtin_elementwise_max(out[2], out[3]));
+    }
     if (LAYOUT == WG_NHWC && (p.K & 3) == 0) {
         // Channels-last with K a multiple of four: staged filter-fastest, stage[pixel][tile][68]
         // (64 filters, rows padded to 68 dwords), then a thread stores four consecutive filters
@@ -312,7 +329,8 @@ __device__ __forceinline__ void f2_output_transform_store(const v4i (&m)[kF2Entr
 #pragma unroll
         for (int o = 0; o < 4; ++o)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) stage[(o * 16 + 4 * (lane >> 4) + q) * kRow + b.wave * 16 + (lane & 15)] = out[o][q];
+            for (int q = 0; q < 4; ++q)
+                if (o < NO) stage[(o * 16 + 4 * (lane >> 4) + q) * kRow + b.wave * 16 + (lane & 15)] = out[o][q];
         __syncthreads();
         const int k4 = b.tid & 15, tile = b.tid >> 4;   // thread: filters 4 k4 .. 4 k4 + 3 of tile `tile`, all four pixels
         const int n = __shfl(b.my_n, tile), ty = __shfl(b.my_ty, tile), tx = __shfl(b.my_tx, tile);
@@ -320,10 +338,16 @@ __device__ __forceinline__ void f2_output_transform_store(const v4i (&m)[kF2Entr
         if (b.tile0 + tile < p.T && kk < p.K) {
 #pragma unroll
             for (int o = 0; o < 4; ++o) {
-                const int h = 2 * ty + (o >> 1), w = 2 * tx + (o & 1);
-                if (h < p.H && w < p.W)
-                    *reinterpret_cast<v4i*>(y + (((size_t)n * p.H + h) * p.W + w) * p.K + kk) =
-                        *reinterpret_cast<const v4i*>(stage + (o * 16 + tile) * kRow + 4 * k4);
+                if (o >= NO) break;
+                const int h = pooled ? ty : 2 * ty + (o >> 1), w = pooled ? tx : 2 * tx + (o & 1);
+                if (h >= Ho || w >= Wo) continue;
+                const v4i v = *reinterpret_cast<const v4i*>(stage + (o * 16 + tile) * kRow + 4 * k4);
+                const size_t at = (((size_t)n * Ho + h) * Wo + w) * p.K + kk;
+                if constexpr (Q8)
+                    *reinterpret_cast<uint32_t*>(q8.out + at) = (uint32_t)(v[0] & 0xff) | ((uint32_t)(v[1] & 0xff) << 8) |
+                                                                ((uint32_t)(v[2] & 0xff) << 16) | ((uint32_t)v[3] << 24);
+                else
+                    *reinterpret_cast<v4i*>(y + at) = v;
             }
         }
         return;
@@ -335,10 +359,13 @@ __device__ __forceinline__ void f2_output_transform_store(const v4i (&m)[kF2Entr
         if (b.tile0 + tl >= p.T || b.k >= p.K) continue;
 #pragma unroll
         for (int o = 0; o < 4; ++o) {
-            const int h = 2 * ty + (o >> 1), w = 2 * tx + (o & 1);
-            if (h >= p.H || w >= p.W) continue;
-            if (LAYOUT == WG_NHWC) y[(((size_t)n * p.H + h) * p.W + w) * p.K + b.k] = out[o][q];
-            else                   y[(((size_t)n * p.K + b.k) * p.H + h) * p.W + w] = out[o][q];
+            if (o >= NO) break;
+            const int h = pooled ? ty : 2 * ty + (o >> 1), w = pooled ? tx : 2 * tx + (o & 1);
+            if (h >= Ho || w >= Wo) continue;
+            const size_t at = LAYOUT == WG_NHWC ? (((size_t)n * Ho + h) * Wo + w) * p.K + b.k
+                                                : (((size_t)n * p.K + b.k) * Ho + h) * Wo + w;
+            if constexpr (Q8) q8.out[at] = (int8_t)out[o][q];
+            else              y[at] = out[o][q];
         }
     }
 }
@@ -347,10 +374,10 @@ __device__ __forceinline__ void f2_output_transform_store(const v4i (&m)[kF2Entr
 // Product phase: wave w owns filter block w (16 filters) of the 16 tiles for all 16 entries; the
 // filter fragments travel through a ring that is filled before the transform, the activation
 // fragments of entry e + 2 are read from LDS while entry e multiplies.
-template <int LAYOUT, bool VEC4, int MODE>
+template <int LAYOUT, bool VEC4, int MODE, bool Q8>
 __global__ __launch_bounds__(256) void f2_conv_kernel(const int8_t* __restrict__ x, const uint8_t* __restrict__ blob,
                                                       size_t table_off, size_t planes_off, int32_t* __restrict__ y,
-                                                      Problem p, ActivationBias ab) {
+                                                      Problem p, ActivationBias ab, Int8Epilogue q8) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int bx, by;
@@ -448,7 +475,7 @@ __global__ __launch_bounds__(256) void f2_conv_kernel(const int8_t* __restrict__
         }
     }
     const F2Block blk = {tid, lane, wave, tile0, kbase, k, my_n, my_ty, my_tx};
-    f2_output_transform_store<LAYOUT>(m, MODE == WG_SCALED ? 2 : 0, blk, p, lds, y);
+    f2_output_transform_store<LAYOUT, Q8>(m, MODE == WG_SCALED ? 2 : 0, blk, p, lds, y, q8);
 }
 
 // ---- activations scaled as well -------------------------------------------------------------------
@@ -642,26 +669,29 @@ __global__ __launch_bounds__(256) void f2_conv_act_scaled_kernel(const int8_t* _
 }
 
 
-template <int LAYOUT, bool VEC4, int MODE>
+template <int LAYOUT, bool VEC4, int MODE, bool Q8>
 hipError_t launch(const int8_t* x, const uint8_t* blob, const F2BlobLayout& bl, int32_t* y, const Problem& p,
-                  const ActivationBias& ab, hipStream_t s) {
+                  const ActivationBias& ab, const Int8Epilogue& q8, hipStream_t s) {
     static bool configured = false;   // per template instance
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&f2_conv_kernel<LAYOUT, VEC4, MODE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&f2_conv_kernel<LAYOUT, VEC4, MODE, Q8>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kF2LdsBytes);
         if (e != hipSuccess) return e;
         configured = true;
     }
     dim3 grid(ceil_div(p.T, kF2Tiles), p.Kp / kF2Filters);
-    f2_conv_kernel<LAYOUT, VEC4, MODE><<<grid, 256, kF2LdsBytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p, ab);
+    f2_conv_kernel<LAYOUT, VEC4, MODE, Q8><<<grid, 256, kF2LdsBytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p, ab, q8);
     return hipGetLastError();
 }
 
 template <int LAYOUT, bool VEC4>
 hipError_t launch_mode(const int8_t* x, const uint8_t* blob, const F2BlobLayout& bl, int32_t* y, const Problem& p, int mode,
-                       const ActivationBias& ab, hipStream_t s) {
-    return mode == WG_LOSSLESS ? launch<LAYOUT, VEC4, WG_LOSSLESS>(x, blob, bl, y, p, ab, s)
-                               : launch<LAYOUT, VEC4, WG_SCALED>(x, blob, bl, y, p, ab, s);
+                       const ActivationBias& ab, const Int8Epilogue& q8, hipStream_t s) {
+    if (q8.out != nullptr)
+        return mode == WG_LOSSLESS ? launch<LAYOUT, VEC4, WG_LOSSLESS, true>(x, blob, bl, y, p, ab, q8, s)
+                                   : launch<LAYOUT, VEC4, WG_SCALED, true>(x, blob, bl, y, p, ab, q8, s);
+    return mode == WG_LOSSLESS ? launch<LAYOUT, VEC4, WG_LOSSLESS, false>(x, blob, bl, y, p, ab, q8, s)
+                               : launch<LAYOUT, VEC4, WG_SCALED, false>(x, blob, bl, y, p, ab, q8, s);
 }
 
 template <int LAYOUT, bool VEC4>
@@ -714,15 +744,15 @@ hipError_t launch_f2_unpack_filter_planes(const void* blob_v, int8_t* dense, int
 }
 
 hipError_t launch_f2_conv(const int8_t* x, int is_unsigned, int zero_point, const void* blob, int32_t* y, const Problem& p,
-                          int layout, int mode, hipStream_t s) {
+                          int layout, int mode, const Int8Epilogue& q8, hipStream_t s) {
     const uint32_t bias = is_unsigned ? (uint32_t)zero_point : 128u;
     const ActivationBias ab = {is_unsigned ? 0u : 0x80808080u, bias * 0x01010101u, (int)(4 * bias)};
     const F2BlobLayout bl = f2_blob_layout(p.Kp, p.C, mode);
     const uint8_t* b = static_cast<const uint8_t*>(blob);
     if (layout == WG_NHWC && p.C % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 4 == 0)
-        return launch_mode<WG_NHWC, true>(x, b, bl, y, p, mode, ab, s);
-    if (layout == WG_NHWC) return launch_mode<WG_NHWC, false>(x, b, bl, y, p, mode, ab, s);
-    return launch_mode<WG_NCHW, false>(x, b, bl, y, p, mode, ab, s);
+        return launch_mode<WG_NHWC, true>(x, b, bl, y, p, mode, ab, q8, s);
+    if (layout == WG_NHWC) return launch_mode<WG_NHWC, false>(x, b, bl, y, p, mode, ab, q8, s);
+    return launch_mode<WG_NCHW, false>(x, b, bl, y, p, mode, ab, q8, s);
 }
 
 hipError_t launch_f2_conv_act_scaled(const int8_t* x, const void* blob, int32_t* y, int32_t* act_table, const Problem& p,

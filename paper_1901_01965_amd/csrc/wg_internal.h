@@ -176,10 +176,11 @@ hipError_t launch_f2_filter_transform(const int8_t* w, int is_unsigned, int zero
                                       void* blob, hipStream_t s);
 hipError_t launch_f2_unpack_filter_planes(const void* blob, int8_t* dense, int32_t* table, int K, int C, int mode,
                                           hipStream_t s);
+struct Int8Epilogue;   // defined with the single-kernel path's launchers below
 hipError_t launch_f2_conv_act_scaled(const int8_t* x, const void* blob, int32_t* y, int32_t* act_table, const Problem& p,
                                      int layout, hipStream_t s);
 hipError_t launch_f2_conv(const int8_t* x, int is_unsigned, int zero_point, const void* blob, int32_t* y, const Problem& p,
-                          int layout, int mode, hipStream_t s);
+                          int layout, int mode, const Int8Epilogue& q8, hipStream_t s);
 
 // ---- workspace ------------------------------------------------------------------
 // [V: int8 [planes][CB][Tp][64]][M: int32 [46 lossless | 36 scaled][Tp][Kp]]

@@ -147,6 +147,11 @@ def test_validation_errors_return_before_any_launch(lib):
     assert f2tu(None, 3, 4, 4, 0, 0, good2, f2_bytes, None) == EINVAL
     assert f2cu(good, 300, good2, good3, 1, 4, 8, 8, 4, 0, 0, None) == EINVAL
     assert f2cu(good, 3, good2, None, 1, 4, 8, 8, 4, 0, 0, None) == EINVAL
+    f2q = lib.winograd_f2x2_conv2d_int8_requant
+    assert f2q(good, good2, None, 1, 4, 8, 8, 4, 0, 0, 3, 1, 0, None) == EINVAL
+    assert f2q(good, good2, good3, 1, 4, 8, 8, 4, 0, 0, 32, 1, 0, None) == EINVAL        # shift out of range
+    assert f2q(good, good2, good3, 1, 4, 8, 8, 4, 0, 2, 3, 1, 0, None) == EINVAL         # unknown mode
+    assert f2q(good, good2, good3, 1, 4, 8, 7, 4, 0, 0, 3, 1, 1, None) == EUNSUPPORTED   # odd W with pooling
     f2a = lib.winograd_f2x2_conv2d_int8_act_scaled
     assert f2a(good, good2, None, 1, 4, 8, 8, 4, 0, None, None) == EINVAL
     assert f2a(good, None, good3, 1, 4, 8, 8, 4, 0, None, None) == EINVAL

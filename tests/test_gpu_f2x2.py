@@ -258,3 +258,43 @@ def test_act_scaled_rejects_a_lossless_blob():
     out = torch.full((1, 6, 6, 8), 1234567, dtype=torch.int32, device="cuda")
     wg.f2x2_conv2d_int8_act_scaled(_x(x, wg.NHWC), packed, wg.NHWC, out=out)
     assert bool((out == 1234567).all())
+
+
+# ---- int8 epilogue: the requantisation that follows a quantised convolution (Section 4.4), inside the kernel ----
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("mode", [wg.LOSSLESS, wg.SCALED])
+@pytest.mark.parametrize("shape,relu,pool", [
+    (shape, relu, pool)
+    for shape in [(1, 4, 4, 4, 4), (2, 16, 16, 16, 16), (1, 70, 33, 10, 6), (3, 8, 100, 6, 14), (1, 130, 65, 8, 8), (1, 3, 5, 7, 9)]
+    for relu, pool in [(True, False), (True, True), (False, False), (False, True)]
+    if not (pool and ((shape[3] | shape[4]) & 1))])                       # pooling needs even H and W
+def test_int8_epilogue_equals_oracle_requantisation(shape, relu, pool, mode, layout):
+    N, C, K, H, W = shape
+    x, g = wl.make_custom(N, C, K, H, W, act="relu", wgt="gauss", seed=90)
+    if mode == wg.LOSSLESS:
+        want32 = oracle.direct_conv2d(x, g)
+    else:
+        want32, flags = oracle.f2_conv2d(x, g, oracle.SCALED, 127)
+        assert (flags & 4) == 0
+    shift = max(0, int(np.abs(want32).max()).bit_length() - 7)
+    want = oracle.requant_relu_pool(want32, shift, relu, pool)
+    packed = wg.f2x2_filter_transform(_g(g, layout), layout, mode)
+    Ho, Wo = (H // 2, W // 2) if pool else (H, W)
+    out = torch.full((N, K, Ho, Wo) if layout == wg.NCHW else (N, Ho, Wo, K), 77, dtype=torch.int8, device="cuda")
+    wg.f2x2_conv2d_int8_requant(_x(x, layout), packed, shift, relu, pool, layout, out=out)
+    got = out.cpu().numpy()
+    assert np.array_equal(got if layout == wg.NCHW else wl.from_nhwc(got), want)
+    assert want.max() > 0 and (relu or pool or want.min() < 0)      # the case exercises both signs where it can
+
+
+def test_int8_epilogue_full_size_cfg3():
+    x, g = wl.make_case("cfg3")
+    xd, gd = _x(x, wg.NHWC), _g(g, wg.NHWC)
+    packed = wg.f2x2_filter_transform(gd, wg.NHWC, wg.LOSSLESS)
+    y32 = wg.f2x2_conv2d_int8(xd, packed, wg.NHWC)
+    shift = max(0, int(y32.abs().max().item()).bit_length() - 7)
+    q = wg.f2x2_conv2d_int8_requant(xd, packed, shift, True, True, wg.NHWC)
+    assert torch.equal(q, wg.requant_relu_pool_int8(y32, shift, True, True, wg.NHWC))
+    want = oracle.requant_relu_pool(oracle.direct_conv2d(x[:1], g), shift, True, True)
+    assert np.array_equal(wl.from_nhwc(q[:1].cpu().numpy()), want)
