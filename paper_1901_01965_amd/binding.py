@@ -118,6 +118,26 @@ def _need(t, dtype, what):
         raise TypeError("%s must be a contiguous CUDA tensor of %s" % (what, dtype))
 
 
+def _out(out, shape, dtype, device, what="out"):
+    """A fresh output tensor, or the caller's after a check of its shape, type and contiguity: a kernel writes
+    `shape` elements of `dtype` wherever the pointer leads."""
+    if out is None:
+        return torch.empty(shape, dtype=dtype, device=device)
+    _need(out, dtype, what)
+    if tuple(out.shape) != tuple(shape):
+        raise ValueError("%s has shape %s, the call writes %s" % (what, tuple(out.shape), tuple(shape)))
+    return out
+
+
+def _match(packed, cls, C, what):
+    """The blob must be of the right algorithm and made for the activation's channel count: the kernels only
+    find a mismatch on the device, where all they can do is leave the output untouched."""
+    if not isinstance(packed, cls):
+        raise TypeError("%s needs a %s, got %s" % (what, cls.__name__, type(packed).__name__))
+    if packed.C != C:
+        raise ValueError("%s: the filters were packed for C = %d, the activations have C = %d" % (what, packed.C, C))
+
+
 AUTO, STAGED, FUSED = 0, 1, 2
 
 
@@ -184,12 +204,12 @@ def winograd_conv2d_int8(x, packed, layout=NCHW, out=None, workspace=None):
     layout = _LAYOUTS[layout]
     _need(x, torch.int8, "x")
     N, C, H, W = _dims(x, layout)
+    _match(packed, PackedFilter, C, "winograd_conv2d_int8")
     K = packed.K
     if workspace is None:
         workspace = make_workspace(N, C, H, W, K, packed.mode, x.device)
-    if out is None:
-        shape = (N, K, H, W) if layout == NCHW else (N, H, W, K)
-        out = torch.empty(shape, dtype=torch.int32, device=x.device)
+    _need(workspace, torch.uint8, "workspace")
+    out = _out(out, (N, K, H, W) if layout == NCHW else (N, H, W, K), torch.int32, x.device)
     _check(load_library().winograd_conv2d_int8(_ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout,
                                                packed.mode, _ptr(workspace), workspace.numel(), _stream()),
            "winograd_conv2d_int8")
@@ -202,11 +222,10 @@ def winograd_conv2d_int8_requant(x, packed, shift, relu=True, pool=False, layout
     layout = _LAYOUTS[layout]
     _need(x, torch.int8, "x")
     N, C, H, W = _dims(x, layout)
+    _match(packed, PackedFilter, C, "winograd_conv2d_int8_requant")
     K = packed.K
     Ho, Wo = (H // 2, W // 2) if pool else (H, W)
-    if out is None:
-        shape = (N, K, Ho, Wo) if layout == NCHW else (N, Ho, Wo, K)
-        out = torch.empty(shape, dtype=torch.int8, device=x.device)
+    out = _out(out, (N, K, Ho, Wo) if layout == NCHW else (N, Ho, Wo, K), torch.int8, x.device)
     _check(load_library().winograd_conv2d_int8_requant(_ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout,
                                                        packed.mode, int(shift), int(relu), int(pool), _stream()),
            "winograd_conv2d_int8_requant")
@@ -218,12 +237,12 @@ def stage_times(x, packed, layout=NCHW, iters=20, out=None, workspace=None):
     layout = _LAYOUTS[layout]
     _need(x, torch.int8, "x")
     N, C, H, W = _dims(x, layout)
+    _match(packed, PackedFilter, C, "stage_times")
     K = packed.K
     if workspace is None:
         workspace = make_workspace(N, C, H, W, K, packed.mode, x.device)
-    if out is None:
-        shape = (N, K, H, W) if layout == NCHW else (N, H, W, K)
-        out = torch.empty(shape, dtype=torch.int32, device=x.device)
+    _need(workspace, torch.uint8, "workspace")
+    out = _out(out, (N, K, H, W) if layout == NCHW else (N, H, W, K), torch.int32, x.device)
     ms = (ctypes.c_float * 4)()
     _check(load_library().winograd_conv2d_int8_stage_times(
         _ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout, packed.mode, _ptr(workspace),
@@ -237,9 +256,9 @@ def direct_conv2d_int8(x, w, layout=NCHW, out=None):
     _need(w, torch.int8, "w")
     N, C, H, W = _dims(x, layout)
     K = w.shape[0]
-    if out is None:
-        shape = (N, K, H, W) if layout == NCHW else (N, H, W, K)
-        out = torch.empty(shape, dtype=torch.int32, device=x.device)
+    if tuple(w.shape) != ((K, C, 3, 3) if layout == NCHW else (K, 3, 3, C)):
+        raise ValueError("w has shape %s, which does not fit activations with C = %d" % (tuple(w.shape), C))
+    out = _out(out, (N, K, H, W) if layout == NCHW else (N, H, W, K), torch.int32, x.device)
     _check(load_library().direct_conv2d_int8(_ptr(x), _ptr(w), _ptr(out), N, C, H, W, K, layout, _stream()),
            "direct_conv2d_int8")
     return out
@@ -250,9 +269,7 @@ def requant_relu_pool_int8(y, shift, relu=True, pool=False, layout=NCHW, out=Non
     _need(y, torch.int32, "y")
     N, K, H, W = _dims(y, layout)
     Ho, Wo = (H // 2, W // 2) if pool else (H, W)
-    if out is None:
-        shape = (N, K, Ho, Wo) if layout == NCHW else (N, Ho, Wo, K)
-        out = torch.empty(shape, dtype=torch.int8, device=y.device)
+    out = _out(out, (N, K, Ho, Wo) if layout == NCHW else (N, Ho, Wo, K), torch.int8, y.device)
     _check(load_library().requant_relu_pool_int8(_ptr(y), _ptr(out), N, K, H, W, layout, int(shift), int(relu),
                                                  int(pool), _stream()), "requant_relu_pool_int8")
     return out
@@ -288,6 +305,7 @@ def debug_contraction(x, packed, layout=NCHW):
     layout = _LAYOUTS[layout]
     _need(x, torch.int8, "x")
     N, C, H, W = _dims(x, layout)
+    _match(packed, PackedFilter, C, "debug_contraction")
     T = N * ((H + 3) // 4) * ((W + 3) // 4)
     out = torch.empty((36, T, packed.K), dtype=torch.int32, device=x.device)
     ws = make_workspace(N, C, H, W, packed.K, packed.mode, x.device)
@@ -330,10 +348,9 @@ def f2x2_conv2d_int8(x, packed, layout=NCHW, out=None, zero_point=None):
     layout = _LAYOUTS[layout]
     _need(x, torch.int8 if zero_point is None else torch.uint8, "x")
     N, C, H, W = _dims(x, layout)
+    _match(packed, F2x2PackedFilter, C, "f2x2_conv2d_int8")
     K = packed.K
-    if out is None:
-        shape = (N, K, H, W) if layout == NCHW else (N, H, W, K)
-        out = torch.empty(shape, dtype=torch.int32, device=x.device)
+    out = _out(out, (N, K, H, W) if layout == NCHW else (N, H, W, K), torch.int32, x.device)
     if zero_point is None:
         _check(load_library().winograd_f2x2_conv2d_int8(_ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout,
                                                         packed.mode, _stream()), "winograd_f2x2_conv2d_int8")
@@ -348,11 +365,10 @@ def f2x2_conv2d_int8_requant(x, packed, shift, relu=True, pool=False, layout=NCH
     layout = _LAYOUTS[layout]
     _need(x, torch.int8, "x")
     N, C, H, W = _dims(x, layout)
+    _match(packed, F2x2PackedFilter, C, "f2x2_conv2d_int8_requant")
     K = packed.K
     Ho, Wo = (H // 2, W // 2) if pool else (H, W)
-    if out is None:
-        shape = (N, K, Ho, Wo) if layout == NCHW else (N, Ho, Wo, K)
-        out = torch.empty(shape, dtype=torch.int8, device=x.device)
+    out = _out(out, (N, K, Ho, Wo) if layout == NCHW else (N, Ho, Wo, K), torch.int8, x.device)
     _check(load_library().winograd_f2x2_conv2d_int8_requant(_ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout,
                                                             packed.mode, int(shift), int(bool(relu)), int(bool(pool)),
                                                             _stream()), "winograd_f2x2_conv2d_int8_requant")
@@ -365,10 +381,11 @@ def f2x2_conv2d_int8_act_scaled(x, packed, layout=NCHW, out=None, want_table=Fal
     layout = _LAYOUTS[layout]
     _need(x, torch.int8, "x")
     N, C, H, W = _dims(x, layout)
+    _match(packed, F2x2PackedFilter, C, "f2x2_conv2d_int8_act_scaled")
+    if packed.mode != SCALED:
+        raise ValueError("f2x2_conv2d_int8_act_scaled needs filters packed in SCALED mode")
     K = packed.K
-    if out is None:
-        shape = (N, K, H, W) if layout == NCHW else (N, H, W, K)
-        out = torch.empty(shape, dtype=torch.int32, device=x.device)
+    out = _out(out, (N, K, H, W) if layout == NCHW else (N, H, W, K), torch.int32, x.device)
     table = None
     if want_table:
         table = torch.empty((N * ((H + 1) // 2) * ((W + 1) // 2), 16, 4), dtype=torch.int32, device=x.device)

@@ -11,8 +11,8 @@ bool valid_layout(int l) { return l == WG_NCHW || l == WG_NHWC; }
 bool valid_mode(int m) { return m == WG_LOSSLESS || m == WG_SCALED; }
 const long long kIndexLimit = 0x7fffffffll;
 
-// Shape checks shared by the convolution entry points; `need_c_limit` applies the
-// int32-exactness bound on the input channels.
+// Shape checks shared by the convolution entry points, including the int32-exactness bound on
+// the input channels.
 int check_shape(int N, int C, int H, int W, int K) {
     if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0) return WG_EINVAL;
     if (C > WG_MAX_CHANNELS) return WG_EUNSUPPORTED;

@@ -1196,6 +1196,24 @@ int compute_units() {
     return cus;
 }
 
+// Barrier among the four transform waves of the streaming kernel (s_barrier would stop the product
+// waves as well): a counter in LDS that only grows, four arrivals per use.  A wave arrives once its
+// own LDS reads have returned and leaves when all four have arrived, so no wave writes the shared
+// buffer while another still reads it.  Every transform wave runs the same (workgroup-uniform)
+// sequence of uses, and all four are resident together, so the wait ends.
+struct TransformWavesBarrier {
+    uint32_t* counter;
+    uint32_t arrivals;   // what the counter reads once everyone has arrived at the current use
+    __device__ inline void sync(int lane) {
+        arrivals += 4;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (lane == 0) __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        while ((int)(__hip_atomic_load(counter, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) - arrivals) < 0)
+            __builtin_amdgcn_s_sleep(1);
+        asm volatile("" ::: "memory");
+    }
+};
+
 // The role-specialised kernel as a stream over tile blocks: a workgroup owns one 32-filter block
 // and walks over many tile blocks (grid: about one workgroup per compute unit), so that the two
 // roles also overlap across tile blocks and layers with a single channel block are pipelined
@@ -1207,6 +1225,10 @@ int compute_units() {
 // Barriers, in the same order on both roles: U_u (u = 1..U) publishes the planes of unit u - 1 and
 // frees the buffer of unit u - 2; after the last channel block of a tile block, D_u (every product
 // wave has finished reading the planes) and S_u (the outputs are staged).
+// The staged outputs of unit u - 2 and the planes of unit u share a buffer, and the four transform
+// waves both read the former (each thread reads rows that other waves' plane writes cover) and
+// write the latter: between the two they meet at a barrier of their own (TransformWavesBarrier;
+// the product waves, which are multiplying unit u - 1 in the other buffer, do not take part).
 // Channels-last, C % 4 = 0 (4-byte pixel loads), K % 4 = 0 (16-byte stores).
 template <int MODE, bool Q8>
 __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __restrict__ x, const uint8_t* __restrict__ blob,
@@ -1250,6 +1272,8 @@ __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __
             v4i none[16];
             store_block<WG_NHWC, Q8, 2>(sc, p, q8, none, k0);
         };
+        TransformWavesBarrier among_us = {reinterpret_cast<uint32_t*>(lds + 2 * kLdsBytes), 0u};
+        if (tid == 0) *among_us.counter = 0u;   // lands before the first s_barrier, long before the first use
         int cb = 0, jb = 0;   // unit u = (tile block number jb of this workgroup, channel block cb)
         if (units > 0) {
             enter_tile_block(blockIdx.x);
@@ -1264,7 +1288,10 @@ __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 __builtin_amdgcn_s_barrier();
             }
-            if (last2) flush(tb2, u & 1);   // staged in the buffer of unit u - 2, which unit u is about to overwrite
+            if (last2) {   // staged in the buffer of unit u - 2, which unit u is about to overwrite
+                flush(tb2, u & 1);
+                among_us.sync(lane);   // every transform wave has read its share before any of them writes planes
+            }
             const int tb = (int)blockIdx.x + jb * (int)gridDim.x;
             if (u < units) {
                 out.sink.base = slot + (u & 1) * kLdsBytes;
@@ -1348,7 +1375,7 @@ int stream_workgroups(int tile_blocks, int filter_blocks) {
 template <int MODE, bool Q8>
 hipError_t launch_stream(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
                          const Int8Epilogue& q8, hipStream_t s) {
-    constexpr int lds_bytes = 2 * kLdsBytes;
+    constexpr int lds_bytes = 2 * kLdsBytes + 16;   // two plane buffers and the transform waves' barrier counter
     static bool configured = false;   // per template instance
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_conv_stream_kernel<MODE, Q8>),

@@ -148,7 +148,10 @@ __global__ __launch_bounds__(64) void narrow_conv_kernel(const int8_t* __restric
             const int Ho = p.H >> (q8.pool ? 1 : 0), Wo = p.W >> (q8.pool ? 1 : 0);
             const int orow = q8.pool ? row >> 1 : row, ocol = q8.pool ? col >> 1 : col;
             int8_t* tile_out = q8.out + (((size_t)n * Ho + orow) * Wo + ocol) * p.K;
-            const int add = rnd + 16 * q8.round, shift = 4 + q8.shift;
+            // With at most four input channels |y| < 2^21, so every shift from 22 on gives 0; capping it
+            // at 24 changes no result and keeps 16 * round and 4 + shift within 32 bits for shifts up to 31.
+            const int sh = min(q8.shift, 24);
+            const int add = rnd + (sh > 0 ? 16 << (sh - 1) : 0), shift = 4 + sh;
             int8_t bytes[16];   // pixel (i, j) of the tile at 4 i + j; pooled: (pi, pj) at 2 pi + pj
             if (q8.pool) {
 #pragma unroll

@@ -72,9 +72,9 @@ def test_cfg4_scaled(name):
     assert np.array_equal(_run(x, g, wg.NCHW, wg.LOSSLESS), oracle.direct_conv2d(x, g))
 
 
-def _vgg_stack_gpu(x, gs, mode, layers):
-    """Runs `layers` of the stack on the GPU (channels-last); returns every layer's int32 output and
-    int8 requantised output as NCHW numpy arrays."""
+def _vgg_stack_gpu(x, gs, mode, layers, keep=slice(None)):
+    """Runs `layers` of the stack on the GPU (channels-last); returns, for the images `keep`, every layer's int8
+    input, int32 output and int8 requantised output as NCHW numpy arrays."""
     act = torch.from_numpy(wl.to_nhwc(x)).cuda()
     outs = []
     for i in layers:
@@ -87,8 +87,9 @@ def _vgg_stack_gpu(x, gs, mode, layers):
         # against the oracle by the callers
         one_kernel = wg.winograd_conv2d_int8_requant(act, packed, wl.VGG16_SHIFTS[i], True, pool, wg.NHWC)
         assert torch.equal(one_kernel, nxt), "layer %d: int8 epilogue differs from the two-kernel result" % i
-        outs.append((wl.from_nhwc(y.cpu().numpy()), wl.from_nhwc(nxt.cpu().numpy())))
+        outs.append(tuple(wl.from_nhwc(t[keep].cpu().numpy()) for t in (act, y, nxt)))
         act = nxt
+        del y
     return outs
 
 
@@ -100,8 +101,9 @@ def test_cfg5_vgg16_stack_one_image(mode):
     x, gs = wl.make_vgg16(batch=1)
     outs = _vgg_stack_gpu(x, gs, mode, range(13))
     layer_in = x
-    for i, (y, nxt) in enumerate(outs):
+    for i, (gpu_in, y, nxt) in enumerate(outs):
         cin, cout, hw, pool = wl.VGG16_LAYERS[i]
+        assert np.array_equal(gpu_in, layer_in)
         if mode == wg.LOSSLESS:
             want = oracle.direct_conv2d(layer_in, gs[i])
         else:
@@ -113,13 +115,24 @@ def test_cfg5_vgg16_stack_one_image(mode):
         layer_in = nxt
 
 
-def test_cfg5_vgg16_first_stage_full_batch():
-    """The two 224x224 layers at the full batch of 16 (the largest workspaces of the stack); the oracle
-    checks the last image, whose tiles sit at the far end of every buffer."""
+@pytest.mark.parametrize("mode", [wg.LOSSLESS, wg.SCALED])
+def test_cfg5_vgg16_stack_full_batch(mode):
+    """All 13 layers at the stack's own batch of 16, where the library picks other kernel variants than at
+    batch 1 (streaming, role-specialised, 64-filter workgroups).  The oracle checks the last image of every
+    layer, whose tiles sit at the far end of every buffer: it is given the GPU's int8 input of that layer (the
+    scheme of the one-image test), so a layer's check does not depend on the layers before it."""
     x, gs = wl.make_vgg16(batch=wl.VGG16_BATCH)
-    outs = _vgg_stack_gpu(x, gs, wg.LOSSLESS, range(2))
-    want0 = oracle.direct_conv2d(x[-1:], gs[0])
-    assert np.array_equal(outs[0][0][-1:], want0)
-    in1 = oracle.requant_relu_pool(want0, wl.VGG16_SHIFTS[0], True, False)
-    assert np.array_equal(outs[0][1][-1:], in1)
-    assert np.array_equal(outs[1][0][-1:], oracle.direct_conv2d(in1, gs[1]))
+    outs = _vgg_stack_gpu(x, gs, mode, range(13), keep=slice(wl.VGG16_BATCH - 1, wl.VGG16_BATCH))
+    assert np.array_equal(outs[0][0], x[-1:])
+    for i, (layer_in, y, nxt) in enumerate(outs):
+        cin, cout, hw, pool = wl.VGG16_LAYERS[i]
+        if mode == wg.LOSSLESS:
+            want = oracle.direct_conv2d(layer_in, gs[i])
+        else:
+            want, flags = oracle.winograd_conv2d(layer_in, gs[i], oracle.SCALED, 127)
+            assert (flags & 5) == 0
+        assert np.array_equal(y, want), "layer %d" % i
+        assert np.array_equal(nxt, oracle.requant_relu_pool(want, wl.VGG16_SHIFTS[i], True, pool)), "layer %d" % i
+        if i + 1 < 13:
+            assert np.array_equal(outs[i + 1][0], nxt), "layer %d: the next layer did not get this output" % i
+        print("layer %d ok" % i, flush=True)

@@ -285,3 +285,67 @@ def test_scaled_error_is_small_relative_to_signal():
     err = np.abs(y.astype(np.int64) - d)
     assert err.mean() < 0.02 * np.abs(d).mean()
     assert err.max() > 0                                      # it is a lossy mode
+
+
+def test_scaled_f4x4_pipeline_followed_by_hand_on_one_tile():
+    """One tile, one channel, one filter, every number below worked out by hand from Section 4.2's steps
+    (none of them comes from the oracle).
+
+    Filter taps g[0][0] = 81, g[0][1] = 56: with a = (4,1,1,1,1,0) and b = (0,1,-1,i,-i,0), the first two
+    columns of G' = 4G, G' g G'^T has row 0 = 4 (81 a + 56 b) = (1296, 548, 100, 324+224i, 324-224i, 0).
+    Image 8x8 with x[3][3] = 88, x[3][4] = -38: tile (1,1) reads rows and columns 3..8, so its patch is
+    88, -38 in the first row, and B^T d B has row 0 = (88, -38, 38, 38i, -38i, 38), every other row zero.
+
+    Scale factors (range 127): x = 127*128/max, y = floor(log2 x), n = floor(x / 2^(y-3)), p = 10 - y:
+      1296: x = 12.54, y = 3, n = 12, p = 7;  reciprocal 2^(7+q)/12 <= 255 -> q = 4, r = round(170.67) = 171
+       548: x = 29.66, y = 4, n = 14, p = 6;  2^(6+q)/14 -> q = 5, r = round(146.29) = 146
+       100: within the range, not scaled
+       324: x = 50.17, y = 5, n = 12, p = 5;  2^(5+q)/12 -> q = 6, r = 171   (Re and Im share it)
+    Scaled filters, round half up: (1296*12 + 64) >> 7 = 122, (548*14 + 32) >> 6 = 120,
+      (324*12 + 16) >> 5 = 122, (224*12 + 16) >> 5 = 84.
+    Products (one channel): 122*88 = 10736; 120*(-38) = -4560; 100*38 = 3800; (122+84i)(38i) = -3192 + 4636i.
+    Scaled back: (10736*171 + 8) >> 4 = 114741; (-4560*146 + 16) >> 5 = floor(-20804.5) = -20805; 3800;
+      (-3192*171 + 32) >> 6 = floor(-8528.1) = -8529; (4636*171 + 32) >> 6 = 12387.
+    Output transform: only row 0 of M is non-zero and A^T has a single 1 in its first column, so only output
+    row 0 is non-zero: with m3 = -8529 + 12387i,
+      Y0 = 114741 - 20805 + 3800 + 2(-8529) = 80678     Y1 = -20805 - 3800 - 2(12387) = -49379
+      Y2 = -20805 + 3800 - 2(-8529) = 53                Y3 = -20805 - 3800 + 2(12387) + 0 = 169
+    and y = (Y + 8) >> 4 = (5042, -3086, 3, 11); the exact convolution there is (5000, -3078, 0, 0).
+    80678 = 16*5042 + 6: shifting by 2 with rounding after each 1-D transform instead (which equals
+    floor((Y + 10) / 16)) would give 5043, so this case tells the two conventions apart."""
+    x = np.zeros((1, 1, 8, 8), np.int8)
+    x[0, 0, 3, 3], x[0, 0, 3, 4] = 88, -38
+    g = np.zeros((1, 1, 3, 3), np.int8)
+    g[0, 0, 0, 0], g[0, 0, 0, 1] = 81, 56
+    t = 3   # tile (ty, tx) = (1, 1) of the 2x2 tiles
+
+    D = oracle.input_transform(x)
+    want_row0 = np.array([[88, 0], [-38, 0], [38, 0], [0, 38], [0, -38], [38, 0]])
+    assert np.array_equal(D[t, 0, 0], want_row0) and not D[t, 0, 1:].any()
+
+    Wt = oracle.filter_transform(g)
+    assert np.array_equal(Wt[0, 0, 0], [[1296, 0], [548, 0], [100, 0], [324, 224], [324, -224], [0, 0]])
+    Ws, tab, mx = oracle.scale_filters(Wt, 127)
+    assert [tuple(tab[0, 0, c]) for c in range(5)] == [(12, 7, 171, 4), (14, 6, 146, 5), (0, 0, 1, 0),
+                                                        (12, 5, 171, 6), (12, 5, 171, 6)]
+    assert list(mx[0, 0]) == [1296, 548, 100, 324, 324, 0]
+    assert np.array_equal(Ws[0, 0, 0], [[122, 0], [120, 0], [100, 0], [122, 84], [122, -84], [0, 0]])
+
+    Mt = oracle.contract(D, Ws)
+    assert np.array_equal(Mt[t, 0, 0], [[10736, 0], [-4560, 0], [3800, 0], [-3192, 4636], [-3192, -4636], [0, 0]])
+    M = oracle.inverse_scale(Mt, tab)
+    assert np.array_equal(M[t, 0, 0], [[114741, 0], [-20805, 0], [3800, 0], [-8529, 12387], [-8529, -12387], [0, 0]])
+    assert not M[t, 0, 1:].any()
+
+    y16, flags = oracle.output_transform(M, 1, 1, 8, 8, shift=0)
+    assert flags == 0 and list(y16[0, 0, 4, 4:8]) == [80678, -49379, 53, 169]
+    y, flags = oracle.output_transform(M, 1, 1, 8, 8, shift=4, round_add=8)
+    assert flags == 0
+    assert list(y[0, 0, 4, 4:8]) == [5042, -3086, 3, 11] and not y[0, 0, 5:8, 4:8].any()
+
+    # the whole pipeline in one call gives the same tile, and is not the per-stage-shift variant
+    yy, flags = oracle.winograd_conv2d(x, g, oracle.SCALED, 127)
+    assert (flags & 5) == 0
+    assert list(yy[0, 0, 4, 4:8]) == [5042, -3086, 3, 11] and not yy[0, 0, 5:8, 4:8].any()
+    assert (80678 + 10) // 16 == 5043 != yy[0, 0, 4, 4]
+    assert list(oracle.direct_conv2d(x, g)[0, 0, 4, 4:8]) == [5000, -3078, 0, 0]
