@@ -85,18 +85,76 @@ def capture_steps(torch, step, count):
         return None
 
 
+def kernel_sources_sha16():
+    """Fingerprint of the HIP sources the library is built from (names and contents of csrc/*, in order)."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_1901_01965_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            with open(os.path.join(csrc, name), "rb") as f:
+                h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+TRAFFIC_PROFILE = os.path.join("profiles", "hbm_traffic_cfg2.txt")
+
+
 def read_profiled_traffic(kernel):
-    """HBM bytes per launch from the committed rocprofv3 counter summary, or None."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_cfg2.txt")
+    """(bytes per launch or None, note): HBM traffic of `kernel` from the committed rocprofv3 counter summary.
+    The summary is stamped with the fingerprint of the kernel sources it was measured on; if the sources have
+    changed since, the figure is stale and None is reported instead."""
+    path = os.path.join(ROOT, TRAFFIC_PROFILE)
+    found, stamp = None, None
     try:
         with open(path) as f:
             for line in f:
                 m = re.match(r"^traffic_bytes_per_launch\s+%s\s+(\d+)" % kernel, line)
                 if m:
-                    return int(m.group(1))
+                    found = int(m.group(1))
+                m = re.match(r"^kernel_sources_sha16\s+([0-9a-f]{16})", line)
+                if m:
+                    stamp = m.group(1)
     except OSError:
-        pass
-    return None
+        return None, "no counter summary at %s" % TRAFFIC_PROFILE
+    if found is None:
+        return None, "%s has no line for %s" % (TRAFFIC_PROFILE, kernel)
+    now = kernel_sources_sha16()
+    if stamp != now:
+        return None, "%s was measured on kernel sources %s, the library is built from %s: figure withheld" % (
+            TRAFFIC_PROFILE, stamp, now)
+    return found, "rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated, from %s (kernel sources %s)" % (TRAFFIC_PROFILE, stamp)
+
+
+def time_replay(torch, step, count, eager=False):
+    """Milliseconds per call of step(): `count` calls recorded into one HIP graph, replayed once untimed and once
+    between two synchronisations (or launched one by one when `eager` or when capture is not possible)."""
+    graph = None if eager else capture_steps(torch, step, count)
+    if graph is not None:
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    if graph is not None:
+        graph.replay()
+    else:
+        for _ in range(count):
+            step()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / count * 1e3, graph is not None
+
+
+def time_stage(torch, wg, stage, iters, xd, packed, layout, y, ws):
+    """Mean milliseconds per launch of one kernel of the path: `iters` untimed launches (settled clocks), then
+    `iters` launches between two events recorded on the stream the launches go to (torch's current stream, the
+    one the binding hands to the library)."""
+    wg.enqueue_stage(xd, packed, stage, iters, layout, out=y, workspace=ws)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    wg.enqueue_stage(xd, packed, stage, iters, layout, out=y, workspace=ws)
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / iters
 
 
 def run_stack(args):
@@ -276,6 +334,8 @@ def main():
                     help="cycle the timed steps over this many separate input/output buffer sets (a working set above "
                          "256 MB defeats the Infinity Cache; the default, 1, is the resident case)")
     ap.add_argument("--eager", action="store_true", help="launch the timed steps one by one instead of as one HIP graph")
+    ap.add_argument("--no-rotated-figure", action="store_true",
+                    help="skip the second timed run over a working set above 512 MB")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--calibration-copy", action="store_true",
@@ -329,38 +389,55 @@ def main():
     torch.cuda.synchronize()
     filter_ms = (time.perf_counter() - t0) / 10 * 1e3
 
-    # optional rotation over several buffer sets (same contents), to take the caches out of the picture
-    sets = [(xd, y)] + [(xd.clone(), torch.empty_like(y)) for _ in range(max(1, args.rotate) - 1)]
-    turn = [0]
+    # rotation over several buffer sets (same contents) takes the caches out of the picture
+    def make_sets(count):
+        return [(xd, y)] + [(xd.clone(), torch.empty_like(y)) for _ in range(max(1, count) - 1)]
 
-    def step():
-        xi, yi = sets[turn[0] % len(sets)]
-        turn[0] += 1
-        wg.winograd_conv2d_int8(xi, packed, layout, out=yi, workspace=ws)
+    def stepper(sets):
+        turn = [0]
 
+        def step():
+            xi, yi = sets[turn[0] % len(sets)]
+            turn[0] += 1
+            wg.winograd_conv2d_int8(xi, packed, layout, out=yi, workspace=ws)
+        return step
+
+    sets = make_sets(args.rotate)
+    step = stepper(sets)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
     # The K timed steps are recorded into one HIP graph (the steps are a few microseconds each, so
     # an interpreter loop would be launch-bound) and replayed once inside the timed region.
-    graph = None if args.eager else capture_steps(torch, step, args.steps)
-    if graph is not None:       # one untimed replay, so that the timed one does not pay the upload
-        graph.replay()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    if graph is not None:
-        graph.replay()
-    else:
-        for _ in range(args.steps):
-            step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / args.steps * 1e3
-    tops = case.direct_ops / (elapsed / args.steps) / 1e12
+    ms_per_step, graphed = time_replay(torch, step, args.steps, args.eager)
+    tops = case.direct_ops / (ms_per_step * 1e-3) / 1e12
 
-    # per-kernel durations: HIP events on the launch stream, inside the library
-    stage_ms = wg.stage_times(xd, packed, layout, iters=max(20, args.steps // 2), out=y, workspace=ws)
-    stage = dict(zip(STAGES, stage_ms))
+    # The same steps over enough separate buffer sets that the working set (inputs + outputs) is above 512 MB,
+    # twice the Infinity Cache: every step then reads its activations from HBM and its output lines are new.
+    rotated = None
+    if args.rotate == 1 and not args.no_rotated_figure:
+        per_set = xd.numel() + 4 * y.numel()
+        count = min(512, -(-(520 << 20) // per_set))
+        if count * per_set < (64 << 30):
+            rsets = make_sets(count)
+            rstep = stepper(rsets)
+            for _ in range(count):
+                rstep()
+            torch.cuda.synchronize()
+            rms, _ = time_replay(torch, rstep, max(args.steps, count), args.eager)
+            rotated = {"buffer_sets": count, "working_set_MB": round(count * per_set / 2**20, 1), "ms_per_step": round(rms, 5),
+                       "TOPS": round(case.direct_ops / (rms * 1e-3) / 1e12, 2)}
+            del rsets, rstep
+
+    # per-kernel durations: events on the launch stream around back-to-back launches of one kernel; the three
+    # staged kernels run once in order first, so that each finds its input in the workspace
+    wg.force_path(wg.STAGED)
+    try:
+        wg.winograd_conv2d_int8(xd, packed, layout, out=y, workspace=ws)
+    finally:
+        wg.force_path(wg.AUTO)
+    iters = max(20, args.steps // 2)
+    stage = {name: time_stage(torch, wg, i, iters, xd, packed, layout, y, ws) for i, name in enumerate(STAGES)}
     alg = algorithmic_bytes(case, args.mode)
     path = wg.conv2d_path(case.N, case.C, case.H, case.W, case.K, mode)
     used = ("fused_conv",) if path == wg.FUSED else STAGES[:3]
@@ -371,10 +448,13 @@ def main():
     roofline = {
         "kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
-        # the committed counter summary covers the default workload only
-        "traffic": read_profiled_traffic(dominant) if default_workload else None,
-        "algorithmic_bytes": alg[dominant], "kernel_ms": round(stage[dominant], 5),
+        "traffic": None, "algorithmic_bytes": alg[dominant], "kernel_ms": round(stage[dominant], 5),
     }
+    # the committed counter summary covers the default workload only, and only the sources it was measured on
+    if default_workload:
+        roofline["traffic"], roofline["traffic_source"] = read_profiled_traffic(dominant)
+    else:
+        roofline["traffic_source"] = "no counter summary for this workload"
     kernels = {
         s: {"ms": round(stage[s], 5), "algorithmic_GBps": round(alg[s] / (stage[s] * 1e-3) / 1e9, 1),
             "hbm_frac": round(alg[s] / (stage[s] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
@@ -455,8 +535,9 @@ def main():
         "config": {"workload": "%s: 3x3 s1 p1 conv N=%d C=%d K=%d H=W=%d, %s, %s mode" % (
             case.name, case.N, case.C, case.K, case.H, args.layout.upper(), args.mode)},
         "path": "fused" if path == wg.FUSED else "staged",
-        "launch": "hip graph of %d steps, one replay" % args.steps if graph is not None else "eager",
+        "launch": "hip graph of %d steps, one replay" % args.steps if graphed else "eager",
         "buffer_sets": len(sets),
+        "rotated": rotated,
         "roofline": roofline,
         "kernels": kernels,
         "filter_transform_ms": round(filter_ms, 4),
@@ -487,6 +568,26 @@ def main():
             "sample": "the whole %s batch through the oracle's Gaussian-integer Winograd path, %d runs, %.1f s"
                       % (case.name, runs, t_cpu),
         }
+        # the same oracle on one thread (OpenMP's own switch; the oracle is not touched), a few runs
+        import ctypes
+        try:
+            gomp = ctypes.CDLL("libgomp.so.1")
+            threads = oracle.num_threads()
+            gomp.omp_set_num_threads(1)
+            try:
+                runs1, t1 = 0, 0.0
+                while t1 < min(3.0, args.cpu_seconds) or runs1 < 1:
+                    t0 = time.perf_counter()
+                    oracle.winograd_conv2d(x_np, g_np, omode)
+                    t1 += time.perf_counter() - t0
+                    runs1 += 1
+            finally:
+                gomp.omp_set_num_threads(threads)
+            result["cpu_baseline_1thread"] = {
+                "value": round(case.direct_ops * runs1 / t1 / 1e12, 5), "unit": "TOPS", "cores": 1, "kind": "oracle",
+                "sample": "the same, %d runs, %.1f s" % (runs1, t1)}
+        except OSError:
+            result["cpu_baseline_1thread"] = None
     print(json.dumps(result))
 
 

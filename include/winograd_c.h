@@ -21,12 +21,11 @@
  *   - 1 <= C <= WG_MAX_CHANNELS keeps every int32 accumulator exact for any
  *     int8 data (16 * 9 * C * 128 * 128 < 2^31).
  *   - Threads and devices: launches go to the device that is current in the
- *     calling thread.  The first call of a kernel variant sets that kernel's
- *     shared-memory limit once per process without locking, so the first call
- *     of each entry point should not race with another call of the same entry
- *     point, and a process should drive one device through this library (the
- *     build targets one GPU).  The winograd_debug_* switches are process-wide
- *     and not thread-safe.
+ *     calling thread.  The first call of a kernel variant raises that kernel's
+ *     shared-memory limit, once per process and under a lock, so calls may come
+ *     from several threads; a process should drive one device through this
+ *     library (the build targets one GPU).  The winograd_debug_* switches are
+ *     process-wide: a call in flight on another thread may see either value.
  */
 #ifndef WINOGRAD_C_H
 #define WINOGRAD_C_H
@@ -241,19 +240,17 @@ int requant_relu_pool_int8(const int32_t* y_dev, int8_t* out_dev, int N, int K, 
 int winograd_conv2d_path(int N, int C, int H, int W, int K, int mode);
 
 /*
- * Measurement aid for benchmarks: enqueues each kernel of winograd_conv2d_int8
- * (same arguments and launch configuration as that call) `iters` times back to
- * back on hip_stream between two HIP events (after `iters` untimed launches of
- * the same kernel, so that clocks have settled), waits, and writes the mean
- * milliseconds per launch to stage_ms_host[0..3] (HOST memory): the staged
- * pipeline's input transform, contraction and output transform, then the fused
- * kernel.  This call blocks.  y_dev holds the
- * convolution result afterwards.  iters >= 1.
+ * Measurement aid for benchmarks: enqueues ONE kernel of winograd_conv2d_int8 (same arguments and
+ * launch configuration as in that call) `iters` times back to back on hip_stream and returns; the
+ * caller brackets the call with its own events on that stream.  stage 0: the staged pipeline's input
+ * transform (Section 3.4's B^T d B), 1: its contraction, 2: its output transform, 3: the single
+ * fused kernel.  Stages 1 and 2 consume what the stage before them left in the workspace, so run
+ * the stages in order once before timing them.  Never synchronises, creates nothing.  iters >= 1.
  */
-int winograd_conv2d_int8_stage_times(const int8_t* x_dev, const void* packed_dev, int32_t* y_dev,
-                                     int N, int C, int H, int W, int K, int layout, int mode,
-                                     void* workspace_dev, size_t workspace_bytes, void* hip_stream,
-                                     int iters, float* stage_ms_host);
+int winograd_conv2d_int8_enqueue_stage(const int8_t* x_dev, const void* packed_dev, int32_t* y_dev,
+                                       int N, int C, int H, int W, int K, int layout, int mode,
+                                       void* workspace_dev, size_t workspace_bytes, void* hip_stream,
+                                       int stage, int iters);
 
 /* ---- stage exports used by the stage-level parity tests ------------------
  * Operand-plane numbering.  The 26 free entries of a transformed tile are
@@ -277,14 +274,14 @@ int winograd_num_activation_planes(int mode);
    (input transform, contraction, output transform as three kernels through
    the workspace) whose intermediate arrays the stage exports below expose.
    path 0 = library's choice (default), 1 = always staged, 2 = always fused.
-   Process-wide; for tests and benchmarks.  Returns WG_EINVAL for any other
-   value. */
+   Process-wide (an atomic flag); for tests and benchmarks.  Returns WG_EINVAL
+   for any other value. */
 int winograd_debug_force_path(int path);
 /* Test hook for the single-kernel path's streaming variant (one workgroup walks over many tile
    blocks of a 32-filter block; the library picks it by itself only for large layers): n > 0
    makes every call whose layout allows it (channels-last, C % 4 = 0, K % 4 = 0) use it with n
-   workgroups per filter block; 0 restores the library's own choice.  Process-wide, not
-   thread-safe, like winograd_debug_force_path. */
+   workgroups per filter block; 0 restores the library's own choice.  Process-wide, like
+   winograd_debug_force_path. */
 int winograd_debug_stream_workgroups(int n);
 int winograd_num_filter_planes(int mode);
 

@@ -60,7 +60,7 @@ def load_library():
         "winograd_f2x2_conv2d_u8": (i, [vp, i, vp, vp, i, i, i, i, i, i, i, vp]),
         "winograd_f2x2_conv2d_int8_act_scaled": (i, [vp, vp, vp, i, i, i, i, i, i, vp, vp]),
         "winograd_f2x2_conv2d_int8_requant": (i, [vp, vp, vp, i, i, i, i, i, i, i, i, i, i, vp]),
-        "winograd_conv2d_int8_stage_times": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp, sz, vp, i, vp]),
+        "winograd_conv2d_int8_enqueue_stage": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp, sz, vp, i, i]),
         "direct_conv2d_int8": (i, [vp, vp, vp, i, i, i, i, i, i, vp]),
         "requant_relu_pool_int8": (i, [vp, vp, i, i, i, i, i, i, i, i, vp]),
         "winograd_debug_input_operands": (i, [vp, vp, i, i, i, i, i, i, vp, sz, vp]),
@@ -79,7 +79,7 @@ EXPORTED_SYMBOLS = (
     "winograd_debug_force_path", "winograd_debug_stream_workgroups", "winograd_conv2d_path", "winograd_debug_tile_decode",
     "winograd_packed_filter_bytes", "winograd_workspace_bytes", "winograd_filter_transform",
     "winograd_packed_filter_check", "winograd_conv2d_int8", "winograd_conv2d_int8_requant",
-    "winograd_conv2d_int8_stage_times",
+    "winograd_conv2d_int8_enqueue_stage",
     "direct_conv2d_int8", "requant_relu_pool_int8",
     "winograd_debug_input_operands", "winograd_debug_filter_operands", "winograd_debug_contraction",
     "winograd_f2x2_packed_filter_bytes", "winograd_f2x2_filter_transform", "winograd_f2x2_conv2d_int8",
@@ -232,22 +232,25 @@ def winograd_conv2d_int8_requant(x, packed, shift, relu=True, pool=False, layout
     return out
 
 
-def stage_times(x, packed, layout=NCHW, iters=20, out=None, workspace=None):
-    """Mean milliseconds per launch of (input transform, contraction, output transform, fused kernel); blocks."""
+STAGE_NAMES = ("input_transform", "contraction", "output_transform", "fused_conv")
+
+
+def enqueue_stage(x, packed, stage, iters, layout=NCHW, out=None, workspace=None):
+    """Enqueues one kernel of winograd_conv2d_int8 (`stage`: an index into STAGE_NAMES) `iters` times on the current
+    stream and returns at once; the caller times it with events on that stream."""
     layout = _LAYOUTS[layout]
     _need(x, torch.int8, "x")
     N, C, H, W = _dims(x, layout)
-    _match(packed, PackedFilter, C, "stage_times")
+    _match(packed, PackedFilter, C, "enqueue_stage")
     K = packed.K
     if workspace is None:
         workspace = make_workspace(N, C, H, W, K, packed.mode, x.device)
     _need(workspace, torch.uint8, "workspace")
     out = _out(out, (N, K, H, W) if layout == NCHW else (N, H, W, K), torch.int32, x.device)
-    ms = (ctypes.c_float * 4)()
-    _check(load_library().winograd_conv2d_int8_stage_times(
+    _check(load_library().winograd_conv2d_int8_enqueue_stage(
         _ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout, packed.mode, _ptr(workspace),
-        workspace.numel(), _stream(), int(iters), ctypes.cast(ms, ctypes.c_void_p)), "winograd_conv2d_int8_stage_times")
-    return [float(v) for v in ms]
+        workspace.numel(), _stream(), int(stage), int(iters)), "winograd_conv2d_int8_enqueue_stage")
+    return out
 
 
 def direct_conv2d_int8(x, w, layout=NCHW, out=None):
@@ -382,8 +385,6 @@ def f2x2_conv2d_int8_act_scaled(x, packed, layout=NCHW, out=None, want_table=Fal
     _need(x, torch.int8, "x")
     N, C, H, W = _dims(x, layout)
     _match(packed, F2x2PackedFilter, C, "f2x2_conv2d_int8_act_scaled")
-    if packed.mode != SCALED:
-        raise ValueError("f2x2_conv2d_int8_act_scaled needs filters packed in SCALED mode")
     K = packed.K
     out = _out(out, (N, K, H, W) if layout == NCHW else (N, H, W, K), torch.int32, x.device)
     table = None

@@ -1,45 +1,19 @@
 // The C ABI: argument validation on the host, then the stage launchers.
-// Nothing here allocates or synchronises except winograd_packed_filter_check.
-#include "wg_internal.h"
+// Nothing here allocates, and nothing synchronises except winograd_packed_filter_check.
+#include <atomic>
+
+#include "api_checks.h"
 
 using namespace wg;
 
 namespace {
 
-bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
-bool valid_layout(int l) { return l == WG_NCHW || l == WG_NHWC; }
-bool valid_mode(int m) { return m == WG_LOSSLESS || m == WG_SCALED; }
-const long long kIndexLimit = 0x7fffffffll;
-
-// Shape checks shared by the convolution entry points, including the int32-exactness bound on
-// the input channels.
-int check_shape(int N, int C, int H, int W, int K) {
-    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0) return WG_EINVAL;
-    if (C > WG_MAX_CHANNELS) return WG_EUNSUPPORTED;
-    const long long hw = (long long)H * W;
-    if (hw > kIndexLimit) return WG_EUNSUPPORTED;
-    if ((long long)N * C > kIndexLimit / hw || (long long)N * K > kIndexLimit / hw) return WG_EUNSUPPORTED;
-    if ((long long)K * C * 9 > kIndexLimit) return WG_EUNSUPPORTED;
-    const long long tiles = (long long)N * ((H + 3) / 4) * ((W + 3) / 4);
-    if (tiles + kTilePad > kIndexLimit / 64) return WG_EUNSUPPORTED;
-    return WG_OK;
-}
-
-int check_filter_shape(int K, int C) {
-    if (K <= 0 || C <= 0) return WG_EINVAL;
-    if (C > WG_MAX_CHANNELS) return WG_EUNSUPPORTED;
-    if ((long long)K * C * 9 > kIndexLimit) return WG_EUNSUPPORTED;
-    return WG_OK;
-}
-
-int status_of(hipError_t e) { return e == hipSuccess ? WG_OK : WG_ERUNTIME; }
-
 // 0: the library's choice (the fused kernel: on every measured shape it is at least as fast as
 // the staged pipeline, which moves the transformed activations and the accumulator planes
 // through memory); 1: always the staged three-kernel pipeline; 2: always the fused kernel.
-int g_forced_path = 0;
+std::atomic<int> g_forced_path{0};
 
-bool use_fused() { return g_forced_path != 1; }
+bool use_fused() { return g_forced_path.load(std::memory_order_relaxed) != 1; }
 
 }  // namespace
 
@@ -238,14 +212,14 @@ int winograd_debug_stream_workgroups(int n) {
 
 int winograd_debug_force_path(int path) {
     if (path < 0 || path > 2) return WG_EINVAL;
-    g_forced_path = path;
+    g_forced_path.store(path, std::memory_order_relaxed);
     return WG_OK;
 }
 
-int winograd_conv2d_int8_stage_times(const int8_t* x_dev, const void* packed_dev, int32_t* y_dev, int N, int C,
-                                     int H, int W, int K, int layout, int mode, void* workspace_dev,
-                                     size_t workspace_bytes, void* hip_stream, int iters, float* stage_ms_host) {
-    if (!stage_ms_host || iters < 1) return WG_EINVAL;
+int winograd_conv2d_int8_enqueue_stage(const int8_t* x_dev, const void* packed_dev, int32_t* y_dev, int N, int C,
+                                       int H, int W, int K, int layout, int mode, void* workspace_dev,
+                                       size_t workspace_bytes, void* hip_stream, int stage, int iters) {
+    if (stage < 0 || stage > 3 || iters < 1) return WG_EINVAL;
     if (int st = check_conv_args(x_dev, packed_dev, y_dev, N, C, H, W, K, layout, mode, workspace_dev,
                                  workspace_bytes))
         return st;
@@ -254,31 +228,14 @@ int winograd_conv2d_int8_stage_times(const int8_t* x_dev, const void* packed_dev
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     int8_t* V = static_cast<int8_t*>(workspace_dev) + wl.v_off;
     int32_t* M = reinterpret_cast<int32_t*>(static_cast<uint8_t*>(workspace_dev) + wl.m_off);
-    hipEvent_t e0, e1;
-    if (hipEventCreate(&e0) != hipSuccess) return WG_ERUNTIME;
-    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return WG_ERUNTIME; }
-    int status = WG_OK;
-    for (int stage = 0; stage < 4 && status == WG_OK; ++stage) {
-        // an untimed pass of the same length first, so that the timed launches run at settled clocks
-        hipError_t e = hipSuccess;
-        for (int i = 0; i < 2 * iters && e == hipSuccess; ++i) {
-            if (i == iters) e = hipEventRecord(e0, s);
-            if (e != hipSuccess) break;
-            if (stage == 0)      e = launch_input_transform(x_dev, p, layout, mode, V, s);
-            else if (stage == 1) e = launch_contraction(V, packed_dev, M, p, mode, s);
-            else if (stage == 2) e = launch_output_transform(M, packed_dev, y_dev, p, layout, mode, s);
-            else                 e = launch_fused_conv(x_dev, packed_dev, y_dev, p, layout, mode, no_int8_epilogue(), s);
-        }
-        if (e == hipSuccess) e = hipEventRecord(e1, s);
-        if (e == hipSuccess) e = hipEventSynchronize(e1);
-        float ms = 0.f;
-        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-        stage_ms_host[stage] = ms / (float)iters;
-        status = status_of(e);
+    hipError_t e = hipSuccess;
+    for (int i = 0; i < iters && e == hipSuccess; ++i) {
+        if (stage == 0)      e = launch_input_transform(x_dev, p, layout, mode, V, s);
+        else if (stage == 1) e = launch_contraction(V, packed_dev, M, p, mode, s);
+        else if (stage == 2) e = launch_output_transform(M, packed_dev, y_dev, p, layout, mode, s);
+        else                 e = launch_fused_conv(x_dev, packed_dev, y_dev, p, layout, mode, no_int8_epilogue(), s);
     }
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
-    return status;
+    return status_of(e);
 }
 
 int direct_conv2d_int8(const int8_t* x_dev, const int8_t* w_dev, int32_t* y_dev, int N, int C, int H, int W,

@@ -289,12 +289,8 @@ __global__ void unpack_accumulators_kernel(const int32_t* M, int32_t* dense, Pro
 
 template <int MODE>
 hipError_t configure_contraction() {
-    static bool done = false;
-    if (done) return hipSuccess;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&contraction_kernel<MODE>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kContractionLds);
-    done = e == hipSuccess;
-    return e;
+    static LdsLimitOnce lds_limit;
+    return lds_limit.set(reinterpret_cast<const void*>(&contraction_kernel<MODE>), kContractionLds);
 }
 
 }  // namespace

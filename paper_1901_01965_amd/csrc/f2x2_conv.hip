@@ -672,13 +672,8 @@ __global__ __launch_bounds__(256) void f2_conv_act_scaled_kernel(const int8_t* _
 template <int LAYOUT, bool VEC4, int MODE, bool Q8>
 hipError_t launch(const int8_t* x, const uint8_t* blob, const F2BlobLayout& bl, int32_t* y, const Problem& p,
                   const ActivationBias& ab, const Int8Epilogue& q8, hipStream_t s) {
-    static bool configured = false;   // per template instance
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&f2_conv_kernel<LAYOUT, VEC4, MODE, Q8>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kF2LdsBytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static LdsLimitOnce lds_limit;   // per template instance
+    if (hipError_t e = lds_limit.set(reinterpret_cast<const void*>(&f2_conv_kernel<LAYOUT, VEC4, MODE, Q8>), kF2LdsBytes)) return e;
     dim3 grid(ceil_div(p.T, kF2Tiles), p.Kp / kF2Filters);
     f2_conv_kernel<LAYOUT, VEC4, MODE, Q8><<<grid, 256, kF2LdsBytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p, ab, q8);
     return hipGetLastError();
@@ -697,13 +692,8 @@ hipError_t launch_mode(const int8_t* x, const uint8_t* blob, const F2BlobLayout&
 template <int LAYOUT, bool VEC4>
 hipError_t launch_act_scaled(const int8_t* x, const uint8_t* blob, const F2BlobLayout& bl, int32_t* y, int32_t* act_table,
                              const Problem& p, const ActivationBias& ab, hipStream_t s) {
-    static bool configured = false;   // per template instance
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&f2_conv_act_scaled_kernel<LAYOUT, VEC4>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kF2LdsBytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static LdsLimitOnce lds_limit;   // per template instance
+    if (hipError_t e = lds_limit.set(reinterpret_cast<const void*>(&f2_conv_act_scaled_kernel<LAYOUT, VEC4>), kF2LdsBytes)) return e;
     dim3 grid(ceil_div(p.T, kF2Tiles), p.Kp / kF2Filters);
     f2_conv_act_scaled_kernel<LAYOUT, VEC4><<<grid, 256, kF2LdsBytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, act_table,
                                                                           p, ab);

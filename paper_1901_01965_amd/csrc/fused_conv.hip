@@ -20,6 +20,7 @@
 // two filter planes per value) and a complex product as its four real products,
 // instead of the three-multiplication forms of Section 3.1 that the staged
 // contraction kernel uses; those would need half again as many operand planes.
+#include <atomic>
 #include <type_traits>
 #include <utility>
 
@@ -1170,13 +1171,8 @@ template <int LAYOUT, bool VEC4, int MODE, bool SUMS, bool Q8>
 hipError_t launch_roles(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
                         const Int8Epilogue& q8, hipStream_t s) {
     constexpr int lds_bytes = 2 * kLdsBytes;
-    static bool configured = false;   // per template instance
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_conv_roles_kernel<LAYOUT, VEC4, MODE, SUMS, Q8>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static LdsLimitOnce lds_limit;   // per template instance
+    if (hipError_t e = lds_limit.set(reinterpret_cast<const void*>(&fused_conv_roles_kernel<LAYOUT, VEC4, MODE, SUMS, Q8>), lds_bytes)) return e;
     dim3 grid(ceil_div(p.T, kFusedTiles), p.Kp / kFusedFilters);
     fused_conv_roles_kernel<LAYOUT, VEC4, MODE, SUMS, Q8><<<grid, 512, lds_bytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p, q8);
     return hipGetLastError();
@@ -1184,15 +1180,13 @@ hipError_t launch_roles(const int8_t* x, const uint8_t* blob, const BlobLayout& 
 
 // Compute units of the current device (256 on MI355X), asked once.
 int compute_units() {
-    static int cus = 0;
-    if (cus == 0) {
+    static const int cus = [] {
         int dev = 0, n = 0;
         if (hipGetDevice(&dev) == hipSuccess &&
             hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cus = n;
-        else
-            cus = 256;
-    }
+            return n;
+        return 256;
+    }();
     return cus;
 }
 
@@ -1366,9 +1360,10 @@ __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __
 
 // Workgroups per filter block of the streaming kernel: about one workgroup per compute unit in
 // total (a test hook can set a smaller number, so that small problems stream, too).
-int g_stream_workgroups = 0;
+std::atomic<int> g_stream_workgroups{0};
 int stream_workgroups(int tile_blocks, int filter_blocks) {
-    const int wanted = g_stream_workgroups > 0 ? g_stream_workgroups : compute_units() / filter_blocks;
+    const int forced = g_stream_workgroups.load(std::memory_order_relaxed);
+    const int wanted = forced > 0 ? forced : compute_units() / filter_blocks;
     return std::max(1, std::min(tile_blocks, wanted));
 }
 
@@ -1376,13 +1371,8 @@ template <int MODE, bool Q8>
 hipError_t launch_stream(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
                          const Int8Epilogue& q8, hipStream_t s) {
     constexpr int lds_bytes = 2 * kLdsBytes + 16;   // two plane buffers and the transform waves' barrier counter
-    static bool configured = false;   // per template instance
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_conv_stream_kernel<MODE, Q8>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static LdsLimitOnce lds_limit;   // per template instance
+    if (hipError_t e = lds_limit.set(reinterpret_cast<const void*>(&fused_conv_stream_kernel<MODE, Q8>), lds_bytes)) return e;
     const int tile_blocks = ceil_div(p.T, kFusedTiles), filter_blocks = p.Kp / kFusedFilters;
     const int gx = stream_workgroups(tile_blocks, filter_blocks);
     fused_conv_stream_kernel<MODE, Q8><<<dim3(gx, filter_blocks), 512, lds_bytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p,
@@ -1396,12 +1386,8 @@ hipError_t launch(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, in
     constexpr int lds_bytes = kLdsBytes + (LOAD == kLoadDirect ? kRawBytes : 0);
     const void* kernel = Q8 ? reinterpret_cast<const void*>(&fused_conv_int8_kernel<LAYOUT, LOAD, MODE, SUMS, WIDE>)
                             : reinterpret_cast<const void*>(&fused_conv_kernel<LAYOUT, LOAD, MODE, SUMS, WIDE>);
-    static bool configured = false;   // per template instance
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static LdsLimitOnce lds_limit;   // per template instance
+    if (hipError_t e = lds_limit.set(kernel, lds_bytes)) return e;
     dim3 grid(ceil_div(p.T, kFusedTiles), p.Kp / (kFusedFilters * (WIDE ? 2 : 1)));
     if constexpr (Q8)
         fused_conv_int8_kernel<LAYOUT, LOAD, MODE, SUMS, WIDE><<<grid, 256, lds_bytes, s>>>(x, blob, bl.table_off, bl.planes_off, p, q8);
@@ -1449,7 +1435,7 @@ hipError_t launch_layout(const int8_t* x, const uint8_t* b, const BlobLayout& bl
 
 }  // namespace
 
-void set_stream_workgroups(int n) { g_stream_workgroups = n > 0 ? n : 0; }
+void set_stream_workgroups(int n) { g_stream_workgroups.store(n > 0 ? n : 0, std::memory_order_relaxed); }
 
 hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int layout, int mode,
                              const Int8Epilogue& q8, hipStream_t s) {
@@ -1461,7 +1447,7 @@ hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, cons
     // and drain of its pipeline cost more than the overlap saves), or when a test asks for it.
     const bool can_stream = layout == WG_NHWC && p.C % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 4 == 0 && (p.K & 3) == 0;
     const int tile_blocks = ceil_div(p.T, kFusedTiles), filter_blocks = p.Kp / kFusedFilters;
-    if (can_stream && (g_stream_workgroups > 0 || tile_blocks >= 6 * stream_workgroups(tile_blocks, filter_blocks))) {
+    if (can_stream && (g_stream_workgroups.load(std::memory_order_relaxed) > 0 || tile_blocks >= 6 * stream_workgroups(tile_blocks, filter_blocks))) {
         if (mode == WG_LOSSLESS)
             return q8.out ? launch_stream<WG_LOSSLESS, true>(x, b, bl, y, p, q8, s) : launch_stream<WG_LOSSLESS, false>(x, b, bl, y, p, q8, s);
         return q8.out ? launch_stream<WG_SCALED, true>(x, b, bl, y, p, q8, s) : launch_stream<WG_SCALED, false>(x, b, bl, y, p, q8, s);

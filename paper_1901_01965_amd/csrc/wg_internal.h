@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "winograd_c.h"
 
 namespace wg {
@@ -235,6 +237,19 @@ hipError_t launch_unpack_filter_planes(const void* blob, int8_t* dense, int32_t*
                                        int mode, hipStream_t s);
 hipError_t launch_unpack_accumulators(const int32_t* M, int32_t* dense, const Problem& p, int mode,
                                       hipStream_t s);
+
+// Raises a kernel's dynamic LDS limit the first time its launcher runs; safe when several host
+// threads make that first call together.  Every call returns the status of the one attempt.
+struct LdsLimitOnce {
+    std::once_flag once;
+    hipError_t status = hipSuccess;
+    hipError_t set(const void* kernel, int lds_bytes) {
+        std::call_once(once, [&] {
+            status = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        });
+        return status;
+    }
+};
 
 // True on the device when the blob header matches; kernels that consume a blob
 // return without side effects otherwise.

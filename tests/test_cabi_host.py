@@ -159,9 +159,11 @@ def test_validation_errors_return_before_any_launch(lib):
     assert f2a(good, good2, good3, 1, 4, 8, 8, 4, 0, odd, None) == EINVAL        # misaligned table export
     assert f2a(good, good2, good3, 1, 1000, 8, 8, 4, 0, None, None) == EUNSUPPORTED
 
-    st = lib.winograd_conv2d_int8_stage_times
-    assert st(good, good2, good3, 1, 4, 8, 8, 4, 0, 0, p(0x40000), ws_bytes, None, 0, good) == EINVAL
-    assert st(good, good2, good3, 1, 4, 8, 8, 4, 0, 0, p(0x40000), ws_bytes, None, 1, None) == EINVAL
+    st = lib.winograd_conv2d_int8_enqueue_stage
+    assert st(good, good2, good3, 1, 4, 8, 8, 4, 0, 0, p(0x40000), ws_bytes, None, 0, 0) == EINVAL    # iters < 1
+    assert st(good, good2, good3, 1, 4, 8, 8, 4, 0, 0, p(0x40000), ws_bytes, None, 4, 1) == EINVAL    # unknown stage
+    assert st(good, good2, good3, 1, 4, 8, 8, 4, 0, 0, None, ws_bytes, None, 0, 1) == EINVAL          # no workspace
+    assert st(good, good2, good3, 1, 4, 8, 8, 4, 0, 0, p(0x40000), ws_bytes - 1, None, 0, 1) == ESMALLBUF
     assert lib.winograd_packed_filter_check(None, 4, 4, 0, None) == EINVAL
     assert lib.winograd_debug_input_operands(None, good, 1, 4, 8, 8, 0, 0, good2, big, None) == EINVAL
     assert lib.winograd_debug_filter_operands(good2, 4, 4, 3, good, good3, None) == EINVAL
