@@ -114,6 +114,25 @@ int winograd_conv2d_int8(const int8_t* x_dev, const void* packed_dev, int32_t* y
                          void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * For callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid it): winograd_conv2d_int8's staged
+ * pipeline (input transform, contraction, output transform) with its workspace
+ * in a buffer of winograd_static_workspace_limit() bytes (64 MiB) that is part
+ * of the library's device image, one per GPU, held until the process ends.  The
+ * call allocates nothing; its first use on a device asks the runtime for the
+ * buffer's address there.  Same arguments, results and error codes as
+ * winograd_conv2d_int8 without the workspace pair; WG_ESMALLBUF if
+ * winograd_workspace_bytes(N, C, H, W, K, mode) exceeds the limit, nothing
+ * enqueued.  Every call on a GPU uses that GPU's one buffer, whatever the
+ * stream: calls that overlap in time on one GPU race.  The buffer keeps the
+ * last call's contents; no call depends on them.
+ */
+size_t winograd_static_workspace_limit(void);
+int winograd_conv2d_int8_static_workspace(const int8_t* x_dev, const void* packed_dev, int32_t* y_dev,
+                                          int N, int C, int H, int W, int K, int layout, int mode,
+                                          void* hip_stream);
+
+/*
  * The same convolution with the requantisation that follows each quantised
  * convolution in a network (Section 4.4) applied before the store, so a layer
  * stack passes int8 from layer to layer and the int32 outputs never reach

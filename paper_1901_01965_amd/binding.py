@@ -52,6 +52,8 @@ def load_library():
         "winograd_packed_filter_check": (i, [vp, i, i, i, vp]),
         "winograd_conv2d_int8": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp, sz, vp]),
         "winograd_conv2d_int8_requant": (i, [vp, vp, vp, i, i, i, i, i, i, i, i, i, i, vp]),
+        "winograd_static_workspace_limit": (sz, []),
+        "winograd_conv2d_int8_static_workspace": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp]),
         "winograd_f2x2_packed_filter_bytes": (sz, [i, i, i]),
         "winograd_f2x2_filter_transform": (i, [vp, i, i, i, i, vp, sz, vp]),
         "winograd_f2x2_conv2d_int8": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp]),
@@ -79,6 +81,7 @@ EXPORTED_SYMBOLS = (
     "winograd_debug_force_path", "winograd_debug_stream_workgroups", "winograd_conv2d_path", "winograd_debug_tile_decode",
     "winograd_packed_filter_bytes", "winograd_workspace_bytes", "winograd_filter_transform",
     "winograd_packed_filter_check", "winograd_conv2d_int8", "winograd_conv2d_int8_requant",
+    "winograd_static_workspace_limit", "winograd_conv2d_int8_static_workspace",
     "winograd_conv2d_int8_enqueue_stage",
     "direct_conv2d_int8", "requant_relu_pool_int8",
     "winograd_debug_input_operands", "winograd_debug_filter_operands", "winograd_debug_contraction",
@@ -213,6 +216,25 @@ def winograd_conv2d_int8(x, packed, layout=NCHW, out=None, workspace=None):
     _check(load_library().winograd_conv2d_int8(_ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout,
                                                packed.mode, _ptr(workspace), workspace.numel(), _stream()),
            "winograd_conv2d_int8")
+    return out
+
+
+def static_workspace_limit():
+    return int(load_library().winograd_static_workspace_limit())
+
+
+def winograd_conv2d_int8_static_workspace(x, packed, layout=NCHW, out=None):
+    """winograd_conv2d_int8's staged pipeline through the scratch buffer inside the library: the call itself
+    allocates nothing (`out` given), and raises WG_ESMALLBUF beyond static_workspace_limit()."""
+    layout = _LAYOUTS[layout]
+    _need(x, torch.int8, "x")
+    N, C, H, W = _dims(x, layout)
+    _match(packed, PackedFilter, C, "winograd_conv2d_int8_static_workspace")
+    K = packed.K
+    out = _out(out, (N, K, H, W) if layout == NCHW else (N, H, W, K), torch.int32, x.device)
+    _check(load_library().winograd_conv2d_int8_static_workspace(_ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K,
+                                                                layout, packed.mode, _stream()),
+           "winograd_conv2d_int8_static_workspace")
     return out
 
 
