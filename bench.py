@@ -343,6 +343,8 @@ def main():
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     ap.add_argument("--algorithm", default="f4x4", choices=("f4x4", "f2x2"),
                     help="f4x4: the complex F(4x4,3x3) path (the headline); f2x2: the rational F(2x2,3x3) path")
+    ap.add_argument("--lossless-variant", type=int, default=0, choices=(0, 1, 2),
+                    help="lossless single-kernel form: 0 the library's choice, 1 limb-pair form wherever possible, 2 never")
     ap.add_argument("--stack", action="store_true",
                     help="time the VGG-16-shaped stack (cfg5) instead of one layer; prints its own JSON line")
     args = ap.parse_args()
@@ -350,6 +352,9 @@ def main():
         sys.exit("bench.py: this build measures one GPU only (the path has no cross-GPU step); use --gpus 1")
     if args.mode == "both-scaled" and (args.stack or args.algorithm != "f2x2"):
         sys.exit("bench.py: --mode both-scaled exists for --algorithm f2x2 only")
+    if args.lossless_variant:
+        import paper_1901_01965_amd as wg_
+        wg_.lossless_variant(args.lossless_variant)
     if args.stack:
         return run_stack(args)
     if args.algorithm == "f2x2":

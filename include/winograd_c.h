@@ -302,6 +302,12 @@ int winograd_debug_force_path(int path);
    workgroups per filter block; 0 restores the library's own choice.  Process-wide, like
    winograd_debug_force_path. */
 int winograd_debug_stream_workgroups(int n);
+/* Test hook for the single-kernel path in WG_LOSSLESS mode, which has two forms of the product phase: one whose
+   matrix-core filter operand carries both int8 limbs of eight filters (a wave owns complete outputs; channels-last
+   inputs with C % 4 = 0), and one with 16 filters per operand and the rows of the Winograd-domain tile split over two
+   waves (any layout).  0: the library's choice, 1: the first form wherever the layout allows, 2: never the first
+   form.  Process-wide, like winograd_debug_force_path. */
+int winograd_debug_lossless_variant(int variant);
 int winograd_num_filter_planes(int mode);
 
 /* Host-only: the (n, ty, tx) the kernels derive from tile index t = (n*TH + ty)*TW + tx for

@@ -108,7 +108,7 @@ __device__ inline int scale_half_up(int v, int n, int p) { return (v * n + (1 <<
 __global__ __launch_bounds__(256) void filter_pack_kernel(const int8_t* w, int K, int C, int layout,
                                                           int mode, int Kp, int CB,
                                                           const ScaleEntry* table, int8_t* planes,
-                                                          int16_t* narrow) {
+                                                          int16_t* narrow, int8_t* pairs) {
     int c = blockIdx.x * 64 + (threadIdx.x & 63);
     int k = blockIdx.y * 4 + (threadIdx.x >> 6);
     if (k >= Kp) return;
@@ -140,6 +140,17 @@ __global__ __launch_bounds__(256) void filter_pack_kernel(const int8_t* w, int K
             put(16 + 3 * j + 0, cr[j]);
             put(16 + 3 * j + 1, ci[j]);
             put(16 + 3 * j + 2, cr[j] + ci[j]);
+        }
+        // the same values as byte-limb pairs, v = 256 h + l (l the low byte, signed), limbs in neighbouring rows
+        auto put_pair = [&](int value_index, int v) {
+            int8_t* at = pairs + filter_pair_offset(value_index, c >> 6, k, 0, c & 63, Kp);
+            at[0] = (int8_t)((v + 128) >> 8);
+            at[kCBlock] = (int8_t)(v & 0xff);
+        };
+        for (int e = 0; e < 16; ++e) put_pair(e, re[e]);
+        for (int j = 0; j < 10; ++j) {
+            put_pair(16 + 2 * j, cr[j]);
+            put_pair(17 + 2 * j, ci[j]);
         }
     } else {
         const ScaleEntry* tk = table + (size_t)k * kEntries;
@@ -197,7 +208,8 @@ hipError_t launch_filter_transform(const int8_t* w, int K, int C, int layout, in
         filter_maxmag_kernel<<<dim3(K, CB), 64, 0, s>>>(w, K, C, layout, maxmag);
     filter_table_kernel<<<ceil_div(entries, 256), 256, 0, s>>>(maxmag, table, entries, mode);
     int16_t* narrow = C <= kNarrowChannels ? reinterpret_cast<int16_t*>(blob + bl.narrow_off) : nullptr;
-    filter_pack_kernel<<<dim3(CB, ceil_div(Kp, 4)), 256, 0, s>>>(w, K, C, layout, mode, Kp, CB, table, planes, narrow);
+    int8_t* pairs = reinterpret_cast<int8_t*>(blob + bl.pairs_off);
+    filter_pack_kernel<<<dim3(CB, ceil_div(Kp, 4)), 256, 0, s>>>(w, K, C, layout, mode, Kp, CB, table, planes, narrow, pairs);
     return hipGetLastError();
 }
 

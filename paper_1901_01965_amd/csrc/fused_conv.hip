@@ -24,17 +24,15 @@
 #include <type_traits>
 #include <utility>
 
-#include "input_transform_core.h"
+#include "kernel_common.h"
 
 namespace wg {
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
 
-constexpr int kFusedTiles = 16;     // tiles per workgroup (rows of the 16x16x64 matrix-core product)
+constexpr int kFusedTiles = kTileBlock;   // tiles per workgroup (rows of the 16x16x64 matrix-core product)
 constexpr int kFusedFilters = 32;   // filters per workgroup: two 16-wide column blocks
 constexpr int kFusedPlanes = 72;    // two-limb activation planes (kSplitTwoLimb)
-constexpr int kPlaneBytes = kFusedTiles * kCBlock;   // one operand plane of the tile block in LDS
 constexpr int kLdsBytes = kFusedPlanes * kPlaneBytes;
 constexpr int kParkBytes = 4 * 16 * 64 * 16;         // four waves x 16 outputs x 64 lanes x 4 registers
 // How the activation patch reaches the transform threads (chosen on the host):
@@ -47,28 +45,6 @@ constexpr int kLoadBytes = 0, kLoadDwords = 1, kLoadDirect = 2;
 constexpr int kRawWaveBytes = 4 * 36 * kCBlock;      // raw patches of a wave's four tiles: 36 pixels x 64 channels
 constexpr int kRawBytes = 4 * kRawWaveBytes;
 static_assert(kParkBytes <= kLdsBytes, "output staging reuses the operand planes' LDS");
-
-// LDS operand plane: the 16-byte piece holding 16 consecutive channels (group c16) of a tile
-// sits in slot c16*16 + ((tile + 4*c16) & 15); lane l of a wave reads slot(l/16, l%16), which
-// tiles the plane without bank conflicts for the 4-byte writes as well as the 16-byte reads.
-__device__ inline int lds_slot(int c16, int tile) { return c16 * 16 + ((tile + 4 * c16) & 15); }
-
-struct LdsPlaneSink {
-    int8_t* base;
-    __device__ inline void put(int plane, uint32_t bytes) const {
-        *reinterpret_cast<uint32_t*>(base + plane * kPlaneBytes) = bytes;
-    }
-};
-
-// compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(<N-1>)
-template <class F, int... Is>
-__device__ inline void static_for_impl(F&& f, std::integer_sequence<int, Is...>) {
-    (f(std::integral_constant<int, Is>{}), ...);
-}
-template <int N, class F>
-__device__ inline void static_for(F&& f) {
-    static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
 
 // ---- per-entry programs ----------------------------------------------------------------
 // An entry's product uses a few activation fragments (from LDS) and filter fragments (from
@@ -152,52 +128,6 @@ template <int MODE> constexpr int b_slot_of(int half, int f) {
     int s = 0;
     while (b_start<MODE>(half, s + 1) <= f) ++s;
     return s;
-}
-
-// Row rule of A^T on (m0, m1, m2, m3, conj(m3), m5) with m0,m1,m2,m5 real:
-//   z0 = m0+m1+m2+2Re m3, z1 = m1-m2-2Im m3, z2 = m1+m2-2Re m3, z3 = m1-m2+2Im m3+m5
-__device__ inline void at_rule(v4i m0, v4i m1, v4i m2, v4i m3r, v4i m3i, v4i m5, v4i z[4]) {
-    const v4i s = m1 + m2, d = m1 - m2;
-    z[0] = m0 + s + 2 * m3r;
-    z[1] = d - 2 * m3i;
-    z[2] = s - 2 * m3r;
-    z[3] = d + 2 * m3i + m5;
-}
-
-// A finished row of M is reduced by the row rule and enters the 16 outputs with the
-// column-rule coefficients of A^T.  Real rows 0,1,2,5 (ROW = 0..3; entries m0,m1,m2,m5 real
-// at positions 0..3, complex m3 at position 4): row 0 -> y0; rows 1, 2 -> (+,+,+,+), (+,-,+,-);
-// row 5 -> y3.  The complex row 3 (ROW = 4; e0,e1,e2,e5 at positions 0..3, e3 = M[3][3] and
-// e4 = M[3][4] at 4, 5; row 4 of M is its conjugate): y0 += 2Re z, y1 -= 2Im z, y2 -= 2Re z,
-// y3 += 2Im z.
-template <int ROW>
-__device__ inline void finish_row(const v4i (&er)[6], const v4i (&ei)[6], v4i (&Y)[16]) {
-    if constexpr (ROW < 4) {
-        v4i z[4];
-        at_rule(er[0], er[1], er[2], er[4], ei[4], er[3], z);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (ROW == 0) Y[j] += z[j];
-            if (ROW == 1) { Y[j] += z[j]; Y[4 + j] += z[j]; Y[8 + j] += z[j]; Y[12 + j] += z[j]; }
-            if (ROW == 2) { Y[j] += z[j]; Y[4 + j] -= z[j]; Y[8 + j] += z[j]; Y[12 + j] -= z[j]; }
-            if (ROW == 3) Y[12 + j] += z[j];
-        }
-    } else {
-        const v4i sr = er[4] + er[5], si = ei[4] + ei[5], dr = er[4] - er[5], di = ei[4] - ei[5];
-        const v4i ar = er[1] + er[2], ai = ei[1] + ei[2], br = er[1] - er[2], bi = ei[1] - ei[2];
-        v4i zr[4], zi[4];
-        zr[0] = er[0] + ar + sr;   zi[0] = ei[0] + ai + si;
-        zr[1] = br - di;           zi[1] = bi + dr;            // (e1-e2) + i (e3-e4)
-        zr[2] = ar - sr;           zi[2] = ai - si;
-        zr[3] = br + di + er[3];   zi[3] = bi - dr + ei[3];    // (e1-e2) - i (e3-e4) + e5
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            Y[j] += 2 * zr[j];
-            Y[4 + j] -= 2 * zi[j];
-            Y[8 + j] -= 2 * zr[j];
-            Y[12 + j] += 2 * zi[j];
-        }
-    }
 }
 
 // Direct global -> LDS transfer of the raw 6x6 patches of a wave's four tiles (one 64-channel
@@ -438,19 +368,6 @@ struct ScaledSums {
 };
 constexpr int kChannelSums = 18;
 static_assert(ScaledSums<0>::kSums == kChannelSums && ScaledSums<1>::kSums == kChannelSums, "both halves keep 18 sums");
-
-// The optional int8 epilogue: v = (y + round) >> shift clamped to [lo, 127].
-__device__ inline int requantise(int y, const Int8Epilogue& q) {
-    return min(max((y + q.round) >> q.shift, q.lo), 127);
-}
-__device__ inline v4i requantise(v4i y, const Int8Epilogue& q) {
-    y = (y + q.round) >> q.shift;
-    const v4i lo = {q.lo, q.lo, q.lo, q.lo}, hi = {127, 127, 127, 127};
-    return __builtin_elementwise_min(__builtin_elementwise_max(y, lo), hi);
-}
-__device__ inline uint32_t pack_bytes(v4i v) {
-    return (uint32_t)(v[0] & 0xff) | ((uint32_t)(v[1] & 0xff) << 8) | ((uint32_t)(v[2] & 0xff) << 16) | ((uint32_t)v[3] << 24);
-}
 
 // Who a thread is when the four product waves store their outputs, and where its tile lies.
 struct StoreContext {
@@ -972,56 +889,6 @@ struct ResidentScaled {
 };
 static_assert(ResidentScaled<0>::kAcc == 36 && ResidentScaled<1>::kAcc == 36, "both halves keep 36 accumulators");
 
-// Patch loads of the role-specialised kernels go through a buffer descriptor over the activation
-// tensor: a load whose offset lies beyond the tensor returns zero, so a pixel outside the image
-// (pad 1, ragged tiles) is an offset that can never be in range instead of a select per pixel and
-// channel block.  Offsets of rows and columns outside the image are kOutsideOffset; they are
-// combined with a saturating addition, so that any sum with an outside part stays at or above
-// 2^31, more than the tensor can hold (the host checks N*C*H*W < 2^31).
-constexpr uint32_t kOutsideOffset = 0x80000000u;
-constexpr int kRawBufferWord3 = 0x00020000;   // untyped 32-bit data, as for every raw buffer on this target
-__device__ inline __amdgpu_buffer_rsrc_t activation_buffer(const int8_t* x, const Problem& p) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(x), 0, p.N * p.H * p.W * p.C, kRawBufferWord3);
-}
-// Offsets (relative to x, channel c_lane of the pixel) of the 6x6 patch of tile (n, ty, tx).
-__device__ inline void patch_offsets(const Problem& p, int n, int ty, int tx, int c_lane, uint32_t pixel[36]) {
-    const int h0 = 4 * ty - 1, w0 = 4 * tx - 1;
-    const uint32_t image = (uint32_t)n * (uint32_t)p.H * (uint32_t)p.W * (uint32_t)p.C + (uint32_t)c_lane;
-    uint32_t row_off[6], col_off[6];
-#pragma unroll
-    for (int a = 0; a < 6; ++a) {
-        row_off[a] = (unsigned)(h0 + a) < (unsigned)p.H ? image + (uint32_t)(h0 + a) * (uint32_t)p.W * (uint32_t)p.C : kOutsideOffset;
-        col_off[a] = (unsigned)(w0 + a) < (unsigned)p.W ? (uint32_t)(w0 + a) * (uint32_t)p.C : kOutsideOffset;
-    }
-#pragma unroll
-    for (int a = 0; a < 6; ++a)
-#pragma unroll
-        for (int b = 0; b < 6; ++b) pixel[6 * a + b] = __builtin_elementwise_add_sat(row_off[a], col_off[b]);
-}
-// One channel block of the patch: 36 loads, nothing waits for them here.  pixel[] holds the
-// offsets of the lane's channel group in channel block 0; the block is a uniform offset on top.
-// Only the last channel block of a C that is not a multiple of 64 has channel groups beyond C:
-// there (a uniform branch) such a lane asks for the outside offset, so that it gets zeros and
-// never touches memory next to the tensor.
-__device__ inline void request_patch(__amdgpu_buffer_rsrc_t xbuf, const Problem& p, const uint32_t pixel[36], int cb,
-                                     int c_lane, uint32_t patch[6][6]) {
-    if ((cb + 1) * kCBlock > p.C) {
-        const bool have = cb * kCBlock + c_lane < p.C;
-#pragma unroll
-        for (int i = 0; i < 36; ++i)
-            patch[i / 6][i % 6] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(xbuf, have ? pixel[i] : kOutsideOffset, cb * kCBlock, 0);
-    } else {
-#pragma unroll
-        for (int i = 0; i < 36; ++i)
-            patch[i / 6][i % 6] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(xbuf, pixel[i], cb * kCBlock, 0);
-    }
-}
-// u = x + 128 on every byte; what does not exist arrived as zeros, i.e. x = 0.
-__device__ inline void bias_buffer_patch(uint32_t patch[6][6]) {
-#pragma unroll
-    for (int i = 0; i < 36; ++i) patch[i / 6][i % 6] ^= kBiasBytes;
-}
-
 // The same computation for layers with several channel blocks, with the two kinds of work on
 // different waves.  Eight waves: waves 0-3 only transform (vector ALU), waves 4-7 only multiply
 // (matrix cores, joins, output transform); each SIMD hosts one of each, so the transform of
@@ -1447,7 +1314,20 @@ hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, cons
     // and drain of its pipeline cost more than the overlap saves), or when a test asks for it.
     const bool can_stream = layout == WG_NHWC && p.C % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 4 == 0 && (p.K & 3) == 0;
     const int tile_blocks = ceil_div(p.T, kFusedTiles), filter_blocks = p.Kp / kFusedFilters;
-    if (can_stream && (g_stream_workgroups.load(std::memory_order_relaxed) > 0 || tile_blocks >= 6 * stream_workgroups(tile_blocks, filter_blocks))) {
+    const bool streams = can_stream && (g_stream_workgroups.load(std::memory_order_relaxed) > 0 ||
+                                        tile_blocks >= 6 * stream_workgroups(tile_blocks, filter_blocks));
+    // Lossless mode, channels-last, one channel block, too few tile blocks to stream over: the limb-pair form (eight waves
+    // per 16 tiles x 32 filters, lossless_conv.hip) against this file's four-wave forms, by rounds of the compute units:
+    // measured on 56x56x64 layers, a round of the former takes 6.5 us, a round of the latter 7.4 us with 32 filters per
+    // workgroup (a grid of at most one round) and 11.7 us with 64 filters.
+    if (mode == WG_LOSSLESS && !streams) {
+        const int form = lossless_pair_conv_choice(x, p, layout);   // 0: not applicable or switched off, 1: the library decides, 2: forced
+        const long long w32 = (long long)tile_blocks * filter_blocks, cus = compute_units();
+        const double pair_cost = 6.5 * (double)((w32 + cus - 1) / cus);
+        const double here_cost = w32 <= cus ? 7.4 : 11.7 * (double)((w32 / 2 + cus - 1) / cus);
+        if (form == 2 || (form == 1 && p.CB == 1 && pair_cost < here_cost)) return launch_lossless_pair_conv(x, blob, y, p, q8, s);
+    }
+    if (streams) {
         if (mode == WG_LOSSLESS)
             return q8.out ? launch_stream<WG_LOSSLESS, true>(x, b, bl, y, p, q8, s) : launch_stream<WG_LOSSLESS, false>(x, b, bl, y, p, q8, s);
         return q8.out ? launch_stream<WG_SCALED, true>(x, b, bl, y, p, q8, s) : launch_stream<WG_SCALED, false>(x, b, bl, y, p, q8, s);

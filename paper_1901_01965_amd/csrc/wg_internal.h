@@ -84,12 +84,13 @@ __host__ __device__ inline int num_filter_planes(int mode) { return mode == WG_L
 // ---- packed filter blob -------------------------------------------------------
 // [BlobHeader, 256 B][maxmag: uint32 [Kp][26]][table: ScaleEntry [Kp][26]]
 // [operand planes: int8 [CB][Kp/16][planes][16][64]][narrow table, only when C <= 4:
-// int16 [Kp][36][4]], each section 256-byte aligned.
+// int16 [Kp][36][4]][limb-pair planes, lossless only: int8 [CB][Kp/8][36][8 filters x 2 limbs][64]],
+// each section 256-byte aligned.
 // The operand planes are fragment-major: the 1 KB piece (16 filters x 64 channels) that one
 // matrix-core instruction consumes is contiguous, and all planes of a (channel block, filter
 // block) follow each other, so a kernel steps from plane to plane with constant offsets.
 constexpr uint32_t kBlobMagic = 0x33344757u;  // "WG43"
-constexpr uint32_t kBlobVersion = 3;
+constexpr uint32_t kBlobVersion = 4;
 
 struct BlobHeader {
     uint32_t magic, version;
@@ -130,8 +131,18 @@ constexpr int kNarrowChannels = 4;
 constexpr int kNarrowValues = 36;
 constexpr int kNarrowFilterBytes = kNarrowValues * kNarrowChannels * 2;   // 288 per filter
 
+// Lossless blobs also carry every Winograd-domain value as a pair of byte limbs, v = 256 h + l with l the
+// low byte of v read as a signed int8 and h = (v + 128) >> 8 in [-8, 8], laid out so that the two limbs of
+// a filter are neighbouring ROWS of one matrix-core operand: a 1 KB fragment holds 8 filters x (h, l) x 64
+// channels of one value.  Values: the 16 real entries, then (Re, Im) of each of the 10 complex entries.
+constexpr int kPairValues = 36;
+constexpr int kPairFilters = 8;   // filters per fragment
+__host__ __device__ inline size_t filter_pair_offset(int value, int cb, int k, int limb, int c64, int Kp) {
+    return (((((size_t)cb * (Kp >> 3) + (k >> 3)) * kPairValues + value) * 16 + 2 * (k & 7) + limb) * kCBlock) + c64;
+}
+
 struct BlobLayout {
-    size_t maxmag_off, table_off, planes_off, narrow_off, total;
+    size_t maxmag_off, table_off, planes_off, narrow_off, pairs_off, total;
 };
 inline BlobLayout blob_layout(int Kp, int C, int mode) {
     const int CB = (C + kCBlock - 1) / kCBlock;
@@ -140,7 +151,8 @@ inline BlobLayout blob_layout(int Kp, int C, int mode) {
     b.table_off = round_up(b.maxmag_off + (size_t)Kp * kEntries * sizeof(uint32_t), 256);
     b.planes_off = round_up(b.table_off + (size_t)Kp * kEntries * sizeof(ScaleEntry), 256);
     b.narrow_off = round_up(b.planes_off + (size_t)num_filter_planes(mode) * CB * Kp * kCBlock, 256);
-    b.total = b.narrow_off + (C <= kNarrowChannels ? (size_t)Kp * kNarrowFilterBytes : 0);
+    b.pairs_off = round_up(b.narrow_off + (C <= kNarrowChannels ? (size_t)Kp * kNarrowFilterBytes : 0), 256);
+    b.total = b.pairs_off + (mode == WG_LOSSLESS ? (size_t)kPairValues * CB * Kp * 2 * kCBlock : 0);
     return b;
 }
 
@@ -224,6 +236,14 @@ hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, cons
 // Test hook: n > 0 makes the single-kernel path use its streaming variant wherever the layout
 // allows, with n workgroups per filter block; 0 restores the library's own choice.
 void set_stream_workgroups(int n);
+// Single-kernel path, lossless mode, channels-last with C % 4 == 0: the form whose filter operand carries
+// both limbs of eight filters (see lossless_conv.hip).  set_lossless_variant: 0 the library's choice,
+// 1 this form wherever the layout allows, 2 never (test hook).
+hipError_t launch_lossless_pair_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p,
+                                     const Int8Epilogue& q8, hipStream_t s);
+// 0: this form does not apply (layout) or is switched off, 1: applies, the dispatcher decides, 2: forced by the test hook
+int lossless_pair_conv_choice(const int8_t* x, const Problem& p, int layout);
+void set_lossless_variant(int v);
 // Single-kernel path for channels-last inputs with C <= kNarrowChannels.
 hipError_t launch_narrow_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int mode,
                               const Int8Epilogue& q8, hipStream_t s);
@@ -256,6 +276,24 @@ struct LdsLimitOnce {
 __device__ inline bool blob_matches(const BlobHeader* h, int K, int C, int mode) {
     return h->magic == kBlobMagic && h->version == kBlobVersion && h->K == K && h->C == C &&
            h->mode == mode;
+}
+
+// The same check in two steps, for kernels that want the header's load in flight while they do other work: the
+// first eight dwords in one scalar load, compared later without short-circuit evaluation (which would turn the
+// comparison into a chain of dependent loads).
+struct BlobHeaderWords {
+    uint32_t w[8];
+};
+__device__ inline BlobHeaderWords read_blob_header(const void* blob) {
+    const uint32_t* h = static_cast<const uint32_t*>(__builtin_assume_aligned(blob, 256));
+    BlobHeaderWords out;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) out.w[i] = h[i];
+    return out;
+}
+__device__ inline bool blob_matches(const BlobHeaderWords& h, int K, int C, int mode) {
+    static_assert(offsetof(BlobHeader, mode) == 16, "magic, version, K, C, mode are the first five dwords");
+    return (h.w[0] == kBlobMagic) & (h.w[1] == kBlobVersion) & ((int)h.w[2] == K) & ((int)h.w[3] == C) & ((int)h.w[4] == mode);
 }
 
 }  // namespace wg
