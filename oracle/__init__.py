@@ -21,8 +21,21 @@ _SRCS = [os.path.join(_HERE, "winograd_oracle.c"), os.path.join(_HERE, "winograd
 _LIB = os.path.join(_HERE, "liboracle.so")
 
 
-def build(force=False):
-    """Compile the oracle with gcc -O2 (OpenMP over the outermost loops only)."""
+_CHECK_SRC = os.path.join(_HERE, "sanitize_check.c")
+_CHECK_BIN = os.path.join(_HERE, "sanitize_check")
+
+
+def build(force=False, sanitize=False):
+    """Compile the oracle with gcc -O2 (OpenMP over the outermost loops only).  sanitize=True builds instead the
+    self-checking program sanitize_check.c together with the oracle's sources under AddressSanitizer and
+    UndefinedBehaviorSanitizer (any finding aborts the program) and returns its path."""
+    if sanitize:
+        srcs = _SRCS + [_CHECK_SRC]
+        if force or not os.path.exists(_CHECK_BIN) or os.path.getmtime(_CHECK_BIN) < max(os.path.getmtime(s) for s in srcs):
+            subprocess.check_call(
+                ["gcc", "-O1", "-g", "-std=c11", "-fopenmp", "-Wall", "-fsanitize=address,undefined",
+                 "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-o", _CHECK_BIN] + srcs + ["-lm"])
+        return _CHECK_BIN
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(s) for s in _SRCS):
         subprocess.check_call(
             ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-o", _LIB] + _SRCS
@@ -303,6 +316,37 @@ def direct_conv2d_i16(x, g):
     flags = lib().oracle_direct_conv2d_i16(_p(x), _p(g), _p(y), N, C, H, W, K)
     assert flags == 0, "output does not fit int32"
     return y
+
+
+def input_transform_i16(x):
+    """D = B^T d B of int16 (int9) activations: int64 [T, C, 6, 6, 2]."""
+    x = _i16(x)
+    N, C, H, W = x.shape
+    out = np.zeros((tiles(N, H, W), C, 6, 6, 2), np.int64)
+    lib().oracle_input_transform_i16(_p(x), N, C, H, W, _p(out))
+    return out
+
+
+def filter_transform_i16(g):
+    """W = G' g G'^T of int16 (int9) filters: int64 [K, C, 6, 6, 2]."""
+    g = _i16(g)
+    K, C = g.shape[:2]
+    out = np.zeros((K, C, 6, 6, 2), np.int64)
+    lib().oracle_filter_transform_i16(_p(g), K, C, _p(out))
+    return out
+
+
+def winograd_conv2d_i16(x, g, mode=LOSSLESS, weight_range=127):
+    """Whole complex-Winograd path on int16 inputs (int9 values).  Returns (y int32 NCHW, flags)."""
+    x, g = _i16(x), _i16(g)
+    N, C, H, W = x.shape
+    K = g.shape[0]
+    assert g.shape == (K, C, 3, 3)
+    y = np.zeros((N, K, H, W), np.int32)
+    flags = lib().oracle_winograd_conv2d_i16(_p(x), _p(g), _p(y), N, C, H, W, K, mode, ctypes.c_int64(weight_range))
+    if flags < 0:
+        raise MemoryError("oracle ran out of memory")
+    return y, int(flags)
 
 
 def f2_filter_transform_i16(g):

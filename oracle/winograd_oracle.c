@@ -28,6 +28,10 @@
  *                               PARITY UNPINNED: the paper prints no worked example
  *                               for it, only the 1.12 / 0.1% mean-error statistics
  *                               (used as a weak pin on the rounding mode).
+ *   *_i16 variants              the same definitions on 16-bit inputs: the quantised tensors of
+ *                               Section 4.1 (uint8 minus zero point = int9); lossless pinned by
+ *                               exact equality with the 16-bit direct convolution, the int8
+ *                               functions on int8 data, and the 16 * 255 = 4080 worst case
  *   oracle_requant_relu_pool    not in the paper (harness glue); pinned by a numpy
  *                               one-liner on small inputs only.
  *
@@ -516,6 +520,84 @@ int oracle_winograd_conv2d(const int8_t* x, const int8_t* g, int32_t* y, int N, 
     if (mode == 1) oracle_scale_filters(Wt, K, C, range, tab, mx);
     for (int n = 0; n < N; ++n) {
         oracle_input_transform(x + (size_t)n * C * H * W, 1, C, H, W, D);
+        oracle_contract(D, Wt, Timg, C, K, M);
+        if (mode == 1) oracle_inverse_scale(M, Timg, K, tab);
+        flags |= oracle_output_transform(M, 1, K, H, W, 4, mode == 1 ? 8 : 0,
+                                         y + (size_t)n * K * H * W);
+    }
+done:
+    free(Wt); free(tab); free(mx); free(D); free(M);
+    return flags;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Section 4.1's data model: tensors quantised to uint8 with a zero point are    */
+/* the integers byte - zero_point in [-255, 255] (int9), carried here as int16.  */
+/* The same definitions as above, written out again for 16-bit inputs.           */
+
+void oracle_input_transform_i16(const int16_t* x, int N, int C, int H, int W, int64_t* out) {
+    int TH = ceil_div(H, 4), TW = ceil_div(W, 4);
+    #pragma omp parallel for collapse(2)
+    for (int n = 0; n < N; ++n)
+        for (int ty = 0; ty < TH; ++ty)
+            for (int tx = 0; tx < TW; ++tx) {
+                size_t t = ((size_t)n * TH + ty) * TW + tx;
+                for (int c = 0; c < C; ++c) {
+                    int64_t d[6][6];
+                    gint D[6][6];
+                    for (int a = 0; a < 6; ++a)
+                        for (int b = 0; b < 6; ++b) {
+                            int hh = 4 * ty - 1 + a, ww = 4 * tx - 1 + b;
+                            d[a][b] = (hh < 0 || hh >= H || ww < 0 || ww >= W)
+                                          ? 0
+                                          : x[(((size_t)n * C + c) * H + hh) * W + ww];
+                        }
+                    tile_input_transform(d, D);
+                    int64_t* o = out + (t * C + c) * 72;
+                    for (int r = 0; r < 6; ++r)
+                        for (int cc = 0; cc < 6; ++cc) {
+                            o[(r * 6 + cc) * 2 + 0] = D[r][cc].re;
+                            o[(r * 6 + cc) * 2 + 1] = D[r][cc].im;
+                        }
+                }
+            }
+}
+
+void oracle_filter_transform_i16(const int16_t* g, int K, int C, int64_t* out) {
+    #pragma omp parallel for
+    for (int k = 0; k < K; ++k)
+        for (int c = 0; c < C; ++c) {
+            int64_t f[3][3];
+            gint Wt[6][6];
+            for (int a = 0; a < 3; ++a)
+                for (int b = 0; b < 3; ++b) f[a][b] = g[(((size_t)k * C + c) * 3 + a) * 3 + b];
+            tile_filter_transform(f, Wt);
+            int64_t* o = out + ((size_t)k * C + c) * 72;
+            for (int r = 0; r < 6; ++r)
+                for (int cc = 0; cc < 6; ++cc) {
+                    o[(r * 6 + cc) * 2 + 0] = Wt[r][cc].re;
+                    o[(r * 6 + cc) * 2 + 1] = Wt[r][cc].im;
+                }
+        }
+}
+
+/* Whole path on 16-bit inputs; modes, range and return value as oracle_winograd_conv2d
+   (flag 4: an output did not fit int32, which int9 data can reach from 230 channels on). */
+int oracle_winograd_conv2d_i16(const int16_t* x, const int16_t* g, int32_t* y, int N, int C, int H,
+                               int W, int K, int mode, int64_t range) {
+    int TH = ceil_div(H, 4), TW = ceil_div(W, 4);
+    int64_t Timg = (int64_t)TH * TW;
+    int64_t* Wt = (int64_t*)malloc((size_t)K * C * 72 * sizeof(int64_t));
+    int32_t* tab = (int32_t*)malloc((size_t)K * 36 * 4 * sizeof(int32_t));
+    int64_t* mx = (int64_t*)malloc((size_t)K * 36 * sizeof(int64_t));
+    int64_t* D = (int64_t*)malloc((size_t)Timg * C * 72 * sizeof(int64_t));
+    int64_t* M = (int64_t*)malloc((size_t)Timg * K * 72 * sizeof(int64_t));
+    int flags = 0;
+    if (!Wt || !tab || !mx || !D || !M) { flags = -1; goto done; }
+    oracle_filter_transform_i16(g, K, C, Wt);
+    if (mode == 1) oracle_scale_filters(Wt, K, C, range, tab, mx);
+    for (int n = 0; n < N; ++n) {
+        oracle_input_transform_i16(x + (size_t)n * C * H * W, 1, C, H, W, D);
         oracle_contract(D, Wt, Timg, C, K, M);
         if (mode == 1) oracle_inverse_scale(M, Timg, K, tab);
         flags |= oracle_output_transform(M, 1, K, H, W, 4, mode == 1 ? 8 : 0,
