@@ -114,6 +114,33 @@ int winograd_conv2d_int8(const int8_t* x_dev, const void* packed_dev, int32_t* y
                          void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The same path on the quantised tensors of Section 4.1: unsigned int8 bytes
+ * with a zero point (0..255) that is subtracted from every byte, i.e. integers
+ * in [-255, 255] (int9): y = sum (x - zero_x) (w - zero_w) in int32, with padding
+ * pixels contributing nothing (they read as the zero point).  G' g G'^T then
+ * reaches 16 * 255 = 4080 (13 bits, the 4 extra bits of Section 3.4 on top of
+ * int9) and B^T d B likewise; WG_SCALED brings the 13-bit filters into +-127
+ * (factors down to 15/2^9) and keeps the activations as two int8 limbs.
+ * winograd_filter_transform_u8: w_dev uint8 in `layout`; same blob size, alignment
+ * and error codes as winograd_filter_transform.  winograd_conv2d_u8: x_dev uint8,
+ * y_dev int32, every element written; needs no workspace.  The two go together:
+ * winograd_conv2d_u8 accepts only blobs from winograd_filter_transform_u8 and
+ * winograd_conv2d_int8 only blobs from winograd_filter_transform (a mismatch
+ * leaves y untouched; winograd_packed_filter_check accepts both kinds).  Signed
+ * int8 filters w enter as the bytes w + 128 with zero point 128.
+ * Channels: the path forms 16 y in int32 and |y| can reach 9 C 255^2, so
+ * C <= 229 (16 * 9 * 229 * 255^2 < 2^31); more return WG_EUNSUPPORTED.  Up to
+ * there WG_LOSSLESS equals the int9 direct convolution bit for bit (sums inside
+ * the path may wrap modulo 2^32; the result does not).  WG_SCALED results
+ * approximate it and are exact functions of the inputs as in winograd_conv2d_int8;
+ * data that drive 16 |y| to within about 1 % of 2^31 can wrap there.
+ */
+int winograd_filter_transform_u8(const uint8_t* w_dev, int zero_point, int K, int C, int layout, int mode,
+                                 void* packed_dev, size_t packed_bytes, void* hip_stream);
+int winograd_conv2d_u8(const uint8_t* x_dev, int zero_point, const void* packed_dev, int32_t* y_dev,
+                       int N, int C, int H, int W, int K, int layout, int mode, void* hip_stream);
+
+/*
  * For callers that cannot allocate device memory (code under HIP graph capture,
  * tight serving loops, harnesses that forbid it): winograd_conv2d_int8's staged
  * pipeline (input transform, contraction, output transform) with its workspace

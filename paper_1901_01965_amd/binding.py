@@ -59,6 +59,8 @@ def load_library():
         "winograd_f2x2_filter_transform": (i, [vp, i, i, i, i, vp, sz, vp]),
         "winograd_f2x2_conv2d_int8": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp]),
         "winograd_f2x2_debug_filter_operands": (i, [vp, i, i, i, vp, vp, vp]),
+        "winograd_filter_transform_u8": (i, [vp, i, i, i, i, i, vp, sz, vp]),
+        "winograd_conv2d_u8": (i, [vp, i, vp, vp, i, i, i, i, i, i, i, vp]),
         "winograd_f2x2_filter_transform_u8": (i, [vp, i, i, i, i, i, vp, sz, vp]),
         "winograd_f2x2_conv2d_u8": (i, [vp, i, vp, vp, i, i, i, i, i, i, i, vp]),
         "winograd_f2x2_conv2d_int8_act_scaled": (i, [vp, vp, vp, i, i, i, i, i, i, vp, vp]),
@@ -89,6 +91,7 @@ EXPORTED_SYMBOLS = (
     "winograd_f2x2_packed_filter_bytes", "winograd_f2x2_filter_transform", "winograd_f2x2_conv2d_int8",
     "winograd_f2x2_debug_filter_operands", "winograd_f2x2_filter_transform_u8", "winograd_f2x2_conv2d_u8",
     "winograd_f2x2_conv2d_int8_act_scaled", "winograd_f2x2_conv2d_int8_requant",
+    "winograd_filter_transform_u8", "winograd_conv2d_u8",
 )
 
 
@@ -136,7 +139,7 @@ def _out(out, shape, dtype, device, what="out"):
 def _match(packed, cls, C, what):
     """The blob must be of the right algorithm and made for the activation's channel count: the kernels only
     find a mismatch on the device, where all they can do is leave the output untouched."""
-    if not isinstance(packed, cls):
+    if type(packed) is not cls:
         raise TypeError("%s needs a %s, got %s" % (what, cls.__name__, type(packed).__name__))
     if packed.C != C:
         raise ValueError("%s: the filters were packed for C = %d, the activations have C = %d" % (what, packed.C, C))
@@ -203,6 +206,39 @@ def winograd_filter_transform(w, layout=NCHW, mode=LOSSLESS, blob=None):
     _check(load_library().winograd_filter_transform(_ptr(w), K, C, layout, mode, _ptr(blob), blob.numel(), _stream()),
            "winograd_filter_transform")
     return PackedFilter(blob, K, C, mode)
+
+
+class PackedFilterU8(PackedFilter):
+    """Blob made from uint8 filters with a zero point (13-bit Winograd-domain values); goes with winograd_conv2d_u8."""
+
+
+MAX_CHANNELS_U8 = 229
+
+
+def winograd_filter_transform_u8(w, zero_point, layout=NCHW, mode=LOSSLESS):
+    """w: uint8 [K,C,3,3] (NCHW) or [K,3,3,C] (NHWC) on the GPU, the filters being w - zero_point -> PackedFilterU8."""
+    layout, mode = _LAYOUTS[layout], _MODES[mode]
+    _need(w, torch.uint8, "w")
+    K = w.shape[0]
+    C = w.shape[1] if layout == NCHW else w.shape[3]
+    nbytes = packed_filter_bytes(K, C, mode)
+    blob = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=w.device)
+    _check(load_library().winograd_filter_transform_u8(_ptr(w), int(zero_point), K, C, layout, mode, _ptr(blob), nbytes,
+                                                       _stream()), "winograd_filter_transform_u8")
+    return PackedFilterU8(blob, K, C, mode)
+
+
+def winograd_conv2d_u8(x, zero_point, packed, layout=NCHW, out=None):
+    """x: uint8 activations in `layout`, the values being x - zero_point; packed: PackedFilterU8.  int32 output."""
+    layout = _LAYOUTS[layout]
+    _need(x, torch.uint8, "x")
+    N, C, H, W = _dims(x, layout)
+    _match(packed, PackedFilterU8, C, "winograd_conv2d_u8")
+    K = packed.K
+    out = _out(out, (N, K, H, W) if layout == NCHW else (N, H, W, K), torch.int32, x.device)
+    _check(load_library().winograd_conv2d_u8(_ptr(x), int(zero_point), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout,
+                                             packed.mode, _stream()), "winograd_conv2d_u8")
+    return out
 
 
 def make_workspace(N, C, H, W, K, mode, device="cuda"):

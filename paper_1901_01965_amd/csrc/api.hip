@@ -50,8 +50,31 @@ int winograd_filter_transform(const int8_t* w_dev, int K, int C, int layout, int
     if (int st = check_filter_shape(K, C)) return st;
     if (!aligned(w_dev, 4) || !aligned(packed_dev, 256)) return WG_EINVAL;
     if (packed_bytes < winograd_packed_filter_bytes(K, C, mode)) return WG_ESMALLBUF;
-    return status_of(launch_filter_transform(w_dev, K, C, layout, mode, packed_dev,
+    return status_of(launch_filter_transform(w_dev, 0, 0, K, C, layout, mode, packed_dev,
                                              static_cast<hipStream_t>(hip_stream)));
+}
+
+int winograd_filter_transform_u8(const uint8_t* w_dev, int zero_point, int K, int C, int layout, int mode, void* packed_dev,
+                                 size_t packed_bytes, void* hip_stream) {
+    if (!w_dev || !packed_dev || !valid_layout(layout) || !valid_mode(mode)) return WG_EINVAL;
+    if (zero_point < 0 || zero_point > 255) return WG_EINVAL;
+    if (int st = check_filter_shape(K, C)) return st;
+    if (C > kMaxChannelsInt9) return WG_EUNSUPPORTED;
+    if (!aligned(w_dev, 4) || !aligned(packed_dev, 256)) return WG_EINVAL;
+    if (packed_bytes < winograd_packed_filter_bytes(K, C, mode)) return WG_ESMALLBUF;
+    return status_of(launch_filter_transform(reinterpret_cast<const int8_t*>(w_dev), 1, zero_point, K, C, layout, mode,
+                                             packed_dev, static_cast<hipStream_t>(hip_stream)));
+}
+
+int winograd_conv2d_u8(const uint8_t* x_dev, int zero_point, const void* packed_dev, int32_t* y_dev, int N, int C, int H,
+                       int W, int K, int layout, int mode, void* hip_stream) {
+    if (!x_dev || !packed_dev || !y_dev || !valid_layout(layout) || !valid_mode(mode)) return WG_EINVAL;
+    if (zero_point < 0 || zero_point > 255) return WG_EINVAL;
+    if (int st = check_shape(N, C, H, W, K)) return st;
+    if (C > kMaxChannelsInt9) return WG_EUNSUPPORTED;
+    if (!aligned(x_dev, 4) || !aligned(y_dev, 4) || !aligned(packed_dev, 256)) return WG_EINVAL;
+    return status_of(launch_fused_conv_u8(x_dev, zero_point, packed_dev, y_dev, make_problem(N, C, H, W, K), layout, mode,
+                                          static_cast<hipStream_t>(hip_stream)));
 }
 
 int winograd_packed_filter_check(const void* packed_dev, int K, int C, int mode, void* hip_stream) {
@@ -61,7 +84,7 @@ int winograd_packed_filter_check(const void* packed_dev, int K, int C, int mode,
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (hipMemcpyAsync(&h, packed_dev, sizeof h, hipMemcpyDeviceToHost, s) != hipSuccess) return WG_ERUNTIME;
     if (hipStreamSynchronize(s) != hipSuccess) return WG_ERUNTIME;
-    const bool ok = h.magic == kBlobMagic && h.version == kBlobVersion && h.K == K && h.C == C && h.mode == mode;
+    const bool ok = (h.magic == kBlobMagic || h.magic == kBlobMagicInt9) && h.version == kBlobVersion && h.K == K && h.C == C && h.mode == mode;
     return ok ? WG_OK : WG_EBLOB;
 }
 

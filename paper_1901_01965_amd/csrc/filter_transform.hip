@@ -41,20 +41,26 @@ __device__ inline void filter_entries(const int g[9], int re[16], int cr[10], in
     cr[9] = a[0] - a[2] + b[1];  ci[9] = b[0] - b[2] - a[1];   // (x0-x2) - i x1
 }
 
-__device__ inline void load_filter(const int8_t* w, int k, int c, int K, int C, int layout, int g[9]) {
+// How the stored filter bytes are read: signed int8, or uint8 minus a zero point (Section 4.1: int9).
+struct FilterBytes {
+    int is_unsigned, zero_point;
+    __device__ inline int value(int8_t b) const { return is_unsigned ? (int)(uint8_t)b - zero_point : (int)b; }
+};
+
+__device__ inline void load_filter(const int8_t* w, FilterBytes fb, int k, int c, int K, int C, int layout, int g[9]) {
     if (k >= K || c >= C) {
         for (int i = 0; i < 9; ++i) g[i] = 0;
         return;
     }
     for (int i = 0; i < 9; ++i)
-        g[i] = (layout == WG_NCHW) ? w[((size_t)k * C + c) * 9 + i] : w[((size_t)k * 9 + i) * C + c];
+        g[i] = fb.value((layout == WG_NCHW) ? w[((size_t)k * C + c) * 9 + i] : w[((size_t)k * 9 + i) * C + c]);
 }
 
-__global__ void blob_init_kernel(uint8_t* blob, int K, int C, int mode, int Kp, int CB, size_t maxmag_off) {
+__global__ void blob_init_kernel(uint8_t* blob, uint32_t magic, int K, int C, int mode, int Kp, int CB, size_t maxmag_off) {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i == 0) {
         BlobHeader* h = reinterpret_cast<BlobHeader*>(blob);
-        h->magic = kBlobMagic; h->version = kBlobVersion;
+        h->magic = magic; h->version = kBlobVersion;
         h->K = K; h->C = C; h->mode = mode; h->range = kWeightRange;
         h->Kp = Kp; h->CB = CB; h->planes = num_filter_planes(mode);
         for (int j = 0; j < 55; ++j) h->reserved[j] = 0;
@@ -65,11 +71,11 @@ __global__ void blob_init_kernel(uint8_t* blob, int K, int C, int mode, int Kp, 
 // Step 2 of Section 4.2: the largest magnitude over input channels at every
 // (filter, entry); a complex entry counts max(|Re|, |Im|).  One wave per
 // (filter, 64-channel block): shuffle reduction, then one atomic per entry.
-__global__ __launch_bounds__(64) void filter_maxmag_kernel(const int8_t* w, int K, int C, int layout,
+__global__ __launch_bounds__(64) void filter_maxmag_kernel(const int8_t* w, FilterBytes fb, int K, int C, int layout,
                                                            uint32_t* maxmag) {
     int k = blockIdx.x, c = blockIdx.y * 64 + threadIdx.x;
     int g[9], re[16], cr[10], ci[10];
-    load_filter(w, k, c, K, C, layout, g);
+    load_filter(w, fb, k, c, K, C, layout, g);
     filter_entries(g, re, cr, ci);
     for (int e = 0; e < kEntries; ++e) {
         int m = e < 16 ? abs(re[e]) : max(abs(cr[e - 16]), abs(ci[e - 16]));
@@ -88,7 +94,7 @@ __global__ void filter_table_kernel(const uint32_t* maxmag, ScaleEntry* table, i
     ScaleEntry s = {0, 0, 1, 0};
     int mx = (int)maxmag[i];
     if (mode == WG_SCALED && mx > kWeightRange) {
-        const int num = kWeightRange * 128;          // mx <= 2048 < num, so y >= 2
+        const int num = kWeightRange * 128;          // mx <= 16 * 255 = 4080 < num / 2, so y >= 1 (int8 filters: mx <= 2048, y >= 2)
         int y = 0;
         while ((mx << (y + 1)) <= num) ++y;
         s.n = (num * 8) / (mx << y);
@@ -105,7 +111,7 @@ __device__ inline int scale_half_up(int v, int n, int p) { return (v * n + (1 <<
 
 // Writes the operand planes.  One thread per (filter row k < Kp, channel c < 64*CB);
 // rows and channels beyond K, C are written as zeros so the contraction needs no masks.
-__global__ __launch_bounds__(256) void filter_pack_kernel(const int8_t* w, int K, int C, int layout,
+__global__ __launch_bounds__(256) void filter_pack_kernel(const int8_t* w, FilterBytes fb, int K, int C, int layout,
                                                           int mode, int Kp, int CB,
                                                           const ScaleEntry* table, int8_t* planes,
                                                           int16_t* narrow, int8_t* pairs) {
@@ -113,7 +119,7 @@ __global__ __launch_bounds__(256) void filter_pack_kernel(const int8_t* w, int K
     int k = blockIdx.y * 4 + (threadIdx.x >> 6);
     if (k >= Kp) return;
     int g[9], re[16], cr[10], ci[10];
-    load_filter(w, k, c, K, C, layout, g);
+    load_filter(w, fb, k, c, K, C, layout, g);
     filter_entries(g, re, cr, ci);
     const size_t plane_stride = kFilterFragBytes;
     int8_t* base = planes + filter_plane_offset(0, c >> 6, k, c & 63, Kp, num_filter_planes(mode));
@@ -194,8 +200,9 @@ __global__ void unpack_filter_planes_kernel(const int8_t* planes, const ScaleEnt
 
 }  // namespace
 
-hipError_t launch_filter_transform(const int8_t* w, int K, int C, int layout, int mode, void* blob_v,
-                                   hipStream_t s) {
+hipError_t launch_filter_transform(const int8_t* w, int is_unsigned, int zero_point, int K, int C, int layout, int mode,
+                                   void* blob_v, hipStream_t s) {
+    const FilterBytes fb = {is_unsigned, zero_point};
     uint8_t* blob = static_cast<uint8_t*>(blob_v);
     const int Kp = ceil_div(K, kFilterPad) * kFilterPad, CB = ceil_div(C, kCBlock);
     const BlobLayout bl = blob_layout(Kp, C, mode);
@@ -203,13 +210,14 @@ hipError_t launch_filter_transform(const int8_t* w, int K, int C, int layout, in
     ScaleEntry* table = reinterpret_cast<ScaleEntry*>(blob + bl.table_off);
     int8_t* planes = reinterpret_cast<int8_t*>(blob + bl.planes_off);
     const int entries = Kp * kEntries;
-    blob_init_kernel<<<ceil_div(entries, 256), 256, 0, s>>>(blob, K, C, mode, Kp, CB, bl.maxmag_off);
+    blob_init_kernel<<<ceil_div(entries, 256), 256, 0, s>>>(blob, is_unsigned ? kBlobMagicInt9 : kBlobMagic, K, C, mode, Kp, CB,
+                                                            bl.maxmag_off);
     if (mode == WG_SCALED)
-        filter_maxmag_kernel<<<dim3(K, CB), 64, 0, s>>>(w, K, C, layout, maxmag);
+        filter_maxmag_kernel<<<dim3(K, CB), 64, 0, s>>>(w, fb, K, C, layout, maxmag);
     filter_table_kernel<<<ceil_div(entries, 256), 256, 0, s>>>(maxmag, table, entries, mode);
     int16_t* narrow = C <= kNarrowChannels ? reinterpret_cast<int16_t*>(blob + bl.narrow_off) : nullptr;
     int8_t* pairs = reinterpret_cast<int8_t*>(blob + bl.pairs_off);
-    filter_pack_kernel<<<dim3(CB, ceil_div(Kp, 4)), 256, 0, s>>>(w, K, C, layout, mode, Kp, CB, table, planes, narrow, pairs);
+    filter_pack_kernel<<<dim3(CB, ceil_div(Kp, 4)), 256, 0, s>>>(w, fb, K, C, layout, mode, Kp, CB, table, planes, narrow, pairs);
     return hipGetLastError();
 }
 

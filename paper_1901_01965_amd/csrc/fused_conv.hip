@@ -566,10 +566,13 @@ __device__ __forceinline__ void store_block(const StoreContext& sc, const Proble
 // outputs; used when there are more workgroups than compute units, where halving the number of
 // repeated transforms outweighs the longer workgroup.
 // Q8: the finished outputs are requantised (and pooled) to int8 at q8.out instead of stored to y.
-template <int LAYOUT, int LOAD, int MODE, bool SUMS, bool WIDE, bool Q8>
+// ENC: how the activation bytes are read (signed int8, or uint8 with a zero point: Section 4.1); the latter only
+// with the load paths that select padding explicitly, and with blobs made from uint8 filters.
+template <int LAYOUT, int LOAD, int MODE, bool SUMS, bool WIDE, bool Q8, class ENC = SignedInt8>
 __device__ __forceinline__ void fused_conv_body(const int8_t* __restrict__ x, const uint8_t* __restrict__ blob,
                                                 size_t table_off, size_t planes_off, int32_t* __restrict__ y,
-                                                const Problem p, const Int8Epilogue q8) {
+                                                const Problem p, const Int8Epilogue q8, const ENC enc = ENC{}) {
+    static_assert(LOAD != kLoadDirect || ENC::kMagic == kBlobMagic, "direct transfers deliver zero bytes for absent pixels");
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kblock = wave & 1, half = wave >> 1;
@@ -636,9 +639,9 @@ __device__ __forceinline__ void fused_conv_body(const int8_t* __restrict__ x, co
     constexpr bool VEC4 = LOAD == kLoadDwords;
     uint32_t patch[6][6];
     if constexpr (LOAD != kLoadDirect) {
-        if (a_t < p.T) load_patch<LAYOUT, VEC4>(x, p, a_n, a_ty, a_tx, 4 * a_cq, patch);
+        if (a_t < p.T) load_patch<LAYOUT, VEC4>(x, p, a_n, a_ty, a_tx, 4 * a_cq, patch, enc);
     }
-    if (!blob_matches(reinterpret_cast<const BlobHeader*>(blob), p.K, p.C, MODE)) return;
+    if (!blob_matches(reinterpret_cast<const BlobHeader*>(blob), p.K, p.C, MODE, ENC::kMagic)) return;
 
     ProductPhase<MODE, 0> phase0;
     ProductPhase<MODE, 1> phase1;
@@ -670,11 +673,11 @@ __device__ __forceinline__ void fused_conv_body(const int8_t* __restrict__ x, co
             }
         }
         if (a_t < p.T) {
-            bias_patch(p, a_ty, a_tx, cb * kCBlock + 4 * a_cq, patch);
-            transform_patch(patch, out);
+            bias_patch(p, a_ty, a_tx, cb * kCBlock + 4 * a_cq, patch, enc);
+            transform_patch(patch, out, enc);
             if constexpr (LOAD != kLoadDirect) {
                 if (cb + 1 < p.CB)   // next block's patch travels while this block's products run
-                    load_patch<LAYOUT, VEC4>(x, p, a_n, a_ty, a_tx, (cb + 1) * kCBlock + 4 * a_cq, patch);
+                    load_patch<LAYOUT, VEC4>(x, p, a_n, a_ty, a_tx, (cb + 1) * kCBlock + 4 * a_cq, patch, enc);
             }
         }
         // the operand planes are complete once every wave's LDS writes have landed; global
@@ -736,6 +739,13 @@ __global__ __launch_bounds__(256) void fused_conv_int8_kernel(const int8_t* __re
                                                               const uint8_t* __restrict__ blob, size_t table_off,
                                                               size_t planes_off, Problem p, Int8Epilogue q8) {
     fused_conv_body<LAYOUT, LOAD, MODE, SUMS, WIDE, true>(x, blob, table_off, planes_off, nullptr, p, q8);
+}
+
+template <int LAYOUT, int LOAD, int MODE, bool SUMS>
+__global__ __launch_bounds__(256) void fused_conv_u8_kernel(const int8_t* __restrict__ x, ZeroPointU8 zero,
+                                                            const uint8_t* __restrict__ blob, size_t table_off,
+                                                            size_t planes_off, int32_t* __restrict__ y, Problem p) {
+    fused_conv_body<LAYOUT, LOAD, MODE, SUMS, false, false, ZeroPointU8>(x, blob, table_off, planes_off, y, p, Int8Epilogue{}, zero);
 }
 
 // Product phase of the role-specialised kernel: the same arithmetic as ProductPhase / ScaledSums
@@ -1300,7 +1310,39 @@ hipError_t launch_layout(const int8_t* x, const uint8_t* b, const BlobLayout& bl
     return launch_mode<WG_NCHW, kLoadBytes, Q8>(x, b, bl, y, p, mode, q8, s);
 }
 
+template <int LAYOUT, int LOAD, int MODE, bool SUMS>
+hipError_t launch_u8(const int8_t* x, ZeroPointU8 zero, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
+                     hipStream_t s) {
+    static LdsLimitOnce lds_limit;   // per template instance
+    if (hipError_t e = lds_limit.set(reinterpret_cast<const void*>(&fused_conv_u8_kernel<LAYOUT, LOAD, MODE, SUMS>), kLdsBytes)) return e;
+    dim3 grid(ceil_div(p.T, kFusedTiles), p.Kp / kFusedFilters);
+    fused_conv_u8_kernel<LAYOUT, LOAD, MODE, SUMS><<<grid, 256, kLdsBytes, s>>>(x, zero, blob, bl.table_off, bl.planes_off, y, p);
+    return hipGetLastError();
+}
+
+template <int LAYOUT, int LOAD>
+hipError_t launch_u8_mode(const int8_t* x, ZeroPointU8 zero, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
+                          int mode, hipStream_t s) {
+    if (mode == WG_LOSSLESS) return launch_u8<LAYOUT, LOAD, WG_LOSSLESS, false>(x, zero, blob, bl, y, p, s);
+    if (p.CB == 1) return launch_u8<LAYOUT, LOAD, WG_SCALED, false>(x, zero, blob, bl, y, p, s);
+    return launch_u8<LAYOUT, LOAD, WG_SCALED, true>(x, zero, blob, bl, y, p, s);
+}
+
 }  // namespace
+
+// uint8 activations with a zero point: the four-wave kernel with the load paths that select padding pixels explicitly
+// (they must read as the zero point, not as zero bytes), for every channel count the int9 path accepts.
+hipError_t launch_fused_conv_u8(const uint8_t* x_u8, int zero_point, const void* blob, int32_t* y, const Problem& p, int layout,
+                                int mode, hipStream_t s) {
+    const BlobLayout bl = blob_layout(p.Kp, p.C, mode);
+    const uint8_t* b = static_cast<const uint8_t*>(blob);
+    const int8_t* x = reinterpret_cast<const int8_t*>(x_u8);
+    const ZeroPointU8 zero = make_zero_point(zero_point);
+    if (layout == WG_NHWC && p.C % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 4 == 0)
+        return launch_u8_mode<WG_NHWC, kLoadDwords>(x, zero, b, bl, y, p, mode, s);
+    if (layout == WG_NHWC) return launch_u8_mode<WG_NHWC, kLoadBytes>(x, zero, b, bl, y, p, mode, s);
+    return launch_u8_mode<WG_NCHW, kLoadBytes>(x, zero, b, bl, y, p, mode, s);
+}
 
 void set_stream_workgroups(int n) { g_stream_workgroups.store(n > 0 ? n : 0, std::memory_order_relaxed); }
 

@@ -8,6 +8,7 @@
 // zero at every entry of B^T d B except (1,1), where the sixteen +1 coefficients
 // add up: D(u) = D(x) + 2048 at (1,1) only, so the bias is removed by one
 // subtraction.  Padding pixels and channels beyond C carry the bias value 128.
+// uint8 tensors with a zero point z (Section 4.1) are the same form with bias z and no XOR.
 #pragma once
 #include "wg_internal.h"
 
@@ -36,14 +37,39 @@ __device__ inline uint32_t pack_high_bytes(Quad v) { return __builtin_amdgcn_per
 
 constexpr uint32_t kBiasBytes = 0x80808080u;
 
+// How the stored bytes encode the integers x that are convolved.  The transform always works on
+// non-negative bytes u = x + bias; the encoding says how a stored byte becomes u (an XOR), which
+// byte stands for x = 0 (what padding pixels and channels beyond C must read as), and what the
+// bias leaves at entry (1,1), in both 16-bit lanes.
+//   SignedInt8:   x is the byte read as int8, u = byte ^ 0x80 = x + 128;
+//   ZeroPointU8:  the quantised tensors of Section 4.1: x = byte - zero_point, an integer in
+//                 [-255, 255]; u is the byte itself, the bias is the zero point.
+struct SignedInt8 {
+    static constexpr uint32_t kMagic = kBlobMagic;       // goes with blobs of signed int8 filters
+    __device__ inline uint32_t flip() const { return kBiasBytes; }
+    __device__ inline uint32_t absent_stored() const { return 0u; }     // the stored byte of x = 0 ...
+    __device__ inline uint32_t absent() const { return kBiasBytes; }    // ... and its u, in all four bytes
+    __device__ inline uint32_t bias11() const { return 0x08000800u; }   // 16 * 128
+};
+struct ZeroPointU8 {
+    static constexpr uint32_t kMagic = kBlobMagicInt9;   // goes with blobs of uint8 filters with a zero point
+    uint32_t zero_bytes;     // the zero point in all four bytes
+    uint32_t zero_sixteen;   // 16 * zero point in both 16-bit halves
+    __device__ inline uint32_t flip() const { return 0u; }
+    __device__ inline uint32_t absent_stored() const { return zero_bytes; }
+    __device__ inline uint32_t absent() const { return zero_bytes; }
+    __device__ inline uint32_t bias11() const { return zero_sixteen; }
+};
+inline ZeroPointU8 make_zero_point(int z) { return ZeroPointU8{(uint32_t)z * 0x01010101u, (uint32_t)(16 * z) * 0x00010001u}; }
+
 // The 6x6 input patch of one tile, four consecutive channels c0..c0+3 per pixel, as raw loads:
 // addresses are clamped into the image so no load sits behind a branch and nothing here waits
 // for data; bias_patch() then applies the bias and replaces out-of-range pixels.
 // VEC4 (channels-last input whose C is a multiple of four, chosen on the host): one 4-byte
 // load per pixel; a channel group is then either wholly inside or wholly beyond C.
-template <int LAYOUT, bool VEC4>
+template <int LAYOUT, bool VEC4, class ENC = SignedInt8>
 __device__ inline void load_patch(const int8_t* __restrict__ x, const Problem& p, int n, int ty, int tx, int c0,
-                                  uint32_t u[6][6]) {
+                                  uint32_t u[6][6], const ENC enc = ENC{}) {
     // Offsets fit 32 bits (the host checks N*C*H*W < 2^31): one multiply per patch row and
     // column instead of 64-bit address arithmetic per pixel.
     const int h0 = 4 * ty - 1, w0 = 4 * tx - 1;
@@ -77,16 +103,17 @@ __device__ inline void load_patch(const int8_t* __restrict__ x, const Problem& p
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const uint32_t e = (uint8_t)img[row_off[a] + col_off[b] + chan_off[i]];
-                    word |= (c0 + i < p.C ? e : 0u) << (8 * i);   // zero = no contribution beyond C
+                    word |= (c0 + i < p.C ? e : (enc.absent_stored() & 0xffu)) << (8 * i);   // x = 0 beyond C
                 }
                 u[a][b] = word;
             }
     }
 }
 
-// u = x + 128 on every byte; pixels outside the image (pad 1) and channel groups beyond C
+// u = x + bias on every byte; pixels outside the image (pad 1) and channel groups beyond C
 // become the bias value itself, i.e. x = 0.
-__device__ inline void bias_patch(const Problem& p, int ty, int tx, int c0, uint32_t u[6][6]) {
+template <class ENC = SignedInt8>
+__device__ inline void bias_patch(const Problem& p, int ty, int tx, int c0, uint32_t u[6][6], const ENC enc = ENC{}) {
     const int h0 = 4 * ty - 1, w0 = 4 * tx - 1;
     const bool have = c0 < p.C;
 #pragma unroll
@@ -94,7 +121,7 @@ __device__ inline void bias_patch(const Problem& p, int ty, int tx, int c0, uint
 #pragma unroll
         for (int b = 0; b < 6; ++b) {
             const bool inside = have && (unsigned)(h0 + a) < (unsigned)p.H && (unsigned)(w0 + b) < (unsigned)p.W;
-            u[a][b] = inside ? (u[a][b] ^ kBiasBytes) : kBiasBytes;
+            u[a][b] = inside ? (u[a][b] ^ enc.flip()) : enc.absent();
         }
 }
 
@@ -171,15 +198,15 @@ struct OperandSplitter {
 
 // Transforms one loaded patch (four channels) and hands every free entry to `out`
 // (real_entry(p, v), complex_entry(j, re, im)): an OperandSplitter emits the operand planes.
-template <class Out>
-__device__ inline void transform_patch(const uint32_t u[6][6], const Out& out) {
+template <class Out, class ENC = SignedInt8>
+__device__ inline void transform_patch(const uint32_t u[6][6], const Out& out, const ENC enc = ENC{}) {
     // column pass: d'[.][b] = B^T applied down each of the six tile columns
     Line col[6];
 #pragma unroll
     for (int b = 0; b < 6; ++b)
         col[b] = bt_rule(unpack_u8x4(u[0][b]), unpack_u8x4(u[1][b]), unpack_u8x4(u[2][b]), unpack_u8x4(u[3][b]),
                          unpack_u8x4(u[4][b]), unpack_u8x4(u[5][b]));
-    const s16x2 bias11 = {2048, 2048};   // what the +128 bias leaves at entry (1,1)
+    const s16x2 bias11 = as_s16x2(enc.bias11());   // what the bias leaves at entry (1,1): 16 * 128 for signed int8
     // row pass on the real rows 0,1,2,5 of d': entries (r, {0,1,2,5}) real, (r,3) complex
 #define WG_REAL_ROW(ri, field)                                                                      \
     {                                                                                               \

@@ -89,7 +89,10 @@ __host__ __device__ inline int num_filter_planes(int mode) { return mode == WG_L
 // The operand planes are fragment-major: the 1 KB piece (16 filters x 64 channels) that one
 // matrix-core instruction consumes is contiguous, and all planes of a (channel block, filter
 // block) follow each other, so a kernel steps from plane to plane with constant offsets.
-constexpr uint32_t kBlobMagic = 0x33344757u;  // "WG43"
+constexpr uint32_t kBlobMagic = 0x33344757u;       // "WG43": signed int8 filters, Winograd-domain values of 12 bits
+constexpr uint32_t kBlobMagicInt9 = 0x39344757u;   // "WG49": uint8 filters minus a zero point (int9), values of 13 bits
+// Channel limit of the int9 path: 16 y is formed in int32 and |y| <= 9 C 255^2, so 16 * 9 * C * 255^2 < 2^31.
+constexpr int kMaxChannelsInt9 = 229;
 constexpr uint32_t kBlobVersion = 4;
 
 struct BlobHeader {
@@ -210,8 +213,10 @@ inline WorkspaceLayout workspace_layout(const Problem& p, int mode) {
 }
 
 // ---- stage launchers (each enqueues on `s` and returns the launch status) --------
-hipError_t launch_filter_transform(const int8_t* w, int K, int C, int layout, int mode, void* blob,
-                                   hipStream_t s);
+// is_unsigned: the bytes are uint8 with the given zero point (values = byte - zero_point, the int9
+// of Section 4.1) and the blob gets kBlobMagicInt9; otherwise signed int8 and zero_point is ignored.
+hipError_t launch_filter_transform(const int8_t* w, int is_unsigned, int zero_point, int K, int C, int layout, int mode,
+                                   void* blob, hipStream_t s);
 hipError_t launch_input_transform(const int8_t* x, const Problem& p, int layout, int mode,
                                   int8_t* V, hipStream_t s);
 hipError_t launch_contraction(const int8_t* V, const void* blob, int32_t* M, const Problem& p,
@@ -244,6 +249,9 @@ hipError_t launch_lossless_pair_conv(const int8_t* x, const void* blob, int32_t*
 // 0: this form does not apply (layout) or is switched off, 1: applies, the dispatcher decides, 2: forced by the test hook
 int lossless_pair_conv_choice(const int8_t* x, const Problem& p, int layout);
 void set_lossless_variant(int v);
+// Single-kernel path for uint8 activations with a zero point and a kBlobMagicInt9 blob (C <= kMaxChannelsInt9).
+hipError_t launch_fused_conv_u8(const uint8_t* x, int zero_point, const void* blob, int32_t* y, const Problem& p, int layout,
+                                int mode, hipStream_t s);
 // Single-kernel path for channels-last inputs with C <= kNarrowChannels.
 hipError_t launch_narrow_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int mode,
                               const Int8Epilogue& q8, hipStream_t s);
@@ -273,8 +281,8 @@ struct LdsLimitOnce {
 
 // True on the device when the blob header matches; kernels that consume a blob
 // return without side effects otherwise.
-__device__ inline bool blob_matches(const BlobHeader* h, int K, int C, int mode) {
-    return h->magic == kBlobMagic && h->version == kBlobVersion && h->K == K && h->C == C &&
+__device__ inline bool blob_matches(const BlobHeader* h, int K, int C, int mode, uint32_t magic = kBlobMagic) {
+    return h->magic == magic && h->version == kBlobVersion && h->K == K && h->C == C &&
            h->mode == mode;
 }
 
