@@ -210,6 +210,25 @@ def inverse_scale(M, tab):
     return M
 
 
+def scale_activations(D, value_range=127):
+    """The rule of Section 4.2 applied per tile to [T,C,6,6,2] transformed activations: (scaled copy, table
+    [T,6,6,4] = (n,p,r,q), max [T,6,6])."""
+    D = np.array(D, dtype=np.int64, order="C", copy=True)
+    T, C = D.shape[:2]
+    tab = np.zeros((T, 6, 6, 4), np.int32)
+    mx = np.zeros((T, 6, 6), np.int64)
+    lib().oracle_scale_activations(_p(D), ctypes.c_int64(T), C, ctypes.c_int64(value_range), _p(tab), _p(mx))
+    return D, tab, mx
+
+
+def inverse_scale_tiles(M, atab):
+    M = np.array(M, dtype=np.int64, order="C", copy=True)
+    T, K = M.shape[:2]
+    atab = np.ascontiguousarray(atab, np.int32)
+    lib().oracle_inverse_scale_tiles(_p(M), ctypes.c_int64(T), K, _p(atab))
+    return M
+
+
 LOSSLESS, SCALED = 0, 1
 
 
@@ -273,7 +292,7 @@ def f2_scale_filters(Wt, weight_range=127):
     return Wt, tab, mx
 
 
-BOTH_SCALED = 2   # F(2x2,3x3) only: filters and activations scaled
+BOTH_SCALED = 2   # filters and activations scaled (signed int8 data)
 
 
 def f2_scale_activations(D, value_range=127):

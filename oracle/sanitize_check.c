@@ -51,6 +51,7 @@ static void one_shape(int N, int C, int K, int H, int W, int extremes) {
     if (oracle_winograd_conv2d(x, g, w, N, C, H, W, K, 0, 127) != 0) fail("lossless F(4x4,3x3) raised a flag");
     if (memcmp(y, w, 4 * ny)) fail("lossless F(4x4,3x3) != direct");
     if (oracle_winograd_conv2d(x, g, w, N, C, H, W, K, 1, 127) & 5) fail("scaled F(4x4,3x3) raised a flag");
+    if (oracle_winograd_conv2d(x, g, w, N, C, H, W, K, 2, 127) & 5) fail("F(4x4,3x3) with scaled activations raised a flag");
     if (oracle_f2_conv2d(x, g, w, N, C, H, W, K, 0, 127) & 5) fail("lossless F(2x2,3x3) raised a flag");
     if (memcmp(y, w, 4 * ny)) fail("lossless F(2x2,3x3) != direct");
     if (oracle_f2_conv2d(x, g, w, N, C, H, W, K, 1, 127) & 5) fail("scaled F(2x2,3x3) raised a flag");

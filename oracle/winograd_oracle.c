@@ -28,6 +28,16 @@
  *                               PARITY UNPINNED: the paper prints no worked example
  *                               for it, only the 1.12 / 0.1% mean-error statistics
  *                               (used as a weak pin on the rounding mode).
+ *   oracle_scale_activations, oracle_inverse_scale_tiles, mode 2 (activations scaled as well)
+ *                               Section 4.1 only remarks that the analysis of Section 4.2
+ *                               carries over to B^T d B; the rule here is that section's with
+ *                               a tile in the place of an output feature map (see the
+ *                               function).  Special cases pinned (no tile needs scaling =>
+ *                               equals mode 1; scaled activations within the range and
+ *                               conjugate-symmetric; table entries from the pinned factor
+ *                               routines; a tile's operands do not depend on other tiles; a
+ *                               single-tile case followed by hand); the general lossy result
+ *                               is PARITY UNPINNED.
  *   *_i16 variants              the same definitions on 16-bit inputs: the quantised tensors of
  *                               Section 4.1 (uint8 minus zero point = int9); lossless pinned by
  *                               exact equality with the 16-bit direct convolution, the int8
@@ -499,10 +509,95 @@ void oracle_inverse_scale(int64_t* M, int64_t T, int K, const int32_t* tab) {
         }
 }
 
+/* The remark that closes Section 4.1: the analysis of Section 4.2 applies to the
+   transformed activations B^T d B as well (12 bits here for int8 data), although
+   they cannot be prepared offline.  The rule below is Section 4.2's with a tile in
+   the place of an output feature map: for every tile and canonical location the
+   largest max(|Re|,|Im|) over the input channels decides one factor n/2^p (none if
+   it is within the range); Re and Im of every channel's value there are multiplied
+   by it, rounding half up; partner locations become the conjugates of the scaled
+   canonical ones.  D: [T][C][6][6][2] in place.  tab: [T][6][6][4] = (n, p, r, q)
+   at every location (partners repeat their canonical entry).  mx_out (may be NULL):
+   [T][6][6]. */
+void oracle_scale_activations(int64_t* D, int64_t T, int C, int64_t range, int32_t* tab,
+                              int64_t* mx_out) {
+    for (int64_t t = 0; t < T; ++t) {
+        for (int r = 0; r < 6; ++r)
+            for (int c = 0; c < 6; ++c) {
+                if (!is_canonical(r, c)) continue;
+                int e = r * 6 + c;
+                int64_t mx = 0;
+                for (int ch = 0; ch < C; ++ch) {
+                    const int64_t* d = D + ((size_t)t * C + ch) * 72;
+                    int64_t a = llabs(d[2 * e]), b = llabs(d[2 * e + 1]);
+                    if (a > mx) mx = a;
+                    if (b > mx) mx = b;
+                }
+                int32_t n, p, rr, q;
+                oracle_scale_factor(mx, range, &n, &p);
+                oracle_inverse_factor(n, p, &rr, &q);
+                if (n != 0)
+                    for (int ch = 0; ch < C; ++ch) {
+                        int64_t* d = D + ((size_t)t * C + ch) * 72;
+                        d[2 * e]     = scale_round(d[2 * e], n, p);
+                        d[2 * e + 1] = scale_round(d[2 * e + 1], n, p);
+                    }
+                int32_t* tb = tab + ((size_t)t * 36 + e) * 4;
+                tb[0] = n; tb[1] = p; tb[2] = rr; tb[3] = q;
+                if (mx_out) mx_out[(size_t)t * 36 + e] = mx;
+            }
+        for (int r = 0; r < 6; ++r)
+            for (int c = 0; c < 6; ++c) {
+                if (is_canonical(r, c)) continue;
+                int pr, pc; partner_of(r, c, &pr, &pc);
+                int e = r * 6 + c, pe = pr * 6 + pc;
+                for (int ch = 0; ch < C; ++ch) {
+                    int64_t* d = D + ((size_t)t * C + ch) * 72;
+                    d[2 * e] = d[2 * pe];
+                    d[2 * e + 1] = -d[2 * pe + 1];
+                }
+                memcpy(tab + ((size_t)t * 36 + e) * 4, tab + ((size_t)t * 36 + pe) * 4,
+                       4 * sizeof(int32_t));
+                if (mx_out) mx_out[(size_t)t * 36 + e] = mx_out[(size_t)t * 36 + pe];
+            }
+    }
+}
+
+/* The tile-side reverse scaling: oracle_inverse_scale with the table of the tile
+   instead of the filter's.  M: [T][K][6][6][2] in place, atab: [T][6][6][4]. */
+void oracle_inverse_scale_tiles(int64_t* M, int64_t T, int K, const int32_t* atab) {
+    #pragma omp parallel for
+    for (int64_t t = 0; t < T; ++t)
+        for (int k = 0; k < K; ++k) {
+            int64_t* m = M + ((size_t)t * K + k) * 72;
+            for (int r = 0; r < 6; ++r)
+                for (int c = 0; c < 6; ++c) {
+                    if (!is_canonical(r, c)) continue;
+                    int e = r * 6 + c;
+                    const int32_t* tb = atab + ((size_t)t * 36 + e) * 4;
+                    if (tb[0] == 0) continue;
+                    m[2 * e]     = scale_round(m[2 * e], tb[2], tb[3]);
+                    m[2 * e + 1] = scale_round(m[2 * e + 1], tb[2], tb[3]);
+                }
+            for (int r = 0; r < 6; ++r)
+                for (int c = 0; c < 6; ++c) {
+                    if (is_canonical(r, c)) continue;
+                    int pr, pc; partner_of(r, c, &pr, &pc);
+                    gint z = gi_conj(gi(m[2 * (pr * 6 + pc)], m[2 * (pr * 6 + pc) + 1]));
+                    m[2 * (r * 6 + c)] = z.re;
+                    m[2 * (r * 6 + c) + 1] = z.im;
+                }
+        }
+}
+
 /* ------------------------------------------------------------------------- */
 /* Whole path, one image at a time so memory stays bounded.                    */
 /* mode 0: lossless, y must equal the direct convolution bit for bit.          */
 /* mode 1: filter-scaled with weight range [-range, range].                    */
+/* mode 2: mode 1 with the activations of every tile scaled into the same      */
+/*         range too (oracle_scale_activations); a channel sum is multiplied   */
+/*         back first by the filter's reciprocal, then by the tile's, each     */
+/*         step rounding half up.                                              */
 /* Returns the OR of oracle_output_transform's flags over the images, or -1    */
 /* when memory runs out.                                                       */
 int oracle_winograd_conv2d(const int8_t* x, const int8_t* g, int32_t* y, int N, int C, int H,
@@ -514,19 +609,22 @@ int oracle_winograd_conv2d(const int8_t* x, const int8_t* g, int32_t* y, int N, 
     int64_t* mx = (int64_t*)malloc((size_t)K * 36 * sizeof(int64_t));
     int64_t* D = (int64_t*)malloc((size_t)Timg * C * 72 * sizeof(int64_t));
     int64_t* M = (int64_t*)malloc((size_t)Timg * K * 72 * sizeof(int64_t));
+    int32_t* atab = (int32_t*)malloc((size_t)Timg * 36 * 4 * sizeof(int32_t));
     int flags = 0;
-    if (!Wt || !tab || !mx || !D || !M) { flags = -1; goto done; }
+    if (!Wt || !tab || !mx || !D || !M || !atab) { flags = -1; goto done; }
     oracle_filter_transform(g, K, C, Wt);
-    if (mode == 1) oracle_scale_filters(Wt, K, C, range, tab, mx);
+    if (mode >= 1) oracle_scale_filters(Wt, K, C, range, tab, mx);
     for (int n = 0; n < N; ++n) {
         oracle_input_transform(x + (size_t)n * C * H * W, 1, C, H, W, D);
+        if (mode == 2) oracle_scale_activations(D, Timg, C, range, atab, NULL);
         oracle_contract(D, Wt, Timg, C, K, M);
-        if (mode == 1) oracle_inverse_scale(M, Timg, K, tab);
-        flags |= oracle_output_transform(M, 1, K, H, W, 4, mode == 1 ? 8 : 0,
+        if (mode >= 1) oracle_inverse_scale(M, Timg, K, tab);
+        if (mode == 2) oracle_inverse_scale_tiles(M, Timg, K, atab);
+        flags |= oracle_output_transform(M, 1, K, H, W, 4, mode >= 1 ? 8 : 0,
                                          y + (size_t)n * K * H * W);
     }
 done:
-    free(Wt); free(tab); free(mx); free(D); free(M);
+    free(Wt); free(tab); free(mx); free(D); free(M); free(atab);
     return flags;
 }
 
