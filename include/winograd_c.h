@@ -141,6 +141,33 @@ int winograd_conv2d_u8(const uint8_t* x_dev, int zero_point, const void* packed_
                        int N, int C, int H, int W, int K, int layout, int mode, void* hip_stream);
 
 /*
+ * The path with the activations scaled as well.  Section 4.1 ends with the
+ * remark that the analysis of Section 4.2 carries over to the activation
+ * transform B^T d B (12 bits here for int8 data) and leaves it out because it
+ * cannot be prepared offline; here it runs inside the convolution kernel.  The
+ * rule is that section's with a tile in the place of an output feature map: for
+ * each tile and each of its 26 free entries the largest max(|Re|, |Im|) over the
+ * input channels decides n/2^p (4-bit n; nothing if the maximum is within
+ * +-127), Re and Im of every channel's value there are multiplied by it,
+ * rounding half up, and a channel sum is multiplied back first by the filter's
+ * reciprocal r/2^q, then by the tile's (each step rounds half up).  Both
+ * operands of the Winograd-domain products are then single int8 values: half
+ * the matrix-core work of WG_SCALED, at the price of a second pass over the
+ * input transform.
+ * packed_dev: a WG_SCALED blob of winograd_filter_transform (signed int8
+ * filters; a mismatch leaves y untouched).  x_dev, y_dev, layout, limits and
+ * error codes as for winograd_conv2d_int8; no workspace.  act_table_dev: NULL,
+ * or int32 [T][26][4] = (n, p, r, q) per tile t = (n*ceil(H/4) + ty)*ceil(W/4)
+ * + tx and free entry in the library's order (the 16 real entries (r, c), r, c
+ * in {0,1,2,5}, row-major; then (r,3) for r in {0,1,2,5}; (3,c) for c in
+ * {0,1,2,5}; (3,3); (3,4)), (0,0,1,0) where nothing was scaled, which the kernel
+ * fills for tests (DEVICE memory, 16-byte aligned).
+ */
+int winograd_conv2d_int8_act_scaled(const int8_t* x_dev, const void* packed_dev, int32_t* y_dev,
+                                    int N, int C, int H, int W, int K, int layout,
+                                    int32_t* act_table_dev, void* hip_stream);
+
+/*
  * For callers that cannot allocate device memory (code under HIP graph capture,
  * tight serving loops, harnesses that forbid it): winograd_conv2d_int8's staged
  * pipeline (input transform, contraction, output transform) with its workspace

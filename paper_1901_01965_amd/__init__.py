@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     LOSSLESS, SCALED, NCHW, NHWC, MAX_CHANNELS, PackedFilter, WinogradError,
     winograd_filter_transform, winograd_conv2d_int8, winograd_conv2d_int8_requant, direct_conv2d_int8,
     winograd_conv2d_int8_static_workspace, static_workspace_limit,
-    winograd_filter_transform_u8, winograd_conv2d_u8, PackedFilterU8, MAX_CHANNELS_U8,
+    winograd_filter_transform_u8, winograd_conv2d_u8, winograd_conv2d_int8_act_scaled, PackedFilterU8, MAX_CHANNELS_U8,
     requant_relu_pool_int8,
     packed_filter_bytes, workspace_bytes, make_workspace, load_library,
     f2x2_filter_transform, f2x2_conv2d_int8, f2x2_debug_filter_operands, F2x2PackedFilter, f2x2_conv2d_int8_act_scaled, f2x2_conv2d_int8_requant,

@@ -60,6 +60,7 @@ def load_library():
         "winograd_f2x2_conv2d_int8": (i, [vp, vp, vp, i, i, i, i, i, i, i, vp]),
         "winograd_f2x2_debug_filter_operands": (i, [vp, i, i, i, vp, vp, vp]),
         "winograd_filter_transform_u8": (i, [vp, i, i, i, i, i, vp, sz, vp]),
+        "winograd_conv2d_int8_act_scaled": (i, [vp, vp, vp, i, i, i, i, i, i, vp, vp]),
         "winograd_conv2d_u8": (i, [vp, i, vp, vp, i, i, i, i, i, i, i, vp]),
         "winograd_f2x2_filter_transform_u8": (i, [vp, i, i, i, i, i, vp, sz, vp]),
         "winograd_f2x2_conv2d_u8": (i, [vp, i, vp, vp, i, i, i, i, i, i, i, vp]),
@@ -91,7 +92,7 @@ EXPORTED_SYMBOLS = (
     "winograd_f2x2_packed_filter_bytes", "winograd_f2x2_filter_transform", "winograd_f2x2_conv2d_int8",
     "winograd_f2x2_debug_filter_operands", "winograd_f2x2_filter_transform_u8", "winograd_f2x2_conv2d_u8",
     "winograd_f2x2_conv2d_int8_act_scaled", "winograd_f2x2_conv2d_int8_requant",
-    "winograd_filter_transform_u8", "winograd_conv2d_u8",
+    "winograd_filter_transform_u8", "winograd_conv2d_u8", "winograd_conv2d_int8_act_scaled",
 )
 
 
@@ -239,6 +240,25 @@ def winograd_conv2d_u8(x, zero_point, packed, layout=NCHW, out=None):
     _check(load_library().winograd_conv2d_u8(_ptr(x), int(zero_point), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout,
                                              packed.mode, _stream()), "winograd_conv2d_u8")
     return out
+
+
+def winograd_conv2d_int8_act_scaled(x, packed, layout=NCHW, out=None, want_table=False):
+    """The complex F(4x4,3x3) path with the activations of every tile scaled into +-127 as well; packed: a SCALED
+    blob of signed int8 filters.  want_table: also return the int32 [T, 26, 4] = (n, p, r, q) table the kernel
+    derived per tile and free entry."""
+    layout = _LAYOUTS[layout]
+    _need(x, torch.int8, "x")
+    N, C, H, W = _dims(x, layout)
+    _match(packed, PackedFilter, C, "winograd_conv2d_int8_act_scaled")
+    K = packed.K
+    out = _out(out, (N, K, H, W) if layout == NCHW else (N, H, W, K), torch.int32, x.device)
+    table = None
+    if want_table:
+        table = torch.empty((N * ((H + 3) // 4) * ((W + 3) // 4), 26, 4), dtype=torch.int32, device=x.device)
+    _check(load_library().winograd_conv2d_int8_act_scaled(
+        _ptr(x), _ptr(packed.blob), _ptr(out), N, C, H, W, K, layout,
+        _ptr(table) if table is not None else ctypes.c_void_p(0), _stream()), "winograd_conv2d_int8_act_scaled")
+    return (out, table) if want_table else out
 
 
 def make_workspace(N, C, H, W, K, mode, device="cuda"):

@@ -77,6 +77,16 @@ int winograd_conv2d_u8(const uint8_t* x_dev, int zero_point, const void* packed_
                                           static_cast<hipStream_t>(hip_stream)));
 }
 
+int winograd_conv2d_int8_act_scaled(const int8_t* x_dev, const void* packed_dev, int32_t* y_dev, int N, int C, int H, int W,
+                                    int K, int layout, int32_t* act_table_dev, void* hip_stream) {
+    if (!x_dev || !packed_dev || !y_dev || !valid_layout(layout)) return WG_EINVAL;
+    if (int st = check_shape(N, C, H, W, K)) return st;
+    if (!aligned(x_dev, 4) || !aligned(y_dev, 4) || !aligned(packed_dev, 256)) return WG_EINVAL;
+    if (act_table_dev && !aligned(act_table_dev, 16)) return WG_EINVAL;
+    return status_of(launch_fused_conv_act_scaled(x_dev, packed_dev, y_dev, act_table_dev, make_problem(N, C, H, W, K), layout,
+                                                  static_cast<hipStream_t>(hip_stream)));
+}
+
 int winograd_packed_filter_check(const void* packed_dev, int K, int C, int mode, void* hip_stream) {
     if (!packed_dev || !valid_mode(mode)) return WG_EINVAL;
     if (int st = check_filter_shape(K, C)) return st;

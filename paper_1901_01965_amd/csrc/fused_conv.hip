@@ -1310,6 +1310,259 @@ hipError_t launch_layout(const int8_t* x, const uint8_t* b, const BlobLayout& bl
     return launch_mode<WG_NCHW, kLoadBytes, Q8>(x, b, bl, y, p, mode, q8, s);
 }
 
+// ---- activations scaled as well (the remark that closes Section 4.1) --------------------------------------------
+// Section 4.1 ends by noting that the analysis of Section 4.2 applies to B^T d B too (12 bits here for int8 data).
+// The rule used is that section's with a tile in the place of an output feature map: at each of a tile's 26 free
+// entries the largest max(|Re|, |Im|) over the input channels decides one factor n/2^p, Re and Im of every channel's
+// value there are multiplied by it (round half up), and the channel sums are multiplied back by its reciprocal r/2^q
+// after the filter's.  Both operands are then single int8 values: one matrix-core instruction per real product, 36
+// operand planes instead of 72, channel sums accumulated by the matrix cores themselves.
+//
+// (n, p, r, q) for every possible maximum of int8 data, one byte each (n = 0: within the range, nothing applied).
+constexpr int kActMax = 16 * 128;
+struct ActScaleTable {
+    uint32_t v[kActMax + 1];
+};
+constexpr ActScaleTable make_act_scale_table() {
+    ActScaleTable t = {};
+    for (int mx = 0; mx <= kActMax; ++mx) {
+        uint32_t n = 0, p = 0, r = 1, q = 0;
+        if (mx > kWeightRange) {
+            const int num = kWeightRange * 128;
+            int y = 0;
+            while ((mx << (y + 1)) <= num) ++y;
+            n = (uint32_t)((num * 8) / (mx << y));
+            p = (uint32_t)(10 - y);
+            for (int qq = 7; qq >= 0; --qq) {
+                const uint32_t rr = ((2u << (p + qq)) + n) / (2 * n);
+                if (rr <= 255) { r = rr; q = (uint32_t)qq; break; }
+            }
+        }
+        t.v[mx] = n | (p << 8) | (r << 16) | (q << 24);
+    }
+    return t;
+}
+__device__ const ActScaleTable kActScale = make_act_scale_table();
+
+constexpr int kActPlanes = 36;                       // 16 real entries, then (Re, Im) of each complex entry
+static_assert(kActPlanes * kPlaneBytes <= kLdsBytes, "the single-limb planes lie where the two-limb planes do");
+constexpr int kActNpOff = kLdsBytes;                 // v4i [tile][26]: (n, n), (half, half), (p, p) in 16-bit pairs
+constexpr int kActRqOff = kActNpOff + 16 * kEntries * 16;   // uint32 [26][tile]: the table entry (r, q in its upper bytes)
+constexpr int kActLdsBytes = kActRqOff + kEntries * 16 * 4;
+
+__device__ inline s16x2 abs_max(Quad v) {
+    const s16x2 zero = {0, 0};
+    return __builtin_elementwise_max(__builtin_elementwise_max(v.a, zero - v.a), __builtin_elementwise_max(v.b, zero - v.b));
+}
+// transform_patch's receiver in the first pass: running maxima per free entry, two channels per register
+struct MaxKeeper {
+    s16x2* mx;
+    __device__ inline void real_entry(int p, Quad v) const { mx[p] = __builtin_elementwise_max(mx[p], abs_max(v)); }
+    __device__ inline void complex_entry(int j, Quad re, Quad im) const {
+        mx[kRealEntries + j] = __builtin_elementwise_max(mx[kRealEntries + j], __builtin_elementwise_max(abs_max(re), abs_max(im)));
+    }
+};
+// ... and in the second: every value times its tile's factor, rounded half up, as one int8 operand plane
+struct ScaledPlanes {
+    LdsPlaneSink sink;
+    const v4i* np;   // this tile's 26 factors
+    __device__ inline uint32_t scaled(int entry, Quad v) const {
+        const v4i t = np[entry];
+        const s16x2 mul = as_s16x2((uint32_t)t[0]), half = as_s16x2((uint32_t)t[1]), sh = as_s16x2((uint32_t)t[2]);
+        return pack_low_bytes(Quad{(v.a * mul + half) >> sh, (v.b * mul + half) >> sh});
+    }
+    __device__ inline void real_entry(int p, Quad v) const { sink.put(p, scaled(p, v)); }
+    __device__ inline void complex_entry(int j, Quad re, Quad im) const {
+        sink.put(kRealEntries + 2 * j, scaled(kRealEntries + j, re));
+        sink.put(kRealEntries + 2 * j + 1, scaled(kRealEntries + j, im));
+    }
+};
+
+// Product phase: the channel sums of a wave's entries (18 of four registers) are the matrix cores' accumulators.
+//   real:    sum += D W;    complex: Re += Dr Wr + Di (-Wi),  Im += Dr Wi + Di Wr
+// Filter fragments come from the scaled blob in ProductPhase<WG_SCALED>'s order (W; Wr, Wi, -Wi).
+template <int HALF>
+struct BothScaledSums {
+    using Phase = ProductPhase<WG_SCALED, HALF>;
+    static constexpr int NE = Phase::NE, NB = Phase::NB;
+    static constexpr int sum_start(int slot) { return ScaledSums<HALF>::sum_start(slot); }
+    template <int SLOT, int I>
+    __device__ inline static v4i load_a(const LaneContext& cx) {
+        constexpr int entry = half_slot(HALF, SLOT).entry;
+        constexpr int plane = is_real(entry) ? entry : kRealEntries + 2 * (entry - kRealEntries) + I;
+        return *reinterpret_cast<const v4i*>(cx.a_lds + plane * kPlaneBytes);
+    }
+    __device__ inline static void run(const LaneContext& cx, v4i (&bring)[kFilterPrefetch], v4i (&sums)[kChannelSums]) {
+        v4i afr[2][2];
+        afr[0][0] = load_a<0, 0>(cx);
+        if constexpr (!is_real(half_slot(HALF, 0).entry)) afr[0][1] = load_a<0, 1>(cx);
+        static_for<NE>([&](auto S) {
+            constexpr int s = S;
+            constexpr int entry = half_slot(HALF, s).entry;
+            constexpr int b0 = b_start<WG_SCALED>(HALF, s), v = sum_start(s);
+            if constexpr (s + 1 < NE) {
+                afr[(s + 1) & 1][0] = load_a<s + 1, 0>(cx);
+                if constexpr (!is_real(half_slot(HALF, s + 1).entry)) afr[(s + 1) & 1][1] = load_a<s + 1, 1>(cx);
+            }
+            auto mac = [&](int a, int b, int sum) {
+                sums[sum] = __builtin_amdgcn_mfma_i32_16x16x64_i8(afr[s & 1][a], bring[(b0 + b) % kFilterPrefetch], sums[sum], 0, 0, 0);
+            };
+            if constexpr (is_real(entry)) {
+                mac(0, 0, v);
+            } else {
+                mac(0, 0, v);        // Dr Wr
+                mac(0, 1, v + 1);    // Dr Wi
+                mac(1, 2, v);        // Di (-Wi)
+                mac(1, 0, v + 1);    // Di Wr
+            }
+            static_for<num_b<WG_SCALED>(entry)>([&](auto I) {
+                if constexpr (b0 + I + kFilterPrefetch < NB)
+                    bring[(b0 + I) % kFilterPrefetch] = Phase::template load_b<b0 + I + kFilterPrefetch>(cx);
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    }
+    // After the last channel block: the filter's reverse scaling, then the tile's (register q of a lane belongs to
+    // tile 4 (lane / 16) + q), and the output transform.
+    __device__ inline static void finish(const LaneContext& cx, const uint32_t* rq_tab, int lane, const v4i (&sums)[kChannelSums],
+                                         v4i (&Y)[16]) {
+        v4i er[6], ei[6];
+        static_for<NE>([&](auto S) {
+            constexpr Slot sl = half_slot(HALF, S);
+            constexpr int v = sum_start(S);
+            v4i re = sums[v], im = {0, 0, 0, 0};
+            if constexpr (!is_real(sl.entry)) im = sums[v + 1];
+            const ReverseScale filter_side(cx.table_k[sl.entry]);
+            const v4i rq = *reinterpret_cast<const v4i*>(rq_tab + sl.entry * 16 + 4 * (lane >> 4));
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const ReverseScale tile_side((int)(((uint32_t)rq[q] >> 16) & 255u), (int)((uint32_t)rq[q] >> 24));
+                re[q] = tile_side(filter_side(re[q]));
+                if constexpr (!is_real(sl.entry)) im[q] = tile_side(filter_side(im[q]));
+            }
+            er[sl.pos] = re;
+            ei[sl.pos] = im;
+            if constexpr (sl.last_in_row) finish_row<sl.row>(er, ei, Y);
+        });
+    }
+};
+
+// grid (ceil(T/16), Kp/32), 256 threads with the roles of fused_conv_body; the blob is a WG_SCALED one of signed int8
+// filters.  Pass 1 transforms every channel block of the workgroup's 16 tiles and keeps the running maxima; each
+// thread then looks up the factors of one or two (tile, entry) pairs; pass 2 transforms again (the patches now come
+// from the caches), scales, and multiplies.  act_table (may be null) receives int32 [T][26][4] = (n, p, r, q).
+template <int LAYOUT, int LOAD>
+__global__ __launch_bounds__(256) void fused_conv_act_scaled_kernel(const int8_t* __restrict__ x, const uint8_t* __restrict__ blob,
+                                                                    size_t table_off, size_t planes_off, int32_t* __restrict__ y,
+                                                                    int32_t* __restrict__ act_table, const Problem p) {
+    static_assert(LOAD != kLoadDirect, "the patch is held in registers");
+    extern __shared__ __attribute__((aligned(16))) int8_t lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int kblock = wave & 1, half = wave >> 1;
+    const int tile0 = blockIdx.x * kFusedTiles, k0 = blockIdx.y * kFusedFilters;
+    const int k = k0 + kblock * 16 + (lane & 15);
+    if (!blob_matches(reinterpret_cast<const BlobHeader*>(blob), p.K, p.C, WG_SCALED)) return;
+
+    int my_n = 0, my_ty = 0, my_tx = 0;
+    if (tile0 + (lane & 15) < p.T) decode_tile(p, tile0 + (lane & 15), my_n, my_ty, my_tx);
+    const int a_tile = tid >> 4, a_cq = tid & 15;
+    const int a_t = tile0 + a_tile;
+    const int a_tx = __shfl(my_tx, a_tile), a_ty = __shfl(my_ty, a_tile), a_n = __shfl(my_n, a_tile);
+    v4i* np_tab = reinterpret_cast<v4i*>(lds + kActNpOff);
+    uint32_t* rq_tab = reinterpret_cast<uint32_t*>(lds + kActRqOff);
+    constexpr bool VEC4 = LOAD == kLoadDwords;
+    uint32_t patch[6][6];
+
+    // ---- pass 1: largest magnitude per (tile, entry) over all channels --------------------------------------
+    s16x2 mx[kEntries];
+#pragma unroll
+    for (int e = 0; e < kEntries; ++e) mx[e] = (s16x2){0, 0};
+    if (a_t < p.T) {
+        load_patch<LAYOUT, VEC4>(x, p, a_n, a_ty, a_tx, 4 * a_cq, patch);
+        for (int cb = 0; cb < p.CB; ++cb) {
+            bias_patch(p, a_ty, a_tx, cb * kCBlock + 4 * a_cq, patch);
+            uint32_t now[6][6];
+#pragma unroll
+            for (int i = 0; i < 36; ++i) now[i / 6][i % 6] = patch[i / 6][i % 6];
+            // the next block's patch, or the first block's again for pass 2, travels meanwhile
+            load_patch<LAYOUT, VEC4>(x, p, a_n, a_ty, a_tx, (cb + 1 < p.CB ? cb + 1 : 0) * kCBlock + 4 * a_cq, patch);
+            transform_patch(now, MaxKeeper{mx});
+        }
+    }
+    // over the sixteen threads of a tile (consecutive lanes), two entries per register
+    s16x2 pm[kEntries / 2];
+#pragma unroll
+    for (int j = 0; j < kEntries / 2; ++j) {
+        pm[j] = (s16x2){max(mx[2 * j].x, mx[2 * j].y), max(mx[2 * j + 1].x, mx[2 * j + 1].y)};
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1)
+            pm[j] = __builtin_elementwise_max(pm[j], as_s16x2((uint32_t)__shfl_xor((int)as_u32(pm[j]), off)));
+    }
+    {   // thread (tile, cq) looks up entry cq of its tile, and entry 16 + cq if there is one
+        int mine[2] = {0, 0};
+#pragma unroll
+        for (int e = 0; e < kEntries; ++e)
+            if (a_cq == (e & 15)) mine[e >> 4] = (e & 1) ? pm[e / 2].y : pm[e / 2].x;
+#pragma unroll
+        for (int part = 0; part < 2; ++part) {
+            const int e = 16 * part + a_cq;
+            if (e >= kEntries) break;
+            const uint32_t entry = kActScale.v[min(mine[part], kActMax)];
+            const uint32_t n = max(entry & 255u, 1u), sh = (entry >> 8) & 255u, hf = (1u << sh) >> 1;
+            np_tab[a_tile * kEntries + e] = (v4i){(int)(n * 0x00010001u), (int)(hf * 0x00010001u), (int)(sh * 0x00010001u), 0};
+            rq_tab[e * 16 + a_tile] = entry;
+            if (act_table != nullptr && blockIdx.y == 0 && a_t < p.T)
+                *reinterpret_cast<v4i*>(act_table + ((size_t)a_t * kEntries + e) * 4) =
+                    (v4i){(int)(entry & 255u), (int)((entry >> 8) & 255u), (int)((entry >> 16) & 255u), (int)(entry >> 24)};
+        }
+    }
+    __syncthreads();
+
+    // ---- pass 2: scaled operands, products --------------------------------------------------------------------
+    ScaledPlanes out;
+    out.sink.base = lds + lds_slot(a_cq >> 2, a_tile) * 16 + (a_cq & 3) * 4;
+    out.np = np_tab + a_tile * kEntries;
+    LaneContext cx;
+    cx.a_lds = lds + lds_slot(lane >> 4, lane & 15) * 16;
+    cx.table_k = reinterpret_cast<const ScaleEntry*>(blob + table_off) + (size_t)k * kEntries;
+    constexpr int NP = 46;
+    const int8_t* b_lane = reinterpret_cast<const int8_t*>(blob + planes_off) + filter_plane_offset(0, 0, k, (lane >> 4) * 16, p.Kp, NP);
+    const size_t b_block_stride = (size_t)(p.Kp >> 4) * NP * kFilterFragBytes;
+    ProductPhase<WG_SCALED, 0> phase0;
+    ProductPhase<WG_SCALED, 1> phase1;
+    v4i sums[kChannelSums];
+#pragma unroll
+    for (int i = 0; i < kChannelSums; ++i) sums[i] = (v4i){0, 0, 0, 0};
+    for (int cb = 0; cb < p.CB; ++cb) {
+        cx.b_glob = b_lane + cb * b_block_stride;
+        if (half == 0) phase0.prefetch(cx); else phase1.prefetch(cx);
+        if (cb > 0) {   // everyone is done reading the previous block's planes
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+        }
+        if (a_t < p.T) {
+            bias_patch(p, a_ty, a_tx, cb * kCBlock + 4 * a_cq, patch);
+            transform_patch(patch, out);
+            if (cb + 1 < p.CB) load_patch<LAYOUT, VEC4>(x, p, a_n, a_ty, a_tx, (cb + 1) * kCBlock + 4 * a_cq, patch);
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        if (half == 0) BothScaledSums<0>::run(cx, phase0.bring, sums); else BothScaledSums<1>::run(cx, phase1.bring, sums);
+    }
+    v4i Y[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) Y[i] = (v4i){0, 0, 0, 0};
+    if (half == 0) BothScaledSums<0>::finish(cx, rq_tab, lane, sums, Y); else BothScaledSums<1>::finish(cx, rq_tab, lane, sums, Y);
+
+    const int my_row = 4 * my_ty, my_col = 4 * my_tx;
+    int my_origin = -1;
+    if (tile0 + (lane & 15) < p.T)
+        my_origin = LAYOUT == WG_NHWC ? ((my_n * p.H + my_row) * p.W + my_col) * p.K : (my_n * p.K * p.H + my_row) * p.W + my_col;
+    const StoreContext sc = {lds, tid, lane, wave, half, kblock, my_n, my_row, my_col, my_origin, 8, y};
+    __syncthreads();   // the operand planes are dead (the tables lie behind them)
+    store_block<LAYOUT, false>(sc, p, Int8Epilogue{}, Y, k0);
+}
+
 template <int LAYOUT, int LOAD, int MODE, bool SUMS>
 hipError_t launch_u8(const int8_t* x, ZeroPointU8 zero, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
                      hipStream_t s) {
@@ -1342,6 +1595,23 @@ hipError_t launch_fused_conv_u8(const uint8_t* x_u8, int zero_point, const void*
         return launch_u8_mode<WG_NHWC, kLoadDwords>(x, zero, b, bl, y, p, mode, s);
     if (layout == WG_NHWC) return launch_u8_mode<WG_NHWC, kLoadBytes>(x, zero, b, bl, y, p, mode, s);
     return launch_u8_mode<WG_NCHW, kLoadBytes>(x, zero, b, bl, y, p, mode, s);
+}
+
+hipError_t launch_fused_conv_act_scaled(const int8_t* x, const void* blob, int32_t* y, int32_t* act_table, const Problem& p,
+                                        int layout, hipStream_t s) {
+    const BlobLayout bl = blob_layout(p.Kp, p.C, WG_SCALED);
+    const uint8_t* b = static_cast<const uint8_t*>(blob);
+    dim3 grid(ceil_div(p.T, kFusedTiles), p.Kp / kFusedFilters);
+    auto go = [&](auto kernel) -> hipError_t {
+        static LdsLimitOnce lds_limit;   // per kernel: the lambda's body is instantiated once per argument type
+        if (hipError_t e = lds_limit.set(reinterpret_cast<const void*>(kernel), kActLdsBytes)) return e;
+        kernel<<<grid, 256, kActLdsBytes, s>>>(x, b, bl.table_off, bl.planes_off, y, act_table, p);
+        return hipGetLastError();
+    };
+    if (layout == WG_NHWC && p.C % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 4 == 0)
+        return go(&fused_conv_act_scaled_kernel<WG_NHWC, kLoadDwords>);
+    if (layout == WG_NHWC) return go(&fused_conv_act_scaled_kernel<WG_NHWC, kLoadBytes>);
+    return go(&fused_conv_act_scaled_kernel<WG_NCHW, kLoadBytes>);
 }
 
 void set_stream_workgroups(int n) { g_stream_workgroups.store(n > 0 ? n : 0, std::memory_order_relaxed); }
