@@ -32,15 +32,22 @@ def _both(lib, x, g, mode):
     finally:
         wg.force_path(wg.AUTO)
     torch.cuda.synchronize()
-    # free device memory as the runtime reports it must not drop across the call (nothing else runs meanwhile; torch's
-    # own allocator is not involved in a ctypes call, and a collection here keeps stray frees out of the window)
+    # Free device memory as the runtime reports it must not drop across the call (nothing else runs meanwhile; torch's
+    # own allocator is not involved in a ctypes call, and a collection here keeps stray frees out of the window).  The
+    # process's first call is left out: that is when the runtime places the library's device image, the 64 MiB array
+    # included, on the GPU.
     gc.collect()
     before = torch.cuda.mem_get_info()[0]
     assert lib.winograd_conv2d_int8_static_workspace(p(xd), p(packed.blob), p(got), N, C, H, W, K, wg.NHWC, mode,
                                                      stream) == 0
     torch.cuda.synchronize()
-    assert torch.cuda.mem_get_info()[0] >= before
+    if _both.calls > 0:
+        assert torch.cuda.mem_get_info()[0] >= before
+    _both.calls += 1
     return got.cpu().numpy(), want.cpu().numpy()
+
+
+_both.calls = 0
 
 
 @pytest.mark.parametrize("mode", [wg.LOSSLESS, wg.SCALED])
