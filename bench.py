@@ -345,6 +345,9 @@ def main():
                     help="f4x4: the complex F(4x4,3x3) path (the headline); f2x2: the rational F(2x2,3x3) path")
     ap.add_argument("--lossless-variant", type=int, default=0, choices=(0, 1, 2),
                     help="lossless single-kernel form: 0 the library's choice, 1 limb-pair form wherever possible, 2 never")
+    ap.add_argument("--scaled-variant", type=int, default=0, choices=(0, 1, 2),
+                    help="scaled single-kernel form: 0 the library's choice, 1 the role-specialised kernel with eight product "
+                         "waves wherever possible, 2 never")
     ap.add_argument("--stack", action="store_true",
                     help="time the VGG-16-shaped stack (cfg5) instead of one layer; prints its own JSON line")
     args = ap.parse_args()
@@ -355,6 +358,9 @@ def main():
     if args.lossless_variant:
         import paper_1901_01965_amd as wg_
         wg_.lossless_variant(args.lossless_variant)
+    if args.scaled_variant:
+        import paper_1901_01965_amd as wg_
+        wg_.scaled_variant(args.scaled_variant)
     if args.stack:
         return run_stack(args)
     if args.algorithm == "f2x2":

@@ -752,11 +752,11 @@ __global__ __launch_bounds__(256) void fused_conv_u8_kernel(const int8_t* __rest
 // without their software pipelining (one set of fragments and accumulators, an eight-deep filter
 // ring), because a product wave there has 256 registers and its waits are covered by the
 // transform wave on the same SIMD.
-template <int MODE, int HALF, bool SUMS>
+template <int MODE, int HALF, bool SUMS, int RING = 8>
 struct LeanProducts {
     using Phase = ProductPhase<MODE, HALF>;
     static constexpr int NE = Phase::NE, NB = Phase::NB;
-    static constexpr int kRing = 8;
+    static constexpr int kRing = RING;
     v4i ring[kRing];
 
     __device__ inline void prefetch(const LaneContext& cx) {
@@ -909,14 +909,31 @@ static_assert(ResidentScaled<0>::kAcc == 36 && ResidentScaled<1>::kAcc == 36, "b
 // barrier j (j = 1..CB) publishes the planes of block j - 1 and frees the buffer that the
 // products of block j - 2 were reading.  32 filters per workgroup (a second pass would not fit
 // the 256 registers a wave has when two share a SIMD).
-template <int LAYOUT, bool VEC4, int MODE, bool SUMS, bool Q8>
-__global__ __launch_bounds__(512) void fused_conv_roles_kernel(const int8_t* __restrict__ x, const uint8_t* __restrict__ blob,
-                                                               size_t table_off, size_t planes_off, int32_t* __restrict__ y,
-                                                               Problem p, Int8Epilogue q8) {
+// PW = 8 (scaled mode, channels-last, 4-byte buffer loads, K % 4 = 0): eight product waves, twelve waves in all, 64 filters
+// per workgroup.  On deep layers the workgroup's pace is set by the transform waves and by what the compute unit's
+// vector-memory path takes in, while the product waves idle half of the time: with two product waves per SIMD one
+// transform serves twice the filters.  Product wave pw owns filter block pw % 4 and half pw / 4 of the entries.  Three
+// waves per SIMD leave a wave 168 registers, so the product waves keep 18 joined channel sums instead of the 36
+// resident limb accumulators, and the transform waves form their patch offsets per load.  The two 32-filter halves
+// stage their outputs in one operand buffer each and store at the same time.
+#ifdef WG_TIMESTAMPS
+// Development aid (never compiled into the library): per-wave sums of the time spent in each part of the channel-block loop.
+__device__ unsigned long long* g_roles_stamps = nullptr;
+#define WG_CLOCK() __builtin_amdgcn_s_memtime()
+#define WG_SPENT(i, since) do { const unsigned long long now_ = WG_CLOCK(); spent[i] += now_ - (since); (since) = now_; } while (0)
+#else
+#define WG_SPENT(i, since) do { } while (0)
+#endif
+
+template <int LAYOUT, bool VEC4, int MODE, bool SUMS, bool Q8, int PW = 4>
+__global__ __launch_bounds__(64 * (4 + PW)) void fused_conv_roles_kernel(const int8_t* __restrict__ x, const uint8_t* __restrict__ blob,
+                                                                         size_t table_off, size_t planes_off, int32_t* __restrict__ y,
+                                                                         Problem p, Int8Epilogue q8) {
+    static_assert(PW == 4 || (PW == 8 && VEC4 && MODE == WG_SCALED && SUMS && LAYOUT == WG_NHWC), "eight product waves: scaled mode, buffer loads");
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     const int lane = threadIdx.x & 63, wave8 = threadIdx.x >> 6;
     const bool transforms = wave8 < 4;
-    const int tid = threadIdx.x & 255, wave = wave8 & 3;   // within the role
+    const int tid = threadIdx.x & 255, wave = wave8 & 3;   // within the role (PW = 8: within the four waves that store together)
     int bx = blockIdx.x, by = blockIdx.y;
     {
         const int total = gridDim.x * gridDim.y;
@@ -927,10 +944,20 @@ __global__ __launch_bounds__(512) void fused_conv_roles_kernel(const int8_t* __r
             bx = w - by * (int)gridDim.x;
         }
     }
-    const int tile0 = bx * kFusedTiles, k0 = by * kFusedFilters;
+    const int tile0 = bx * kFusedTiles, k0 = by * (kFusedFilters * (PW / 4));
     if (!blob_matches(reinterpret_cast<const BlobHeader*>(blob), p.K, p.C, MODE)) return;
     int my_n = 0, my_ty = 0, my_tx = 0;
     if (tile0 + (lane & 15) < p.T) decode_tile(p, tile0 + (lane & 15), my_n, my_ty, my_tx);
+#ifdef WG_TIMESTAMPS
+    unsigned long long spent[4] = {0, 0, 0, 0}, mark = WG_CLOCK();
+    const unsigned long long entered = mark;
+    auto report = [&]() {
+        if (g_roles_stamps != nullptr && lane == 0) {
+            unsigned long long* o = g_roles_stamps + ((size_t)(blockIdx.y * gridDim.x + blockIdx.x) * 12 + wave8) * 8;
+            o[0] = spent[0]; o[1] = spent[1]; o[2] = spent[2]; o[3] = spent[3]; o[4] = WG_CLOCK() - entered; o[6] = entered;
+        }
+    };
+#endif
 
     if (transforms) {
         const int a_tile = tid >> 4, a_cq = tid & 15;
@@ -945,10 +972,19 @@ __global__ __launch_bounds__(512) void fused_conv_roles_kernel(const int8_t* __r
         // pixel); lossless mode, where the product waves do, measured 3 % faster with plain
         // loads from clamped addresses.
         constexpr bool kBuffer = VEC4 && MODE == WG_SCALED;
-        uint32_t pixel[VEC4 ? 36 : 1];
+        uint32_t pixel[VEC4 && PW == 4 ? 36 : 1];
+        uint32_t row_off[PW == 8 ? 6 : 1], col_off[PW == 8 ? 6 : 1];   // PW = 8: offsets are formed per load (registers are scarce)
         const __amdgpu_buffer_rsrc_t xbuf = activation_buffer(x, p);
         auto request = [&](int cb) {
-            if constexpr (kBuffer) {
+            if constexpr (PW == 8) {
+                // channel groups beyond C (last block of a C that is not a multiple of 64: a uniform branch) get zeros
+                const bool have = (cb + 1) * kCBlock <= p.C || cb * kCBlock + 4 * a_cq < p.C;
+#pragma unroll
+                for (int i = 0; i < 36; ++i) {
+                    const uint32_t at = __builtin_elementwise_add_sat(row_off[i / 6], col_off[i % 6]);
+                    patch[i / 6][i % 6] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(xbuf, have ? at : kOutsideOffset, cb * kCBlock, 0);
+                }
+            } else if constexpr (kBuffer) {
                 request_patch(xbuf, p, pixel, cb, 4 * a_cq, patch);
             } else if constexpr (VEC4) {
                 const int c0 = cb * kCBlock + 4 * a_cq;
@@ -959,7 +995,15 @@ __global__ __launch_bounds__(512) void fused_conv_roles_kernel(const int8_t* __r
                 load_patch<LAYOUT, false>(x, p, a_n, a_ty, a_tx, cb * kCBlock + 4 * a_cq, patch);
             }
         };
-        if constexpr (kBuffer) {
+        if constexpr (PW == 8) {
+            const int h0 = 4 * a_ty - 1, w0 = 4 * a_tx - 1;
+            const uint32_t image = (uint32_t)a_n * (uint32_t)p.H * (uint32_t)p.W * (uint32_t)p.C + (uint32_t)(4 * a_cq);
+#pragma unroll
+            for (int a = 0; a < 6; ++a) {
+                row_off[a] = (unsigned)(h0 + a) < (unsigned)p.H ? image + (uint32_t)(h0 + a) * (uint32_t)p.W * (uint32_t)p.C : kOutsideOffset;
+                col_off[a] = (unsigned)(w0 + a) < (unsigned)p.W ? (uint32_t)(w0 + a) * (uint32_t)p.C : kOutsideOffset;
+            }
+        } else if constexpr (kBuffer) {
             patch_offsets(p, a_n, a_ty, a_tx, 4 * a_cq, pixel);
         } else if constexpr (VEC4) {
             const int h0 = 4 * a_ty - 1, w0 = 4 * a_tx - 1;
@@ -972,19 +1016,30 @@ __global__ __launch_bounds__(512) void fused_conv_roles_kernel(const int8_t* __r
                                                 (uint32_t)min(max(w0 + b, 0), p.W - 1)) * (uint32_t)p.C;
         }
         if (a_t < p.T) request(0);
+        WG_SPENT(3, mark);
         for (int cb = 0; cb < p.CB; ++cb) {
             if (cb > 0) {   // barrier cb
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 __builtin_amdgcn_s_barrier();
             }
+            WG_SPENT(0, mark);   // LDS writes landed + barrier
             out.sink.base = slot + (cb & 1) * kLdsBytes;
             if (a_t < p.T) {
+#ifdef WG_TIMESTAMPS
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                WG_SPENT(1, mark);   // wait for the patch
+#endif
                 if constexpr (kBuffer) bias_buffer_patch(patch);
                 else bias_patch(p, a_ty, a_tx, cb * kCBlock + 4 * a_cq, patch);
                 transform_patch(patch, out);
+                WG_SPENT(2, mark);   // transform
                 if (cb + 1 < p.CB) request(cb + 1);
+                WG_SPENT(3, mark);   // requests
             }
         }
+#ifdef WG_TIMESTAMPS
+        report();
+#endif
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();   // barrier CB: the last block's planes are published
         __syncthreads();                // the two barriers of the product waves' store
@@ -992,8 +1047,12 @@ __global__ __launch_bounds__(512) void fused_conv_roles_kernel(const int8_t* __r
         return;
     }
 
-    const int kblock = wave & 1, half = wave >> 1;
-    const int k = k0 + kblock * 16 + (lane & 15);
+    // PW = 4: wave = 2 half + kblock.  PW = 8: product wave pw = wave8 - 4 owns filter block pw % 4 and half pw / 4; the
+    // waves of filter blocks 2 group, 2 group + 1 store together (`wave` counts within that group, as store_block expects)
+    const int pw = wave8 - 4;
+    const int kblock4 = PW == 8 ? (pw & 3) : (wave & 1), half = PW == 8 ? (pw >> 2) : (wave >> 1);
+    const int kblock = kblock4 & 1, group = kblock4 >> 1;
+    const int k = k0 + kblock4 * 16 + (lane & 15);
     LaneContext cx;
     cx.table_k = reinterpret_cast<const ScaleEntry*>(blob + table_off) + (size_t)k * kEntries;
     constexpr int NP = MODE == WG_LOSSLESS ? 138 : 46;
@@ -1004,31 +1063,60 @@ __global__ __launch_bounds__(512) void fused_conv_roles_kernel(const int8_t* __r
 #pragma unroll
     for (int i = 0; i < 16; ++i) Y[i] = (v4i){0, 0, 0, 0};
     // SUMS: the product waves do no output transform per block.  Scaled: all 36 limb-product
-    // accumulators stay resident; lossless: 18 joined channel sums (54 accumulators would not fit).
-    constexpr bool RESIDENT = SUMS && MODE == WG_SCALED;
-    std::conditional_t<RESIDENT, ResidentScaled<0>, LeanProducts<MODE, 0, SUMS>> phase0;
-    std::conditional_t<RESIDENT, ResidentScaled<1>, LeanProducts<MODE, 1, SUMS>> phase1;
+    // accumulators stay resident (PW = 4), or 18 joined channel sums (PW = 8: 168 registers per wave); lossless: 18
+    // joined channel sums (54 accumulators would not fit).
+    constexpr bool RESIDENT = SUMS && MODE == WG_SCALED && PW == 4;
+    constexpr int kLeanRing = PW == 8 ? 10 : 8;
+    std::conditional_t<RESIDENT, ResidentScaled<0>, LeanProducts<MODE, 0, SUMS, kLeanRing>> phase0;
+    std::conditional_t<RESIDENT, ResidentScaled<1>, LeanProducts<MODE, 1, SUMS, kLeanRing>> phase1;
     constexpr int kSumRegs = RESIDENT ? 36 : (SUMS ? kChannelSums : 1);
     v4i sums[kSumRegs];
     if constexpr (SUMS) {
 #pragma unroll
         for (int i = 0; i < kSumRegs; ++i) sums[i] = (v4i){0, 0, 0, 0};
     }
-    for (int cb = 0; cb < p.CB; ++cb) {
-        cx.b_glob = b_lane + cb * b_block_stride;
-        if (half == 0) phase0.prefetch(cx); else phase1.prefetch(cx);
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();   // barrier cb + 1
-        cx.a_lds = lds + (cb & 1) * kLdsBytes + lds_slot(lane >> 4, lane & 15) * 16;
-        if constexpr (RESIDENT) {
-            if (half == 0) phase0.run(cx, sums); else phase1.run(cx, sums);
-        } else {
-            if (half == 0) phase0.run(cx, sums, Y); else phase1.run(cx, sums, Y);
+    if constexpr (PW == 8) {
+        // one loop per half (the same barriers in both), so that each is allocated registers on its own
+        auto blocks = [&](auto& phase) {
+            for (int cb = 0; cb < p.CB; ++cb) {
+                cx.b_glob = b_lane + cb * b_block_stride;
+                phase.prefetch(cx);
+                WG_SPENT(3, mark);   // ring prefetch issue
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();   // barrier cb + 1
+                WG_SPENT(0, mark);   // barrier
+                cx.a_lds = lds + (cb & 1) * kLdsBytes + lds_slot(lane >> 4, lane & 15) * 16;
+                phase.run(cx, sums, Y);
+                WG_SPENT(2, mark);   // products
+            }
+        };
+        if (half == 0) blocks(phase0); else blocks(phase1);
+    } else {
+        for (int cb = 0; cb < p.CB; ++cb) {
+            cx.b_glob = b_lane + cb * b_block_stride;
+            if (half == 0) phase0.prefetch(cx); else phase1.prefetch(cx);
+            WG_SPENT(3, mark);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();   // barrier cb + 1
+            WG_SPENT(0, mark);
+            cx.a_lds = lds + (cb & 1) * kLdsBytes + lds_slot(lane >> 4, lane & 15) * 16;
+            if constexpr (RESIDENT) {
+                if (half == 0) phase0.run(cx, sums); else phase1.run(cx, sums);
+            } else {
+                if (half == 0) phase0.run(cx, sums, Y); else phase1.run(cx, sums, Y);
+            }
+            WG_SPENT(2, mark);
         }
     }
+#ifdef WG_TIMESTAMPS
+    report();
+#endif
     if constexpr (RESIDENT) {
         if (half == 0) ResidentScaled<0>::finish(cx, sums, Y);
         else           ResidentScaled<1>::finish(cx, sums, Y);
+    } else if constexpr (SUMS && MODE == WG_SCALED) {
+        if (half == 0) ScaledSums<0>::template finish<0>(cx, sums, Y);
+        else           ScaledSums<1>::template finish<0>(cx, sums, Y);
     } else if constexpr (SUMS) {
         if (half == 0) LeanProducts<MODE, 0, true>::finish_lossless(sums, Y);
         else           LeanProducts<MODE, 1, true>::finish_lossless(sums, Y);
@@ -1038,20 +1126,39 @@ __global__ __launch_bounds__(512) void fused_conv_roles_kernel(const int8_t* __r
     if (tile0 + (lane & 15) < p.T)
         my_origin = LAYOUT == WG_NHWC ? ((my_n * p.H + my_row) * p.W + my_col) * p.K
                                       : (my_n * p.K * p.H + my_row) * p.W + my_col;
-    const StoreContext sc = {lds, tid, lane, wave, half, kblock, my_n, my_row, my_col, my_origin,
-                             MODE == WG_SCALED ? 8 : 0, y};
-    __syncthreads();   // the operand planes are dead
-    store_block<LAYOUT, Q8>(sc, p, q8, Y, k0);
+    if constexpr (PW == 8) {
+        // the two 32-filter halves of the workgroup stage in one operand buffer each and store side by side (the host
+        // gives this form only channels-last outputs with K % 4 = 0, the layout store_block's two parts exist for)
+        const int gtid = (2 * half + kblock) * 64 + lane;
+        const StoreContext sc = {lds + group * kLdsBytes, gtid, lane, 2 * half + kblock, half, kblock, my_n, my_row, my_col, my_origin, 8, y};
+        __syncthreads();   // the operand planes are dead
+        store_block<LAYOUT, Q8, 1>(sc, p, q8, Y, k0 + group * kFusedFilters);
+        __syncthreads();
+        store_block<LAYOUT, Q8, 2>(sc, p, q8, Y, k0 + group * kFusedFilters);
+#ifdef WG_TIMESTAMPS
+        if (g_roles_stamps != nullptr && lane == 0)
+            g_roles_stamps[((size_t)(blockIdx.y * gridDim.x + blockIdx.x) * 12 + wave8) * 8 + 5] = WG_CLOCK() - entered;
+#endif
+    } else {
+        const StoreContext sc = {lds, tid, lane, wave, half, kblock, my_n, my_row, my_col, my_origin,
+                                 MODE == WG_SCALED ? 8 : 0, y};
+        __syncthreads();   // the operand planes are dead
+        store_block<LAYOUT, Q8>(sc, p, q8, Y, k0);
+#ifdef WG_TIMESTAMPS
+        if (g_roles_stamps != nullptr && lane == 0)
+            g_roles_stamps[((size_t)(blockIdx.y * gridDim.x + blockIdx.x) * 12 + wave8) * 8 + 5] = WG_CLOCK() - entered;
+#endif
+    }
 }
 
-template <int LAYOUT, bool VEC4, int MODE, bool SUMS, bool Q8>
+template <int LAYOUT, bool VEC4, int MODE, bool SUMS, bool Q8, int PW = 4>
 hipError_t launch_roles(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
                         const Int8Epilogue& q8, hipStream_t s) {
     constexpr int lds_bytes = 2 * kLdsBytes;
     static LdsLimitOnce lds_limit;   // per template instance
-    if (hipError_t e = lds_limit.set(reinterpret_cast<const void*>(&fused_conv_roles_kernel<LAYOUT, VEC4, MODE, SUMS, Q8>), lds_bytes)) return e;
-    dim3 grid(ceil_div(p.T, kFusedTiles), p.Kp / kFusedFilters);
-    fused_conv_roles_kernel<LAYOUT, VEC4, MODE, SUMS, Q8><<<grid, 512, lds_bytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p, q8);
+    if (hipError_t e = lds_limit.set(reinterpret_cast<const void*>(&fused_conv_roles_kernel<LAYOUT, VEC4, MODE, SUMS, Q8, PW>), lds_bytes)) return e;
+    dim3 grid(ceil_div(p.T, kFusedTiles), p.Kp / (kFusedFilters * (PW / 4)));   // Kp is a multiple of 64
+    fused_conv_roles_kernel<LAYOUT, VEC4, MODE, SUMS, Q8, PW><<<grid, 64 * (4 + PW), lds_bytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p, q8);
     return hipGetLastError();
 }
 
@@ -1293,10 +1400,13 @@ hipError_t launch_mode(const int8_t* x, const uint8_t* blob, const BlobLayout& b
     return launch<LAYOUT, LOAD, WG_SCALED, true, false, Q8>(x, blob, bl, y, p, q8, s);
 }
 
+std::atomic<int> g_scaled_variant{0};
+
 template <bool Q8>
 hipError_t launch_roles_mode(const int8_t* x, const uint8_t* b, const BlobLayout& bl, int32_t* y, const Problem& p,
-                             int mode, const Int8Epilogue& q8, hipStream_t s) {
+                             int mode, const Int8Epilogue& q8, hipStream_t s, bool wide = false) {
     if (mode == WG_LOSSLESS) return launch_roles<WG_NHWC, true, WG_LOSSLESS, true, Q8>(x, b, bl, y, p, q8, s);
+    if (wide) return launch_roles<WG_NHWC, true, WG_SCALED, true, Q8, 8>(x, b, bl, y, p, q8, s);
     return launch_roles<WG_NHWC, true, WG_SCALED, true, Q8>(x, b, bl, y, p, q8, s);
 }
 
@@ -1614,6 +1724,14 @@ hipError_t launch_fused_conv_act_scaled(const int8_t* x, const void* blob, int32
     return go(&fused_conv_act_scaled_kernel<WG_NCHW, kLoadBytes>);
 }
 
+#ifdef WG_TIMESTAMPS
+extern "C" int winograd_debug_set_roles_stamps(void* dev_ptr) {
+    return hipMemcpyToSymbol(HIP_SYMBOL(g_roles_stamps), &dev_ptr, sizeof dev_ptr) == hipSuccess ? 0 : -5;
+}
+#endif
+
+void set_scaled_variant(int v) { g_scaled_variant.store(v, std::memory_order_relaxed); }
+
 void set_stream_workgroups(int n) { g_stream_workgroups.store(n > 0 ? n : 0, std::memory_order_relaxed); }
 
 hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, const Problem& p, int layout, int mode,
@@ -1638,6 +1756,18 @@ hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, cons
         const double pair_cost = 6.5 * (double)((w32 + cus - 1) / cus);
         const double here_cost = w32 <= cus ? 7.4 : 11.7 * (double)((w32 / 2 + cus - 1) / cus);
         if (form == 2 || (form == 1 && p.CB == 1 && pair_cost < here_cost)) return launch_lossless_pair_conv(x, blob, y, p, q8, s);
+    }
+    // Scaled mode, channels-last, K % 4 = 0, several channel blocks: the role-specialised kernel with eight product waves
+    // and 64 filters per workgroup, as soon as the 32-filter grid would need more than one round of the compute units
+    // (measured on the layers of the VGG-16-shaped stack at N = 16 and on the 128-, 256- and 512-channel configurations:
+    // 15-30 % faster than the streaming, 64-filter four-wave and 32-filter role-specialised forms there; with a 64-filter
+    // grid of at most half the compute units the 32-filter form, which then fills the chip in one round, stays ahead).
+    if (mode == WG_SCALED && layout == WG_NHWC && p.C % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 4 == 0 && (p.K & 3) == 0) {
+        const int variant = g_scaled_variant.load(std::memory_order_relaxed);
+        const long long wide_grid = (long long)tile_blocks * (p.Kp / (2 * kFusedFilters));
+        if (variant == 1 || (variant == 0 && p.CB >= 2 && 2 * wide_grid > compute_units()))
+            return q8.out != nullptr ? launch_roles_mode<true>(x, b, bl, y, p, mode, q8, s, true)
+                                     : launch_roles_mode<false>(x, b, bl, y, p, mode, q8, s, true);
     }
     if (streams) {
         if (mode == WG_LOSSLESS)
