@@ -346,7 +346,7 @@ def main():
     ap.add_argument("--lossless-variant", type=int, default=0, choices=(0, 1, 2),
                     help="lossless single-kernel form: 0 the library's choice, 1 limb-pair form wherever possible, 2 never")
     ap.add_argument("--scaled-variant", type=int, default=0, choices=(0, 1, 2),
-                    help="scaled single-kernel form: 0 the library's choice, 1 the role-specialised kernel with eight product "
+                    help="role-specialised kernel: 0 the library's choice, 1 the form with eight product "
                          "waves wherever possible, 2 never")
     ap.add_argument("--stack", action="store_true",
                     help="time the VGG-16-shaped stack (cfg5) instead of one layer; prints its own JSON line")

@@ -362,10 +362,10 @@ int winograd_debug_stream_workgroups(int n);
    waves (any layout).  0: the library's choice, 1: the first form wherever the layout allows, 2: never the first
    form.  Process-wide, like winograd_debug_force_path. */
 int winograd_debug_lossless_variant(int variant);
-/* The same switch for WG_SCALED mode, whose role-specialised single-kernel form (transform and products on separate waves)
+/* A switch of the same kind for the role-specialised single-kernel form (transform and products on separate waves), which
    exists with four product waves and 32 filters per workgroup and with eight product waves and 64 filters (channels-last
-   inputs with C % 4 = 0 and K % 4 = 0).  0: the library's choice, 1: the second form wherever the layout allows, 2: never
-   the second form. */
+   inputs with C % 4 = 0 and K % 4 = 0; both modes, whatever the name says).  0: the library's choice, 1: the second form
+   wherever the layout allows, 2: never the second form. */
 int winograd_debug_scaled_variant(int variant);
 int winograd_num_filter_planes(int mode);
 

@@ -167,8 +167,8 @@ def lossless_variant(v):
 
 
 def scaled_variant(v):
-    """Test hook: 0 = library's choice of the scaled single-kernel form, 1 = the role-specialised kernel with eight
-    product waves (64 filters per workgroup) wherever the layout allows, 2 = never that form."""
+    """Test hook (both modes): 0 = library's choice, 1 = the role-specialised kernel with eight product waves (64 filters
+    per workgroup) wherever the layout allows, 2 = never that form."""
     _check(load_library().winograd_debug_scaled_variant(int(v)), "winograd_debug_scaled_variant")
 
 

@@ -909,13 +909,14 @@ static_assert(ResidentScaled<0>::kAcc == 36 && ResidentScaled<1>::kAcc == 36, "b
 // barrier j (j = 1..CB) publishes the planes of block j - 1 and frees the buffer that the
 // products of block j - 2 were reading.  32 filters per workgroup (a second pass would not fit
 // the 256 registers a wave has when two share a SIMD).
-// PW = 8 (scaled mode, channels-last, 4-byte buffer loads, K % 4 = 0): eight product waves, twelve waves in all, 64 filters
-// per workgroup.  On deep layers the workgroup's pace is set by the transform waves and by what the compute unit's
-// vector-memory path takes in, while the product waves idle half of the time: with two product waves per SIMD one
-// transform serves twice the filters.  Product wave pw owns filter block pw % 4 and half pw / 4 of the entries.  Three
-// waves per SIMD leave a wave 168 registers, so the product waves keep 18 joined channel sums instead of the 36
-// resident limb accumulators, and the transform waves form their patch offsets per load.  The two 32-filter halves
-// stage their outputs in one operand buffer each and store at the same time.
+// PW = 8 (channels-last, 4-byte buffer loads, K % 4 = 0): eight product waves, twelve waves in all, 64 filters per workgroup.
+// On deep layers the workgroup's pace is set by the transform waves and by what the compute unit's vector-memory path
+// takes in, while the product waves of the eight-wave form idle half of the time: with two product waves per SIMD one
+// transform (and one set of patch loads) serves twice the filters.  Product wave pw owns filter block pw % 4 and half
+// pw / 4 of the entries.  Three waves per SIMD leave a wave 168 registers, so in both modes the product waves keep 18
+// joined channel sums (scaled mode: instead of the 36 resident limb accumulators), with a loop per half so that each
+// half is allocated registers on its own, and the transform waves form their patch offsets per load.  The two 32-filter
+// halves stage their outputs in one operand buffer each and store at the same time.
 #ifdef WG_TIMESTAMPS
 // Development aid (never compiled into the library): per-wave sums of the time spent in each part of the channel-block loop.
 __device__ unsigned long long* g_roles_stamps = nullptr;
@@ -929,7 +930,7 @@ template <int LAYOUT, bool VEC4, int MODE, bool SUMS, bool Q8, int PW = 4>
 __global__ __launch_bounds__(64 * (4 + PW)) void fused_conv_roles_kernel(const int8_t* __restrict__ x, const uint8_t* __restrict__ blob,
                                                                          size_t table_off, size_t planes_off, int32_t* __restrict__ y,
                                                                          Problem p, Int8Epilogue q8) {
-    static_assert(PW == 4 || (PW == 8 && VEC4 && MODE == WG_SCALED && SUMS && LAYOUT == WG_NHWC), "eight product waves: scaled mode, buffer loads");
+    static_assert(PW == 4 || (PW == 8 && VEC4 && SUMS && LAYOUT == WG_NHWC), "eight product waves: channels-last, buffer loads, channel sums");
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     const int lane = threadIdx.x & 63, wave8 = threadIdx.x >> 6;
     const bool transforms = wave8 < 4;
@@ -971,7 +972,7 @@ __global__ __launch_bounds__(64 * (4 + PW)) void fused_conv_roles_kernel(const i
         // where these waves set the pace, loads through the buffer descriptor (no select per
         // pixel); lossless mode, where the product waves do, measured 3 % faster with plain
         // loads from clamped addresses.
-        constexpr bool kBuffer = VEC4 && MODE == WG_SCALED;
+        constexpr bool kBuffer = VEC4 && (MODE == WG_SCALED || PW == 8);
         uint32_t pixel[VEC4 && PW == 4 ? 36 : 1];
         uint32_t row_off[PW == 8 ? 6 : 1], col_off[PW == 8 ? 6 : 1];   // PW = 8: offsets are formed per load (registers are scarce)
         const __amdgpu_buffer_rsrc_t xbuf = activation_buffer(x, p);
@@ -1066,7 +1067,7 @@ __global__ __launch_bounds__(64 * (4 + PW)) void fused_conv_roles_kernel(const i
     // accumulators stay resident (PW = 4), or 18 joined channel sums (PW = 8: 168 registers per wave); lossless: 18
     // joined channel sums (54 accumulators would not fit).
     constexpr bool RESIDENT = SUMS && MODE == WG_SCALED && PW == 4;
-    constexpr int kLeanRing = PW == 8 ? 10 : 8;
+    constexpr int kLeanRing = PW == 8 ? (MODE == WG_SCALED ? 10 : 6) : 8;
     std::conditional_t<RESIDENT, ResidentScaled<0>, LeanProducts<MODE, 0, SUMS, kLeanRing>> phase0;
     std::conditional_t<RESIDENT, ResidentScaled<1>, LeanProducts<MODE, 1, SUMS, kLeanRing>> phase1;
     constexpr int kSumRegs = RESIDENT ? 36 : (SUMS ? kChannelSums : 1);
@@ -1130,7 +1131,8 @@ __global__ __launch_bounds__(64 * (4 + PW)) void fused_conv_roles_kernel(const i
         // the two 32-filter halves of the workgroup stage in one operand buffer each and store side by side (the host
         // gives this form only channels-last outputs with K % 4 = 0, the layout store_block's two parts exist for)
         const int gtid = (2 * half + kblock) * 64 + lane;
-        const StoreContext sc = {lds + group * kLdsBytes, gtid, lane, 2 * half + kblock, half, kblock, my_n, my_row, my_col, my_origin, 8, y};
+        const StoreContext sc = {lds + group * kLdsBytes, gtid, lane, 2 * half + kblock, half, kblock, my_n, my_row, my_col, my_origin,
+                                 MODE == WG_SCALED ? 8 : 0, y};
         __syncthreads();   // the operand planes are dead
         store_block<LAYOUT, Q8, 1>(sc, p, q8, Y, k0 + group * kFusedFilters);
         __syncthreads();
@@ -1405,6 +1407,7 @@ std::atomic<int> g_scaled_variant{0};
 template <bool Q8>
 hipError_t launch_roles_mode(const int8_t* x, const uint8_t* b, const BlobLayout& bl, int32_t* y, const Problem& p,
                              int mode, const Int8Epilogue& q8, hipStream_t s, bool wide = false) {
+    if (mode == WG_LOSSLESS && wide) return launch_roles<WG_NHWC, true, WG_LOSSLESS, true, Q8, 8>(x, b, bl, y, p, q8, s);
     if (mode == WG_LOSSLESS) return launch_roles<WG_NHWC, true, WG_LOSSLESS, true, Q8>(x, b, bl, y, p, q8, s);
     if (wide) return launch_roles<WG_NHWC, true, WG_SCALED, true, Q8, 8>(x, b, bl, y, p, q8, s);
     return launch_roles<WG_NHWC, true, WG_SCALED, true, Q8>(x, b, bl, y, p, q8, s);
@@ -1757,15 +1760,19 @@ hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, cons
         const double here_cost = w32 <= cus ? 7.4 : 11.7 * (double)((w32 / 2 + cus - 1) / cus);
         if (form == 2 || (form == 1 && p.CB == 1 && pair_cost < here_cost)) return launch_lossless_pair_conv(x, blob, y, p, q8, s);
     }
-    // Scaled mode, channels-last, K % 4 = 0, several channel blocks: the role-specialised kernel with eight product waves
-    // and 64 filters per workgroup, as soon as the 32-filter grid would need more than one round of the compute units
-    // (measured on the layers of the VGG-16-shaped stack at N = 16 and on the 128-, 256- and 512-channel configurations:
-    // 15-30 % faster than the streaming, 64-filter four-wave and 32-filter role-specialised forms there; with a 64-filter
+    // Channels-last, K % 4 = 0, several channel blocks: the role-specialised kernel with eight product waves and 64 filters
+    // per workgroup, as soon as the 32-filter grid would need more than one round of the compute units (with a 64-filter
     // grid of at most half the compute units the 32-filter form, which then fills the chip in one round, stays ahead).
-    if (mode == WG_SCALED && layout == WG_NHWC && p.C % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 4 == 0 && (p.K & 3) == 0) {
+    // Measured on the layers of the VGG-16-shaped stack at N = 16 and on the 128-, 256- and 512-channel configurations.
+    // Scaled mode: 15-30 % faster than the streaming, 64-filter four-wave and 32-filter role-specialised forms wherever
+    // there are two or more channel blocks.  Lossless mode (twice the matrix-core work and filter bytes per product):
+    // +15-25 % from four channel blocks on, +10 % with two where the layer is too small to stream, level or behind
+    // where the streaming form applies to a two-block layer.
+    if (layout == WG_NHWC && p.C % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 4 == 0 && (p.K & 3) == 0) {
         const int variant = g_scaled_variant.load(std::memory_order_relaxed);
         const long long wide_grid = (long long)tile_blocks * (p.Kp / (2 * kFusedFilters));
-        if (variant == 1 || (variant == 0 && p.CB >= 2 && 2 * wide_grid > compute_units()))
+        const bool deep_enough = mode == WG_SCALED ? p.CB >= 2 : (p.CB >= 4 || (p.CB >= 2 && !streams));
+        if (variant == 1 || (variant == 0 && deep_enough && 2 * wide_grid > compute_units()))
             return q8.out != nullptr ? launch_roles_mode<true>(x, b, bl, y, p, mode, q8, s, true)
                                      : launch_roles_mode<false>(x, b, bl, y, p, mode, q8, s, true);
     }

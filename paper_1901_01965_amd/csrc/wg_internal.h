@@ -249,7 +249,7 @@ hipError_t launch_lossless_pair_conv(const int8_t* x, const void* blob, int32_t*
 // 0: this form does not apply (layout) or is switched off, 1: applies, the dispatcher decides, 2: forced by the test hook
 int lossless_pair_conv_choice(const int8_t* x, const Problem& p, int layout);
 void set_lossless_variant(int v);
-// Test hook for scaled mode: 0 the library's choice, 1 the role-specialised kernel with eight product waves (64 filters
+// Test hook (both modes): 0 the library's choice, 1 the role-specialised kernel with eight product waves (64 filters
 // per workgroup) wherever the layout allows (channels-last, C % 4 = 0, K % 4 = 0), 2 never that form.
 void set_scaled_variant(int v);
 // Single-kernel path with the activations scaled per tile as well (WG_SCALED blob of signed int8 filters).

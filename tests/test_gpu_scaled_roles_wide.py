@@ -24,7 +24,9 @@ def _dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def _want(x, g):
+def _want(x, g, mode=None):
+    if mode == wg.LOSSLESS:
+        return oracle.direct_conv2d(x, g)
     want, flags = oracle.winograd_conv2d(x, g, oracle.SCALED, 127)
     assert (flags & 5) == 0
     return want
@@ -45,18 +47,19 @@ SHAPES = [  # N, C, K, H, W (channels-last, C % 4 == 0, C > 4)
 ]
 
 
+@pytest.mark.parametrize("mode", [wg.SCALED, wg.LOSSLESS])
 @pytest.mark.parametrize("act", ["relu", "uniform"])
 @pytest.mark.parametrize("shape", SHAPES)
-def test_scaled_equals_oracle(shape, act):
+def test_equals_oracle(shape, act, mode):
     N, C, K, H, W = shape
     x, g = wl.make_custom(N, C, K, H, W, act=act, wgt="uniform" if act == "uniform" else "gauss", seed=191)
     if act == "uniform":
         g[0] = -128                       # Winograd-domain magnitude 2048: the factor's p = 8
         x[0, :, : max(1, H // 2)] = -128
-    packed = wg.winograd_filter_transform(_dev(wl.to_krsc(g)), wg.NHWC, wg.SCALED)
+    packed = wg.winograd_filter_transform(_dev(wl.to_krsc(g)), wg.NHWC, mode)
     out = torch.full((N, H, W, K), 1357911, dtype=torch.int32, device="cuda")
     wg.winograd_conv2d_int8(_dev(wl.to_nhwc(x)), packed, wg.NHWC, out=out)
-    assert np.array_equal(wl.from_nhwc(out.cpu().numpy()), _want(x, g))
+    assert np.array_equal(wl.from_nhwc(out.cpu().numpy()), _want(x, g, mode))
 
 
 @pytest.mark.parametrize("xv", [-128, 127])
