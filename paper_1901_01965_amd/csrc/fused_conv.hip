@@ -752,7 +752,10 @@ __global__ __launch_bounds__(256) void fused_conv_u8_kernel(const int8_t* __rest
 // without their software pipelining (one set of fragments and accumulators, an eight-deep filter
 // ring), because a product wave there has 256 registers and its waits are covered by the
 // transform wave on the same SIMD.
-template <int MODE, int HALF, bool SUMS, int RING = 8>
+// AHEAD: the activation fragments of the next entry are asked for before the current entry's
+// matrix-core instructions (a second set of fragment registers), for callers whose product waves
+// are the longer chain of the two roles.
+template <int MODE, int HALF, bool SUMS, int RING = 8, bool AHEAD = false>
 struct LeanProducts {
     using Phase = ProductPhase<MODE, HALF>;
     static constexpr int NE = Phase::NE, NB = Phase::NB;
@@ -766,13 +769,22 @@ struct LeanProducts {
     // sums: the 18 channel sums of ScaledSums (SUMS), else unused; Y: the outputs (not SUMS)
     __device__ inline void run(const LaneContext& cx, v4i (&sums)[SUMS ? kChannelSums : 1], v4i (&Y)[16]) {
         v4i er[6], ei[6];
+        v4i afr2[AHEAD ? 2 : 1][4];
+        if constexpr (AHEAD)
+            static_for<num_a<MODE>(half_slot(HALF, 0).entry)>([&](auto I) { afr2[0][I] = Phase::template load_a<0, I>(cx); });
         static_for<NE>([&](auto S) {
             constexpr int s = S;
             constexpr Slot sl = half_slot(HALF, s);
             constexpr int entry = sl.entry;
             constexpr int b0 = b_start<MODE>(HALF, s);
-            v4i afr[4], acc[9];
-            static_for<num_a<MODE>(entry)>([&](auto I) { afr[I] = Phase::template load_a<s, I>(cx); });
+            v4i acc[9];
+            v4i (&afr)[4] = afr2[AHEAD ? (s & 1) : 0];
+            if constexpr (!AHEAD) {
+                static_for<num_a<MODE>(entry)>([&](auto I) { afr[I] = Phase::template load_a<s, I>(cx); });
+            } else if constexpr (s + 1 < NE) {
+                static_for<num_a<MODE>(half_slot(HALF, s + 1).entry)>(
+                    [&](auto I) { afr2[(s + 1) & 1][I] = Phase::template load_a<s + 1, I>(cx); });
+            }
             static_for<num_ops<MODE>(entry)>([&](auto I) {
                 constexpr Op op = entry_op<MODE>(entry, I);
                 constexpr v4i zero = {0, 0, 0, 0};
@@ -1224,6 +1236,19 @@ __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __
     const int my_blocks = (tile_blocks - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
     const int units = my_blocks * p.CB;
     const int rnd = MODE == WG_SCALED ? 8 : 0;
+#ifdef WG_TIMESTAMPS
+    // ticks per part of the unit loop, summed per wave: 8 numbers per wave, 12 wave slots per workgroup
+    unsigned long long spent[6] = {0, 0, 0, 0, 0, 0}, mark = WG_CLOCK();
+    const unsigned long long entered = mark;
+    auto report = [&]() {
+        if (g_roles_stamps != nullptr && lane == 0) {
+            unsigned long long* o = g_roles_stamps + ((size_t)(blockIdx.y * gridDim.x + blockIdx.x) * 12 + wave8) * 8;
+            for (int i = 0; i < 6; ++i) o[i] = spent[i];
+            o[6] = WG_CLOCK() - entered;
+            o[7] = (unsigned long long)units;
+        }
+    };
+#endif
 
     if (transforms) {
         const int a_tile = tid >> 4, a_cq = tid & 15;
@@ -1264,37 +1289,51 @@ __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __
         bool last1 = false, last2 = false;
         int tb1 = 0, tb2 = 0;
         for (int u = 0; u <= units; ++u) {
+            WG_SPENT(5, mark);   // requests
             if (u > 0) {   // U_u
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 __builtin_amdgcn_s_barrier();
             }
+            WG_SPENT(0, mark);   // barrier U
             if (last2) {   // staged in the buffer of unit u - 2, which unit u is about to overwrite
                 flush(tb2, u & 1);
                 among_us.sync(lane);   // every transform wave has read its share before any of them writes planes
             }
+            WG_SPENT(1, mark);   // flush
             const int tb = (int)blockIdx.x + jb * (int)gridDim.x;
             if (u < units) {
                 out.sink.base = slot + (u & 1) * kLdsBytes;
                 if (a_t < p.T) {
+#ifdef WG_TIMESTAMPS
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                    WG_SPENT(2, mark);   // wait for the patch
+#endif
                     bias_buffer_patch(patch);
                     transform_patch(patch, out);
                 }
             }
-            if (last1) {   // D_{u-1}, S_{u-1}
-                __syncthreads();
-                __syncthreads();
-            }
-            last2 = last1; tb2 = tb1;
-            last1 = u < units && cb == p.CB - 1; tb1 = tb;
-            if (u < units) {   // next unit's patch
+            WG_SPENT(3, mark);   // transform
+            const bool last0 = u < units && cb == p.CB - 1;
+            if (u < units) {   // next unit's patch, asked for before the waits below so that they cover its latency
                 if (++cb == p.CB) { cb = 0; ++jb; }
                 if (u + 1 < units) {
                     if (cb == 0) enter_tile_block((int)blockIdx.x + jb * (int)gridDim.x);
                     if (a_t < p.T) request(cb);
                 }
             }
+            WG_SPENT(5, mark);   // requests
+            if (last1) {   // D_{u-1}, S_{u-1}
+                __syncthreads();
+                __syncthreads();
+            }
+            WG_SPENT(4, mark);   // barriers D and S
+            last2 = last1; tb2 = tb1;
+            last1 = last0; tb1 = tb;
         }
         if (last2) flush(tb2, (units + 1) & 1);   // the last tile block, staged in the buffer of unit U - 1
+#ifdef WG_TIMESTAMPS
+        report();
+#endif
         return;
     }
 
@@ -1308,8 +1347,9 @@ __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __
     const size_t b_block_stride = (size_t)(p.Kp >> 4) * NP * kFilterFragBytes;
     // 18 joined channel sums per wave in both modes (36 resident accumulators plus the outputs
     // would not fit the 256 registers here)
-    LeanProducts<MODE, 0, true> phase0;
-    LeanProducts<MODE, 1, true> phase1;
+    // scaled mode has the registers for a second set of activation fragments (lossless mode would spill)
+    LeanProducts<MODE, 0, true, 8, MODE == WG_SCALED> phase0;
+    LeanProducts<MODE, 1, true, 8, MODE == WG_SCALED> phase1;
     constexpr int kSumRegs = kChannelSums;
     v4i sums[kSumRegs];
     v4i Y[16];
@@ -1321,10 +1361,13 @@ __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __
         }
         cx.b_glob = b_lane + cb * b_block_stride;
         if (half == 0) phase0.prefetch(cx); else phase1.prefetch(cx);
+        WG_SPENT(5, mark);   // prefetch issue
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();   // U_{u+1}
+        WG_SPENT(0, mark);   // barrier U
         cx.a_lds = lds + (u & 1) * kLdsBytes + lds_slot(lane >> 4, lane & 15) * 16;
         if (half == 0) phase0.run(cx, sums, Y); else phase1.run(cx, sums, Y);
+        WG_SPENT(1, mark);   // products
         if (++cb == p.CB) {
             cb = 0;
 #pragma unroll
@@ -1336,12 +1379,18 @@ __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __
                 if (half == 0) LeanProducts<MODE, 0, true>::finish_lossless(sums, Y);
                 else           LeanProducts<MODE, 1, true>::finish_lossless(sums, Y);
             }
+            WG_SPENT(2, mark);   // finish
             __syncthreads();   // D_u: every product wave has finished reading this unit's planes
+            WG_SPENT(3, mark);   // barrier D
             const StoreContext sc = {lds + (u & 1) * kLdsBytes, tid, lane, wave, half, kblock, 0, 0, 0, -1, rnd, y};
             store_block<WG_NHWC, Q8, 1>(sc, p, q8, Y, k0);
             __syncthreads();   // S_u: staged
+            WG_SPENT(4, mark);   // staging and barrier S
         }
     }
+#ifdef WG_TIMESTAMPS
+    report();
+#endif
 }
 
 // Workgroups per filter block of the streaming kernel: about one workgroup per compute unit in
