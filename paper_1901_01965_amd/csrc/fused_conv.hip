@@ -185,6 +185,7 @@ struct LaneContext {
     const int8_t* a_lds;        // this lane's 16-byte slot in plane 0
     const int8_t* b_glob;       // this lane's 16 bytes of filter plane 0, current channel block
     const ScaleEntry* table_k;  // scaling table row of this lane's filter (scaled mode)
+    const uint32_t* parked;     // role-specialised kernels, scaled mode: see park_scales
 };
 
 constexpr int kFilterPrefetch = 16;   // filter fragments in flight per wave (covers L2 latency)
@@ -293,6 +294,45 @@ struct ProductPhase {
     }
 };
 
+// Role-specialised kernels, scaled mode: the reverse-scaling factors (r, q) of the entries a
+// product wave owns, read once at the start of the kernel (while the wave would only wait for
+// the first operand planes) and parked in LDS as q << 8 | r, [slot][filter of the wave], so that
+// the reverse scaling after the last channel block does not begin with a trip to L2.  Lane
+// group g = lane / 16 reads slots g, 4 + g, 8 + g, 12 + g of filter lane % 16: ask() issues the
+// four loads, park() writes what they brought, and a caller puts its first filter prefetch
+// between the two so that one wait covers both.  Each wave writes and later reads its own 1 KB
+// (16 slots x 16 filters), in program order: no barrier.
+constexpr int kParkedScaleBytes = 16 * 16 * 4;
+template <int HALF>
+struct ParkedScales {
+    static constexpr int NE = ProductPhase<WG_SCALED, HALF>::NE;
+    int2 rq[4];
+    __device__ inline void ask(const LaneContext& cx, int lane) {
+        const int g = lane >> 4;
+        static_for<4>([&](auto J) {
+            int entry = half_slot(HALF, 4 * J).entry;   // slot 4 J + g, clamped to the last slot
+            static_for<3>([&](auto G) {
+                constexpr int slot = 4 * J + G + 1 < NE ? 4 * J + G + 1 : NE - 1;
+                if (g > G) entry = half_slot(HALF, slot).entry;
+            });
+            rq[J] = *reinterpret_cast<const int2*>(&cx.table_k[entry].r);
+        });
+    }
+    __device__ inline void park(LaneContext& cx, int8_t* area, int lane) {
+        uint32_t* const base = reinterpret_cast<uint32_t*>(area) + (lane & 15);
+        const int g = lane >> 4;
+        static_for<4>([&](auto J) {
+            if (4 * J + g < NE) base[(4 * J + g) * 16] = ((uint32_t)rq[J].y << 8) | (uint32_t)rq[J].x;   // r <= 255, q <= 7
+        });
+        cx.parked = base;
+    }
+};
+template <int SLOT>
+__device__ inline ReverseScale parked_scale(const LaneContext& cx) {
+    const uint32_t v = cx.parked[SLOT * 16];
+    return ReverseScale((int)(v & 0xffu), (int)(v >> 8));
+}
+
 // Scaled mode over several channel blocks: the products of every entry a wave owns accumulate
 // in registers across the blocks (run, once per block), and the reverse scaling and the output
 // transform are applied to the finished channel sums (finish, once).
@@ -346,7 +386,7 @@ struct ScaledSums {
     }
 
     // After the last channel block: reverse scaling of the finished sums and the output transform.
-    template <int PASS = 0>
+    template <int PASS = 0, bool PARKED = false>
     __device__ inline static void finish(const LaneContext& cx, const v4i (&sums)[kSums], v4i (&Y)[16]) {
         v4i er[6], ei[6];
         static_for<NE>([&](auto S) {
@@ -354,7 +394,8 @@ struct ScaledSums {
             constexpr int v = sum_start(S);
             v4i re = sums[v], im = {0, 0, 0, 0};
             if constexpr (!is_real(sl.entry)) im = sums[v + 1];
-            const ReverseScale unscale(cx.table_k[PASS * kFusedFilters * kEntries + sl.entry]);   // Section 4.2
+            const ReverseScale unscale = PARKED ? parked_scale<S>(cx)   // Section 4.2
+                                                : ReverseScale(cx.table_k[PASS * kFusedFilters * kEntries + sl.entry]);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 re[q] = unscale(re[q]);
@@ -897,7 +938,7 @@ struct ResidentScaled {
             constexpr int v = acc_start(S);
             v4i re = (acc[v] << kByteLimbShift) + acc[v + 1], im = {0, 0, 0, 0};
             if constexpr (!is_real(sl.entry)) im = (acc[v + 2] << kByteLimbShift) + acc[v + 3];
-            const ReverseScale unscale(cx.table_k[sl.entry]);   // Section 4.2
+            const ReverseScale unscale = parked_scale<S>(cx);   // Section 4.2
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 re[q] = unscale(re[q]);
@@ -1068,6 +1109,9 @@ __global__ __launch_bounds__(64 * (4 + PW)) void fused_conv_roles_kernel(const i
     const int k = k0 + kblock4 * 16 + (lane & 15);
     LaneContext cx;
     cx.table_k = reinterpret_cast<const ScaleEntry*>(blob + table_off) + (size_t)k * kEntries;
+    cx.parked = nullptr;
+    constexpr bool PARKED = SUMS && MODE == WG_SCALED;
+    int8_t* const scale_area = lds + 2 * kLdsBytes + pw * kParkedScaleBytes;   // behind the two plane buffers: 1 KB per product wave
     constexpr int NP = MODE == WG_LOSSLESS ? 138 : 46;
     const int8_t* b_lane = reinterpret_cast<const int8_t*>(blob + planes_off) +
                            filter_plane_offset(0, 0, k, (lane >> 4) * 16, p.Kp, NP);
@@ -1090,10 +1134,18 @@ __global__ __launch_bounds__(64 * (4 + PW)) void fused_conv_roles_kernel(const i
     }
     if constexpr (PW == 8) {
         // one loop per half (the same barriers in both), so that each is allocated registers on its own
-        auto blocks = [&](auto& phase) {
+        auto blocks = [&](auto& phase, auto H) {
+            // the first block's filter prefetch goes out between the request for the reverse-scaling factors and their parking
+            ParkedScales<H> scales;
+            if constexpr (PARKED) scales.ask(cx, lane);
+            cx.b_glob = b_lane;
+            phase.prefetch(cx);
+            if constexpr (PARKED) scales.park(cx, scale_area, lane);
             for (int cb = 0; cb < p.CB; ++cb) {
-                cx.b_glob = b_lane + cb * b_block_stride;
-                phase.prefetch(cx);
+                if (cb > 0) {
+                    cx.b_glob = b_lane + cb * b_block_stride;
+                    phase.prefetch(cx);
+                }
                 WG_SPENT(3, mark);   // ring prefetch issue
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 __builtin_amdgcn_s_barrier();   // barrier cb + 1
@@ -1103,11 +1155,25 @@ __global__ __launch_bounds__(64 * (4 + PW)) void fused_conv_roles_kernel(const i
                 WG_SPENT(2, mark);   // products
             }
         };
-        if (half == 0) blocks(phase0); else blocks(phase1);
+        if (half == 0) blocks(phase0, std::integral_constant<int, 0>{}); else blocks(phase1, std::integral_constant<int, 1>{});
     } else {
+        cx.b_glob = b_lane;
+        if (half == 0) {
+            ParkedScales<0> scales;
+            if constexpr (PARKED) scales.ask(cx, lane);
+            phase0.prefetch(cx);
+            if constexpr (PARKED) scales.park(cx, scale_area, lane);
+        } else {
+            ParkedScales<1> scales;
+            if constexpr (PARKED) scales.ask(cx, lane);
+            phase1.prefetch(cx);
+            if constexpr (PARKED) scales.park(cx, scale_area, lane);
+        }
         for (int cb = 0; cb < p.CB; ++cb) {
-            cx.b_glob = b_lane + cb * b_block_stride;
-            if (half == 0) phase0.prefetch(cx); else phase1.prefetch(cx);
+            if (cb > 0) {
+                cx.b_glob = b_lane + cb * b_block_stride;
+                if (half == 0) phase0.prefetch(cx); else phase1.prefetch(cx);
+            }
             WG_SPENT(3, mark);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             __builtin_amdgcn_s_barrier();   // barrier cb + 1
@@ -1128,8 +1194,8 @@ __global__ __launch_bounds__(64 * (4 + PW)) void fused_conv_roles_kernel(const i
         if (half == 0) ResidentScaled<0>::finish(cx, sums, Y);
         else           ResidentScaled<1>::finish(cx, sums, Y);
     } else if constexpr (SUMS && MODE == WG_SCALED) {
-        if (half == 0) ScaledSums<0>::template finish<0>(cx, sums, Y);
-        else           ScaledSums<1>::template finish<0>(cx, sums, Y);
+        if (half == 0) ScaledSums<0>::template finish<0, true>(cx, sums, Y);
+        else           ScaledSums<1>::template finish<0, true>(cx, sums, Y);
     } else if constexpr (SUMS) {
         if (half == 0) LeanProducts<MODE, 0, true>::finish_lossless(sums, Y);
         else           LeanProducts<MODE, 1, true>::finish_lossless(sums, Y);
@@ -1168,7 +1234,8 @@ __global__ __launch_bounds__(64 * (4 + PW)) void fused_conv_roles_kernel(const i
 template <int LAYOUT, bool VEC4, int MODE, bool SUMS, bool Q8, int PW = 4>
 hipError_t launch_roles(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
                         const Int8Epilogue& q8, hipStream_t s) {
-    constexpr int lds_bytes = 2 * kLdsBytes;
+    constexpr int lds_bytes = 2 * kLdsBytes + PW * kParkedScaleBytes;   // two plane buffers, the parked reverse-scaling factors
+    static_assert(lds_bytes <= 160 * 1024, "fits the LDS of a compute unit");
     static LdsLimitOnce lds_limit;   // per template instance
     if (hipError_t e = lds_limit.set(reinterpret_cast<const void*>(&fused_conv_roles_kernel<LAYOUT, VEC4, MODE, SUMS, Q8, PW>), lds_bytes)) return e;
     dim3 grid(ceil_div(p.T, kFusedTiles), p.Kp / (kFusedFilters * (PW / 4)));   // Kp is a multiple of 64
@@ -1341,6 +1408,8 @@ __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __
     const int k = k0 + kblock * 16 + (lane & 15);
     LaneContext cx;
     cx.table_k = reinterpret_cast<const ScaleEntry*>(blob + table_off) + (size_t)k * kEntries;
+    cx.parked = nullptr;
+    int8_t* const scale_area = lds + 2 * kLdsBytes + 64 + wave * kParkedScaleBytes;   // behind the plane buffers and the barrier counter
     constexpr int NP = MODE == WG_LOSSLESS ? 138 : 46;
     const int8_t* b_lane = reinterpret_cast<const int8_t*>(blob + planes_off) +
                            filter_plane_offset(0, 0, k, (lane >> 4) * 16, p.Kp, NP);
@@ -1354,27 +1423,45 @@ __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __
     v4i sums[kSumRegs];
     v4i Y[16];
     int cb = 0;
+    if (units > 0) {
+        // the first unit's filter prefetch goes out between the request for the reverse-scaling factors and their parking
+        cx.b_glob = b_lane;
+        if (half == 0) {
+            ParkedScales<0> scales;
+            if constexpr (MODE == WG_SCALED) scales.ask(cx, lane);
+            phase0.prefetch(cx);
+            if constexpr (MODE == WG_SCALED) scales.park(cx, scale_area, lane);
+        } else {
+            ParkedScales<1> scales;
+            if constexpr (MODE == WG_SCALED) scales.ask(cx, lane);
+            phase1.prefetch(cx);
+            if constexpr (MODE == WG_SCALED) scales.park(cx, scale_area, lane);
+        }
+    }
     for (int u = 0; u < units; ++u) {
         if (cb == 0) {
 #pragma unroll
             for (int i = 0; i < kSumRegs; ++i) sums[i] = (v4i){0, 0, 0, 0};
         }
-        cx.b_glob = b_lane + cb * b_block_stride;
-        if (half == 0) phase0.prefetch(cx); else phase1.prefetch(cx);
-        WG_SPENT(5, mark);   // prefetch issue
+        WG_SPENT(5, mark);   // clearing the sums
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();   // U_{u+1}
         WG_SPENT(0, mark);   // barrier U
         cx.a_lds = lds + (u & 1) * kLdsBytes + lds_slot(lane >> 4, lane & 15) * 16;
         if (half == 0) phase0.run(cx, sums, Y); else phase1.run(cx, sums, Y);
         WG_SPENT(1, mark);   // products
-        if (++cb == p.CB) {
-            cb = 0;
+        const bool last = cb == p.CB - 1;
+        cb = last ? 0 : cb + 1;
+        if (u + 1 < units) {   // the next unit's first filter fragments travel while this one is finished and staged
+            cx.b_glob = b_lane + cb * b_block_stride;
+            if (half == 0) phase0.prefetch(cx); else phase1.prefetch(cx);
+        }
+        if (last) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) Y[i] = (v4i){0, 0, 0, 0};
             if constexpr (MODE == WG_SCALED) {
-                if (half == 0) ScaledSums<0>::template finish<0>(cx, sums, Y);
-                else           ScaledSums<1>::template finish<0>(cx, sums, Y);
+                if (half == 0) ScaledSums<0>::template finish<0, true>(cx, sums, Y);
+                else           ScaledSums<1>::template finish<0, true>(cx, sums, Y);
             } else {
                 if (half == 0) LeanProducts<MODE, 0, true>::finish_lossless(sums, Y);
                 else           LeanProducts<MODE, 1, true>::finish_lossless(sums, Y);
@@ -1405,7 +1492,8 @@ int stream_workgroups(int tile_blocks, int filter_blocks) {
 template <int MODE, bool Q8>
 hipError_t launch_stream(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
                          const Int8Epilogue& q8, hipStream_t s) {
-    constexpr int lds_bytes = 2 * kLdsBytes + 16;   // two plane buffers and the transform waves' barrier counter
+    // two plane buffers, the transform waves' barrier counter, the parked reverse-scaling factors
+    constexpr int lds_bytes = 2 * kLdsBytes + 64 + 4 * kParkedScaleBytes;
     static LdsLimitOnce lds_limit;   // per template instance
     if (hipError_t e = lds_limit.set(reinterpret_cast<const void*>(&fused_conv_stream_kernel<MODE, Q8>), lds_bytes)) return e;
     const int tile_blocks = ceil_div(p.T, kFusedTiles), filter_blocks = p.Kp / kFusedFilters;
