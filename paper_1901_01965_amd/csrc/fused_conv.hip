@@ -54,6 +54,11 @@ static_assert(kParkBytes <= kLdsBytes, "output staging reuses the operand planes
 //                      acc 0-2: Dr*Wr, 3-5: Di*Wi, 6-8: Dr*Wi + Di*Wr, each as (hh, mid, ll)
 //   scaled, real:      A = (h, l)  B = (W)             acc = (h, l)
 //   scaled, complex:   B = (Wr, Wi, -Wi)               acc = (Re h, Re l, Im h, Im l)
+//   scaled, complex, without the -Wi plane (kScaledTwoPlanes as MODE of the helpers below: a
+//   third less filter traffic per complex entry for two subtractions per register):
+//                      B = (Wr, Wi)                    acc = (Dr*Wr h, l, Im h, Im l, Di*Wi h, l)
+constexpr int kScaledTwoPlanes = 2;
+static_assert(kScaledTwoPlanes != WG_LOSSLESS && kScaledTwoPlanes != WG_SCALED, "a value of its own");
 struct Op {
     int a, b, acc;
     bool init;   // first instruction into this accumulator (starts from zero)
@@ -61,7 +66,7 @@ struct Op {
 constexpr bool is_real(int entry) { return entry < kRealEntries; }
 template <int MODE> constexpr int num_a(int entry) { return is_real(entry) ? 2 : 4; }
 template <int MODE> constexpr int num_b(int entry) {
-    return MODE == WG_LOSSLESS ? (is_real(entry) ? 2 : 4) : (is_real(entry) ? 1 : 3);
+    return MODE == WG_LOSSLESS ? (is_real(entry) ? 2 : 4) : (is_real(entry) ? 1 : (MODE == kScaledTwoPlanes ? 2 : 3));
 }
 template <int MODE> constexpr int num_ops(int entry) {
     return MODE == WG_LOSSLESS ? (is_real(entry) ? 4 : 16) : (is_real(entry) ? 2 : 8);
@@ -89,7 +94,10 @@ template <int MODE> constexpr Op entry_op(int entry, int i) {
     constexpr Op scaled_real[2] = {{0, 0, 0, true}, {1, 0, 1, true}};
     constexpr Op scaled_complex[8] = {{0, 0, 0, true}, {1, 0, 1, true}, {0, 1, 2, true}, {1, 1, 3, true},
                                       {2, 2, 0, false}, {3, 2, 1, false}, {2, 0, 2, false}, {3, 0, 3, false}};
+    constexpr Op two_planes_complex[8] = {{0, 0, 0, true}, {1, 0, 1, true}, {0, 1, 2, true}, {1, 1, 3, true},
+                                          {2, 1, 4, true}, {3, 1, 5, true}, {2, 0, 2, false}, {3, 0, 3, false}};
     if (MODE == WG_LOSSLESS) return is_real(entry) ? lossless_real[i] : lossless_complex[i];
+    if (MODE == kScaledTwoPlanes) return is_real(entry) ? scaled_real[i] : two_planes_complex[i];
     return is_real(entry) ? scaled_real[i] : scaled_complex[i];
 }
 
@@ -232,7 +240,7 @@ struct ProductPhase {
     __device__ inline void prefetch(const LaneContext& cx) {
         static_for<NPRE>([&](auto I) { bring[I] = load_b<I>(cx); });
     }
-    static_assert(NB >= kFilterPrefetch || MODE == WG_SCALED, "the ring is full from the first pass on");
+    static_assert(NB >= kFilterPrefetch || MODE != WG_LOSSLESS, "the ring is full from the first pass on");
 
     // One 64-channel block of this wave's rows.  Software pipeline over entries: while entry i's
     // matrix-core instructions run, entry i+1's activation fragments come from LDS, the filter
@@ -798,7 +806,9 @@ __global__ __launch_bounds__(256) void fused_conv_u8_kernel(const int8_t* __rest
 // are the longer chain of the two roles.
 template <int MODE, int HALF, bool SUMS, int RING = 8, bool AHEAD = false>
 struct LeanProducts {
-    using Phase = ProductPhase<MODE, HALF>;
+    // joined channel sums in scaled mode: complex entries without the -Wi plane
+    static constexpr int PM = MODE == WG_SCALED && SUMS ? kScaledTwoPlanes : MODE;
+    using Phase = ProductPhase<PM, HALF>;
     static constexpr int NE = Phase::NE, NB = Phase::NB;
     static constexpr int kRing = RING;
     v4i ring[kRing];
@@ -812,35 +822,39 @@ struct LeanProducts {
         v4i er[6], ei[6];
         v4i afr2[AHEAD ? 2 : 1][4];
         if constexpr (AHEAD)
-            static_for<num_a<MODE>(half_slot(HALF, 0).entry)>([&](auto I) { afr2[0][I] = Phase::template load_a<0, I>(cx); });
+            static_for<num_a<PM>(half_slot(HALF, 0).entry)>([&](auto I) { afr2[0][I] = Phase::template load_a<0, I>(cx); });
         static_for<NE>([&](auto S) {
             constexpr int s = S;
             constexpr Slot sl = half_slot(HALF, s);
             constexpr int entry = sl.entry;
-            constexpr int b0 = b_start<MODE>(HALF, s);
+            constexpr int b0 = b_start<PM>(HALF, s);
             v4i acc[9];
             v4i (&afr)[4] = afr2[AHEAD ? (s & 1) : 0];
             if constexpr (!AHEAD) {
-                static_for<num_a<MODE>(entry)>([&](auto I) { afr[I] = Phase::template load_a<s, I>(cx); });
+                static_for<num_a<PM>(entry)>([&](auto I) { afr[I] = Phase::template load_a<s, I>(cx); });
             } else if constexpr (s + 1 < NE) {
-                static_for<num_a<MODE>(half_slot(HALF, s + 1).entry)>(
+                static_for<num_a<PM>(half_slot(HALF, s + 1).entry)>(
                     [&](auto I) { afr2[(s + 1) & 1][I] = Phase::template load_a<s + 1, I>(cx); });
             }
-            static_for<num_ops<MODE>(entry)>([&](auto I) {
-                constexpr Op op = entry_op<MODE>(entry, I);
+            static_for<num_ops<PM>(entry)>([&](auto I) {
+                constexpr Op op = entry_op<PM>(entry, I);
                 constexpr v4i zero = {0, 0, 0, 0};
                 acc[op.acc] = __builtin_amdgcn_mfma_i32_16x16x64_i8(afr[op.a], ring[(b0 + op.b) % kRing],
                                                                     op.init ? zero : acc[op.acc], 0, 0, 0);
             });
-            static_for<num_b<MODE>(entry)>([&](auto I) {
+            static_for<num_b<PM>(entry)>([&](auto I) {
                 if constexpr (b0 + I + kRing < NB) ring[(b0 + I) % kRing] = Phase::template load_b<b0 + I + kRing>(cx);
             });
             if constexpr (SUMS) {
                 // joined values only; scaling (scaled mode) and the output transform wait for finish()
                 constexpr int v = ScaledSums<HALF>::sum_start(s);
-                if constexpr (MODE == WG_SCALED) {
-                    sums[v] += (acc[0] << kByteLimbShift) + acc[1];
-                    if constexpr (!is_real(entry)) sums[v + 1] += (acc[2] << kByteLimbShift) + acc[3];
+                if constexpr (MODE == WG_SCALED) {   // Re = Dr Wr - Di Wi,  Im = Dr Wi + Di Wr
+                    if constexpr (is_real(entry)) {
+                        sums[v] += (acc[0] << kByteLimbShift) + acc[1];
+                    } else {
+                        sums[v] += ((acc[0] - acc[4]) << kByteLimbShift) + (acc[1] - acc[5]);
+                        sums[v + 1] += (acc[2] << kByteLimbShift) + acc[3];
+                    }
                 } else if constexpr (is_real(entry)) {
                     sums[v] += join_limbs(acc[0], acc[1], acc[2]);
                 } else {
