@@ -367,6 +367,10 @@ int winograd_debug_lossless_variant(int variant);
    inputs with C % 4 = 0 and K % 4 = 0; both modes, whatever the name says).  0: the library's choice, 1: the second form
    wherever the layout allows, 2: never the second form. */
 int winograd_debug_scaled_variant(int variant);
+/* The same switch for the streaming form of that kernel (a workgroup walks over many tile blocks; chosen for large
+   layers), which also exists with eight product waves and 64 filters per workgroup.  0: the library's choice, 1: eight
+   product waves wherever a layer streams, 2: never. */
+int winograd_debug_stream_variant(int variant);
 int winograd_num_filter_planes(int mode);
 
 /* Host-only: the (n, ty, tx) the kernels derive from tile index t = (n*TH + ty)*TW + tx for

@@ -14,5 +14,5 @@ from .binding import (  # noqa: F401
     requant_relu_pool_int8,
     packed_filter_bytes, workspace_bytes, make_workspace, load_library,
     f2x2_filter_transform, f2x2_conv2d_int8, f2x2_debug_filter_operands, F2x2PackedFilter, f2x2_conv2d_int8_act_scaled, f2x2_conv2d_int8_requant,
-    debug_input_operands, debug_filter_operands, debug_contraction, enqueue_stage, STAGE_NAMES, force_path, stream_workgroups, lossless_variant, scaled_variant, conv2d_path, AUTO, STAGED, FUSED,
+    debug_input_operands, debug_filter_operands, debug_contraction, enqueue_stage, STAGE_NAMES, force_path, stream_workgroups, lossless_variant, scaled_variant, stream_variant, conv2d_path, AUTO, STAGED, FUSED,
 )

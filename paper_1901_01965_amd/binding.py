@@ -46,6 +46,7 @@ def load_library():
         "winograd_debug_stream_workgroups": (i, [i]),
         "winograd_debug_lossless_variant": (i, [i]),
         "winograd_debug_scaled_variant": (i, [i]),
+        "winograd_debug_stream_variant": (i, [i]),
         "winograd_conv2d_path": (i, [i, i, i, i, i, i]),
         "winograd_debug_tile_decode": (i, [i, i, i, i, i, i, vp]),
         "winograd_packed_filter_bytes": (sz, [i, i, i]),
@@ -83,7 +84,7 @@ def load_library():
 
 EXPORTED_SYMBOLS = (
     "winograd_status_string", "winograd_num_activation_planes", "winograd_num_filter_planes",
-    "winograd_debug_force_path", "winograd_debug_stream_workgroups", "winograd_debug_lossless_variant", "winograd_debug_scaled_variant", "winograd_conv2d_path", "winograd_debug_tile_decode",
+    "winograd_debug_force_path", "winograd_debug_stream_workgroups", "winograd_debug_lossless_variant", "winograd_debug_scaled_variant", "winograd_debug_stream_variant", "winograd_conv2d_path", "winograd_debug_tile_decode",
     "winograd_packed_filter_bytes", "winograd_workspace_bytes", "winograd_filter_transform",
     "winograd_packed_filter_check", "winograd_conv2d_int8", "winograd_conv2d_int8_requant",
     "winograd_static_workspace_limit", "winograd_conv2d_int8_static_workspace",
@@ -164,6 +165,12 @@ def lossless_variant(v):
     """Test hook: 0 = library's choice of the lossless single-kernel form, 1 = limb-pair form wherever the layout
     allows, 2 = never the limb-pair form."""
     _check(load_library().winograd_debug_lossless_variant(int(v)), "winograd_debug_lossless_variant")
+
+
+def stream_variant(v):
+    """Test hook: 0 = library's choice of the streaming kernel's form, 1 = eight product waves (64 filters per
+    workgroup) wherever a layer streams, 2 = never."""
+    _check(load_library().winograd_debug_stream_variant(int(v)), "winograd_debug_stream_variant")
 
 
 def scaled_variant(v):

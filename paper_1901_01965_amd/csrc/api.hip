@@ -255,6 +255,12 @@ int winograd_debug_scaled_variant(int variant) {
     return WG_OK;
 }
 
+int winograd_debug_stream_variant(int variant) {
+    if (variant < 0 || variant > 2) return WG_EINVAL;
+    set_stream_variant(variant);
+    return WG_OK;
+}
+
 int winograd_debug_force_path(int path) {
     if (path < 0 || path > 2) return WG_EINVAL;
     g_forced_path.store(path, std::memory_order_relaxed);

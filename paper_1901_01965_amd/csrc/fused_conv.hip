@@ -102,15 +102,17 @@ template <int MODE> constexpr Op entry_op(int entry, int i) {
 }
 
 // ---- which entries a wave owns, in order ---------------------------------------------------
-// Half 0 owns rows 0,1,2 of M, half 1 rows 5 and 3.  A real row RI (rows 0,1,2,5) holds
-// entries 4RI..4RI+3 and the complex entry 16+RI; the complex row holds entries 20..25.
+// Half 0 owns rows 0,1,2 of M, half 1 rows 5 and 3; "half" 2 is all five rows, for a wave that
+// owns every entry.  A real row RI (rows 0,1,2,5) holds entries 4RI..4RI+3 and the complex
+// entry 16+RI; the complex row holds entries 20..25.
+constexpr int kAllRows = 2;
 constexpr int row_entries(int row) { return row < 4 ? 5 : 6; }
 constexpr int row_entry(int row, int pos) {
     return row < 4 ? (pos < 4 ? 4 * row + pos : kRealEntries + row) : kRealEntries + 4 + pos;
 }
-constexpr int half_rows(int half) { return half == 0 ? 3 : 2; }
-constexpr int half_row(int half, int i) { return half == 0 ? i : (i == 0 ? 3 : 4); }
-constexpr int half_entries(int half) { return half == 0 ? 15 : 11; }
+constexpr int half_rows(int half) { return half == 0 ? 3 : (half == 1 ? 2 : 5); }
+constexpr int half_row(int half, int i) { return half == 1 ? (i == 0 ? 3 : 4) : i; }
+constexpr int half_entries(int half) { return half == 0 ? 15 : (half == 1 ? 11 : 26); }
 struct Slot {
     int entry, row, pos;
     bool last_in_row;
@@ -309,15 +311,17 @@ struct ProductPhase {
 // group g = lane / 16 reads slots g, 4 + g, 8 + g, 12 + g of filter lane % 16: ask() issues the
 // four loads, park() writes what they brought, and a caller puts its first filter prefetch
 // between the two so that one wait covers both.  Each wave writes and later reads its own 1 KB
-// (16 slots x 16 filters), in program order: no barrier.
+// (16 slots x 16 filters; 2 KB for a wave that owns all 26 entries), in program order: no barrier.
 constexpr int kParkedScaleBytes = 16 * 16 * 4;
 template <int HALF>
 struct ParkedScales {
     static constexpr int NE = ProductPhase<WG_SCALED, HALF>::NE;
-    int2 rq[4];
+    static constexpr int kRounds = (NE + 3) / 4;   // a wave that owns every entry: seven loads per lane, 2 KB
+    static constexpr int kBytes = kRounds * 4 * 16 * 4;
+    int2 rq[kRounds];
     __device__ inline void ask(const LaneContext& cx, int lane) {
         const int g = lane >> 4;
-        static_for<4>([&](auto J) {
+        static_for<kRounds>([&](auto J) {
             int entry = half_slot(HALF, 4 * J).entry;   // slot 4 J + g, clamped to the last slot
             static_for<3>([&](auto G) {
                 constexpr int slot = 4 * J + G + 1 < NE ? 4 * J + G + 1 : NE - 1;
@@ -329,7 +333,7 @@ struct ParkedScales {
     __device__ inline void park(LaneContext& cx, int8_t* area, int lane) {
         uint32_t* const base = reinterpret_cast<uint32_t*>(area) + (lane & 15);
         const int g = lane >> 4;
-        static_for<4>([&](auto J) {
+        static_for<kRounds>([&](auto J) {
             if (4 * J + g < NE) base[(4 * J + g) * 16] = ((uint32_t)rq[J].y << 8) | (uint32_t)rq[J].x;   // r <= 255, q <= 7
         });
         cx.parked = base;
@@ -411,7 +415,11 @@ struct ScaledSums {
             }
             er[sl.pos] = re;
             ei[sl.pos] = im;
-            if constexpr (sl.last_in_row) finish_row<sl.row>(er, ei, Y);
+            if constexpr (sl.last_in_row) {
+                finish_row<sl.row>(er, ei, Y);
+                // all rows in one wave: row by row, so that a row's sums are dead before the next row's work begins
+                if constexpr (HALF == kAllRows) __builtin_amdgcn_sched_barrier(0);
+            }
         });
     }
 };
@@ -431,7 +439,8 @@ struct StoreContext {
 // the four waves hold in Yp.  All four waves call it together (it contains one barrier).
 // PART 1 / PART 2 (channels-last with K % 4 = 0 only): just the staging of Yp into LDS / just
 // the adding and storing of what was staged, for callers that put their own barrier between
-// the two and may run them on different waves.
+// the two and may run them on different waves.  PART 3: PART 2 for a caller whose waves own every
+// entry and staged one finished copy (in the place of half 0): nothing is added.
 template <int LAYOUT, bool Q8, int PART = 0>
 __device__ __forceinline__ void store_block(const StoreContext& sc, const Problem& p, const Int8Epilogue& q8,
                                             const v4i (&Yp)[16], int kbase) {
@@ -449,7 +458,12 @@ __device__ __forceinline__ void store_block(const StoreContext& sc, const Proble
         // contiguous bytes this block owns of a pixel.
         constexpr int kRow = 36, kHalf = 16 * 16 * kRow;
         static_assert(2 * kHalf * 4 <= kLdsBytes, "staging fits the operand planes' LDS");
-        if constexpr (PART != 2) {
+        // the second half's staged copy of four consecutive filters (none with PART 3)
+        auto other_half = [&](int at) {
+            if constexpr (PART == 3) return (v4i){0, 0, 0, 0};
+            else return *reinterpret_cast<const v4i*>(parki + kHalf + at);
+        };
+        if constexpr (PART < 2) {
             int* dst = parki + half * kHalf + (4 * (lane >> 4)) * kRow + kblock * 16 + (lane & 15);
 #pragma unroll
             for (int o = 0; o < 16; ++o)
@@ -465,7 +479,7 @@ __device__ __forceinline__ void store_block(const StoreContext& sc, const Proble
             // finished int32 outputs of filters 4*g .. 4*g+3 of the block
             auto staged = [&](int o, int tile, int g) {
                 const int at = (o * 16 + tile) * kRow + 4 * g;
-                return (*reinterpret_cast<const v4i*>(parki + at) + *reinterpret_cast<const v4i*>(parki + kHalf + at) + rnd) >> 4;
+                return (*reinterpret_cast<const v4i*>(parki + at) + other_half(at) + rnd) >> 4;
             };
             if (q8.pool) {
                 // 16 tiles x 2x2 pooled pixels = 64 pixels; thread: four filters of pixels px and px + 32
@@ -521,7 +535,7 @@ __device__ __forceinline__ void store_block(const StoreContext& sc, const Proble
         for (int ps = 0; ps < 8; ++ps) {
             const int i = ps >> 1, tile = 8 * (ps & 1) + (px >> 2);
             const int at = ((4 * i + j) * 16 + tile) * kRow + 4 * k4;
-            v[ps] = (*reinterpret_cast<const v4i*>(parki + at) + *reinterpret_cast<const v4i*>(parki + kHalf + at) + rnd) >> 4;
+            v[ps] = (*reinterpret_cast<const v4i*>(parki + at) + other_half(at) + rnd) >> 4;
         }
 #pragma unroll
         for (int ps = 0; ps < 8; ++ps) {
@@ -804,13 +818,15 @@ __global__ __launch_bounds__(256) void fused_conv_u8_kernel(const int8_t* __rest
 // AHEAD: the activation fragments of the next entry are asked for before the current entry's
 // matrix-core instructions (a second set of fragment registers), for callers whose product waves
 // are the longer chain of the two roles.
-template <int MODE, int HALF, bool SUMS, int RING = 8, bool AHEAD = false>
+// PIPE: an entry's vector work runs beside the next entry's matrix-core instructions (a second set of accumulators).
+template <int MODE, int HALF, bool SUMS, int RING = 8, bool AHEAD = false, bool PIPE = false>
 struct LeanProducts {
-    // joined channel sums in scaled mode: complex entries without the -Wi plane
-    static constexpr int PM = MODE == WG_SCALED && SUMS ? kScaledTwoPlanes : MODE;
+    // scaled mode with joined channel sums, or in a wave that owns every entry: complex entries without the -Wi plane
+    static constexpr int PM = MODE == WG_SCALED && (SUMS || HALF == kAllRows) ? kScaledTwoPlanes : MODE;
     using Phase = ProductPhase<PM, HALF>;
     static constexpr int NE = Phase::NE, NB = Phase::NB;
     static constexpr int kRing = RING;
+    static constexpr int kSums = SUMS ? ScaledSums<HALF>::kSums : 1;   // 18 per half, 36 for a wave that owns every entry
     v4i ring[kRing];
 
     __device__ inline void prefetch(const LaneContext& cx) {
@@ -818,17 +834,16 @@ struct LeanProducts {
     }
 
     // sums: the 18 channel sums of ScaledSums (SUMS), else unused; Y: the outputs (not SUMS)
-    __device__ inline void run(const LaneContext& cx, v4i (&sums)[SUMS ? kChannelSums : 1], v4i (&Y)[16]) {
+    __device__ inline void run(const LaneContext& cx, v4i (&sums)[kSums], v4i (&Y)[16]) {
         v4i er[6], ei[6];
         v4i afr2[AHEAD ? 2 : 1][4];
         if constexpr (AHEAD)
             static_for<num_a<PM>(half_slot(HALF, 0).entry)>([&](auto I) { afr2[0][I] = Phase::template load_a<0, I>(cx); });
-        static_for<NE>([&](auto S) {
+        // the matrix-core part of slot S: activation fragments, products into acc, refill of the filter ring
+        auto multiply = [&](auto S, v4i (&acc)[9]) {
             constexpr int s = S;
-            constexpr Slot sl = half_slot(HALF, s);
-            constexpr int entry = sl.entry;
+            constexpr int entry = half_slot(HALF, s).entry;
             constexpr int b0 = b_start<PM>(HALF, s);
-            v4i acc[9];
             v4i (&afr)[4] = afr2[AHEAD ? (s & 1) : 0];
             if constexpr (!AHEAD) {
                 static_for<num_a<PM>(entry)>([&](auto I) { afr[I] = Phase::template load_a<s, I>(cx); });
@@ -845,6 +860,12 @@ struct LeanProducts {
             static_for<num_b<PM>(entry)>([&](auto I) {
                 if constexpr (b0 + I + kRing < NB) ring[(b0 + I) % kRing] = Phase::template load_b<b0 + I + kRing>(cx);
             });
+        };
+        // the vector part of slot S: limbs joined; then into the channel sums, or reverse scaling and output transform
+        auto reduce = [&](auto S, const v4i (&acc)[9]) {
+            constexpr int s = S;
+            constexpr Slot sl = half_slot(HALF, s);
+            constexpr int entry = sl.entry;
             if constexpr (SUMS) {
                 // joined values only; scaling (scaled mode) and the output transform wait for finish()
                 constexpr int v = ScaledSums<HALF>::sum_start(s);
@@ -871,9 +892,12 @@ struct LeanProducts {
                         im = join_limbs(acc[6], acc[7], acc[8]);
                     }
                 } else {
-                    re = (acc[0] << kByteLimbShift) + acc[1];
+                    if constexpr (is_real(entry)) re = (acc[0] << kByteLimbShift) + acc[1];
+                    else if constexpr (PM == kScaledTwoPlanes) re = ((acc[0] - acc[4]) << kByteLimbShift) + (acc[1] - acc[5]);
+                    else re = (acc[0] << kByteLimbShift) + acc[1];
                     if constexpr (!is_real(entry)) im = (acc[2] << kByteLimbShift) + acc[3];
-                    const ReverseScale unscale(cx.table_k[entry]);   // Section 4.2
+                    // Section 4.2 (a wave that owns every entry exists only where the factors were parked)
+                    const ReverseScale unscale = HALF == kAllRows ? parked_scale<s>(cx) : ReverseScale(cx.table_k[entry]);
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         re[q] = unscale(re[q]);
@@ -883,15 +907,45 @@ struct LeanProducts {
                 er[sl.pos] = re;
                 ei[sl.pos] = im;
                 if constexpr (sl.last_in_row) finish_row<sl.row>(er, ei, Y);
+                if constexpr (HALF == kAllRows) {
+                    // Pins the entry's value, and a finished row's outputs, to this place.  Left alone, the compiler moves
+                    // the vector work of all 26 entries behind the last matrix-core instruction (into the block that
+                    // stages the outputs) and keeps every accumulator alive until then.
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        asm volatile("" ::"v"(re[q]));
+                        if constexpr (!is_real(entry)) asm volatile("" ::"v"(im[q]));
+                    }
+                    if constexpr (sl.last_in_row) {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) asm volatile("" ::"v"(Y[i][q]));
+                    }
+                }
             }
-            __builtin_amdgcn_sched_barrier(0);
-        });
+        };
+        if constexpr (PIPE) {
+            // slot s + 1's matrix-core instructions are issued before slot s's vector work, which then runs beside them
+            v4i acc2[2][9];
+            static_for<NE + 1>([&](auto S) {
+                if constexpr (S < NE) multiply(S, acc2[S & 1]);
+                if constexpr (S > 0) reduce(std::integral_constant<int, S - 1>{}, acc2[(S - 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        } else {
+            static_for<NE>([&](auto S) {
+                v4i acc[9];
+                multiply(S, acc);
+                reduce(S, acc);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        }
     }
 
     // SUMS, lossless mode, after the last channel block: the output transform of the channel sums
     // (it is linear, so it may as well run once on the sums as once per block).
-    __device__ inline static void finish_lossless(const v4i (&sums)[SUMS ? kChannelSums : 1], v4i (&Y)[16]) {
-        static_assert(!SUMS || kChannelSums == ScaledSums<HALF>::kSums, "same sum layout as ScaledSums");
+    __device__ inline static void finish_lossless(const v4i (&sums)[kSums], v4i (&Y)[16]) {
         v4i er[6], ei[6];
         static_for<NE>([&](auto S) {
             constexpr Slot sl = half_slot(HALF, S);
@@ -899,7 +953,10 @@ struct LeanProducts {
             er[sl.pos] = sums[v];
             if constexpr (!is_real(sl.entry)) ei[sl.pos] = sums[v + 1];
             else                              ei[sl.pos] = (v4i){0, 0, 0, 0};
-            if constexpr (sl.last_in_row) finish_row<sl.row>(er, ei, Y);
+            if constexpr (sl.last_in_row) {
+                finish_row<sl.row>(er, ei, Y);
+                if constexpr (HALF == kAllRows) __builtin_amdgcn_sched_barrier(0);   // row by row (see ScaledSums::finish)
+            }
         });
     }
 };
@@ -1303,7 +1360,10 @@ struct TransformWavesBarrier {
 // write the latter: between the two they meet at a barrier of their own (TransformWavesBarrier;
 // the product waves, which are multiplying unit u - 1 in the other buffer, do not take part).
 // Channels-last, C % 4 = 0 (4-byte pixel loads), K % 4 = 0 (16-byte stores).
-template <int MODE, bool Q8>
+// WIDE: 64 filters per workgroup.  Each product wave owns every entry of its 16 filters (36 joined channel
+// sums), so one transform serves twice the filters, no halves are added, and the workgroup stages one
+// finished copy of its outputs (32 filters in the place of each half), which the transform waves write out.
+template <int MODE, bool Q8, bool WIDE = false>
 __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __restrict__ x, const uint8_t* __restrict__ blob,
                                                                 size_t table_off, size_t planes_off, int32_t* __restrict__ y,
                                                                 Problem p, Int8Epilogue q8, int tile_blocks) {
@@ -1311,7 +1371,7 @@ __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __
     const int lane = threadIdx.x & 63, wave8 = threadIdx.x >> 6;
     const bool transforms = wave8 < 4;
     const int tid = threadIdx.x & 255, wave = wave8 & 3;   // within the role
-    const int k0 = blockIdx.y * kFusedFilters;
+    const int k0 = blockIdx.y * kFusedFilters * (WIDE ? 2 : 1);
     if (!blob_matches(reinterpret_cast<const BlobHeader*>(blob), p.K, p.C, MODE)) return;
     // this workgroup's tile blocks: blockIdx.x, blockIdx.x + gridDim.x, ...
     const int my_blocks = (tile_blocks - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
@@ -1354,9 +1414,18 @@ __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __
             if (t < p.T) decode_tile(p, t, n, ty, tx);
             const int row = 4 * ty, col = 4 * tx;
             const int origin = t < p.T ? ((n * p.H + row) * p.W + col) * p.K : -1;
-            const StoreContext sc = {lds + buffer * kLdsBytes, tid, lane, wave, 0, 0, n, row, col, origin, rnd, y};
             v4i none[16];
-            store_block<WG_NHWC, Q8, 2>(sc, p, q8, none, k0);
+            if constexpr (WIDE) {
+                constexpr int kCopyBytes = 16 * 16 * 36 * 4;   // one staged copy of 32 filters (store_block's layout)
+#pragma unroll
+                for (int g = 0; g < 2; ++g) {
+                    const StoreContext sc = {lds + buffer * kLdsBytes + g * kCopyBytes, tid, lane, wave, 0, 0, n, row, col, origin, rnd, y};
+                    store_block<WG_NHWC, Q8, 3>(sc, p, q8, none, k0 + g * kFusedFilters);
+                }
+            } else {
+                const StoreContext sc = {lds + buffer * kLdsBytes, tid, lane, wave, 0, 0, n, row, col, origin, rnd, y};
+                store_block<WG_NHWC, Q8, 2>(sc, p, q8, none, k0);
+            }
         };
         TransformWavesBarrier among_us = {reinterpret_cast<uint32_t*>(lds + 2 * kLdsBytes), 0u};
         if (tid == 0) *among_us.counter = 0u;   // lands before the first s_barrier, long before the first use
@@ -1418,16 +1487,68 @@ __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __
         return;
     }
 
+    // WIDE: wave w owns filters 16 w .. 16 w + 15 of the 64 and every entry; in the staging it stands where wave
+    // (half = w / 2, kblock = w % 2) of a 32-filter workgroup stands, so that copy w / 2 holds filters 32 (w / 2) ..
     const int kblock = wave & 1, half = wave >> 1;
-    const int k = k0 + kblock * 16 + (lane & 15);
+    const int k = k0 + (WIDE ? wave : kblock) * 16 + (lane & 15);
     LaneContext cx;
     cx.table_k = reinterpret_cast<const ScaleEntry*>(blob + table_off) + (size_t)k * kEntries;
     cx.parked = nullptr;
-    int8_t* const scale_area = lds + 2 * kLdsBytes + 64 + wave * kParkedScaleBytes;   // behind the plane buffers and the barrier counter
+    // behind the plane buffers and the barrier counter
+    int8_t* const scale_area = lds + 2 * kLdsBytes + 64 + wave * (WIDE ? ParkedScales<kAllRows>::kBytes : kParkedScaleBytes);
     constexpr int NP = MODE == WG_LOSSLESS ? 138 : 46;
     const int8_t* b_lane = reinterpret_cast<const int8_t*>(blob + planes_off) +
                            filter_plane_offset(0, 0, k, (lane >> 4) * 16, p.Kp, NP);
     const size_t b_block_stride = (size_t)(p.Kp >> 4) * NP * kFilterFragBytes;
+    if constexpr (WIDE) {
+        // Every entry of 16 filters in one wave.  36 joined channel sums next to the fragments would not fit the registers,
+        // so each channel block's products go through the reverse scaling and the output transform at once and the
+        // outputs accumulate: exact in lossless mode (the transform is linear); in scaled mode the reverse scaling applies
+        // to the channel sum (Section 4.2), so there the host uses this form for one-block layers only.
+        LeanProducts<MODE, kAllRows, false, 8, true, true> all;
+        v4i unused[1];
+        v4i Y[16];
+        int cb = 0;
+        if (units > 0) {
+            cx.b_glob = b_lane;
+            ParkedScales<kAllRows> scales;
+            if constexpr (MODE == WG_SCALED) scales.ask(cx, lane);
+            all.prefetch(cx);
+            if constexpr (MODE == WG_SCALED) scales.park(cx, scale_area, lane);
+        }
+        for (int u = 0; u < units; ++u) {
+            if (cb == 0) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) Y[i] = (v4i){0, 0, 0, 0};
+            }
+            WG_SPENT(5, mark);   // clearing the outputs
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();   // U_{u+1}
+            WG_SPENT(0, mark);   // barrier U
+            cx.a_lds = lds + (u & 1) * kLdsBytes + lds_slot(lane >> 4, lane & 15) * 16;
+            all.run(cx, unused, Y);
+            WG_SPENT(1, mark);   // products
+            const bool last = cb == p.CB - 1;
+            cb = last ? 0 : cb + 1;
+            if (u + 1 < units) {   // the next unit's first filter fragments travel while this one is staged
+                cx.b_glob = b_lane + cb * b_block_stride;
+                all.prefetch(cx);
+            }
+            if (last) {
+                WG_SPENT(2, mark);   // prefetch issue
+                __syncthreads();   // D_u: every product wave has finished reading this unit's planes
+                WG_SPENT(3, mark);   // barrier D
+                const StoreContext sc = {lds + (u & 1) * kLdsBytes, tid, lane, wave, half, kblock, 0, 0, 0, -1, rnd, y};
+                store_block<WG_NHWC, Q8, 1>(sc, p, q8, Y, k0);
+                __syncthreads();   // S_u: staged
+                WG_SPENT(4, mark);   // staging and barrier S
+            }
+        }
+#ifdef WG_TIMESTAMPS
+        report();
+#endif
+        return;
+    }
     // 18 joined channel sums per wave in both modes (36 resident accumulators plus the outputs
     // would not fit the 256 registers here)
     // scaled mode has the registers for a second set of activation fragments (lossless mode would spill)
@@ -1497,23 +1618,26 @@ __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __
 // Workgroups per filter block of the streaming kernel: about one workgroup per compute unit in
 // total (a test hook can set a smaller number, so that small problems stream, too).
 std::atomic<int> g_stream_workgroups{0};
+// Test hook for the streaming kernel's 64-filter form: 0 the library's choice, 1 wherever a layer streams, 2 never.
+std::atomic<int> g_stream_variant{0};
 int stream_workgroups(int tile_blocks, int filter_blocks) {
     const int forced = g_stream_workgroups.load(std::memory_order_relaxed);
     const int wanted = forced > 0 ? forced : compute_units() / filter_blocks;
     return std::max(1, std::min(tile_blocks, wanted));
 }
 
-template <int MODE, bool Q8>
+template <int MODE, bool Q8, bool WIDE = false>
 hipError_t launch_stream(const int8_t* x, const uint8_t* blob, const BlobLayout& bl, int32_t* y, const Problem& p,
                          const Int8Epilogue& q8, hipStream_t s) {
     // two plane buffers, the transform waves' barrier counter, the parked reverse-scaling factors
-    constexpr int lds_bytes = 2 * kLdsBytes + 64 + 4 * kParkedScaleBytes;
+    constexpr int lds_bytes = 2 * kLdsBytes + 64 + 4 * (WIDE ? ParkedScales<kAllRows>::kBytes : kParkedScaleBytes);
+    static_assert(lds_bytes <= 160 * 1024, "fits the LDS of a compute unit");
     static LdsLimitOnce lds_limit;   // per template instance
-    if (hipError_t e = lds_limit.set(reinterpret_cast<const void*>(&fused_conv_stream_kernel<MODE, Q8>), lds_bytes)) return e;
-    const int tile_blocks = ceil_div(p.T, kFusedTiles), filter_blocks = p.Kp / kFusedFilters;
+    if (hipError_t e = lds_limit.set(reinterpret_cast<const void*>(&fused_conv_stream_kernel<MODE, Q8, WIDE>), lds_bytes)) return e;
+    const int tile_blocks = ceil_div(p.T, kFusedTiles), filter_blocks = p.Kp / (kFusedFilters * (WIDE ? 2 : 1));   // Kp is a multiple of 64
     const int gx = stream_workgroups(tile_blocks, filter_blocks);
-    fused_conv_stream_kernel<MODE, Q8><<<dim3(gx, filter_blocks), 512, lds_bytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p,
-                                                                                     q8, tile_blocks);
+    fused_conv_stream_kernel<MODE, Q8, WIDE><<<dim3(gx, filter_blocks), 512, lds_bytes, s>>>(x, blob, bl.table_off, bl.planes_off, y, p,
+                                                                                           q8, tile_blocks);
     return hipGetLastError();
 }
 
@@ -1885,6 +2009,7 @@ extern "C" int winograd_debug_set_roles_stamps(void* dev_ptr) {
 #endif
 
 void set_scaled_variant(int v) { g_scaled_variant.store(v, std::memory_order_relaxed); }
+void set_stream_variant(int v) { g_stream_variant.store(v, std::memory_order_relaxed); }
 
 void set_stream_workgroups(int n) { g_stream_workgroups.store(n > 0 ? n : 0, std::memory_order_relaxed); }
 
@@ -1928,8 +2053,16 @@ hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, cons
                                      : launch_roles_mode<false>(x, b, bl, y, p, mode, q8, s, true);
     }
     if (streams) {
-        if (mode == WG_LOSSLESS)
+        // the 64-filter form: lossless mode, or one channel block (see the kernel), unless the padding to 64 filters
+        // would add a 32-filter block of nothing
+        const int variant = g_stream_variant.load(std::memory_order_relaxed);
+        const bool whole = (p.K & 63) == 0 || (p.K & 63) > 32;
+        const bool wide = (mode == WG_LOSSLESS || p.CB == 1) && (variant == 1 || (variant == 0 && whole));
+        if (mode == WG_LOSSLESS) {
+            if (wide) return q8.out ? launch_stream<WG_LOSSLESS, true, true>(x, b, bl, y, p, q8, s) : launch_stream<WG_LOSSLESS, false, true>(x, b, bl, y, p, q8, s);
             return q8.out ? launch_stream<WG_LOSSLESS, true>(x, b, bl, y, p, q8, s) : launch_stream<WG_LOSSLESS, false>(x, b, bl, y, p, q8, s);
+        }
+        if (wide) return q8.out ? launch_stream<WG_SCALED, true, true>(x, b, bl, y, p, q8, s) : launch_stream<WG_SCALED, false, true>(x, b, bl, y, p, q8, s);
         return q8.out ? launch_stream<WG_SCALED, true>(x, b, bl, y, p, q8, s) : launch_stream<WG_SCALED, false>(x, b, bl, y, p, q8, s);
     }
     // Transform and products on separate waves (channels-last with 4-byte pixel loads): with

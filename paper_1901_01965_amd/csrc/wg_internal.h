@@ -252,6 +252,8 @@ void set_lossless_variant(int v);
 // Test hook (both modes): 0 the library's choice, 1 the role-specialised kernel with eight product waves (64 filters
 // per workgroup) wherever the layout allows (channels-last, C % 4 = 0, K % 4 = 0), 2 never that form.
 void set_scaled_variant(int v);
+// The same for the streaming kernel's form with eight product waves (0, 1: wherever the layer streams, 2: never).
+void set_stream_variant(int v);
 // Single-kernel path with the activations scaled per tile as well (WG_SCALED blob of signed int8 filters).
 // act_table: null, or int32 [T][26][4] that receives every tile's (n, p, r, q).
 hipError_t launch_fused_conv_act_scaled(const int8_t* x, const void* blob, int32_t* y, int32_t* act_table, const Problem& p,
