@@ -2042,12 +2042,12 @@ hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, cons
     // Measured on the layers of the VGG-16-shaped stack at N = 16 and on the 128-, 256- and 512-channel configurations.
     // Scaled mode: 15-30 % faster than the streaming, 64-filter four-wave and 32-filter role-specialised forms wherever
     // there are two or more channel blocks.  Lossless mode (twice the matrix-core work and filter bytes per product):
-    // +15-25 % from four channel blocks on, +10 % with two where the layer is too small to stream, level or behind
-    // where the streaming form applies to a two-block layer.
+    // +10-25 % with two or more channel blocks where the layer is too small to stream; where it streams, the streaming
+    // kernel's 64-filter form is level (two blocks) or 4 % ahead (four blocks) and takes the layer.
     if (layout == WG_NHWC && p.C % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 4 == 0 && (p.K & 3) == 0) {
         const int variant = g_scaled_variant.load(std::memory_order_relaxed);
         const long long wide_grid = (long long)tile_blocks * (p.Kp / (2 * kFusedFilters));
-        const bool deep_enough = mode == WG_SCALED ? p.CB >= 2 : (p.CB >= 4 || (p.CB >= 2 && !streams));
+        const bool deep_enough = p.CB >= 2 && (mode == WG_SCALED || !streams);
         if (variant == 1 || (variant == 0 && deep_enough && 2 * wide_grid > compute_units()))
             return q8.out != nullptr ? launch_roles_mode<true>(x, b, bl, y, p, mode, q8, s, true)
                                      : launch_roles_mode<false>(x, b, bl, y, p, mode, q8, s, true);
