@@ -1622,8 +1622,11 @@ std::atomic<int> g_stream_workgroups{0};
 std::atomic<int> g_stream_variant{0};
 int stream_workgroups(int tile_blocks, int filter_blocks) {
     const int forced = g_stream_workgroups.load(std::memory_order_relaxed);
-    const int wanted = forced > 0 ? forced : compute_units() / filter_blocks;
-    return std::max(1, std::min(tile_blocks, wanted));
+    if (forced > 0) return std::max(1, std::min(tile_blocks, forced));
+    // as many as the compute units allow, then as few as still finish in the same number of rounds
+    const int wanted = std::max(1, compute_units() / filter_blocks);
+    const int rounds = ceil_div(tile_blocks, wanted);
+    return std::max(1, ceil_div(tile_blocks, rounds));
 }
 
 template <int MODE, bool Q8, bool WIDE = false>
@@ -2023,7 +2026,14 @@ hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, cons
     // and drain of its pipeline cost more than the overlap saves), or when a test asks for it.
     const bool can_stream = layout == WG_NHWC && p.C % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 4 == 0 && (p.K & 3) == 0;
     const int tile_blocks = ceil_div(p.T, kFusedTiles), filter_blocks = p.Kp / kFusedFilters;
-    const bool streams = can_stream && (g_stream_workgroups.load(std::memory_order_relaxed) > 0 ||
+    // The 64-filter form of that kernel (see below for when it applies) is also the fastest form for a layer with one
+    // channel block as soon as the 32-filter grid exceeds one round of the compute units, whatever the number of tile
+    // blocks per workgroup (56x56x64 at N = 12 .. 48: 8-30 % ahead of the limb-pair and 64-filter four-wave kernels).
+    const int stream_variant = g_stream_variant.load(std::memory_order_relaxed);
+    const bool whole64 = (p.K & 63) == 0 || (p.K & 63) > 32;   // padding to 64 filters adds no 32-filter block of nothing
+    const bool wide_one_block = can_stream && p.CB == 1 && whole64 && stream_variant == 0 &&
+                                (long long)tile_blocks * filter_blocks > compute_units();
+    const bool streams = can_stream && (g_stream_workgroups.load(std::memory_order_relaxed) > 0 || wide_one_block ||
                                         tile_blocks >= 6 * stream_workgroups(tile_blocks, filter_blocks));
     // Lossless mode, channels-last, one channel block, too few tile blocks to stream over: the limb-pair form (eight waves
     // per 16 tiles x 32 filters, lossless_conv.hip) against this file's four-wave forms, by rounds of the compute units:
@@ -2055,9 +2065,7 @@ hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, cons
     if (streams) {
         // the 64-filter form: lossless mode, or one channel block (see the kernel), unless the padding to 64 filters
         // would add a 32-filter block of nothing
-        const int variant = g_stream_variant.load(std::memory_order_relaxed);
-        const bool whole = (p.K & 63) == 0 || (p.K & 63) > 32;
-        const bool wide = (mode == WG_LOSSLESS || p.CB == 1) && (variant == 1 || (variant == 0 && whole));
+        const bool wide = (mode == WG_LOSSLESS || p.CB == 1) && (stream_variant == 1 || (stream_variant == 0 && whole64));
         if (mode == WG_LOSSLESS) {
             if (wide) return q8.out ? launch_stream<WG_LOSSLESS, true, true>(x, b, bl, y, p, q8, s) : launch_stream<WG_LOSSLESS, false, true>(x, b, bl, y, p, q8, s);
             return q8.out ? launch_stream<WG_LOSSLESS, true>(x, b, bl, y, p, q8, s) : launch_stream<WG_LOSSLESS, false>(x, b, bl, y, p, q8, s);

@@ -94,3 +94,20 @@ def test_extreme_activations_and_most_channels():
             wg.stream_workgroups(2)
             y = wg.winograd_conv2d_int8(_dev(wl.to_nhwc(x)), packed, wg.NHWC)
             assert np.array_equal(wl.from_nhwc(y.cpu().numpy()), _want(x, g, mode))
+
+
+def test_one_block_layers_beyond_one_round_take_this_form_by_default():
+    """No hooks: a 64-channel layer whose 32-filter grid exceeds one round of the compute units (the quoted layer's shape
+    at batch 12, one or two tile blocks per workgroup) goes to this form by the library's own choice: equal to the direct
+    kernel everywhere, and to the oracle on the first and the last image, both modes."""
+    wg.stream_variant(0)
+    wg.scaled_variant(0)
+    N, C, K, H, W = 12, 64, 64, 56, 56
+    x, g = wl.make_custom(N, C, K, H, W, act="relu", wgt="gauss", seed=296)
+    xd, gd = _dev(wl.to_nhwc(x)), _dev(wl.to_krsc(g))
+    y = wg.winograd_conv2d_int8(xd, wg.winograd_filter_transform(gd, wg.NHWC, wg.LOSSLESS), wg.NHWC)
+    assert torch.equal(y, wg.direct_conv2d_int8(xd, gd, wg.NHWC))
+    ys = wg.winograd_conv2d_int8(xd, wg.winograd_filter_transform(gd, wg.NHWC, wg.SCALED), wg.NHWC)
+    for sl in (slice(0, 1), slice(N - 1, N)):
+        assert np.array_equal(wl.from_nhwc(y[sl].cpu().numpy()), oracle.direct_conv2d(x[sl], g))
+        assert np.array_equal(wl.from_nhwc(ys[sl].cpu().numpy()), _want(x[sl], g, wg.SCALED))
