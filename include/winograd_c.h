@@ -368,8 +368,9 @@ int winograd_debug_lossless_variant(int variant);
    wherever the layout allows, 2: never the second form. */
 int winograd_debug_scaled_variant(int variant);
 /* The same switch for the streaming form of that kernel (a workgroup walks over many tile blocks; chosen for large
-   layers), which also exists with eight product waves and 64 filters per workgroup.  0: the library's choice, 1: eight
-   product waves wherever a layer streams, 2: never. */
+   layers), which also exists with 64 filters per workgroup (each product wave owns every entry of 16 filters; lossless
+   mode, or one channel block).  0: the library's choice, 1: the 64-filter form wherever a layer streams and the form
+   applies, 2: never. */
 int winograd_debug_stream_variant(int variant);
 int winograd_num_filter_planes(int mode);
 

@@ -168,8 +168,8 @@ def lossless_variant(v):
 
 
 def stream_variant(v):
-    """Test hook: 0 = library's choice of the streaming kernel's form, 1 = eight product waves (64 filters per
-    workgroup) wherever a layer streams, 2 = never."""
+    """Test hook: 0 = library's choice of the streaming kernel's form, 1 = 64 filters per workgroup wherever a layer
+    streams and the form applies (lossless mode, or one channel block), 2 = never."""
     _check(load_library().winograd_debug_stream_variant(int(v)), "winograd_debug_stream_variant")
 
 
