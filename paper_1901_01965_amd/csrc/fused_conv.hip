@@ -1360,9 +1360,10 @@ struct TransformWavesBarrier {
 // write the latter: between the two they meet at a barrier of their own (TransformWavesBarrier;
 // the product waves, which are multiplying unit u - 1 in the other buffer, do not take part).
 // Channels-last, C % 4 = 0 (4-byte pixel loads), K % 4 = 0 (16-byte stores).
-// WIDE: 64 filters per workgroup.  Each product wave owns every entry of its 16 filters (36 joined channel
-// sums), so one transform serves twice the filters, no halves are added, and the workgroup stages one
-// finished copy of its outputs (32 filters in the place of each half), which the transform waves write out.
+// WIDE: 64 filters per workgroup.  Each product wave owns every entry of its 16 filters (and keeps no
+// channel sums: see the product side), so one transform serves twice the filters, no halves are added, and
+// the workgroup stages one finished copy of its outputs (32 filters in the place of each half), which the
+// transform waves write out.
 template <int MODE, bool Q8, bool WIDE = false>
 __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __restrict__ x, const uint8_t* __restrict__ blob,
                                                                 size_t table_off, size_t planes_off, int32_t* __restrict__ y,
@@ -1505,7 +1506,8 @@ __global__ __launch_bounds__(512) void fused_conv_stream_kernel(const int8_t* __
         // so each channel block's products go through the reverse scaling and the output transform at once and the
         // outputs accumulate: exact in lossless mode (the transform is linear); in scaled mode the reverse scaling applies
         // to the channel sum (Section 4.2), so there the host uses this form for one-block layers only.
-        LeanProducts<MODE, kAllRows, false, 8, true, true> all;
+        // filter ring: lossless mode has twice the fragments per entry and the registers for twelve in flight
+        LeanProducts<MODE, kAllRows, false, MODE == WG_SCALED ? 8 : 12, true, true> all;
         v4i unused[1];
         v4i Y[16];
         int cb = 0;
