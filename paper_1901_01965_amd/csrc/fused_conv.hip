@@ -2035,7 +2035,13 @@ hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, cons
     const bool whole64 = (p.K & 63) == 0 || (p.K & 63) > 32;   // padding to 64 filters adds no 32-filter block of nothing
     const bool wide_one_block = can_stream && p.CB == 1 && whole64 && stream_variant == 0 &&
                                 (long long)tile_blocks * filter_blocks > compute_units();
-    const bool streams = can_stream && (g_stream_workgroups.load(std::memory_order_relaxed) > 0 || wide_one_block ||
+    // Scaled mode, one channel block, a 32-filter grid of at most one round: the streaming kernel's 32-filter form with
+    // one tile block per workgroup (its eight waves: four transform, four multiply) is 10-14 % ahead of the four-wave
+    // kernel (56x56x64 at N = 8: 9.3 -> 8.5 us); lossless mode has the limb-pair kernel for these layers.
+    const bool forced_stream = g_stream_workgroups.load(std::memory_order_relaxed) > 0;
+    const bool narrow_one_round = can_stream && mode == WG_SCALED && p.CB == 1 && stream_variant == 0 && !forced_stream &&
+                                  (long long)tile_blocks * filter_blocks <= compute_units();
+    const bool streams = can_stream && (forced_stream || wide_one_block || narrow_one_round ||
                                         tile_blocks >= 6 * stream_workgroups(tile_blocks, filter_blocks));
     // Lossless mode, channels-last, one channel block, too few tile blocks to stream over: the limb-pair form (eight waves
     // per 16 tiles x 32 filters, lossless_conv.hip) against this file's four-wave forms, by rounds of the compute units:
@@ -2067,7 +2073,8 @@ hipError_t launch_fused_conv(const int8_t* x, const void* blob, int32_t* y, cons
     if (streams) {
         // the 64-filter form: lossless mode, or one channel block (see the kernel), unless the padding to 64 filters
         // would add a 32-filter block of nothing
-        const bool wide = (mode == WG_LOSSLESS || p.CB == 1) && (stream_variant == 1 || (stream_variant == 0 && whole64));
+        const bool wide = !narrow_one_round && (mode == WG_LOSSLESS || p.CB == 1) &&
+                          (stream_variant == 1 || (stream_variant == 0 && whole64));
         if (mode == WG_LOSSLESS) {
             if (wide) return q8.out ? launch_stream<WG_LOSSLESS, true, true>(x, b, bl, y, p, q8, s) : launch_stream<WG_LOSSLESS, false, true>(x, b, bl, y, p, q8, s);
             return q8.out ? launch_stream<WG_LOSSLESS, true>(x, b, bl, y, p, q8, s) : launch_stream<WG_LOSSLESS, false>(x, b, bl, y, p, q8, s);
