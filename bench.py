@@ -127,13 +127,25 @@ def read_profiled_traffic(kernel):
     return found, "rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated, from %s (kernel sources %s)" % (TRAFFIC_PROFILE, stamp)
 
 
-def time_replay(torch, step, count, eager=False):
-    """Milliseconds per call of step(): `count` calls recorded into one HIP graph, replayed once untimed and once
-    between two synchronisations (or launched one by one when `eager` or when capture is not possible)."""
+SETTLE_MS = 30.0   # untimed replays before the timed one: the device's clocks take some 10 ms of load to settle
+
+
+def time_replay(torch, step, count, eager=False, settle_ms=SETTLE_MS):
+    """Milliseconds per call of step(): `count` calls recorded into one HIP graph, replayed untimed until the device has
+    been busy for `settle_ms` (measured: a 20-step replay of the 7.5 us layer right after start-up runs 6 % slower than
+    the same replay 10 ms later), then once between two synchronisations: the timed region is exactly `count` calls
+    (launched one by one when `eager` or when capture is not possible)."""
     graph = None if eager else capture_steps(torch, step, count)
-    if graph is not None:
-        graph.replay()
-    torch.cuda.synchronize()
+    busy0 = time.perf_counter()
+    while True:
+        if graph is not None:
+            graph.replay()
+        else:
+            for _ in range(count):
+                step()
+        torch.cuda.synchronize()
+        if graph is None or (time.perf_counter() - busy0) * 1e3 >= settle_ms:   # eager (profiling) runs: one untimed pass
+            break
     t0 = time.perf_counter()
     if graph is not None:
         graph.replay()
@@ -336,6 +348,8 @@ def main():
     ap.add_argument("--eager", action="store_true", help="launch the timed steps one by one instead of as one HIP graph")
     ap.add_argument("--no-rotated-figure", action="store_true",
                     help="skip the second timed run over a working set above 512 MB")
+    ap.add_argument("--no-large-batch-figure", action="store_true",
+                    help="skip the extra measurement of the default layer at N = 256 (both modes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--calibration-copy", action="store_true",
@@ -557,7 +571,8 @@ def main():
         "config": {"workload": "%s: 3x3 s1 p1 conv N=%d C=%d K=%d H=W=%d, %s, %s mode" % (
             case.name, case.N, case.C, case.K, case.H, args.layout.upper(), args.mode)},
         "path": "fused" if path == wg.FUSED else "staged",
-        "launch": "hip graph of %d steps, one replay" % args.steps if graphed else "eager",
+        "launch": ("hip graph of %d steps: untimed replays for %d ms, then one timed replay" % (args.steps, SETTLE_MS)
+                   if graphed else "eager"),
         "buffer_sets": len(sets),
         "rotated": rotated,
         "roofline": roofline,
@@ -569,6 +584,30 @@ def main():
                           "equals_int32_path_then_requantisation": int8_matches},
         "gpu_lossless_equals_gpu_direct": same_as_direct,
     }
+
+    # The same layer at N = 256, both modes, for context: where the headline batch (196 workgroups, one round) is bound by
+    # launch and per-workgroup latency, this shows what the kernels sustain once every compute unit has a dozen tile blocks.
+    if default_workload and not args.no_large_batch_figure:
+        import dataclasses
+        big = dataclasses.replace(case, N=256)
+        xb_np, _ = wl.make_case(big)
+        xb = torch.from_numpy(wl.to_nhwc(xb_np)).to(dev)
+        yb = torch.empty((big.N, big.H, big.W, big.K), dtype=torch.int32, device=dev)
+        figure = {"workload": "N=256 C=%d K=%d H=W=%d, NHWC" % (big.C, big.K, big.H)}
+        for name, m in (("lossless", wg.LOSSLESS), ("scaled", wg.SCALED)):
+            pk = packed if m == mode else wg.winograd_filter_transform(gd, layout, m)
+            wsb = wg.make_workspace(big.N, big.C, big.H, big.W, big.K, m)
+
+            def big_step():
+                wg.winograd_conv2d_int8(xb, pk, layout, out=yb, workspace=wsb)
+
+            for _ in range(10):
+                big_step()
+            torch.cuda.synchronize()
+            bms, _ = time_replay(torch, big_step, 100, args.eager)   # as `--batch 256 --steps 100` measures it
+            figure[name] = {"ms_per_step": round(bms, 5), "TOPS": round(big.direct_ops / (bms * 1e-3) / 1e12, 2)}
+        result["large_batch"] = figure
+        del xb, yb
 
     if not args.no_cpu_baseline:
         import oracle
