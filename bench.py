@@ -208,18 +208,7 @@ def run_stack(args):
         for _ in range(max(1, args.warmup // 4)):
             fn()
         torch.cuda.synchronize()
-        graph = None if args.eager else capture_steps(torch, fn, count)
-        if graph is not None:
-            graph.replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        if graph is not None:
-            graph.replay()
-        else:
-            for _ in range(count):
-                fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / count * 1e3, graph is not None
+        return time_replay(torch, fn, count, args.eager)
 
     steps = min(args.steps, 50)
     ms, graphed = timed(step, steps)
@@ -255,7 +244,8 @@ def run_stack(args):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": "cfg5: VGG-16-shaped stack of 13 3x3 convolutions, N=%d, NHWC, %s mode, int8 between layers "
                                "(power-of-two requantisation, ReLU, 2x2 max-pool after layers 2,4,7,10,13)" % (batch, args.mode)},
-        "launch": "hip graph of %d steps, one replay" % steps if graphed else "eager",
+        "launch": ("hip graph of %d steps: untimed replays for %d ms, then one timed replay" % (steps, SETTLE_MS)
+                   if graphed else "eager"),
         "layers": layers,
         "int32_conv_plus_requant_kernel_ms": round(two_ms, 4), "final_activations_equal": same,
         "direct_conv_plus_requant_kernel_ms": round(direct_ms, 4), "final_activations_equal_direct": same_direct,
@@ -297,18 +287,7 @@ def run_f2x2(args):
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    graph = None if args.eager else capture_steps(torch, step, args.steps)
-    if graph is not None:
-        graph.replay()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    if graph is not None:
-        graph.replay()
-    else:
-        for _ in range(args.steps):
-            step()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    ms, graphed = time_replay(torch, step, args.steps, args.eager)
     yd = wg.direct_conv2d_int8(xd, gd, layout)
     tiles2 = case.N * ((case.H + 1) // 2) * ((case.W + 1) // 2)
     alg = 4 * tiles2 * case.C + (32 if mode == wg.LOSSLESS else 16) * case.K * case.C + 16 * tiles2 * case.K
@@ -321,7 +300,8 @@ def run_f2x2(args):
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "%s: 3x3 s1 p1 conv N=%d C=%d K=%d H=W=%d, %s, %s mode, rational F(2x2,3x3)" % (
             case.name, case.N, case.C, case.K, case.H, args.layout.upper(), args.mode)},
-        "launch": "hip graph of %d steps, one replay" % args.steps if graph is not None else "eager",
+        "launch": ("hip graph of %d steps: untimed replays for %d ms, then one timed replay" % (args.steps, SETTLE_MS)
+                   if graphed else "eager"),
         "roofline": {"kernel": "f2_conv", "bound": "hbm", "achieved": round(alg / (ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
                      "algorithmic_bytes": alg, "kernel_ms": round(ms, 5)},
@@ -523,19 +503,7 @@ def main():
     for _ in range(3):
         direct_step()
     torch.cuda.synchronize()
-    direct_runs = 20
-    dgraph = None if args.eager else capture_steps(torch, direct_step, direct_runs)
-    if dgraph is not None:
-        dgraph.replay()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    if dgraph is not None:
-        dgraph.replay()
-    else:
-        for _ in range(direct_runs):
-            direct_step()
-    torch.cuda.synchronize()
-    direct_ms = (time.perf_counter() - t0) / direct_runs * 1e3
+    direct_ms, _ = time_replay(torch, direct_step, max(20, args.steps), args.eager)
     same_as_direct = bool(torch.equal(y, yd)) if mode == wg.LOSSLESS else None
 
     # the same convolution with requantisation and ReLU applied before the store (int8 output), for context
@@ -548,18 +516,7 @@ def main():
     for _ in range(3):
         int8_step()
     torch.cuda.synchronize()
-    qgraph = None if args.eager else capture_steps(torch, int8_step, args.steps)
-    if qgraph is not None:
-        qgraph.replay()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    if qgraph is not None:
-        qgraph.replay()
-    else:
-        for _ in range(args.steps):
-            int8_step()
-    torch.cuda.synchronize()
-    int8_ms = (time.perf_counter() - t0) / args.steps * 1e3
+    int8_ms, _ = time_replay(torch, int8_step, args.steps, args.eager)
     int8_matches = bool(torch.equal(y8, wg.requant_relu_pool_int8(y, shift, True, False, layout)))
 
     result = {
