@@ -96,13 +96,17 @@ def test_extreme_activations_and_most_channels():
             assert np.array_equal(wl.from_nhwc(y.cpu().numpy()), _want(x, g, mode))
 
 
-def test_one_block_layers_beyond_one_round_take_this_form_by_default():
-    """No hooks: a 64-channel layer whose 32-filter grid exceeds one round of the compute units (the quoted layer's shape
-    at batch 12, one or two tile blocks per workgroup) goes to this form by the library's own choice: equal to the direct
-    kernel everywhere, and to the oracle on the first and the last image, both modes."""
+@pytest.mark.parametrize("N", [8, 12, 40])
+def test_library_choice_on_the_quoted_layer_at_small_and_medium_batch(N):
+    """No hooks: the quoted layer's shape (64 channels, 64 filters, 56x56) at batches around the points where the library
+    changes kernels.  N = 8: one round of 32-filter workgroups (lossless: limb-pair kernel; scaled: the streaming kernel's
+    32-filter form, one tile block per workgroup).  N = 12: the 32-filter grid exceeds one round, the 64-filter grid does
+    not (lossless: this file's 64-filter streaming form; scaled: the role-specialised kernel with eight product waves).
+    N = 40: both exceed it (64-filter streaming form in both modes).  Lossless equals the direct kernel everywhere; both
+    modes equal the oracle on the first and the last image."""
     wg.stream_variant(0)
     wg.scaled_variant(0)
-    N, C, K, H, W = 12, 64, 64, 56, 56
+    C, K, H, W = 64, 64, 56, 56
     x, g = wl.make_custom(N, C, K, H, W, act="relu", wgt="gauss", seed=296)
     xd, gd = _dev(wl.to_nhwc(x)), _dev(wl.to_krsc(g))
     y = wg.winograd_conv2d_int8(xd, wg.winograd_filter_transform(gd, wg.NHWC, wg.LOSSLESS), wg.NHWC)
